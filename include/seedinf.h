@@ -1,0 +1,190 @@
+/*
+ * seedinf.h -- C ABI of libseedinf: SEED RL's central batched inference step
+ * on one MI355X (gfx950).
+ *
+ * The operation (Section 3, "Detailed Learner architecture"): an inference
+ * thread holds a batch of observations, previous rewards and per-actor
+ * recurrent states gathered from many actors; one call runs the agent network
+ * forward on the whole batch and returns the selected actions and the new
+ * recurrent states.  Network families: the R2D2 conv stack + linear + LSTM +
+ * dueling heads (Appendix A.3.1), and the deep ResNet torso the paper names
+ * for DeepMind Lab (Section 4.1) and Football (Section 4.2) with a linear
+ * layer, an optional LSTM core and policy/value heads.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the device that was current
+ *     when the handle was created; "host" pointers are ordinary host memory.
+ *   - All arrays are dense, row-major, C order.  Activations are NHWC;
+ *     convolution kernels are [kh][kw][cin][cout]; dense matrices are
+ *     [in][out].
+ *   - Every function returns a seed_status_t (except where noted); nothing
+ *     throws or aborts across this boundary.  On an error return no output
+ *     array has been written.
+ *   - The caller owns every pointer it passes.  The library owns the handle,
+ *     its repacked copy of the weights and a workspace sized for max_batch.
+ *   - One handle is used from one host thread and one stream at a time.
+ */
+#ifndef SEEDINF_H
+#define SEEDINF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct seed_infer seed_infer_t; /* opaque */
+
+typedef enum {
+    SEED_OK = 0,
+    SEED_ERR_INVALID_ARG = 1,      /* null pointer, bad size, bad field value */
+    SEED_ERR_UNSUPPORTED_ARCH = 2, /* a network this build has no kernels for */
+    SEED_ERR_BATCH_TOO_LARGE = 3,  /* B > max_batch given at creation */
+    SEED_ERR_ALIASING = 4,         /* an output overlaps an input it must not */
+    SEED_ERR_DEVICE = 5,           /* a HIP runtime call failed (see last_error) */
+    SEED_ERR_OOM = 6               /* device or host allocation failed */
+} seed_status_t;
+
+enum { SEED_TORSO_CONV_STACK = 0, SEED_TORSO_RESNET = 1 };
+enum { SEED_HEAD_POLICY_VALUE = 0, SEED_HEAD_DUELING_Q = 1 };
+enum { SEED_SELECT_GREEDY = 0, SEED_SELECT_GUMBEL = 1 };
+enum { SEED_PRECISION_FP32 = 0, SEED_PRECISION_BF16 = 1 };
+
+#define SEED_MAX_LAYERS 4
+#define SEED_MAX_ACTIONS 64
+
+/*
+ * Network description (plain data; set struct_size = sizeof(seed_arch_t)).
+ *
+ * torso == SEED_TORSO_CONV_STACK (Appendix A.3.1): n_conv layers of
+ *   conv(conv_k[i] x conv_k[i], stride conv_stride[i], "valid" padding,
+ *   conv_ch[i] filters) + ReLU; then flatten (h, w, c order), a linear layer of
+ *   fc_units, ReLU.
+ * torso == SEED_TORSO_RESNET (the model Sections 4.1 / 4.2 name): n_sections
+ *   sections; section s is conv 3x3 SAME to section_ch[s] channels (no ReLU),
+ *   max-pool 3x3 stride 2 SAME (window cells outside the image are ignored;
+ *   odd total padding puts the extra cell after), then two residual blocks
+ *   x + conv3x3(ReLU(conv3x3(ReLU(x)))); after the last section ReLU, flatten,
+ *   linear fc_units, ReLU.
+ * lstm_units > 0 (Appendix A.3.1): an LSTM step whose input is
+ *   [linear output, one-hot(prev_action, num_actions), prev_reward];
+ *   gate columns ordered input | forget | cell | output; no peepholes.
+ * head == SEED_HEAD_POLICY_VALUE: logits[num_actions] and a scalar value, both
+ *   linear in the core output.  head == SEED_HEAD_DUELING_Q (Section 3.2,
+ *   Appendix A.3.1): value and advantage streams, each linear(head_hidden) +
+ *   ReLU + linear; Q = V + Adv - mean(Adv).
+ * select: greedy argmax (lowest index wins ties) or Gumbel-max sampling
+ *   argmax_j(logit_j - log(-log(u_j))) with caller-supplied uniforms, which
+ *   draws from softmax(logits) ("sampled actions", Section 3).
+ * precision: SEED_PRECISION_FP32 computes everything in fp32.
+ *   SEED_PRECISION_BF16 feeds bf16 operands to the matrix cores with fp32
+ *   accumulation; the residual stream, LSTM gate math, cell state, heads and
+ *   selection stay fp32.  Inputs and outputs have the same types in both.
+ */
+typedef struct {
+    uint32_t struct_size;
+    int32_t obs_h, obs_w, obs_c;
+    int32_t torso;
+    int32_t n_conv;
+    int32_t conv_ch[SEED_MAX_LAYERS], conv_k[SEED_MAX_LAYERS], conv_stride[SEED_MAX_LAYERS];
+    int32_t n_sections;
+    int32_t section_ch[SEED_MAX_LAYERS];
+    int32_t fc_units;
+    int32_t lstm_units;   /* 0 = no recurrent core */
+    int32_t num_actions;  /* 1 .. SEED_MAX_ACTIONS */
+    int32_t head;
+    int32_t head_hidden;  /* dueling hidden width; ignored for policy/value */
+    int32_t select;
+    int32_t precision;
+    int32_t max_batch;    /* largest B seed_infer_step will be called with */
+} seed_arch_t;
+
+/*
+ * Length of the canonical flat fp32 weight vector for `arch`, or 0 if the
+ * arch is invalid.  Order: per conv W[kh][kw][cin][cout] then b[cout], layers
+ * in forward order (ResNet section: conv0, block1.a, block1.b, block2.a,
+ * block2.b); linear W[in][out], b; LSTM W[(fc_units+num_actions+1)+lstm_units]
+ * [4*lstm_units] with rows [linear features | action rows | reward row | h rows]
+ * and column blocks [i|f|g|o], then b[4*lstm_units]; heads: policy W[n][A], b[A],
+ * value W[n][1], b[1]; or dueling value W1[n][hid], b1, W2[hid][1], b2, then
+ * advantage W1[n][hid], b1, W2[hid][A], b2.  Host-only; touches no device.
+ */
+size_t seed_infer_weight_count(const seed_arch_t* arch);
+
+/*
+ * Validate `arch` without touching a device.  Returns SEED_OK,
+ * SEED_ERR_INVALID_ARG (null, wrong struct_size, non-positive sizes, a conv
+ * that does not fit its input, ...) or SEED_ERR_UNSUPPORTED_ARCH (valid in
+ * principle but outside the shapes the kernels were written for).
+ */
+seed_status_t seed_infer_validate(const seed_arch_t* arch);
+
+/*
+ * Create a handle on the current HIP device.  weights_host: host pointer to
+ * n_weights fp32 values in the canonical order; n_weights must equal
+ * seed_infer_weight_count(arch).  The weights are copied and repacked (to
+ * bf16 tiles in bf16 mode) before the call returns; the caller may free them.
+ * Allocates the workspace for max_batch rows once.  *out is set only on
+ * SEED_OK.  Validation errors are reported before any device call is made.
+ */
+seed_status_t seed_infer_create(const seed_arch_t* arch, const float* weights_host,
+                                size_t n_weights, seed_infer_t** out);
+
+/*
+ * One inference step on B gathered rows (Section 3).  All array arguments are
+ * device pointers.  The work is enqueued on `hip_stream` (a hipStream_t, NULL =
+ * the default stream) and the call returns without synchronising; it allocates
+ * nothing.
+ *
+ *   obs          [B, obs_h, obs_w, obs_c] uint8 frames (scaled by 1/255 inside)
+ *   prev_action  [B] int32  } required iff lstm_units > 0, else must be NULL;
+ *   prev_reward  [B] fp32   } an action outside [0, num_actions) gives an
+ *   h_in, c_in   [B, lstm_units] fp32 } all-zero one-hot
+ *   uniforms     [B, num_actions] fp32 in (0,1); required iff select is
+ *                SEED_SELECT_GUMBEL, else must be NULL
+ *   action_out   [B] int32
+ *   logits_out   [B, num_actions] fp32: policy logits, or Q-values (dueling)
+ *   value_out    [B] fp32: value head, or the dueling value stream
+ *   h_out, c_out [B, lstm_units] fp32; required iff lstm_units > 0; must not
+ *                overlap h_in / c_in (SEED_ERR_ALIASING): the caller ping-pongs
+ *   probs_out    [B, num_actions] fp32 softmax(logits_out), or NULL to skip
+ *
+ * B == 0 is a no-op returning SEED_OK.  B < 0 is SEED_ERR_INVALID_ARG,
+ * B > max_batch is SEED_ERR_BATCH_TOO_LARGE.
+ */
+seed_status_t seed_infer_step(seed_infer_t* handle, int32_t B,
+                              const uint8_t* obs,
+                              const int32_t* prev_action, const float* prev_reward,
+                              const float* h_in, const float* c_in,
+                              const float* uniforms,
+                              int32_t* action_out, float* logits_out, float* value_out,
+                              float* h_out, float* c_out, float* probs_out,
+                              void* hip_stream);
+
+/*
+ * Test/diagnostic tap: copy an intermediate of the most recent step into a
+ * device buffer as fp32 (converted from the internal storage type), enqueued
+ * on `hip_stream` after the step's work.  which = 0: the rectified, flattened
+ * torso output [B, torso_features]; which = 1: the linear layer's rectified
+ * output [B, fc_units].  `capacity` is the number of floats `dst` can hold.
+ */
+seed_status_t seed_infer_read_intermediate(seed_infer_t* handle, int32_t which, int32_t B,
+                                           float* dst, size_t capacity, void* hip_stream);
+
+/* Number of features the torso feeds the linear layer (H*W*C), 0 if invalid. */
+size_t seed_infer_torso_features(const seed_arch_t* arch);
+
+/* Text of the most recent error on this handle ("" if none); never NULL.
+ * With handle == NULL returns the text of the last failed seed_infer_create or
+ * seed_infer_validate on the calling thread.  Owned by the library. */
+const char* seed_infer_last_error(const seed_infer_t* handle);
+
+/* Free the handle and everything it owns.  NULL is allowed.  The caller must
+ * have synchronised every stream the handle was used on. */
+void seed_infer_destroy(seed_infer_t* handle);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEEDINF_H */

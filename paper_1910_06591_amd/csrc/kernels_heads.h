@@ -1,0 +1,104 @@
+// Output heads and action selection, fp32, one wavefront per batch row.
+//
+// The last linear maps (core -> logits/value, or dueling hidden -> advantage /
+// value) are short dot products over n <= 8192 inputs and A <= 64 outputs: the
+// 64 lanes split into 64/P groups (P = power of two >= A), lane (g, a) sums
+// the inputs i = g, g + 64/P, ... for output a, and the groups are combined with
+// xor-shuffles.  Softmax, the dueling mean and the (Gumbel-)argmax are row
+// reductions over the first P lanes, again by shuffles: no LDS, no atomics, so
+// results are bit-reproducible run to run.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cfloat>
+#include <cstdint>
+
+namespace seedinf {
+
+struct HeadsArgs {
+    const float* vec_a; int ld_a;    // [B, n] input of the A action outputs
+    const float* vec_v; int ld_v;    // [B, n] input of the value output
+    const float* w_a;                // [n][A]
+    const float* b_a;                // [A]
+    const float* w_v;                // [n]
+    const float* b_v;                // [1]
+    const float* uniforms;           // [B, A] or nullptr (greedy)
+    int32_t* action;                 // [B]
+    float* logits;                   // [B, A]
+    float* value;                    // [B]
+    float* probs;                    // [B, A] or nullptr
+    int n, A, B;
+    int dueling;                     // 1: logits = V + Adv - mean(Adv)
+};
+
+template <int P>
+__global__ __launch_bounds__(256) void heads_select_kernel(HeadsArgs p)
+{
+    constexpr int G = 64 / P;
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= p.B) return;                      // whole wavefront leaves together
+    const int a = lane & (P - 1);
+    const int g = lane / P;
+    const bool live = a < p.A;
+
+    // action outputs
+    float acc = 0.0f;
+    {
+        const float* v = p.vec_a + (size_t)row * p.ld_a;
+        if (live)
+            for (int i = g; i < p.n; i += G) acc = fmaf(v[i], p.w_a[(size_t)i * p.A + a], acc);
+    }
+#pragma unroll
+    for (int off = P; off < 64; off <<= 1) acc += __shfl_xor(acc, off, 64);
+    float out = live ? acc + p.b_a[a] : 0.0f;
+
+    // value output: all 64 lanes share the dot product
+    float vacc = 0.0f;
+    {
+        const float* v = p.vec_v + (size_t)row * p.ld_v;
+        for (int i = lane; i < p.n; i += 64) vacc = fmaf(v[i], p.w_v[i], vacc);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) vacc += __shfl_xor(vacc, off, 64);
+    const float val = vacc + p.b_v[0];
+
+    if (p.dueling) {
+        float s = out;                            // dead lanes hold 0
+#pragma unroll
+        for (int off = P / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        out = live ? val + out - s / (float)p.A : 0.0f;
+    }
+
+    if (lane < p.A) p.logits[(size_t)row * p.A + lane] = out;
+    if (lane == 0) p.value[row] = val;
+
+    if (p.probs) {
+        float m = live ? out : -INFINITY;
+#pragma unroll
+        for (int off = P / 2; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+        float e = live ? expf(out - m) : 0.0f;
+        float s = e;
+#pragma unroll
+        for (int off = P / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (lane < p.A) p.probs[(size_t)row * p.A + lane] = e / s;
+    }
+
+    // selection: argmax of logits (+ Gumbel noise), lowest index wins ties
+    float key = live ? out : -INFINITY;
+    if (p.uniforms && live) {
+        float u = p.uniforms[(size_t)row * p.A + a];
+        u = fminf(fmaxf(u, FLT_MIN), 1.0f - 5.9604644775390625e-8f);
+        key = out - logf(-logf(u));
+    }
+    int best = a;
+#pragma unroll
+    for (int off = P / 2; off > 0; off >>= 1) {
+        float ok = __shfl_xor(key, off, 64);
+        int ob = __shfl_xor(best, off, 64);
+        if (ok > key || (ok == key && ob < best)) { key = ok; best = ob; }
+    }
+    if (lane == 0) p.action[row] = best;
+}
+
+}  // namespace seedinf

@@ -1,0 +1,312 @@
+// libseedinf host side: C ABI, validation, weight upload/repack, workspace and
+// the per-step kernel sequence.  See include/seedinf.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/seedinf.h"
+#include "plan.h"
+#include "kernels_fp32.h"
+#include "kernels_heads.h"
+#include "bf16_path.h"
+
+using namespace seedinf;
+
+struct seed_infer {
+    Plan plan;
+    int device = -1;
+    float* d_w = nullptr;          // canonical flat fp32 weights
+    float* d_act[2] = {nullptr, nullptr};   // fp32 ping-pong activations (fp32 mode)
+    float* d_fc = nullptr;         // [max_batch, fc_units] fp32 (fp32 mode)
+    float* d_hid = nullptr;        // [max_batch, 2*head_hidden] dueling hidden, fp32
+    const float* feat_f32 = nullptr;   // where the last fp32-mode step left the torso features
+    Bf16State* bf = nullptr;       // everything the bf16 path owns
+    std::string err;
+};
+
+static thread_local std::string g_create_err;
+
+#define HIP_TRY(h, expr)                                                              \
+    do {                                                                              \
+        hipError_t e_ = (expr);                                                       \
+        if (e_ != hipSuccess) {                                                       \
+            (h)->err = std::string(#expr) + ": " + hipGetErrorString(e_);             \
+            return e_ == hipErrorOutOfMemory ? SEED_ERR_OOM : SEED_ERR_DEVICE;        \
+        }                                                                             \
+    } while (0)
+
+extern "C" size_t seed_infer_weight_count(const seed_arch_t* arch)
+{
+    Plan p;
+    std::string err;
+    if (make_plan(arch, p, err) != SEED_OK) return 0;
+    return p.n_weights;
+}
+
+extern "C" size_t seed_infer_torso_features(const seed_arch_t* arch)
+{
+    Plan p;
+    std::string err;
+    if (make_plan(arch, p, err) != SEED_OK) return 0;
+    return p.flat;
+}
+
+static seed_status_t validate_impl(const seed_arch_t* arch, Plan& p, std::string& err)
+{
+    seed_status_t st = make_plan(arch, p, err);
+    if (st != SEED_OK) return st;
+    if (arch->precision == SEED_PRECISION_BF16) return bf16_supported(p, err);
+    return SEED_OK;
+}
+
+extern "C" seed_status_t seed_infer_validate(const seed_arch_t* arch)
+{
+    Plan p;
+    g_create_err.clear();
+    return validate_impl(arch, p, g_create_err);
+}
+
+extern "C" const char* seed_infer_last_error(const seed_infer_t* h)
+{
+    return h ? h->err.c_str() : g_create_err.c_str();
+}
+
+static void free_all(seed_infer* h)
+{
+    if (!h) return;
+    if (h->bf) { bf16_destroy(h->bf); h->bf = nullptr; }
+    if (h->d_w) (void)hipFree(h->d_w);
+    if (h->d_act[0]) (void)hipFree(h->d_act[0]);
+    if (h->d_act[1]) (void)hipFree(h->d_act[1]);
+    if (h->d_fc) (void)hipFree(h->d_fc);
+    if (h->d_hid) (void)hipFree(h->d_hid);
+    delete h;
+}
+
+extern "C" void seed_infer_destroy(seed_infer_t* h) { free_all(h); }
+
+static seed_status_t create_impl(seed_infer* h, const float* weights_host)
+{
+    const Plan& p = h->plan;
+    const seed_arch_t& a = p.arch;
+    HIP_TRY(h, hipGetDevice(&h->device));
+    HIP_TRY(h, hipMalloc(&h->d_w, p.n_weights * sizeof(float)));
+    HIP_TRY(h, hipMemcpy(h->d_w, weights_host, p.n_weights * sizeof(float), hipMemcpyHostToDevice));
+    const size_t mb = (size_t)a.max_batch;
+    if (a.head == SEED_HEAD_DUELING_Q) HIP_TRY(h, hipMalloc(&h->d_hid, mb * 2 * a.head_hidden * sizeof(float)));
+    if (a.precision == SEED_PRECISION_FP32) {
+        HIP_TRY(h, hipMalloc(&h->d_act[0], mb * p.max_act * sizeof(float)));
+        HIP_TRY(h, hipMalloc(&h->d_act[1], mb * p.max_act * sizeof(float)));
+        HIP_TRY(h, hipMalloc(&h->d_fc, mb * a.fc_units * sizeof(float)));
+    } else {
+        seed_status_t st = bf16_create(p, weights_host, h->d_w, &h->bf, h->err);
+        if (st != SEED_OK) return st;
+    }
+    HIP_TRY(h, hipDeviceSynchronize());
+    return SEED_OK;
+}
+
+extern "C" seed_status_t seed_infer_create(const seed_arch_t* arch, const float* weights_host,
+                                           size_t n_weights, seed_infer_t** out)
+{
+    g_create_err.clear();
+    if (!out) { g_create_err = "out is NULL"; return SEED_ERR_INVALID_ARG; }
+    seed_infer* h = new (std::nothrow) seed_infer;
+    if (!h) { g_create_err = "host allocation failed"; return SEED_ERR_OOM; }
+    seed_status_t st = validate_impl(arch, h->plan, g_create_err);
+    if (st == SEED_OK && !weights_host) { g_create_err = "weights_host is NULL"; st = SEED_ERR_INVALID_ARG; }
+    if (st == SEED_OK && n_weights != h->plan.n_weights) {
+        char msg[128];
+        snprintf(msg, sizeof msg, "n_weights is %zu, this arch has %zu", n_weights, h->plan.n_weights);
+        g_create_err = msg;
+        st = SEED_ERR_INVALID_ARG;
+    }
+    if (st != SEED_OK) { delete h; return st; }
+    st = create_impl(h, weights_host);
+    if (st != SEED_OK) {
+        g_create_err = h->err;
+        free_all(h);
+        return st;
+    }
+    *out = h;
+    return SEED_OK;
+}
+
+static inline unsigned blocks_for(size_t n, unsigned per = 256) { return (unsigned)((n + per - 1) / per); }
+
+static bool overlaps(const void* a, size_t na, const void* b, size_t nb)
+{
+    const char* pa = (const char*)a;
+    const char* pb = (const char*)b;
+    return pa < pb + nb && pb < pa + na;
+}
+
+template <typename TIn>
+static void launch_conv_f32(hipStream_t s, const TIn* x, const float* w, const ConvLayer& c, const float* resid,
+                            float* y, int B, int relu_in, int relu_out)
+{
+    size_t total = (size_t)B * c.OH * c.OW * c.Cout;
+    hipLaunchKernelGGL(conv2d_f32_kernel<TIn>, dim3(blocks_for(total)), dim3(256), 0, s, x, w + c.w_off, w + c.b_off,
+                       resid, y, B, c.H, c.W, c.Cin, c.OH, c.OW, c.Cout, c.k, c.stride, c.pad, relu_in, relu_out);
+}
+
+// fp32 torso + linear layer.  Leaves the rectified linear output in h->d_fc.
+static void torso_fc_f32(seed_infer* h, hipStream_t s, int B, const uint8_t* obs)
+{
+    const Plan& p = h->plan;
+    const float* w = h->d_w;
+    float* cur = nullptr;
+    if (p.arch.torso == SEED_TORSO_CONV_STACK) {
+        for (size_t l = 0; l < p.convs.size(); ++l) {
+            float* dst = h->d_act[l & 1];
+            if (l == 0) launch_conv_f32<uint8_t>(s, obs, w, p.convs[l], nullptr, dst, B, 0, 1);
+            else launch_conv_f32<float>(s, cur, w, p.convs[l], nullptr, dst, B, 0, 1);
+            cur = dst;
+        }
+    } else {
+        float* a0 = h->d_act[0];
+        float* a1 = h->d_act[1];
+        for (size_t si = 0; si < p.sections.size(); ++si) {
+            const Section& sec = p.sections[si];
+            if (si == 0) launch_conv_f32<uint8_t>(s, obs, w, sec.conv0, nullptr, a0, B, 0, 0);
+            else launch_conv_f32<float>(s, a1, w, sec.conv0, nullptr, a0, B, 0, 0);
+            const ConvLayer& c0 = sec.conv0;
+            size_t total = (size_t)B * sec.PH * sec.PW * c0.Cout;
+            hipLaunchKernelGGL(maxpool3x3s2_f32_kernel, dim3(blocks_for(total)), dim3(256), 0, s, a0, a1, B, c0.OH, c0.OW,
+                               c0.Cout, sec.PH, sec.PW, sec.pool_pad_h, sec.pool_pad_w, 0);
+            const bool last_sec = si + 1 == p.sections.size();
+            for (int blk = 0; blk < 2; ++blk) {
+                launch_conv_f32<float>(s, a1, w, sec.block[2 * blk], nullptr, a0, B, 1, 0);
+                // x <- x + conv_b(ReLU(t)); the torso's closing ReLU rides on the very last block
+                launch_conv_f32<float>(s, a0, w, sec.block[2 * blk + 1], a1, a1, B, 1, last_sec && blk == 1);
+            }
+        }
+        cur = a1;
+    }
+    h->feat_f32 = cur;
+    const seed_arch_t& a = p.arch;
+    hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (a.fc_units + 63) / 64), dim3(256), 0, s, cur, w + p.fc_w, w + p.fc_b,
+                       h->d_fc, (int)p.flat, a.fc_units, (int)p.flat, a.fc_units, 1);
+}
+
+template <int P>
+static void launch_heads_p(hipStream_t s, const HeadsArgs& ha)
+{
+    hipLaunchKernelGGL(heads_select_kernel<P>, dim3((ha.B + 3) / 4), dim3(256), 0, s, ha);
+}
+
+static void launch_heads(hipStream_t s, const HeadsArgs& ha)
+{
+    int A = ha.A;
+    if (A <= 2) launch_heads_p<2>(s, ha);
+    else if (A <= 4) launch_heads_p<4>(s, ha);
+    else if (A <= 8) launch_heads_p<8>(s, ha);
+    else if (A <= 16) launch_heads_p<16>(s, ha);
+    else if (A <= 32) launch_heads_p<32>(s, ha);
+    else launch_heads_p<64>(s, ha);
+}
+
+extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8_t* obs,
+                                         const int32_t* prev_action, const float* prev_reward,
+                                         const float* h_in, const float* c_in, const float* uniforms,
+                                         int32_t* action_out, float* logits_out, float* value_out,
+                                         float* h_out, float* c_out, float* probs_out, void* hip_stream)
+{
+    if (!h) return SEED_ERR_INVALID_ARG;
+    const Plan& p = h->plan;
+    const seed_arch_t& a = p.arch;
+    auto fail = [&](seed_status_t st, const char* m) { h->err = m; return st; };
+    if (B < 0) return fail(SEED_ERR_INVALID_ARG, "B is negative");
+    if (B > a.max_batch) return fail(SEED_ERR_BATCH_TOO_LARGE, "B exceeds max_batch");
+    if (B == 0) return SEED_OK;
+    if (!obs || !action_out || !logits_out || !value_out) return fail(SEED_ERR_INVALID_ARG, "obs, action_out, logits_out and value_out are required");
+    const bool rec = a.lstm_units > 0;
+    if (rec && (!prev_action || !prev_reward || !h_in || !c_in || !h_out || !c_out))
+        return fail(SEED_ERR_INVALID_ARG, "a recurrent arch needs prev_action, prev_reward, h_in, c_in, h_out and c_out");
+    if (!rec && (prev_action || prev_reward || h_in || c_in || h_out || c_out))
+        return fail(SEED_ERR_INVALID_ARG, "a feed-forward arch takes no recurrent arguments (pass NULL)");
+    if (a.select == SEED_SELECT_GUMBEL && !uniforms) return fail(SEED_ERR_INVALID_ARG, "Gumbel-max selection needs uniforms");
+    if (a.select == SEED_SELECT_GREEDY && uniforms) return fail(SEED_ERR_INVALID_ARG, "greedy selection takes no uniforms (pass NULL)");
+    if (rec) {
+        size_t nb = (size_t)B * a.lstm_units * sizeof(float);
+        if (overlaps(h_out, nb, h_in, nb) || overlaps(h_out, nb, c_in, nb) || overlaps(c_out, nb, h_in, nb) ||
+            overlaps(c_out, nb, c_in, nb) || overlaps(h_out, nb, c_out, nb))
+            return fail(SEED_ERR_ALIASING, "h_out / c_out must not overlap h_in / c_in or each other");
+    }
+    int dev = -1;
+    HIP_TRY(h, hipGetDevice(&dev));
+    if (dev != h->device) return fail(SEED_ERR_INVALID_ARG, "current HIP device differs from the handle's device");
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    const float* w = h->d_w;
+    const float* core = nullptr;       // fp32 [B, p.core]
+    int ld_core = p.core;
+
+    if (a.precision == SEED_PRECISION_FP32) {
+        torso_fc_f32(h, s, B, obs);
+        core = h->d_fc;
+        if (rec) {
+            hipLaunchKernelGGL(lstm_f32_kernel, dim3(B, (a.lstm_units + 255) / 256), dim3(256), 0, s, h->d_fc, prev_action,
+                               prev_reward, h_in, c_in, w + p.lstm_w, w + p.lstm_b, h_out, c_out, B, a.fc_units,
+                               a.num_actions, a.lstm_units);
+            core = h_out;
+        }
+        if (a.head == SEED_HEAD_DUELING_Q) {
+            int hid = a.head_hidden;
+            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(256), 0, s, core, w + p.v1_w, w + p.v1_b,
+                               h->d_hid, p.core, hid, ld_core, 2 * hid, 1);
+            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(256), 0, s, core, w + p.a1_w, w + p.a1_b,
+                               h->d_hid + hid, p.core, hid, ld_core, 2 * hid, 1);
+        }
+    } else {
+        seed_status_t st = bf16_step(h->bf, p, w, s, B, obs, prev_action, prev_reward, h_in, c_in, h_out, c_out,
+                                     h->d_hid, &core, &ld_core, h->err);
+        if (st != SEED_OK) return st;
+    }
+
+    HeadsArgs ha{};
+    ha.n = p.core; ha.A = a.num_actions; ha.B = B;
+    ha.uniforms = uniforms; ha.action = action_out; ha.logits = logits_out; ha.value = value_out; ha.probs = probs_out;
+    if (a.head == SEED_HEAD_POLICY_VALUE) {
+        ha.vec_a = core; ha.ld_a = ld_core; ha.vec_v = core; ha.ld_v = ld_core;
+        ha.w_a = w + p.pol_w; ha.b_a = w + p.pol_b; ha.w_v = w + p.val_w; ha.b_v = w + p.val_b;
+        ha.dueling = 0;
+    } else {
+        int hid = a.head_hidden;
+        ha.n = hid;
+        ha.vec_v = h->d_hid; ha.ld_v = 2 * hid; ha.vec_a = h->d_hid + hid; ha.ld_a = 2 * hid;
+        ha.w_a = w + p.a2_w; ha.b_a = w + p.a2_b; ha.w_v = w + p.v2_w; ha.b_v = w + p.v2_b;
+        ha.dueling = 1;
+    }
+    launch_heads(s, ha);
+    HIP_TRY(h, hipGetLastError());
+    return SEED_OK;
+}
+
+extern "C" seed_status_t seed_infer_read_intermediate(seed_infer_t* h, int32_t which, int32_t B, float* dst,
+                                                      size_t capacity, void* hip_stream)
+{
+    if (!h) return SEED_ERR_INVALID_ARG;
+    const Plan& p = h->plan;
+    auto fail = [&](seed_status_t st, const char* m) { h->err = m; return st; };
+    if (!dst || B <= 0 || B > p.arch.max_batch) return fail(SEED_ERR_INVALID_ARG, "bad dst or B");
+    if (which != 0 && which != 1) return fail(SEED_ERR_INVALID_ARG, "which must be 0 or 1");
+    size_t n = (size_t)B * (which == 0 ? p.flat : (size_t)p.arch.fc_units);
+    if (capacity < n) return fail(SEED_ERR_INVALID_ARG, "dst too small");
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (p.arch.precision == SEED_PRECISION_FP32) {
+        const float* src = which == 0 ? h->feat_f32 : h->d_fc;
+        if (!src) return fail(SEED_ERR_INVALID_ARG, "no step has run yet");
+        hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(n)), dim3(256), 0, s, src, dst, n);
+    } else {
+        seed_status_t st = bf16_read_intermediate(h->bf, p, which, B, dst, s, h->err);
+        if (st != SEED_OK) return st;
+    }
+    HIP_TRY(h, hipGetLastError());
+    return SEED_OK;
+}

@@ -1,0 +1,226 @@
+"""ctypes binding over libseedinf's C ABI (include/seedinf.h).
+
+Argument marshalling only: every step of the inference path runs in the HIP
+library.  PyTorch supplies device memory and the stream.  There is no CPU
+fallback: if the shared library is missing or a call fails, this raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_PKG)
+LIB_PATH = os.path.join(_PKG, "libseedinf.so")
+SOURCES = [os.path.join(_PKG, "csrc", f) for f in
+           ("seedinf.hip", "plan.h", "kernels_fp32.h", "kernels_heads.h", "bf16_path.h")]
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+STATUS = {0: "SEED_OK", 1: "SEED_ERR_INVALID_ARG", 2: "SEED_ERR_UNSUPPORTED_ARCH", 3: "SEED_ERR_BATCH_TOO_LARGE",
+          4: "SEED_ERR_ALIASING", 5: "SEED_ERR_DEVICE", 6: "SEED_ERR_OOM"}
+EXPORTS = ["seed_infer_weight_count", "seed_infer_validate", "seed_infer_create", "seed_infer_step",
+           "seed_infer_read_intermediate", "seed_infer_torso_features", "seed_infer_last_error",
+           "seed_infer_destroy"]
+
+
+class SeedError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+class SeedArch(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("obs_h", C.c_int32), ("obs_w", C.c_int32), ("obs_c", C.c_int32),
+        ("torso", C.c_int32),
+        ("n_conv", C.c_int32),
+        ("conv_ch", C.c_int32 * 4), ("conv_k", C.c_int32 * 4), ("conv_stride", C.c_int32 * 4),
+        ("n_sections", C.c_int32),
+        ("section_ch", C.c_int32 * 4),
+        ("fc_units", C.c_int32), ("lstm_units", C.c_int32), ("num_actions", C.c_int32),
+        ("head", C.c_int32), ("head_hidden", C.c_int32), ("select", C.c_int32),
+        ("precision", C.c_int32), ("max_batch", C.c_int32),
+    ]
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile csrc/ into libseedinf.so for gfx950 with hipcc (cross-compiles
+    without a GPU)."""
+    cmd = ["hipcc", *HIPCC_FLAGS, SOURCES[0], "-o", LIB_PATH]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + r.stderr)
+    if verbose:
+        print(" ".join(cmd))
+    return LIB_PATH
+
+
+_lib = None
+
+
+def load_library():
+    """Load libseedinf.so (torch first, so both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    import torch  # noqa: F401  (loads the HIP runtime the library links against)
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(LIB_PATH)
+    lib.seed_infer_weight_count.restype = C.c_size_t
+    lib.seed_infer_weight_count.argtypes = [C.POINTER(SeedArch)]
+    lib.seed_infer_torso_features.restype = C.c_size_t
+    lib.seed_infer_torso_features.argtypes = [C.POINTER(SeedArch)]
+    lib.seed_infer_validate.restype = C.c_int
+    lib.seed_infer_validate.argtypes = [C.POINTER(SeedArch)]
+    lib.seed_infer_create.restype = C.c_int
+    lib.seed_infer_create.argtypes = [C.POINTER(SeedArch), C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
+    lib.seed_infer_step.restype = C.c_int
+    lib.seed_infer_step.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 13
+    lib.seed_infer_read_intermediate.restype = C.c_int
+    lib.seed_infer_read_intermediate.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.seed_infer_last_error.restype = C.c_char_p
+    lib.seed_infer_last_error.argtypes = [C.c_void_p]
+    lib.seed_infer_destroy.restype = None
+    lib.seed_infer_destroy.argtypes = [C.c_void_p]
+    _lib = lib
+    return lib
+
+
+def make_arch(cfg: dict, max_batch: int | None = None, precision: str | None = None) -> SeedArch:
+    """seed_arch_t from a workload config dict (see workloads.CONFIGS)."""
+    a = SeedArch()
+    a.struct_size = C.sizeof(SeedArch)
+    a.obs_h, a.obs_w, a.obs_c = cfg["obs_h"], cfg["obs_w"], cfg["obs_c"]
+    a.torso = cfg["torso"]
+    convs = cfg.get("convs", [])
+    a.n_conv = len(convs)
+    for i, (ch, k, s) in enumerate(convs):
+        a.conv_ch[i], a.conv_k[i], a.conv_stride[i] = ch, k, s
+    secs = cfg.get("sections", [])
+    a.n_sections = len(secs)
+    for i, ch in enumerate(secs):
+        a.section_ch[i] = ch
+    a.fc_units = cfg["fc_units"]
+    a.lstm_units = cfg.get("lstm_units", 0)
+    a.num_actions = cfg["num_actions"]
+    a.head = cfg.get("head", 0)
+    a.head_hidden = cfg.get("head_hidden", 0)
+    a.select = cfg.get("select", 0)
+    prec = precision if precision is not None else cfg.get("precision", "fp32")
+    a.precision = {"fp32": 0, "bf16": 1}[prec]
+    a.max_batch = max_batch if max_batch is not None else cfg.get("batch", 1)
+    return a
+
+
+def weight_count(arch: SeedArch) -> int:
+    return int(load_library().seed_infer_weight_count(C.byref(arch)))
+
+
+def torso_features(arch: SeedArch) -> int:
+    return int(load_library().seed_infer_torso_features(C.byref(arch)))
+
+
+def validate(arch: SeedArch) -> tuple[int, str]:
+    lib = load_library()
+    st = lib.seed_infer_validate(C.byref(arch))
+    return st, lib.seed_infer_last_error(None).decode()
+
+
+def _ptr(t, dtype, shape, name):
+    import torch
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
+        raise TypeError(f"{name} must be contiguous {dtype} of shape {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+    return C.c_void_p(t.data_ptr())
+
+
+class SeedInfer:
+    """Handle on one network instance (seed_infer_create ... seed_infer_destroy)."""
+
+    def __init__(self, arch: SeedArch, weights: np.ndarray):
+        self.lib = load_library()
+        self.arch = arch
+        w = np.ascontiguousarray(weights, dtype=np.float32)
+        self._h = C.c_void_p()
+        st = self.lib.seed_infer_create(C.byref(arch), w.ctypes.data_as(C.c_void_p), w.size, C.byref(self._h))
+        if st != 0:
+            self._h = None
+            raise SeedError(st, self.lib.seed_infer_last_error(None).decode())
+        self.A, self.Hn = arch.num_actions, arch.lstm_units
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self.lib.seed_infer_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def step_raw(self, B, obs, prev_action, prev_reward, h_in, c_in, uniforms, action, logits, value,
+                 h_out, c_out, probs, stream=0):
+        """Direct call with raw pointers/ints (used by the error-path tests)."""
+        st = self.lib.seed_infer_step(self._h, B, obs, prev_action, prev_reward, h_in, c_in, uniforms, action,
+                                      logits, value, h_out, c_out, probs, stream)
+        return st, self.lib.seed_infer_last_error(self._h).decode()
+
+    def step(self, obs, prev_action=None, prev_reward=None, h_in=None, c_in=None, uniforms=None,
+             want_probs=True, out=None, stream=None):
+        """Run one inference step on device tensors; returns a dict of device
+        tensors (allocated here with torch unless `out` supplies them)."""
+        import torch
+        a = self.arch
+        B = obs.shape[0]
+        dev = obs.device
+        if out is None:
+            out = {"action": torch.empty(B, dtype=torch.int32, device=dev),
+                   "logits": torch.empty(B, self.A, dtype=torch.float32, device=dev),
+                   "value": torch.empty(B, dtype=torch.float32, device=dev)}
+            if self.Hn:
+                out["h"] = torch.empty(B, self.Hn, dtype=torch.float32, device=dev)
+                out["c"] = torch.empty(B, self.Hn, dtype=torch.float32, device=dev)
+            if want_probs:
+                out["probs"] = torch.empty(B, self.A, dtype=torch.float32, device=dev)
+        s = torch.cuda.current_stream(dev).cuda_stream if stream is None else stream
+        st = self.lib.seed_infer_step(
+            self._h, B,
+            _ptr(obs, torch.uint8, (B, a.obs_h, a.obs_w, a.obs_c), "obs"),
+            _ptr(prev_action, torch.int32, (B,), "prev_action"),
+            _ptr(prev_reward, torch.float32, (B,), "prev_reward"),
+            _ptr(h_in, torch.float32, (B, self.Hn), "h_in"),
+            _ptr(c_in, torch.float32, (B, self.Hn), "c_in"),
+            _ptr(uniforms, torch.float32, (B, self.A), "uniforms"),
+            _ptr(out["action"], torch.int32, (B,), "action"),
+            _ptr(out["logits"], torch.float32, (B, self.A), "logits"),
+            _ptr(out["value"], torch.float32, (B,), "value"),
+            _ptr(out.get("h"), torch.float32, (B, self.Hn), "h_out"),
+            _ptr(out.get("c"), torch.float32, (B, self.Hn), "c_out"),
+            _ptr(out.get("probs"), torch.float32, (B, self.A), "probs"),
+            C.c_void_p(s))
+        if st != 0:
+            raise SeedError(st, self.lib.seed_infer_last_error(self._h).decode())
+        return out
+
+    def read_intermediate(self, which: int, B: int, stream=None):
+        """Diagnostic tap: 0 = torso features [B, H*W*C], 1 = linear output [B, fc_units] (fp32)."""
+        import torch
+        n = torso_features(self.arch) if which == 0 else self.arch.fc_units
+        dst = torch.empty(B, n, dtype=torch.float32, device="cuda")
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        st = self.lib.seed_infer_read_intermediate(self._h, which, B, C.c_void_p(dst.data_ptr()), dst.numel(),
+                                                   C.c_void_p(s))
+        if st != 0:
+            raise SeedError(st, self.lib.seed_infer_last_error(self._h).decode())
+        return dst

@@ -1,0 +1,65 @@
+"""The parity rule used by every GPU-vs-oracle comparison.
+
+Floating-point outputs are compared per batch row against a scale taken from
+the oracle's row: |g - o| <= tol * max(1, max_j |o_j|).  (Element-wise relative
+error is ill-posed for logits near zero.)  tol is 1e-4 in fp32 mode and 2e-2
+in bf16 mode.  Actions must be identical except on rows where the oracle's
+top two candidates (logits plus Gumbel noise, or Q-values) lie within
+2 * tol * scale of each other; there the GPU may pick either of the oracle's
+top two, which is verified through the GPU's own logits.
+"""
+import numpy as np
+
+
+def to_device(batch):
+    import torch
+    return {k: (None if v is None else torch.from_numpy(v).cuda()) for k, v in batch.items()}
+
+
+def row_scale(ref_rows):
+    r = np.abs(ref_rows.reshape(ref_rows.shape[0], -1)).max(axis=1)
+    return np.maximum(1.0, r)
+
+
+def check_against_oracle(got, ref, tol, uniforms=None):
+    """got / ref: dicts of numpy arrays (action, logits, value, [h, c], [probs]).
+    Raises AssertionError on a violation; returns a small report."""
+    B = ref["logits"].shape[0]
+    scale = row_scale(ref["logits"])
+    worst = 0.0
+
+    def cmp(name, g, o, sc):
+        nonlocal worst
+        g = g.reshape(B, -1).astype(np.float64)
+        o = o.reshape(B, -1).astype(np.float64)
+        assert np.isfinite(g).all(), f"{name}: non-finite values"
+        err = np.abs(g - o).max(axis=1) / sc
+        worst = max(worst, float(err.max()))
+        bad = np.nonzero(err > tol)[0]
+        assert bad.size == 0, f"{name}: {bad.size} rows exceed tol {tol}: worst row {bad[0]} err {err[bad[0]]:.3e}"
+
+    cmp("logits", got["logits"], ref["logits"], scale)
+    cmp("value", got["value"], ref["value"], np.maximum(scale, np.abs(ref["value"].astype(np.float64))))
+    if "h" in ref:
+        cmp("h", got["h"], ref["h"], row_scale(ref["h"]))
+        cmp("c", got["c"], ref["c"], row_scale(ref["c"]))
+    if "probs" in got and "probs" in ref:
+        # probabilities: absolute error bounded by the logit error (softmax is 1-Lipschitz in max norm x2)
+        g, o = got["probs"].astype(np.float64), ref["probs"].astype(np.float64)
+        assert np.abs(g.sum(1) - 1).max() < 1e-5
+        assert np.abs(g - o).max(axis=1).max() <= 2 * tol * scale.max()
+    # actions
+    ga, oa = got["action"], ref["action"]
+    A = ref["logits"].shape[1]
+    assert ga.dtype == np.int32 and ((ga >= 0) & (ga < A)).all()
+    near = ref["margin"].astype(np.float64) <= 2 * tol * scale
+    differ = ga != oa
+    assert not (differ & ~near).any(), f"actions differ on {int((differ & ~near).sum())} rows with a clear margin"
+    # on near-tie rows the GPU's choice must be one of the oracle's top two candidates
+    for b in np.nonzero(differ)[0]:
+        keys = ref["logits"][b].astype(np.float64)
+        if uniforms is not None:
+            keys = keys - np.log(-np.log(uniforms[b].astype(np.float64)))
+        top2 = np.argsort(-keys, kind="stable")[:2]
+        assert ga[b] in top2, f"row {b}: action {ga[b]} is not among the oracle's top two {top2}"
+    return {"max_rel_err": worst, "actions_equal": int((~differ).sum()), "near_ties": int(near.sum())}

@@ -1,0 +1,138 @@
+"""GPU parity: libseedinf through its C ABI against the CPU oracle on the same
+seeded inputs (see tests/parity.py for the rule).  fp32 mode: 1e-4; bf16
+mode: 2e-2."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1910_06591_amd import seedinf, workloads as wl
+from tests.parity import check_against_oracle, to_device
+
+pytestmark = pytest.mark.gpu
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+CORE_KEYS = ("prev_action", "prev_reward", "h_in", "c_in", "uniforms")
+
+
+def run_case(orc, cfg, B, precision, max_batch=None, weights=None, seed_shift=0, intermediates=True):
+    import torch
+    weights = wl.make_weights(cfg, bf16_representable=(precision == "bf16")) if weights is None else weights
+    batch = wl.make_batch(cfg, B, seed_shift=seed_shift)
+    print(f"case {cfg['label']} B={B} {precision}", flush=True)
+    net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=max_batch or B, precision=precision), weights)
+    out = net.step(**to_device(batch))
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    ref = orc.forward(oracle.make_arch(cfg), weights, batch["obs"], want_intermediates=intermediates,
+                      **{k: batch[k] for k in CORE_KEYS})
+    tol = TOL[precision]
+    if intermediates:
+        for which, key in ((0, "torso_feat"), (1, "fc_act")):
+            g = net.read_intermediate(which, B).cpu().numpy().astype(np.float64)
+            o = ref[key].astype(np.float64)
+            sc = np.maximum(1.0, np.abs(o).max(axis=1))
+            err = np.abs(g - o).max(axis=1) / sc
+            assert err.max() <= tol, f"{key}: worst row err {err.max():.3e}"
+    rep = check_against_oracle(got, ref, tol, batch["uniforms"])
+    print("   ", rep, flush=True)
+    net.close()
+    return got, ref, rep
+
+
+def test_c1_fp32_full(orc):
+    cfg = wl.CONFIGS["C1"]
+    run_case(orc, cfg, cfg["batch"], "fp32")
+
+
+@pytest.mark.parametrize("name,B", [("C2", 5), ("C3", 3), ("C4", 2)])
+def test_fp32_mode_every_family(orc, name, B):
+    """Every network family in fp32 mode at a small ragged batch: tight
+    tolerance, so an indexing slip anywhere cannot hide behind bf16 rounding."""
+    run_case(orc, wl.CONFIGS[name], B, "fp32")
+
+
+def test_fp32_odd_shapes(orc):
+    """Shapes that are not multiples of any tile: odd image, odd channels,
+    odd pooled sizes (pool padding before = 1), A not a power of two."""
+    cfg = dict(label="odd resnet", obs_h=13, obs_w=19, obs_c=5, torso=1, sections=[6, 10], fc_units=37,
+               lstm_units=21, num_actions=7, head=0, head_hidden=0, select=1, precision="fp32", obs_kind="uniform",
+               index=11)
+    run_case(orc, cfg, 3, "fp32")
+    cfg2 = dict(label="odd stack", obs_h=23, obs_w=17, obs_c=3, torso=0, convs=[(7, 5, 2), (9, 3, 1)], fc_units=50,
+                lstm_units=0, num_actions=33, head=1, head_hidden=29, select=0, precision="fp32", obs_kind="uniform",
+                index=12)
+    run_case(orc, cfg2, 2, "fp32")
+
+
+def test_fp32_b1_and_max_batch_larger_than_b(orc):
+    cfg = wl.CONFIGS["C1"]
+    run_case(orc, cfg, 1, "fp32", max_batch=16)
+
+
+def test_repeatable_and_row_independent(orc):
+    """Same inputs twice give bit-identical outputs (no atomics anywhere), and
+    a row's result does not depend on its neighbours."""
+    import torch
+    cfg = wl.CONFIGS["C1"]
+    w = wl.make_weights(cfg)
+    batch = wl.make_batch(cfg, 8)
+    net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=8), w)
+    dev = to_device(batch)
+    o1 = {k: v.clone() for k, v in net.step(**dev).items()}
+    o2 = net.step(**dev)
+    torch.cuda.synchronize()
+    for k in o1:
+        assert torch.equal(o1[k], o2[k]), k
+    sub = {k: (None if v is None else v[3:4].contiguous()) for k, v in dev.items()}
+    o3 = net.step(**sub)
+    torch.cuda.synchronize()
+    for k in o1:
+        assert torch.equal(o1[k][3:4], o3[k]), k
+    net.close()
+
+
+def test_error_paths_on_device(orc):
+    import torch
+    cfg = wl.CONFIGS["C3"]
+    w = wl.make_weights(cfg, bf16_representable=False)
+    net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=4, precision="fp32"), w)
+    batch = to_device(wl.make_batch(cfg, 4))
+    A, Hn = cfg["num_actions"], cfg["lstm_units"]
+    act = torch.full((4,), -7, dtype=torch.int32, device="cuda")
+    logits = torch.full((4, A), 123.0, device="cuda")
+    value = torch.zeros(4, device="cuda")
+    ho, co = torch.zeros(4, Hn, device="cuda"), torch.zeros(4, Hn, device="cuda")
+    p = lambda t: C.c_void_p(t.data_ptr())
+    args = [p(batch["obs"]), p(batch["prev_action"]), p(batch["prev_reward"]), p(batch["h_in"]), p(batch["c_in"]),
+            p(batch["uniforms"]), p(act), p(logits), p(value), p(ho), p(co), None]
+    st, msg = net.step_raw(5, *args)
+    assert st == 3 and "max_batch" in msg
+    st, _ = net.step_raw(-1, *args)
+    assert st == 1
+    bad = list(args); bad[9] = p(batch["h_in"])          # h_out aliases h_in
+    st, _ = net.step_raw(4, *bad)
+    assert st == 4
+    bad = list(args); bad[0] = None                      # obs missing
+    assert net.step_raw(4, *bad)[0] == 1
+    bad = list(args); bad[5] = None                      # uniforms missing for Gumbel selection
+    assert net.step_raw(4, *bad)[0] == 1
+    bad = list(args); bad[3] = None                      # recurrent arch without h_in
+    assert net.step_raw(4, *bad)[0] == 1
+    torch.cuda.synchronize()
+    # no output was written by any failed call
+    assert (act == -7).all() and (logits == 123.0).all()
+    assert net.step_raw(0, *args)[0] == 0                # B = 0 is a no-op
+    torch.cuda.synchronize()
+    assert (act == -7).all()
+    assert net.step_raw(4, *args)[0] == 0
+    torch.cuda.synchronize()
+    assert (act >= 0).all()
+    # out-of-range previous action behaves as an all-zero one-hot (oracle does the same)
+    b2 = wl.make_batch(cfg, 4)
+    b2["prev_action"][:] = [-1, A, 3, 10**6]
+    out = net.step(**to_device(b2))
+    torch.cuda.synchronize()
+    ref = orc.forward(oracle.make_arch(cfg), w, b2["obs"], **{k: b2[k] for k in CORE_KEYS})
+    check_against_oracle({k: v.cpu().numpy() for k, v in out.items()}, ref, 1e-4, b2["uniforms"])
+    net.close()
