@@ -1,0 +1,75 @@
+// Shared device-side types and helpers of the bf16 (matrix-core) kernels.
+//
+// MFMA used everywhere: v_mfma_f32_16x16x32_bf16, D[16x16] += A[16x32] * B[32x16].
+// Lane l of the wavefront holds
+//   A: row m = l % 16, the 8 values k = 8*(l/16) .. 8*(l/16)+7
+//   B: column n = l % 16, the 8 values k = 8*(l/16) .. 8*(l/16)+7
+//   D: column n = l % 16, the 4 rows m = 4*(l/16) .. 4*(l/16)+3
+// All kernels put the WEIGHTS in A (m = output feature / channel) and the
+// ACTIVATIONS in B (n = batch row or pixel), so a lane ends up holding four
+// consecutive output channels of one pixel: one packed 8-byte NHWC store.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace seedinf {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ bf16x4 to_bf16x4(floatx4 v)
+{
+    bf16x4 r;
+    r[0] = (__bf16)v[0]; r[1] = (__bf16)v[1]; r[2] = (__bf16)v[2]; r[3] = (__bf16)v[3];
+    return r;
+}
+
+__device__ __forceinline__ floatx4 relu4(floatx4 v)
+{
+    floatx4 r;
+    r[0] = fmaxf(v[0], 0.0f); r[1] = fmaxf(v[1], 0.0f); r[2] = fmaxf(v[2], 0.0f); r[3] = fmaxf(v[3], 0.0f);
+    return r;
+}
+
+__device__ __forceinline__ floatx4 to_floatx4(bf16x4 v)
+{
+    floatx4 r;
+    r[0] = (float)v[0]; r[1] = (float)v[1]; r[2] = (float)v[2]; r[3] = (float)v[3];
+    return r;
+}
+
+__device__ __forceinline__ floatx4 max4(floatx4 a, floatx4 b)
+{
+    floatx4 r;
+    r[0] = fmaxf(a[0], b[0]); r[1] = fmaxf(a[1], b[1]); r[2] = fmaxf(a[2], b[2]); r[3] = fmaxf(a[3], b[3]);
+    return r;
+}
+
+// 8 fp32 -> 8 bf16 (round to nearest even, the hardware conversion)
+__device__ __forceinline__ bf16x8 to_bf16x8(floatx4 lo, floatx4 hi)
+{
+    bf16x8 r;
+    r[0] = (__bf16)lo[0]; r[1] = (__bf16)lo[1]; r[2] = (__bf16)lo[2]; r[3] = (__bf16)lo[3];
+    r[4] = (__bf16)hi[0]; r[5] = (__bf16)hi[1]; r[6] = (__bf16)hi[2]; r[7] = (__bf16)hi[3];
+    return r;
+}
+
+// 8 bytes (two dwords, little endian) -> 8 bf16 holding the integers 0..255 exactly
+__device__ __forceinline__ bf16x8 u8x8_to_bf16x8(uint32_t lo, uint32_t hi)
+{
+    bf16x8 r;
+    r[0] = (__bf16)(float)(lo & 0xff); r[1] = (__bf16)(float)((lo >> 8) & 0xff);
+    r[2] = (__bf16)(float)((lo >> 16) & 0xff); r[3] = (__bf16)(float)(lo >> 24);
+    r[4] = (__bf16)(float)(hi & 0xff); r[5] = (__bf16)(float)((hi >> 8) & 0xff);
+    r[6] = (__bf16)(float)((hi >> 16) & 0xff); r[7] = (__bf16)(float)(hi >> 24);
+    return r;
+}
+
+}  // namespace seedinf

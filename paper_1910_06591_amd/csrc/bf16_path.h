@@ -1,37 +1,410 @@
-// bf16 (matrix-core) path: state, support check and per-step kernel sequence.
+// bf16 (matrix-core) path: host-side weight packing, device state, support
+// check and the per-step kernel sequence.
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <cstring>
 #include <string>
+#include <vector>
 
 #include "plan.h"
+#include "kernels_fp32.h"
+#include "gemm_bf16.h"
+#include "conv_stack_bf16.h"
+#include "resnet_bf16.h"
 
 namespace seedinf {
 
-struct Bf16State;
+// ---- the deep-ResNet torsos this build has fused kernels for ----------------
+// DMLab-shaped: 72x96x3 frames, sections 16/32/32.
+using DmS1 = SecCfg<72, 96, 3, 16, IN_U8_C3, 9>;
+using DmS2 = SecCfg<36, 48, 16, 32, IN_LDS, 9>;
+using DmS3 = SecCfg<18, 24, 32, 32, IN_LDS, 9>;
+// Football-shaped: 72x96x16 minimap planes, sections 16/32/32/32.
+using FbS1 = SecCfg<72, 96, 16, 16, IN_U8_PLANAR, 8>;
+using FbS4 = SecCfg<9, 12, 32, 32, IN_LDS, 5>;
 
-inline seed_status_t bf16_supported(const Plan&, std::string& err)
+enum { TORSO_NONE = 0, TORSO_DMLAB = 1, TORSO_FOOTBALL = 2 };
+
+inline int match_resnet(const seed_arch_t& a)
 {
-    err = "bf16 path not built yet";
-    return SEED_ERR_UNSUPPORTED_ARCH;
+    if (a.torso != SEED_TORSO_RESNET || a.obs_h != 72 || a.obs_w != 96) return TORSO_NONE;
+    if (a.obs_c == 3 && a.n_sections == 3 && a.section_ch[0] == 16 && a.section_ch[1] == 32 && a.section_ch[2] == 32)
+        return TORSO_DMLAB;
+    if (a.obs_c == 16 && a.n_sections == 4 && a.section_ch[0] == 16 && a.section_ch[1] == 32 &&
+        a.section_ch[2] == 32 && a.section_ch[3] == 32)
+        return TORSO_FOOTBALL;
+    return TORSO_NONE;
 }
-inline seed_status_t bf16_create(const Plan&, const float*, const float*, Bf16State**, std::string& err)
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+inline seed_status_t bf16_supported(const Plan& p, std::string& err)
 {
-    err = "bf16 path not built yet";
-    return SEED_ERR_UNSUPPORTED_ARCH;
+    const seed_arch_t& a = p.arch;
+    auto no = [&](const char* m) { err = std::string("bf16 mode: ") + m + " (fp32 mode supports every valid arch)"; return SEED_ERR_UNSUPPORTED_ARCH; };
+    if (a.torso == SEED_TORSO_RESNET) {
+        if (match_resnet(a) == TORSO_NONE)
+            return no("fused ResNet kernels exist for 72x96x3 frames with sections 16/32/32 and 72x96x16 frames with sections 16/32/32/32");
+    } else {
+        for (size_t l = 0; l < p.convs.size(); ++l) {
+            const ConvLayer& c = p.convs[l];
+            if (c.Cout % 16) return no("conv channels must be multiples of 16");
+            if ((c.k * c.Cin) % 8 || (c.k * c.k * c.Cin) % 32) return no("conv k*Cin must be a multiple of 8 and k*k*Cin of 32");
+            if ((c.W * c.Cin) % 8 || (c.stride * c.Cin) % 8 || ((size_t)c.H * c.W * c.Cin) % 8) return no("conv rows must be 8-element aligned");
+        }
+        if (p.flat % 32) return no("the conv stack's flattened output must be a multiple of 32 values");
+    }
+    if (a.lstm_units % 16) return no("lstm_units must be a multiple of 16");
+    if (a.head == SEED_HEAD_DUELING_Q && a.head_hidden % 16) return no("head_hidden must be a multiple of 16");
+    return SEED_OK;
 }
-inline void bf16_destroy(Bf16State*) {}
-inline seed_status_t bf16_step(Bf16State*, const Plan&, const float*, hipStream_t, int, const uint8_t*, const int32_t*,
-                               const float*, const float*, const float*, float*, float*, float*, const float**, int*,
-                               std::string& err)
+
+// ---- host-side packing --------------------------------------------------------
+inline uint16_t f32_to_bf16_bits(float f)
 {
-    err = "bf16 path not built yet";
-    return SEED_ERR_UNSUPPORTED_ARCH;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
 }
-inline seed_status_t bf16_read_intermediate(Bf16State*, const Plan&, int, int, float*, hipStream_t, std::string& err)
+
+// A-operand fragments [ftile][kchunk][lane][8] from value(f, k)
+template <class F>
+inline void pack_a(std::vector<uint16_t>& out, int n_ftiles, int kchunks, F value)
 {
-    err = "bf16 path not built yet";
-    return SEED_ERR_UNSUPPORTED_ARCH;
+    size_t base = out.size();
+    out.resize(base + (size_t)n_ftiles * kchunks * 64 * 8);
+    uint16_t* d = out.data() + base;
+    for (int ft = 0; ft < n_ftiles; ++ft)
+        for (int kc = 0; kc < kchunks; ++kc)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int e = 0; e < 8; ++e)
+                    *d++ = f32_to_bf16_bits(value(ft * 16 + (lane & 15), kc * 32 + 8 * (lane >> 4) + e));
+}
+
+struct ConvStackLayerDev { size_t wp_off; size_t koff_off; int kchunks; };
+
+struct Bf16State {
+    int torso_kind = TORSO_NONE;
+    int n_cu = 256;
+    char* arena = nullptr;
+    // packed weights (byte offsets into arena resolved to pointers)
+    const bf16x8* wp_fc = nullptr; const float* bias_fc = nullptr; int kc_fc = 0, ft_fc = 0;
+    const bf16x8* wp_lstm = nullptr; int kc1_lstm = 0;
+    const bf16x8* wp_hid = nullptr; const float* bias_hid = nullptr; int ft_hid = 0;
+    std::vector<ConvStackLayerDev> stack;
+    const bf16x8* wp_conv = nullptr; const int* koff = nullptr;
+    SecWeights sec[4];
+    // activations
+    __bf16* act[2] = {nullptr, nullptr};
+    __bf16* feat = nullptr; int ldf = 0;
+    __bf16* fc_bf16 = nullptr; int ldfc = 0;
+    float* fc_f32 = nullptr;
+};
+
+inline void bf16_destroy(Bf16State* s)
+{
+    if (!s) return;
+    if (s->arena) (void)hipFree(s->arena);
+    delete s;
+}
+
+#define BF_TRY(expr)                                                             \
+    do {                                                                         \
+        hipError_t e_ = (expr);                                                  \
+        if (e_ != hipSuccess) {                                                  \
+            err = std::string(#expr) + ": " + hipGetErrorString(e_);             \
+            return e_ == hipErrorOutOfMemory ? SEED_ERR_OOM : SEED_ERR_DEVICE;   \
+        }                                                                        \
+    } while (0)
+
+template <class S>
+inline void pack_section(std::vector<uint16_t>& pk, const float* w, const Section& sec, size_t (&off)[5])
+{
+    const ConvLayer& c0 = sec.conv0;
+    const float* w0 = w + c0.w_off;
+    off[0] = pk.size();
+    if (S::INKIND == IN_U8_C3) {
+        // K slot s = kchunk*4 + lanegroup: s < 6 -> kernel row s/2, pixel pair s%2; element e -> pixel e/4, channel e%4
+        pack_a(pk, S::FT, 2, [&](int f, int k) -> float {
+            int s = k / 8, e = k % 8;
+            if (s > 5) return 0.f;
+            int kh = s / 2, kw = 2 * (s % 2) + e / 4, ch = e % 4;
+            if (kw > 2 || ch > 2) return 0.f;
+            return w0[((size_t)(kh * 3 + kw) * 3 + ch) * S::C + f];
+        });
+    } else {
+        pack_a(pk, S::FT, S::KC0, [&](int f, int k) -> float { return k < 9 * S::CIN ? w0[(size_t)k * S::C + f] : 0.f; });
+    }
+    for (int j = 0; j < 4; ++j) {
+        const float* wb = w + sec.block[j].w_off;
+        off[1 + j] = pk.size();
+        pack_a(pk, S::FT, S::KCB, [&](int f, int k) -> float { return k < 9 * S::C ? wb[(size_t)k * S::C + f] : 0.f; });
+    }
+}
+
+inline seed_status_t bf16_create(const Plan& p, const float* w, const float* d_w, Bf16State** out, std::string& err)
+{
+    const seed_arch_t& a = p.arch;
+    Bf16State* s = new Bf16State;
+    *out = s;                                  // owned by the handle from here on (freed on any failure by the caller)
+    int dev = 0;
+    BF_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    BF_TRY(hipGetDeviceProperties(&prop, dev));
+    s->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    s->torso_kind = match_resnet(a);
+    s->ldf = round_up((int)p.flat, 32);
+    s->ldfc = round_up(a.fc_units, 32);
+
+    std::vector<uint16_t> pk;                  // all packed bf16 weights
+    std::vector<float> fb;                     // padded fp32 biases
+    std::vector<int> ko;                       // conv-stack offset tables
+    size_t sec_off[4][5];
+    if (a.torso == SEED_TORSO_RESNET) {
+        if (s->torso_kind == TORSO_DMLAB) {
+            pack_section<DmS1>(pk, w, p.sections[0], sec_off[0]);
+            pack_section<DmS2>(pk, w, p.sections[1], sec_off[1]);
+            pack_section<DmS3>(pk, w, p.sections[2], sec_off[2]);
+        } else {
+            pack_section<FbS1>(pk, w, p.sections[0], sec_off[0]);
+            pack_section<DmS2>(pk, w, p.sections[1], sec_off[1]);
+            pack_section<DmS3>(pk, w, p.sections[2], sec_off[2]);
+            pack_section<FbS4>(pk, w, p.sections[3], sec_off[3]);
+        }
+    } else {
+        for (const ConvLayer& c : p.convs) {
+            ConvStackLayerDev d;
+            const int K = c.k * c.k * c.Cin;
+            d.kchunks = K / 32;
+            d.wp_off = pk.size();
+            const float* wl = w + c.w_off;
+            pack_a(pk, c.Cout / 16, d.kchunks, [&](int f, int k) -> float { return wl[(size_t)k * c.Cout + f]; });
+            d.koff_off = ko.size();
+            for (int kc = 0; kc < d.kchunks; ++kc)
+                for (int g = 0; g < 4; ++g) {
+                    int k0 = kc * 32 + g * 8;
+                    int kh = k0 / (c.k * c.Cin), rem = k0 % (c.k * c.Cin);
+                    ko.push_back(kh * c.W * c.Cin + rem);
+                }
+            s->stack.push_back(d);
+        }
+    }
+    // linear layer: K = ldf (zero rows past flat), features padded to whole tiles
+    const int F = a.fc_units;
+    s->ft_fc = (F + 15) / 16;
+    s->kc_fc = s->ldf / 32;
+    const size_t off_fc = pk.size();
+    {
+        const float* wf = w + p.fc_w;
+        const int flat = (int)p.flat;
+        pack_a(pk, s->ft_fc, s->kc_fc, [&](int f, int k) -> float { return (k < flat && f < F) ? wf[(size_t)k * F + f] : 0.f; });
+    }
+    const size_t off_bfc = fb.size();
+    for (int f = 0; f < s->ft_fc * 16; ++f) fb.push_back(f < F ? w[p.fc_b + f] : 0.f);
+    // LSTM: K = [ldfc feature columns | h columns]; feature tile (ut, gate)
+    size_t off_lstm = 0;
+    const int Hn = a.lstm_units;
+    if (Hn > 0) {
+        off_lstm = pk.size();
+        s->kc1_lstm = s->ldfc / 32;
+        const int kc2 = (Hn + 31) / 32;
+        const float* wl = w + p.lstm_w;
+        const int G4 = 4 * Hn, ldfc = s->ldfc, A = a.num_actions;
+        pack_a(pk, (Hn / 16) * 4, s->kc1_lstm + kc2, [&](int f, int k) -> float {
+            int ft = f / 16, m = f % 16;
+            int col = (ft % 4) * Hn + (ft / 4) * 16 + m;
+            if (k < ldfc) return k < F ? wl[(size_t)k * G4 + col] : 0.f;
+            int hk = k - ldfc;
+            return hk < Hn ? wl[(size_t)(F + A + 1 + hk) * G4 + col] : 0.f;
+        });
+    }
+    // dueling hidden layers: features [value stream | advantage stream]
+    size_t off_hid = 0, off_bhid = 0;
+    if (a.head == SEED_HEAD_DUELING_Q) {
+        const int hid = a.head_hidden, core = p.core;
+        const int kc = Hn > 0 ? (core + 31) / 32 : s->ldfc / 32;
+        s->ft_hid = 2 * hid / 16;
+        off_hid = pk.size();
+        const float* wv = w + p.v1_w;
+        const float* wa = w + p.a1_w;
+        pack_a(pk, s->ft_hid, kc, [&](int f, int k) -> float {
+            if (k >= core) return 0.f;
+            return f < hid ? wv[(size_t)k * hid + f] : wa[(size_t)k * hid + (f - hid)];
+        });
+        off_bhid = fb.size();
+        for (int f = 0; f < hid; ++f) fb.push_back(w[p.v1_b + f]);
+        for (int f = 0; f < hid; ++f) fb.push_back(w[p.a1_b + f]);
+    }
+
+    // arena layout
+    auto al = [](size_t v) { return (v + 255) / 256 * 256; };
+    const size_t mb = (size_t)a.max_batch;
+    size_t o = 0;
+    const size_t o_pk = o; o += al(pk.size() * 2);
+    const size_t o_fb = o; o += al(fb.size() * 4 + 16);
+    const size_t o_ko = o; o += al(ko.size() * 4 + 16);
+    size_t o_act[2] = {0, 0};
+    if (a.torso == SEED_TORSO_CONV_STACK && p.convs.size() > 1) {
+        size_t m = 0;
+        for (size_t l = 0; l + 1 < p.convs.size(); ++l) {
+            size_t n = (size_t)p.convs[l].OH * p.convs[l].OW * p.convs[l].Cout;
+            if (n > m) m = n;
+        }
+        o_act[0] = o; o += al(mb * m * 2);
+        o_act[1] = o; o += al(mb * m * 2);
+    }
+    const size_t o_feat = o; o += al(mb * s->ldf * 2);
+    const size_t o_fcb = o; o += al(mb * s->ldfc * 2);
+    const size_t o_fcf = o; o += al(mb * F * 4);
+    BF_TRY(hipMalloc((void**)&s->arena, o));
+    BF_TRY(hipMemset(s->arena, 0, o));        // padding columns of feat / fc stay zero for ever
+    BF_TRY(hipMemcpy(s->arena + o_pk, pk.data(), pk.size() * 2, hipMemcpyHostToDevice));
+    if (!fb.empty()) BF_TRY(hipMemcpy(s->arena + o_fb, fb.data(), fb.size() * 4, hipMemcpyHostToDevice));
+    if (!ko.empty()) BF_TRY(hipMemcpy(s->arena + o_ko, ko.data(), ko.size() * 4, hipMemcpyHostToDevice));
+
+    const uint16_t* dpk = (const uint16_t*)(s->arena + o_pk);
+    auto frag = [&](size_t off) { return (const bf16x8*)(dpk + off); };
+    const float* dfb = (const float*)(s->arena + o_fb);
+    s->wp_fc = frag(off_fc); s->bias_fc = dfb + off_bfc;
+    if (Hn > 0) s->wp_lstm = frag(off_lstm);
+    if (a.head == SEED_HEAD_DUELING_Q) { s->wp_hid = frag(off_hid); s->bias_hid = dfb + off_bhid; }
+    s->wp_conv = frag(0);
+    s->koff = (const int*)(s->arena + o_ko);
+    if (a.torso == SEED_TORSO_RESNET) {
+        for (size_t si = 0; si < p.sections.size(); ++si) {
+            SecWeights& sw = s->sec[si];
+            sw.w0 = frag(sec_off[si][0]);
+            sw.b0 = d_w + p.sections[si].conv0.b_off;
+            for (int j = 0; j < 4; ++j) {
+                sw.wb[j] = frag(sec_off[si][1 + j]);
+                sw.bb[j] = d_w + p.sections[si].block[j].b_off;
+            }
+        }
+    }
+    s->act[0] = (__bf16*)(s->arena + o_act[0]);
+    s->act[1] = (__bf16*)(s->arena + o_act[1]);
+    s->feat = (__bf16*)(s->arena + o_feat);
+    s->fc_bf16 = (__bf16*)(s->arena + o_fcb);
+    s->fc_f32 = (float*)(s->arena + o_fcf);
+
+    // the fused torso kernels use more than 64 KiB of LDS
+    if (s->torso_kind == TORSO_DMLAB) {
+        BF_TRY(hipFuncSetAttribute((const void*)resnet3_bf16_kernel<DmS1, DmS2, DmS3>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, Net3<DmS1, DmS2, DmS3>::LDS_BYTES));
+    } else if (s->torso_kind == TORSO_FOOTBALL) {
+        BF_TRY(hipFuncSetAttribute((const void*)resnet4_bf16_kernel<FbS1, DmS2, DmS3, FbS4>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, Net4<FbS1, DmS2, DmS3, FbS4>::LDS_BYTES));
+    }
+    return SEED_OK;
+}
+
+template <int EPI>
+inline void launch_gemm(hipStream_t st, const GemmArgs& g, int wave_groups)
+{
+    const int gy = (wave_groups + 3) / 4;
+    if (g.rows >= 2048) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI>), dim3((g.rows + 63) / 64, gy), dim3(256), 0, st, g);
+    else if (g.rows >= 512) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI>), dim3((g.rows + 31) / 32, gy), dim3(256), 0, st, g);
+    else hipLaunchKernelGGL((gemm_bf16_kernel<1, EPI>), dim3((g.rows + 15) / 16, gy), dim3(256), 0, st, g);
+}
+
+template <int FT, bool U8>
+inline void launch_conv_stack(hipStream_t st, const ConvStackArgs& c)
+{
+    const long npix = (long)c.B * c.OH * c.OW;
+    const int gy = c.Cout / (16 * FT);
+    if (npix >= 65536) hipLaunchKernelGGL((conv_stack_bf16_kernel<FT, 2, U8>), dim3((unsigned)((npix + 127) / 128), gy), dim3(256), 0, st, c);
+    else hipLaunchKernelGGL((conv_stack_bf16_kernel<FT, 1, U8>), dim3((unsigned)((npix + 63) / 64), gy), dim3(256), 0, st, c);
+}
+
+// Runs torso, linear layer, recurrent core and dueling hidden layers.  On
+// return *core / *ld_core name the fp32 rows the output heads read.
+inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hipStream_t st, int B, const uint8_t* obs,
+                               const int32_t* prev_action, const float* prev_reward, const float* h_in,
+                               const float* c_in, float* h_out, float* c_out, float* d_hid, const float** core,
+                               int* ld_core, std::string& err)
+{
+    const seed_arch_t& a = p.arch;
+    (void)err;
+    if (a.torso == SEED_TORSO_RESNET) {
+        TorsoArgs t{};
+        t.obs = obs; t.feat = s->feat; t.ldf = s->ldf; t.B = B;
+        for (int i = 0; i < 4; ++i) t.sec[i] = s->sec[i];
+        const int grid = B < s->n_cu ? B : s->n_cu;
+        constexpr int LDS_DM = Net3<DmS1, DmS2, DmS3>::LDS_BYTES;
+        constexpr int LDS_FB = Net4<FbS1, DmS2, DmS3, FbS4>::LDS_BYTES;
+        static_assert(LDS_DM <= 160 * 1024 && LDS_FB <= 160 * 1024, "torso does not fit the 160 KiB of LDS");
+        if (s->torso_kind == TORSO_DMLAB)
+            hipLaunchKernelGGL((resnet3_bf16_kernel<DmS1, DmS2, DmS3>), dim3(grid), dim3(RN_THREADS), LDS_DM, st, t);
+        else
+            hipLaunchKernelGGL((resnet4_bf16_kernel<FbS1, DmS2, DmS3, FbS4>), dim3(grid), dim3(RN_THREADS), LDS_FB, st, t);
+    } else {
+        const void* x = obs;
+        for (size_t l = 0; l < p.convs.size(); ++l) {
+            const ConvLayer& c = p.convs[l];
+            const bool last = l + 1 == p.convs.size();
+            ConvStackArgs ca{};
+            ca.x = x; ca.wp = s->wp_conv + s->stack[l].wp_off / 8; ca.bias = d_w + c.b_off;
+            ca.koff = s->koff + s->stack[l].koff_off; ca.y = last ? s->feat : s->act[l & 1];
+            ca.B = B; ca.H = c.H; ca.W = c.W; ca.Cin = c.Cin; ca.OH = c.OH; ca.OW = c.OW; ca.Cout = c.Cout;
+            ca.stride = c.stride; ca.kchunks = s->stack[l].kchunks; ca.scale = l == 0 ? 1.0f / 255.0f : 1.0f;
+            const int nft = c.Cout / 16;
+            const int ft = nft % 4 == 0 ? 4 : (nft % 2 == 0 ? 2 : 1);
+            if (l == 0) {
+                if (ft == 4) launch_conv_stack<4, true>(st, ca); else if (ft == 2) launch_conv_stack<2, true>(st, ca); else launch_conv_stack<1, true>(st, ca);
+            } else {
+                if (ft == 4) launch_conv_stack<4, false>(st, ca); else if (ft == 2) launch_conv_stack<2, false>(st, ca); else launch_conv_stack<1, false>(st, ca);
+            }
+            x = ca.y;
+        }
+    }
+    // linear layer + ReLU -> bf16 (for the core GEMM) and fp32 (for heads / taps)
+    {
+        GemmArgs g{};
+        g.x1 = s->feat; g.ld1 = s->ldf; g.kc1 = s->kc_fc; g.k2 = 0;
+        g.wp = s->wp_fc; g.n_ftiles = s->ft_fc; g.rows = B; g.bias_pad = s->bias_fc;
+        g.y_bf16 = s->fc_bf16; g.ldy_bf16 = s->ldfc; g.y_f32 = s->fc_f32; g.ldy_f32 = a.fc_units; g.n_out = a.fc_units;
+        launch_gemm<EPI_RELU>(st, g, (s->ft_fc + 3) / 4);
+    }
+    *core = s->fc_f32; *ld_core = a.fc_units;
+    if (a.lstm_units > 0) {
+        GemmArgs g{};
+        g.x1 = s->fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->kc1_lstm;
+        g.x2 = h_in; g.ld2 = a.lstm_units; g.k2 = a.lstm_units;
+        g.wp = s->wp_lstm; g.n_ftiles = (a.lstm_units / 16) * 4; g.rows = B;
+        g.lstm_w = d_w + p.lstm_w; g.lstm_b = d_w + p.lstm_b; g.prev_action = prev_action; g.prev_reward = prev_reward;
+        g.c_in = c_in; g.h_out = h_out; g.c_out = c_out; g.F = a.fc_units; g.A = a.num_actions; g.Hn = a.lstm_units;
+        launch_gemm<EPI_LSTM>(st, g, a.lstm_units / 16);
+        *core = h_out; *ld_core = a.lstm_units;
+    }
+    if (a.head == SEED_HEAD_DUELING_Q) {
+        GemmArgs g{};
+        if (a.lstm_units > 0) { g.kc1 = 0; g.x1 = s->fc_bf16; g.ld1 = s->ldfc; g.x2 = h_out; g.ld2 = a.lstm_units; g.k2 = a.lstm_units; }
+        else { g.x1 = s->fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->ldfc / 32; g.k2 = 0; }
+        g.wp = s->wp_hid; g.n_ftiles = s->ft_hid; g.rows = B; g.bias_pad = s->bias_hid;
+        g.y_bf16 = nullptr; g.y_f32 = d_hid; g.ldy_f32 = 2 * a.head_hidden; g.n_out = 2 * a.head_hidden;
+        launch_gemm<EPI_RELU>(st, g, (s->ft_hid + 3) / 4);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { err = std::string("kernel launch: ") + hipGetErrorString(e); return SEED_ERR_DEVICE; }
+    return SEED_OK;
+}
+
+inline seed_status_t bf16_read_intermediate(Bf16State* s, const Plan& p, int which, int B, float* dst, hipStream_t st,
+                                            std::string& err)
+{
+    (void)err;
+    if (which == 0) {
+        size_t total = (size_t)B * p.flat;
+        hipLaunchKernelGGL(bf16_rows_to_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s->feat, s->ldf, dst,
+                           (int)p.flat, total);
+    } else {
+        size_t total = (size_t)B * p.arch.fc_units;
+        hipLaunchKernelGGL(copy_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s->fc_f32, dst, total);
+    }
+    return SEED_OK;
 }
 
 }  // namespace seedinf

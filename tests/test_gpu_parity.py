@@ -136,3 +136,12 @@ def test_error_paths_on_device(orc):
     ref = orc.forward(oracle.make_arch(cfg), w, b2["obs"], **{k: b2[k] for k in CORE_KEYS})
     check_against_oracle({k: v.cpu().numpy() for k, v in out.items()}, ref, 1e-4, b2["uniforms"])
     net.close()
+
+
+# ------------------------------------------------------------------ bf16 mode
+
+@pytest.mark.parametrize("name,B", [("C2", 7), ("C3", 5), ("C4", 3)])
+def test_bf16_small_ragged(orc, name, B):
+    """bf16 matrix-core path, small ragged batches (fewer rows than one MFMA
+    row tile; several images per persistent workgroup are covered below)."""
+    run_case(orc, wl.CONFIGS[name], B, "bf16")
