@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the central inference step on one MI355X.
+
+One "step" = one pass of the whole hot path (uint8 frames -> torso -> linear
+-> LSTM -> heads -> action selection) over one batch of synthetic DMLab-shaped
+input already resident in HBM.  The headline workload is the DMLab deep-ResNet
++ LSTM-256 agent at batch 4096 in bf16.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--no-extras] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16, published
+HBM_PEAK_GBS = 8000.0
+
+
+def torso_macs_per_frame(cfg):
+    from paper_1910_06591_amd import workloads as wl
+    h, w, c = wl.torso_out_shape(cfg)
+    tail = dict(cfg)
+    full = wl.macs_per_frame(cfg)
+    # everything after the torso: linear + core + heads
+    fc = cfg["fc_units"]
+    rest = h * w * c * fc
+    core, A = fc, cfg["num_actions"]
+    if cfg["lstm_units"]:
+        rest += (fc + A + 1 + cfg["lstm_units"]) * 4 * cfg["lstm_units"]
+        core = cfg["lstm_units"]
+    rest += core * (A + 1) if cfg["head"] == 0 else 2 * core * cfg["head_hidden"] + cfg["head_hidden"] * (A + 1)
+    return full - rest
+
+
+def time_config(cfg, B, steps, warmup, weights=None, profile=True):
+    """Returns dict with ms_per_step (wall over K steps between syncs), p50 of
+    per-step event pairs, and the torso kernel's mean duration."""
+    import numpy as np
+    import torch
+    from paper_1910_06591_amd import seedinf, workloads as wl
+
+    weights = wl.make_weights(cfg) if weights is None else weights
+    batch = wl.make_batch(cfg, B)
+    dev = {k: (None if v is None else torch.from_numpy(v).cuda()) for k, v in batch.items()}
+    net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=B), weights)
+    A, Hn = cfg["num_actions"], cfg["lstm_units"]
+    out = {"action": torch.empty(B, dtype=torch.int32, device="cuda"),
+           "logits": torch.empty(B, A, device="cuda"), "value": torch.empty(B, device="cuda")}
+    if Hn:
+        out["h"], out["c"] = torch.empty(B, Hn, device="cuda"), torch.empty(B, Hn, device="cuda")
+    for _ in range(warmup):
+        net.step(out=out, **dev)
+    torch.cuda.synchronize()
+    if profile:
+        net.set_profiling(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.step(out=out, **dev)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    res = {"ms_per_step": (t1 - t0) * 1e3 / steps}
+    if profile:
+        ms, n = net.profile_read()
+        res["torso_ms"] = ms / max(n, 1)
+        net.set_profiling(False)
+    # per-step latency distribution (separate loop so the events do not sit in the timed region)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in evs:
+        a.record()
+        net.step(out=out, **dev)
+        b.record()
+    torch.cuda.synchronize()
+    lat = np.sort(np.array([a.elapsed_time(b) for a, b in evs]))
+    res.update(p10_ms=float(lat[int(0.1 * (steps - 1))]), p50_ms=float(lat[(steps - 1) // 2]),
+               p90_ms=float(lat[int(0.9 * (steps - 1))]))
+    net.close()
+    return res
+
+
+def cpu_baseline(cfg, rows):
+    """The CPU oracle as it stands, on `rows` rows of the same workload."""
+    import oracle
+    from paper_1910_06591_amd import workloads as wl
+    orc = oracle.Oracle("f32")
+    weights = wl.make_weights(cfg)
+    b = wl.make_batch(cfg, rows)
+    kw = {k: b[k] for k in ("prev_action", "prev_reward", "h_in", "c_in", "uniforms")}
+    arch = oracle.make_arch(cfg)
+    orc.forward(arch, weights, b["obs"][:2], **{k: (None if v is None else v[:2]) for k, v in kw.items()})
+    t0 = time.perf_counter()
+    orc.forward(arch, weights, b["obs"], **kw)
+    dt = time.perf_counter() - t0
+    return {"value": rows / dt, "unit": "frames/s", "cores": int(orc.lib.oracle_num_threads()), "kind": "oracle",
+            "sample": f"{rows} rows of the same workload, one oracle_forward call ({dt:.1f} s wall)"}
+
+
+def read_traffic():
+    """HBM bytes per launch of the torso kernel from the committed rocprofv3
+    counter summary (profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", "resnet_torso_c5_b4096_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--batch", type=int, default=4096)
+    ap.add_argument("--no-extras", action="store_true", help="skip the batch sweep and the other configs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-rows", type=int, default=512)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU; --gpus must be 1 (the step shards by batch rows "
+              "with no exchange, so N GPUs are N independent copies)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1910_06591_amd import seedinf, workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(seedinf.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+
+    cfg = wl.CONFIGS["C5"]
+    B = args.batch
+    weights = wl.make_weights(cfg)
+    r = time_config(cfg, B, args.steps, args.warmup, weights)
+    fps = B / (r["ms_per_step"] * 1e-3)
+    flops_step = 2.0 * wl.macs_per_frame(cfg) * B
+    torso_flops = 2.0 * torso_macs_per_frame(cfg) * B
+    achieved = torso_flops / (r["torso_ms"] * 1e-3) / 1e12
+    line = {
+        "metric": "batched inference frames/sec at batch B (1 GPU)",
+        "value": fps, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"C5: DMLab deep-ResNet (16/32/32) + LSTM-256 agent, 72x96x3 uint8 frames, batch {B}, "
+                               "15 actions, Gumbel-max sampling", "batch": B},
+        "p50_ms": r["p50_ms"], "p10_ms": r["p10_ms"], "p90_ms": r["p90_ms"],
+        "step_tflops": flops_step / (r["ms_per_step"] * 1e-3) / 1e12,
+        "step_frac_of_bf16_peak": flops_step / (r["ms_per_step"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "resnet3_bf16_kernel (fused torso)", "achieved": achieved,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                     "kernel_ms": r["torso_ms"], "traffic": read_traffic()},
+    }
+    if not args.no_extras:
+        sweep = []
+        for b in cfg["sweep"]:
+            k = max(20, min(args.steps, 200))
+            s = time_config(cfg, b, k, args.warmup, weights)
+            sweep.append({"batch": b, "frames_per_s": b / (s["p50_ms"] * 1e-3), "p50_ms": s["p50_ms"],
+                          "frac_of_bf16_peak": 2.0 * wl.macs_per_frame(cfg) * b / (s["p50_ms"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                          "torso_ms": s["torso_ms"]})
+        line["sweep"] = sweep
+        others = []
+        for name in ("C1", "C2", "C3", "C4"):
+            c = wl.CONFIGS[name]
+            s = time_config(c, c["batch"], max(20, min(args.steps, 100)), args.warmup)
+            others.append({"config": name, "batch": c["batch"], "dtype": c["precision"],
+                           "frames_per_s": c["batch"] / (s["p50_ms"] * 1e-3), "p50_ms": s["p50_ms"],
+                           "tflops": 2.0 * wl.macs_per_frame(c) * c["batch"] / (s["p50_ms"] * 1e-3) / 1e12})
+        line["other_workloads"] = others
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(cfg, args.cpu_rows)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -172,6 +172,20 @@ seed_status_t seed_infer_step(seed_infer_t* handle, int32_t B,
 seed_status_t seed_infer_read_intermediate(seed_infer_t* handle, int32_t which, int32_t B,
                                            float* dst, size_t capacity, void* hip_stream);
 
+/*
+ * Kernel timing for callers that measure (benchmarks, profilers).  With
+ * profiling enabled, every seed_infer_step brackets its dominant kernel (the
+ * torso: the fused ResNet kernel, or the conv-stack layers) with HIP events on
+ * the step's stream, up to `SEED_PROFILE_SLOTS` steps between reads.
+ * seed_infer_profile_read waits for the recorded events, returns the summed
+ * torso time in milliseconds and the number of steps it covers, and starts a
+ * new measurement.  Enabling allocates events (not allowed under graph
+ * capture); disabled (the default) the step records nothing.
+ */
+#define SEED_PROFILE_SLOTS 4096
+seed_status_t seed_infer_set_profiling(seed_infer_t* handle, int32_t enable);
+seed_status_t seed_infer_profile_read(seed_infer_t* handle, float* torso_ms_sum, int32_t* n_steps);
+
 /* Number of features the torso feeds the linear layer (H*W*C), 0 if invalid. */
 size_t seed_infer_torso_features(const seed_arch_t* arch);
 

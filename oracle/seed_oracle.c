@@ -41,6 +41,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #ifdef ORACLE_F64
 typedef double real;
@@ -70,6 +73,16 @@ typedef struct {
 } oracle_arch;
 
 int oracle_sizeof_real(void) { return (int)sizeof(real); }
+
+/* threads oracle_forward spreads batch rows over (1 without OpenMP) */
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ---------------------------------------------------------------- layers */
 

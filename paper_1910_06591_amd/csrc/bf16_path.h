@@ -324,10 +324,11 @@ inline void launch_conv_stack(hipStream_t st, const ConvStackArgs& c)
 inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hipStream_t st, int B, const uint8_t* obs,
                                const int32_t* prev_action, const float* prev_reward, const float* h_in,
                                const float* c_in, float* h_out, float* c_out, float* d_hid, const float** core,
-                               int* ld_core, std::string& err)
+                               int* ld_core, hipEvent_t ev0, hipEvent_t ev1, std::string& err)
 {
     const seed_arch_t& a = p.arch;
     (void)err;
+    if (ev0) (void)hipEventRecord(ev0, st);
     if (a.torso == SEED_TORSO_RESNET) {
         TorsoArgs t{};
         t.obs = obs; t.feat = s->feat; t.ldf = s->ldf; t.B = B;
@@ -360,6 +361,7 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
             x = ca.y;
         }
     }
+    if (ev1) (void)hipEventRecord(ev1, st);
     // linear layer + ReLU -> bf16 (for the core GEMM) and fp32 (for heads / taps)
     {
         GemmArgs g{};

@@ -26,6 +26,8 @@ struct seed_infer {
     float* d_hid = nullptr;        // [max_batch, 2*head_hidden] dueling hidden, fp32
     const float* feat_f32 = nullptr;   // where the last fp32-mode step left the torso features
     Bf16State* bf = nullptr;       // everything the bf16 path owns
+    std::vector<hipEvent_t> ev;    // profiling: 2 events per slot (empty = profiling off)
+    int ev_used = 0;
     std::string err;
 };
 
@@ -80,6 +82,7 @@ static void free_all(seed_infer* h)
 {
     if (!h) return;
     if (h->bf) { bf16_destroy(h->bf); h->bf = nullptr; }
+    for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
     if (h->d_w) (void)hipFree(h->d_w);
     if (h->d_act[0]) (void)hipFree(h->d_act[0]);
     if (h->d_act[1]) (void)hipFree(h->d_act[1]);
@@ -247,8 +250,13 @@ extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8
     const float* core = nullptr;       // fp32 [B, p.core]
     int ld_core = p.core;
 
+    const bool prof = !h->ev.empty() && h->ev_used < SEED_PROFILE_SLOTS;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (prof) { ev0 = h->ev[2 * h->ev_used]; ev1 = h->ev[2 * h->ev_used + 1]; ++h->ev_used; }
     if (a.precision == SEED_PRECISION_FP32) {
+        if (prof) HIP_TRY(h, hipEventRecord(ev0, s));
         torso_fc_f32(h, s, B, obs);
+        if (prof) HIP_TRY(h, hipEventRecord(ev1, s));
         core = h->d_fc;
         if (rec) {
             hipLaunchKernelGGL(lstm_f32_kernel, dim3(B, (a.lstm_units + 255) / 256), dim3(256), 0, s, h->d_fc, prev_action,
@@ -265,7 +273,7 @@ extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8
         }
     } else {
         seed_status_t st = bf16_step(h->bf, p, w, s, B, obs, prev_action, prev_reward, h_in, c_in, h_out, c_out,
-                                     h->d_hid, &core, &ld_core, h->err);
+                                     h->d_hid, &core, &ld_core, ev0, ev1, h->err);
         if (st != SEED_OK) return st;
     }
 
@@ -308,5 +316,39 @@ extern "C" seed_status_t seed_infer_read_intermediate(seed_infer_t* h, int32_t w
         if (st != SEED_OK) return st;
     }
     HIP_TRY(h, hipGetLastError());
+    return SEED_OK;
+}
+
+extern "C" seed_status_t seed_infer_set_profiling(seed_infer_t* h, int32_t enable)
+{
+    if (!h) return SEED_ERR_INVALID_ARG;
+    if (enable && h->ev.empty()) {
+        h->ev.reserve(2 * SEED_PROFILE_SLOTS);
+        for (int i = 0; i < 2 * SEED_PROFILE_SLOTS; ++i) {
+            hipEvent_t e;
+            HIP_TRY(h, hipEventCreate(&e));
+            h->ev.push_back(e);
+        }
+    } else if (!enable) {
+        for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
+        h->ev.clear();
+    }
+    h->ev_used = 0;
+    return SEED_OK;
+}
+
+extern "C" seed_status_t seed_infer_profile_read(seed_infer_t* h, float* torso_ms_sum, int32_t* n_steps)
+{
+    if (!h || !torso_ms_sum || !n_steps) return SEED_ERR_INVALID_ARG;
+    float sum = 0.f;
+    for (int i = 0; i < h->ev_used; ++i) {
+        HIP_TRY(h, hipEventSynchronize(h->ev[2 * i + 1]));
+        float ms = 0.f;
+        HIP_TRY(h, hipEventElapsedTime(&ms, h->ev[2 * i], h->ev[2 * i + 1]));
+        sum += ms;
+    }
+    *torso_ms_sum = sum;
+    *n_steps = h->ev_used;
+    h->ev_used = 0;
     return SEED_OK;
 }

@@ -24,7 +24,7 @@ STATUS = {0: "SEED_OK", 1: "SEED_ERR_INVALID_ARG", 2: "SEED_ERR_UNSUPPORTED_ARCH
           4: "SEED_ERR_ALIASING", 5: "SEED_ERR_DEVICE", 6: "SEED_ERR_OOM"}
 EXPORTS = ["seed_infer_weight_count", "seed_infer_validate", "seed_infer_create", "seed_infer_step",
            "seed_infer_read_intermediate", "seed_infer_torso_features", "seed_infer_last_error",
-           "seed_infer_destroy"]
+           "seed_infer_destroy", "seed_infer_set_profiling", "seed_infer_profile_read"]
 
 
 class SeedError(RuntimeError):
@@ -87,6 +87,10 @@ def load_library():
     lib.seed_infer_read_intermediate.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.seed_infer_last_error.restype = C.c_char_p
     lib.seed_infer_last_error.argtypes = [C.c_void_p]
+    lib.seed_infer_set_profiling.restype = C.c_int
+    lib.seed_infer_set_profiling.argtypes = [C.c_void_p, C.c_int32]
+    lib.seed_infer_profile_read.restype = C.c_int
+    lib.seed_infer_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.seed_infer_destroy.restype = None
     lib.seed_infer_destroy.argtypes = [C.c_void_p]
     _lib = lib
@@ -212,6 +216,19 @@ class SeedInfer:
         if st != 0:
             raise SeedError(st, self.lib.seed_infer_last_error(self._h).decode())
         return out
+
+    def set_profiling(self, enable: bool):
+        st = self.lib.seed_infer_set_profiling(self._h, int(enable))
+        if st != 0:
+            raise SeedError(st, self.lib.seed_infer_last_error(self._h).decode())
+
+    def profile_read(self):
+        """(summed torso-kernel milliseconds, number of steps covered) since the last read."""
+        ms, n = C.c_float(), C.c_int32()
+        st = self.lib.seed_infer_profile_read(self._h, C.byref(ms), C.byref(n))
+        if st != 0:
+            raise SeedError(st, self.lib.seed_infer_last_error(self._h).decode())
+        return ms.value, n.value
 
     def read_intermediate(self, which: int, B: int, stream=None):
         """Diagnostic tap: 0 = torso features [B, H*W*C], 1 = linear output [B, fc_units] (fp32)."""
