@@ -11,18 +11,18 @@
 #include "kernels_fp32.h"
 #include "gemm_bf16.h"
 #include "conv_stack_bf16.h"
-#include "resnet_bf16.h"
+#include "resnet_fused.h"
 
 namespace seedinf {
 
 // ---- the deep-ResNet torsos this build has fused kernels for ----------------
 // DMLab-shaped: 72x96x3 frames, sections 16/32/32.
-using DmS1 = SecCfg<72, 96, 3, 16, IN_U8_C3, 9>;
-using DmS2 = SecCfg<36, 48, 16, 32, IN_LDS, 9>;
-using DmS3 = SecCfg<18, 24, 32, 32, IN_LDS, 9>;
+using DmS1 = SecCfg<72, 96, 3, 16, IN_U8_C3, 4, 36>;
+using DmS2 = SecCfg<36, 48, 16, 32, IN_LDS, 8, 0>;
+using DmS3 = SecCfg<18, 24, 32, 32, IN_LDS, 4, 0>;
 // Football-shaped: 72x96x16 minimap planes, sections 16/32/32/32.
-using FbS1 = SecCfg<72, 96, 16, 16, IN_U8_PLANAR, 8>;
-using FbS4 = SecCfg<9, 12, 32, 32, IN_LDS, 5>;
+using FbS1 = SecCfg<72, 96, 16, 16, IN_U8_PLANAR, 4, 8>;
+using FbS4 = SecCfg<9, 12, 32, 32, IN_LDS, 5, 0>;
 
 enum { TORSO_NONE = 0, TORSO_DMLAB = 1, TORSO_FOOTBALL = 2 };
 
@@ -120,6 +120,14 @@ inline void bf16_destroy(Bf16State* s)
         }                                                                        \
     } while (0)
 
+// one 1 KiB chunk after a layer's fragments: its first C floats are the layer's biases
+inline void pack_bias_chunk(std::vector<uint16_t>& pk, const float* bias, int C)
+{
+    size_t base = pk.size();
+    pk.resize(base + 512, 0);
+    memcpy(pk.data() + base, bias, (size_t)C * sizeof(float));
+}
+
 template <class S>
 inline void pack_section(std::vector<uint16_t>& pk, const float* w, const Section& sec, size_t (&off)[5])
 {
@@ -138,10 +146,12 @@ inline void pack_section(std::vector<uint16_t>& pk, const float* w, const Sectio
     } else {
         pack_a(pk, S::FT, S::KC0, [&](int f, int k) -> float { return k < 9 * S::CIN ? w0[(size_t)k * S::C + f] : 0.f; });
     }
+    pack_bias_chunk(pk, w + c0.b_off, S::C);
     for (int j = 0; j < 4; ++j) {
         const float* wb = w + sec.block[j].w_off;
         off[1 + j] = pk.size();
         pack_a(pk, S::FT, S::KCB, [&](int f, int k) -> float { return k < 9 * S::C ? wb[(size_t)k * S::C + f] : 0.f; });
+        pack_bias_chunk(pk, w + sec.block[j].b_off, S::C);
     }
 }
 
@@ -277,11 +287,7 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, const float* d_w
         for (size_t si = 0; si < p.sections.size(); ++si) {
             SecWeights& sw = s->sec[si];
             sw.w0 = frag(sec_off[si][0]);
-            sw.b0 = d_w + p.sections[si].conv0.b_off;
-            for (int j = 0; j < 4; ++j) {
-                sw.wb[j] = frag(sec_off[si][1 + j]);
-                sw.bb[j] = d_w + p.sections[si].block[j].b_off;
-            }
+            for (int j = 0; j < 4; ++j) sw.wb[j] = frag(sec_off[si][1 + j]);
         }
     }
     s->act[0] = (__bf16*)(s->arena + o_act[0]);
