@@ -38,6 +38,15 @@ __device__ __forceinline__ floatx4 relu4(floatx4 v)
     return r;
 }
 
+// ReLU on four packed bf16 values: as signed 16-bit integers every negative float is negative
+// and every non-negative float is non-negative, so max(x, 0) per 16-bit lane is exact.
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x4 relu_bf16x4(bf16x4 v)
+{
+    const shortx4 z = {0, 0, 0, 0};
+    return __builtin_bit_cast(bf16x4, __builtin_elementwise_max(__builtin_bit_cast(shortx4, v), z));
+}
+
 __device__ __forceinline__ floatx4 to_floatx4(bf16x4 v)
 {
     floatx4 r;

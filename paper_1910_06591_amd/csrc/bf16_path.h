@@ -19,10 +19,10 @@ namespace seedinf {
 // DMLab-shaped: 72x96x3 frames, sections 16/32/32.
 using DmS1 = SecCfg<72, 96, 3, 16, IN_U8_C3, 4, 36>;
 using DmS2 = SecCfg<36, 48, 16, 32, IN_LDS, 8, 0>;
-using DmS3 = SecCfg<18, 24, 32, 32, IN_LDS, 4, 0>;
+using DmS3 = SecCfg<18, 24, 32, 32, IN_LDS, 4, 0, 4>;
 // Football-shaped: 72x96x16 minimap planes, sections 16/32/32/32.
 using FbS1 = SecCfg<72, 96, 16, 16, IN_U8_PLANAR, 4, 8>;
-using FbS4 = SecCfg<9, 12, 32, 32, IN_LDS, 5, 0>;
+using FbS4 = SecCfg<9, 12, 32, 32, IN_LDS, 5, 0, 2>;
 
 enum { TORSO_NONE = 0, TORSO_DMLAB = 1, TORSO_FOOTBALL = 2 };
 
@@ -120,6 +120,18 @@ inline void bf16_destroy(Bf16State* s)
         }                                                                        \
     } while (0)
 
+// weight of output channel f at packed K index k (chunk k/32, lane group (k%32)/8, element k%8) of a 3x3
+// convolution with CIN input channels, following the kernels' K layout (KMap)
+template <int CIN>
+inline float planar_weight(const float* w, int cout, int f, int k)
+{
+    const int kc = k / 32, g = (k % 32) / 8, e = k % 8;
+    const int tap = KMap<CIN>::tap(kc, g);
+    if (tap < 0 || tap > 8) return 0.f;
+    const int ch = KMap<CIN>::cg(kc, g) * 8 + e;
+    return w[((size_t)tap * CIN + ch) * cout + f];
+}
+
 // one 1 KiB chunk after a layer's fragments: its first C floats are the layer's biases
 inline void pack_bias_chunk(std::vector<uint16_t>& pk, const float* bias, int C)
 {
@@ -134,7 +146,7 @@ inline void pack_section(std::vector<uint16_t>& pk, const float* w, const Sectio
     const ConvLayer& c0 = sec.conv0;
     const float* w0 = w + c0.w_off;
     off[0] = pk.size();
-    if (S::INKIND == IN_U8_C3) {
+    if constexpr (S::INKIND == IN_U8_C3) {
         // K slot s = kchunk*4 + lanegroup: s < 6 -> kernel row s/2, pixel pair s%2; element e -> pixel e/4, channel e%4
         pack_a(pk, S::FT, 2, [&](int f, int k) -> float {
             int s = k / 8, e = k % 8;
@@ -144,13 +156,13 @@ inline void pack_section(std::vector<uint16_t>& pk, const float* w, const Sectio
             return w0[((size_t)(kh * 3 + kw) * 3 + ch) * S::C + f];
         });
     } else {
-        pack_a(pk, S::FT, S::KC0, [&](int f, int k) -> float { return k < 9 * S::CIN ? w0[(size_t)k * S::C + f] : 0.f; });
+        pack_a(pk, S::FT, S::KC0, [&](int f, int k) -> float { return planar_weight<S::CIN>(w0, S::C, f, k); });
     }
     pack_bias_chunk(pk, w + c0.b_off, S::C);
     for (int j = 0; j < 4; ++j) {
         const float* wb = w + sec.block[j].w_off;
         off[1 + j] = pk.size();
-        pack_a(pk, S::FT, S::KCB, [&](int f, int k) -> float { return k < 9 * S::C ? wb[(size_t)k * S::C + f] : 0.f; });
+        pack_a(pk, S::FT, S::KCB, [&](int f, int k) -> float { return planar_weight<S::C>(wb, S::C, f, k); });
         pack_bias_chunk(pk, w + sec.block[j].b_off, S::C);
     }
 }

@@ -55,7 +55,10 @@ __device__ unsigned long long seed_phase_cycles[32];
 #define PHASE_DECL do { } while (0)
 #endif
 
-constexpr int RN_WAVES = 8;
+#ifndef SEEDINF_RN_WAVES
+#define SEEDINF_RN_WAVES 8
+#endif
+constexpr int RN_WAVES = SEEDINF_RN_WAVES;
 constexpr int RN_THREADS = RN_WAVES * 64;
 constexpr int LDS_TOTAL = 160 * 1024;
 constexpr int WSLOT_BYTES = 19 * 1024;          // largest layer: 18 fragments of 1 KiB + the bias chunk
@@ -71,8 +74,9 @@ __device__ __forceinline__ void lds_barrier()
 
 // Compile-time description of one section.
 //   NB = bands of pooled rows per conv0 pass, SR = pooled rows per input strip
-//   (uint8 sections only; IN_LDS sections have their whole input resident).
-template <int H_, int W_, int CIN_, int C_, int INKIND_, int NB_, int SR_>
+//   (uint8 sections only; IN_LDS sections have their whole input resident), NWA = wavefronts that
+//   own pooled tiles: small maps use fewer, so fewer wavefronts re-read the layer's whole A operand.
+template <int H_, int W_, int CIN_, int C_, int INKIND_, int NB_, int SR_, int NWA_ = RN_WAVES>
 struct SecCfg {
     static constexpr int H = H_, W = W_, CIN = CIN_, C = C_, INKIND = INKIND_, NB = NB_;
     static constexpr int PH = (H + 1) / 2, PW = (W + 1) / 2;
@@ -82,12 +86,14 @@ struct SecCfg {
     static constexpr int FT = C / 16;
     static constexpr int KC0 = INKIND == IN_U8_C3 ? 2 : (9 * CIN + 31) / 32;
     static constexpr int KCB = (9 * C + 31) / 32;
+    static constexpr int NK0 = INKIND == IN_U8_C3 ? 2 : (CIN == 16 ? 3 : 1);   // offset registers conv0 keeps per lane
     static constexpr int W0_FRAGS = FT * KC0, WB_FRAGS = FT * KCB;
     // a staged weight set = the fragments + one 1 KiB chunk whose first C floats are the biases
     static constexpr int W0_SET = W0_FRAGS + 1, WB_SET = WB_FRAGS + 1;
     static constexpr int NPIX = PH * PW;
     static constexpr int NTILES = (NPIX + 15) / 16;
-    static constexpr int NT = (NTILES + RN_WAVES - 1) / RN_WAVES;
+    static constexpr int NWA = NWA_;                        // wavefronts that own pooled tiles (x-read and blocks)
+    static constexpr int NT = (NTILES + NWA - 1) / NWA;
     static constexpr int NCS = (W + 15) / 16;               // 16-column strips of the conv0 output
     static constexpr int NUNITS = NCS * NB;
     static constexpr int NU = (NUNITS + RN_WAVES - 1) / RN_WAVES;
@@ -106,7 +112,8 @@ struct SecCfg {
     static constexpr int PRE_N = INKIND == IN_LDS ? 1 : (PRE_ITEMS + RN_THREADS - 1) / RN_THREADS;
     static_assert(C % 16 == 0, "section channels must be a multiple of 16");
     static_assert(W % 2 == 0, "even width (pool padding only after the last column)");
-    static_assert(INKIND == IN_U8_C3 ? CIN == 3 : CIN % 8 == 0, "input channels: 3 (uint8) or a multiple of 8");
+    static_assert(INKIND == IN_U8_C3 ? CIN == 3 : (CIN == 16 || CIN == 32), "input channels: 3 (uint8), 16 or 32");
+    static_assert(C == 16 || C == 32, "section channels: 16 or 32");
     static_assert(INKIND != IN_U8_C3 || ((W * 3) % 4 == 0 && W % 4 == 0), "3-channel rows must be whole dwords");
     static_assert(INKIND != IN_U8_PLANAR || CIN == 16, "planar uint8 input: 16 channels");
     static_assert(INKIND != IN_U8_C3 || NSTRIPS == 1, "the 3-channel frame is kept whole");
@@ -159,21 +166,44 @@ __device__ __forceinline__ void load_a_frags(bf16x8 (&w)[NF], const char* slot, 
     for (int i = 0; i < NF; ++i) w[i] = *(const bf16x8*)(slot + (i * 64 + lane) * 16);
 }
 
-// offsets (in 16-byte cells) of each K chunk's fragment relative to the pixel's
-// tap (0,0) cell in plane 0, for a planar map with `plane` cells per plane and
-// `pitch` cells per row.  Taps past the 9th point at the 9th (their weights are 0).
-template <int CIN, int KC>
-__device__ __forceinline__ void planar_koff(int (&koff)[KC], int g, int plane, int pitch)
-{
-#pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-        int k0 = kc * 32 + g * 8;
-        int tap = k0 / CIN;
-        int cg = (k0 % CIN) / 8;
-        if (tap > 8) { tap = 8; cg = 0; }
-        koff[kc] = cg * plane + (tap / 3) * pitch + (tap % 3);
+// ---- K layout of the 3x3 convolutions over planar maps --------------------------------------
+// A K chunk is 32 values = 4 lane groups x 8 channels.  The fragment a lane reads for chunk kc sits at
+//   (its pixel's tap (0,0) cell) + lane base [which one: kbase(kc)] + immediate kimm(kc)
+// so per output tile only the (at most three) lane bases are added in registers; the per-chunk part is a
+// compile-time ds_read offset.
+//   32 input channels: chunk kc = tap kc, lane group g = channel group g.
+//   16 input channels: chunks 0..2 = kernel row kc, lane group g -> kernel column g>>1, channel group g&1;
+//     chunk 3 = column 2 of kernel rows 0 (g < 2) and 2 (g >= 2); chunk 4 = column 2 of kernel row 1
+//     (g < 2; the g >= 2 half is padding with zero weights and re-reads chunk 3's cell).
+//   The host packs each layer's weights in the same order (kmap_tap / kmap_cg in the packer).
+template <int CIN>
+struct KMap {
+    static_assert(CIN == 16 || CIN == 32, "planar convolutions take 16 or 32 input channels");
+    static constexpr int KC = CIN == 16 ? 5 : 9;
+    static constexpr int NBASE = CIN == 16 ? 3 : 1;
+    static constexpr int kbase(int kc) { return CIN == 16 ? (kc < 3 ? 0 : kc - 2) : 0; }
+    static constexpr int kimm(int kc, int pitch) { return CIN == 16 ? (kc < 3 ? kc * pitch : 0) : (kc / 3) * pitch + kc % 3; }
+    // host + device: kernel tap (kh*3+kw, or -1 for padding) and channel group of slot (kc, g)
+    static constexpr int tap(int kc, int g)
+    {
+        if (CIN == 32) return kc;
+        if (kc < 3) return kc * 3 + (g >> 1);
+        if (kc == 3) return (g < 2 ? 0 : 2) * 3 + 2;
+        return g < 2 ? 1 * 3 + 2 : -1;
     }
-}
+    static constexpr int cg(int kc, int g) { return CIN == 32 ? g : (g & 1); }
+    __device__ static __forceinline__ void lane_bases(int (&lb)[NBASE], int g, int plane, int pitch)
+    {
+        if constexpr (CIN == 32) {
+            lb[0] = g * plane;
+        } else {
+            const int pl = (g & 1) * plane;
+            lb[0] = pl + (g >> 1);
+            lb[1] = pl + 2 + (g < 2 ? 0 : 2 * pitch);
+            lb[2] = pl + 2 + (g < 2 ? pitch : 2 * pitch);
+        }
+    }
+};
 
 // ---- uint8 frame prefetch --------------------------------------------------------
 template <class S>
@@ -285,39 +315,46 @@ __device__ __forceinline__ void prefetch_commit(const Prefetch<S>& p, char* buf0
 }
 
 // ---- conv0 + max-pool ----------------------------------------------------------------
-// h[n] = max(v[n], v[n+1], v[n+2]) within each row of 16 lanes; lanes whose neighbour lies outside the
-// row keep the partial maximum (a DPP op with an invalid source lane leaves its destination untouched).
-__device__ __forceinline__ float hmax3_row16(float v)
+// h[n] = max(v[n], v[n+1], v[n+2]) within each row of 16 lanes, for the four channels a lane holds.
+// A DPP op whose source lane lies outside the row leaves its destination untouched, so lane 14 ends
+// with max(v[14], v[15]) (completed later from the next strip's edge column) and lane 15 with
+// garbage; only even lanes are pooled outputs.
+__device__ __forceinline__ floatx4 hmax3_row16(floatx4 v)
 {
-#ifdef SEEDINF_DPP_BUILTIN
-    const int i = __builtin_bit_cast(int, v);
-    const float s1 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(i, i, 0x101, 0xf, 0xf, false));
-    const float s2 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(i, i, 0x102, 0xf, 0xf, false));
-    return fmaxf(fmaxf(v, s1), s2);
-#endif
-    // h and v must be different registers: the second op still needs the unshifted v
-    float h;
-    asm volatile("v_mov_b32 %0, %1\n\ts_nop 0\n\t"
-                 "v_max_f32_dpp %0, %1, %0 row_shl:1 row_mask:0xf bank_mask:0xf\n\t"
-                 "v_max_f32_dpp %0, %1, %0 row_shl:2 row_mask:0xf bank_mask:0xf"
-                 : "=&v"(h) : "v"(v));
-    return h;
+    float h0, h1, h2, h3;
+    asm volatile("s_nop 1\n\t"
+                 "v_max_f32_dpp %0, %4, %4 row_shl:1 row_mask:0xf bank_mask:0xf\n\t"
+                 "v_max_f32_dpp %1, %5, %5 row_shl:1 row_mask:0xf bank_mask:0xf\n\t"
+                 "v_max_f32_dpp %2, %6, %6 row_shl:1 row_mask:0xf bank_mask:0xf\n\t"
+                 "v_max_f32_dpp %3, %7, %7 row_shl:1 row_mask:0xf bank_mask:0xf\n\t"
+                 "v_max_f32_dpp %0, %4, %0 row_shl:2 row_mask:0xf bank_mask:0xf\n\t"
+                 "v_max_f32_dpp %1, %5, %1 row_shl:2 row_mask:0xf bank_mask:0xf\n\t"
+                 "v_max_f32_dpp %2, %6, %2 row_shl:2 row_mask:0xf bank_mask:0xf\n\t"
+                 "v_max_f32_dpp %3, %7, %3 row_shl:2 row_mask:0xf bank_mask:0xf"
+                 : "=&v"(h0), "=&v"(h1), "=&v"(h2), "=&v"(h3)
+                 : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]));
+    return floatx4{h0, h1, h2, h3};
 }
 
 // B fragments of one conv0 output tile (16 consecutive columns of one conv row); `base` = cell index of
 // the tile's tap (0,0) in plane 0.
 template <class S>
-__device__ __forceinline__ void conv0_load(bf16x8 (&b)[S::KC0], const char* in, int base, const int (&koff)[S::KC0])
+__device__ __forceinline__ void conv0_load(bf16x8 (&b)[S::KC0], const char* in, int base, const int (&koff)[S::NK0])
 {
+    if constexpr (S::INKIND == IN_U8_C3) {
 #pragma unroll
-    for (int kc = 0; kc < S::KC0; ++kc) {
-        if constexpr (S::INKIND == IN_U8_C3) {
+        for (int kc = 0; kc < S::KC0; ++kc) {
             const char* s = in + (base + koff[kc]) * 8;
             const bf16x4 lo = *(const bf16x4*)s, hi = *(const bf16x4*)(s + 8);
             b[kc] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        } else {
-            b[kc] = *(const bf16x8*)(in + (base + koff[kc]) * 16);
         }
+    } else {
+        using K = KMap<S::CIN>;
+        const char* pa[K::NBASE];
+#pragma unroll
+        for (int q = 0; q < K::NBASE; ++q) pa[q] = in + (base + koff[q]) * 16;
+#pragma unroll
+        for (int kc = 0; kc < S::KC0; ++kc) b[kc] = *(const bf16x8*)(pa[K::kbase(kc)] + K::kimm(kc, S::IPITCH) * 16);
     }
 }
 
@@ -336,6 +373,7 @@ __device__ __forceinline__ void conv0_mma(floatx4 (&acc)[S::FT], const bf16x8 (&
 // (so conv row r's tap row kh sits in buffer row r - 1 + kh - rbuf0).  Writes un-rectified
 // pooled bf16 values into `xout` (planar map with halo, this section's pooled geometry) and
 // each strip's first-column vertical maxima into `edge`.  `wslot`: conv0's staged weight set.
+// The two conv rows of pooled row py+1 are read from LDS while those of row py are multiplied.
 template <class S>
 __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edge, const bf16x8 (&w0)[S::W0_FRAGS],
                                            const char* wslot, int pr0, int pr1, int rbuf0, int lane, int wave)
@@ -346,7 +384,7 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
     floatx4 bv[S::FT];
 #pragma unroll
     for (int j = 0; j < S::FT; ++j) bv[j] = *(const floatx4*)(wslot + S::W0_FRAGS * 1024 + (j * 4 + g) * 16);
-    int koff[S::KC0];
+    int koff[S::NK0];                                     // 3-channel frame: per-chunk offsets; planar: lane bases
     if constexpr (S::INKIND == IN_U8_C3) {
         // K slot s = kc*4 + g -> (kernel row s/2, pixel pair s%2); 8-byte cells
 #pragma unroll
@@ -356,7 +394,7 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
             koff[kc] = (s >> 1) * S::IPITCH + (s & 1) * 2;
         }
     } else {
-        planar_koff<S::CIN, S::KC0>(koff, g, S::IPLANE, S::IPITCH);
+        KMap<S::CIN>::lane_bases(koff, g, S::IPLANE, S::IPITCH);
     }
     const int npr = pr1 - pr0;
     const floatx4 NEG = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
@@ -373,8 +411,10 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
         const int colc = live ? col : S::W - 1;
         // cell index of conv row r, tap (0,0): (r - 1 - rbuf0) * IPITCH + colc
         const int cbase = colc - (1 + rbuf0) * S::IPITCH;
-        floatx4 top[S::FT], mid[S::FT], bot[S::FT];
-        bf16x8 fa[S::KC0], fb[S::KC0];
+        floatx4 top[S::FT];
+        // second fragment set (software pipeline) only where the registers allow it
+        constexpr bool PIPE = S::W0_FRAGS * 4 + S::KC0 * 16 <= 128;
+        bf16x8 fa[S::KC0], fb[S::KC0], ga[PIPE ? S::KC0 : 1], gb[PIPE ? S::KC0 : 1];
         const int rt = 2 * pb0 - S::PADH;
         if (rt >= 0) {
             conv0_load<S>(fa, in, cbase + rt * S::IPITCH, koff);
@@ -383,32 +423,82 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
 #pragma unroll
             for (int j = 0; j < S::FT; ++j) top[j] = NEG;
         }
-        // output addresses of this unit's first pooled row; they advance by one row per iteration
+        // output addresses of this unit's first pooled row; they advance by one row per pooled row
         const int px = col >> 1;
         int xoff = ((pb0 + 1) * S::PITCH + px + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
         int eoff = ((cs * S::PH + pb0) * S::C + g * 4) * 2;
-#pragma unroll 1
-        for (int py = pb0; py < pb1; ++py) {
+        const bool wr_edge = n == 0 && cs > 0;
+        const bool wr_pool = live && !(n & 1);
+
+        // rows of pooled row py: mid = 2 py - PADH + 1 (always inside the image), bot = mid + 1 (may not exist)
+        auto load_pair = [&](bf16x8 (&a)[S::KC0], bf16x8 (&c)[S::KC0], int py) {
             const int rm = 2 * py - S::PADH + 1;
-            const bool has_bot = rm + 1 < S::H;             // uniform
-            conv0_load<S>(fa, in, cbase + rm * S::IPITCH, koff);
-            conv0_load<S>(fb, in, cbase + (has_bot ? rm + 1 : rm) * S::IPITCH, koff);
-            conv0_mma<S>(mid, fa, w0);
-            conv0_mma<S>(bot, fb, w0);
+            conv0_load<S>(a, in, cbase + rm * S::IPITCH, koff);
+            conv0_load<S>(c, in, cbase + (rm + 1 < S::H ? rm + 1 : rm) * S::IPITCH, koff);
+        };
+        auto finish_row = [&](const bf16x8 (&a)[S::KC0], const bf16x8 (&c)[S::KC0]) {
+            floatx4 mid[S::FT], bot[S::FT];
+            conv0_mma<S>(mid, a, w0);
+            conv0_mma<S>(bot, c, w0);
 #pragma unroll
             for (int j = 0; j < S::FT; ++j) {
                 floatx4 v = max4(max4(top[j], mid[j]), bot[j]) * SCALE + bv[j];
                 if (!FULL && !live) v = NEG;
-                if (n == 0 && cs > 0) *(bf16x4*)(edge + eoff + j * 32) = to_bf16x4(v);
-                floatx4 h;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) h[i] = hmax3_row16(v[i]);
-                if (live && !(n & 1)) *(bf16x4*)(xout + xoff + j * (2 * S::PLANE * 16)) = to_bf16x4(h);
+                if (wr_edge) *(bf16x4*)(edge + eoff + j * 32) = to_bf16x4(v);
+                const floatx4 h = hmax3_row16(v);
+                if (wr_pool) *(bf16x4*)(xout + xoff + j * (2 * S::PLANE * 16)) = to_bf16x4(h);
                 top[j] = bot[j];
             }
             xoff += S::PITCH * 16;
             eoff += S::C * 2;
+        };
+        if constexpr (PIPE) {
+            load_pair(fa, fb, pb0);
+#pragma unroll 1
+            for (int py = pb0; py < pb1; py += 2) {
+                if (py + 1 < pb1) load_pair(ga, gb, py + 1);
+                finish_row(fa, fb);
+                if (py + 1 < pb1) {
+                    if (py + 2 < pb1) load_pair(fa, fb, py + 2);
+                    finish_row(ga, gb);
+                }
+            }
+        } else {
+#pragma unroll 1
+            for (int py = pb0; py < pb1; ++py) {
+                load_pair(fa, fb, py);
+                finish_row(fa, fb);
+            }
         }
+    }
+}
+
+// Per-lane cell index (row * PITCH + column, plane 0, tap (0,0)) of the pixel this lane holds in each of
+// the wavefront's tiles; pixels past the end of the map are clamped to the last one.  NWA = wavefronts
+// that own tiles in this section.
+// (row, column) of pixel t*16 + n of the pooled map, clamped to the last pixel.  The division runs on the
+// tile's first pixel, which is uniform across the wavefront (scalar unit); lanes only wrap rows.
+template <class S>
+__device__ __forceinline__ void tile_pixel(int t, int n, int& y, int& xx)
+{
+    const int p0 = t * 16;
+    y = p0 / S::PW;
+    xx = p0 % S::PW + n;
+#pragma unroll
+    for (int k = 0; k < (15 + S::PW - 1) / S::PW; ++k)
+        if (xx >= S::PW) { xx -= S::PW; ++y; }
+    if (S::NPIX % 16 != 0 && y >= S::PH) { y = S::PH - 1; xx = S::PW - 1; }
+}
+
+template <class S>
+__device__ __forceinline__ void tile_table(int (&tb)[S::NT], int lane, int wave)
+{
+    const int n = lane & 15;
+#pragma unroll
+    for (int i = 0; i < S::NT; ++i) {
+        int y, xx;
+        tile_pixel<S>(wave + S::NWA * i, n, y, xx);
+        tb[i] = y * S::PITCH + xx;
     }
 }
 
@@ -417,42 +507,38 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
 // to dst, 2 = store ReLU(v) to the global feature row.  The B fragments of tile
 // i+1 are read from LDS while tile i's MFMAs run.
 template <class S, bool ADD_X, int OUT>
-__device__ __forceinline__ void block_conv(const char* src, char* dst, const char* wslot,
+__device__ __forceinline__ void block_conv(const char* src, char* dst, const char* wslot, const int (&tb)[S::NT],
                                            floatx4 (&x)[S::NT][S::FT], __bf16* __restrict__ feat_row, int lane, int wave)
 {
+    if (wave >= S::NWA) return;                            // uniform per wavefront
     const int g = lane >> 4, n = lane & 15;
+    constexpr bool WHOLE = S::NPIX % 16 == 0;              // no partial last tile
     bf16x8 w[S::WB_FRAGS];
     load_a_frags(w, wslot, lane);
     floatx4 bv[S::FT];
 #pragma unroll
     for (int j = 0; j < S::FT; ++j) bv[j] = *(const floatx4*)(wslot + S::WB_FRAGS * 1024 + (j * 4 + g) * 16);
-    int koff[S::KCB];
-    planar_koff<S::C, S::KCB>(koff, g, S::PLANE, S::PITCH);
-
-    auto tile_base = [&](int i, int& p, int& y, int& xx) {
-        p = (wave + RN_WAVES * i) * 16 + n;
-        const int pc = p < S::NPIX ? p : S::NPIX - 1;
-        y = pc / S::PW; xx = pc % S::PW;
-        return y * S::PITCH + xx;
-    };
-    bf16x8 bcur[S::KCB], bnxt[S::KCB];
-    int p, y, xx;
-    {
-        const int base = tile_base(0, p, y, xx);
+    using K = KMap<S::C>;
+    int lb[K::NBASE];
+    K::lane_bases(lb, g, S::PLANE, S::PITCH);
+    auto load_b = [&](bf16x8 (&b)[S::KCB], int tbase) {
+        const char* pa[K::NBASE];
 #pragma unroll
-        for (int kc = 0; kc < S::KCB; ++kc) bcur[kc] = *(const bf16x8*)(src + (base + koff[kc]) * 16);
-    }
+        for (int q = 0; q < K::NBASE; ++q) pa[q] = src + (tbase + lb[q]) * 16;
+#pragma unroll
+        for (int kc = 0; kc < S::KCB; ++kc) b[kc] = *(const bf16x8*)(pa[K::kbase(kc)] + K::kimm(kc, S::PITCH) * 16);
+    };
+    // destination of this lane's four channels, tile base excluded
+    char* dstl = dst + ((S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8);
+
+    bf16x8 bcur[S::KCB], bnxt[S::KCB];
+    load_b(bcur, tb[0]);
 #pragma unroll
     for (int i = 0; i < S::NT; ++i) {
-        const int t = wave + RN_WAVES * i;
+        const int t = wave + S::NWA * i;
         if (t >= S::NTILES) break;
-        int pn = 0, yn = 0, xn = 0;
-        const bool more = i + 1 < S::NT && t + RN_WAVES < S::NTILES;     // uniform
-        if (more) {
-            const int base = tile_base(i + 1, pn, yn, xn);
-#pragma unroll
-            for (int kc = 0; kc < S::KCB; ++kc) bnxt[kc] = *(const bf16x8*)(src + (base + koff[kc]) * 16);
-        }
+        const bool more = i + 1 < S::NT && t + S::NWA < S::NTILES;     // uniform
+        if (more) load_b(bnxt, tb[i + 1 < S::NT ? i + 1 : i]);
         floatx4 acc[S::FT];
 #pragma unroll
         for (int j = 0; j < S::FT; ++j) acc[j] = ADD_X ? x[i][j] + bv[j] : bv[j];
@@ -460,23 +546,20 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
         for (int kc = 0; kc < S::KCB; ++kc)
 #pragma unroll
             for (int j = 0; j < S::FT; ++j) acc[j] = mfma16(w[j * S::KCB + kc], bcur[kc], acc[j]);
+        const int p = t * 16 + n;
 #pragma unroll
         for (int j = 0; j < S::FT; ++j) {
             if (ADD_X) x[i][j] = acc[j];
-            if (p < S::NPIX) {
-                const floatx4 v = OUT == 1 ? acc[j] : relu4(acc[j]);
-                if (OUT == 2) {
-                    *(bf16x4*)(feat_row + (size_t)p * S::C + j * 16 + g * 4) = to_bf16x4(v);
-                } else {
-                    const int cgo = 2 * j + (g >> 1);
-                    *(bf16x4*)(dst + (cgo * S::PLANE + (y + 1) * S::PITCH + xx + 1) * 16 + (g & 1) * 8) = to_bf16x4(v);
-                }
+            if (WHOLE || p < S::NPIX) {
+                const bf16x4 vb = to_bf16x4(acc[j]);
+                const bf16x4 out = OUT == 1 ? vb : relu_bf16x4(vb);
+                if (OUT == 2) *(bf16x4*)(feat_row + (size_t)p * S::C + j * 16 + g * 4) = out;
+                else *(bf16x4*)(dstl + tb[i] * 16 + j * (2 * S::PLANE * 16)) = out;
             }
         }
         if (more) {
 #pragma unroll
             for (int kc = 0; kc < S::KCB; ++kc) bcur[kc] = bnxt[kc];
-            p = pn; y = yn; xx = xn;
         }
     }
 }
@@ -505,7 +588,8 @@ struct LdsMap {
     static constexpr int BUF0 = 0;
     static constexpr int BUF1 = r256(B0_);
     static constexpr int EDGE = BUF1 + r256(B1_);
-    static constexpr int WSA = EDGE + r256(EDGE_);
+    static constexpr int NEUTRAL = EDGE + EDGE_;                   // 8 bytes of bf16 -inf: 'no edge column'
+    static constexpr int WSA = EDGE + r256(EDGE_ + 16);
     static constexpr int WSB_HI = WSA + WSLOT_BYTES;
     static constexpr int PERM = LDS_TOTAL - r256(PERM_);           // first layer's weights, resident for the whole kernel
     static constexpr int WSB_HI_CAP = PERM - WSB_HI;
@@ -575,54 +659,52 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     }
 
     // ---------------- x <- pooled map (+ edge columns); R = ReLU(x) ----------------
+    int tb[S::NT];
+    tile_table<S>(tb, lane, wave);
     {
         WStage<S::WB_SET> st;
         wstage_issue(st, sw.wb[1], tid);
         zero_halo<S::C / 8, S::PH, S::PW>(buf0, tid);
+        if (wave < S::NWA) {
+            constexpr bool WHOLE = S::NPIX % 16 == 0;
+            const int loff = (S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
 #pragma unroll
-        for (int i = 0; i < S::NT; ++i) {
-            const int t = wave + RN_WAVES * i;
-            if (t >= S::NTILES) break;
-            const int p = t * 16 + n;
-            const bool ok = p < S::NPIX;
-            const int pc = ok ? p : S::NPIX - 1;
-            const int y = pc / S::PW, xx = pc % S::PW;
-            // the pooled value of a strip's last column lacks its right neighbour: it is the next strip's edge column
-            const bool fix = (xx & 7) == 7 && xx + 1 < S::PW;
-            const int cs = fix ? (xx + 1) >> 3 : 0;
-            const int off = ((y + 1) * S::PITCH + xx + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
-            const int eoff = ((cs * S::PH + y) * S::C + g * 4) * 2;
-            bf16x4 pv[S::FT], ev[S::FT];
+            for (int i = 0; i < S::NT; ++i) {
+                const int t = wave + S::NWA * i;
+                if (t >= S::NTILES) break;
+                const int p = t * 16 + n;
+                int y, xx;
+                tile_pixel<S>(t, n, y, xx);
+                // the pooled value of a strip's last column lacks its right neighbour: it is the next strip's edge
+                // column; every other lane reads the neutral (-inf) cell instead
+                const bool fix = (xx & 7) == 7 && xx + 1 < S::PW;
+                const int eoff = fix ? M::EDGE + (((((xx + 1) >> 3) * S::PH + y) * S::C + g * 4) * 2) : M::NEUTRAL;
+                const int off = tb[i] * 16 + loff;
 #pragma unroll
-            for (int j = 0; j < S::FT; ++j) {
-                pv[j] = *(const bf16x4*)(buf1 + off + j * (2 * S::PLANE * 16));
-                ev[j] = *(const bf16x4*)(edge + eoff + j * 32);
-            }
-#pragma unroll
-            for (int j = 0; j < S::FT; ++j) {
-                floatx4 v = to_floatx4(pv[j]);
-                const floatx4 e = to_floatx4(ev[j]);
-                if (fix) v = max4(v, e);
-                if (!ok) v = floatx4{0.f, 0.f, 0.f, 0.f};
-                x[i][j] = v;
-                if (ok) *(bf16x4*)(buf0 + off + j * (2 * S::PLANE * 16)) = to_bf16x4(relu4(v));
+                for (int j = 0; j < S::FT; ++j) {
+                    const bf16x4 pv = *(const bf16x4*)(buf1 + off + j * (2 * S::PLANE * 16));
+                    const bf16x4 ev = *(const bf16x4*)(lds + eoff + (fix ? j * 32 : 0));
+                    const floatx4 v = max4(to_floatx4(pv), to_floatx4(ev));
+                    x[i][j] = v;
+                    if (WHOLE || p < S::NPIX) *(bf16x4*)(buf0 + off + j * (2 * S::PLANE * 16)) = relu_bf16x4(to_bf16x4(v));
+                }
             }
         }
         lds_barrier();
         PHASE_MARK(SI * 8 + 3);
 
         // ---------------- residual blocks ----------------
-        block_conv<S, false, 0>(buf0, buf1, lds + SL::B0, x, nullptr, lane, wave);
+        block_conv<S, false, 0>(buf0, buf1, lds + SL::B0, tb, x, nullptr, lane, wave);
         wstage_commit(st, lds + SL::B1, tid);
         lds_barrier();
         PHASE_MARK(SI * 8 + 4);
         wstage_issue(st, sw.wb[2], tid);
-        block_conv<S, true, 0>(buf1, buf0, lds + SL::B1, x, nullptr, lane, wave);
+        block_conv<S, true, 0>(buf1, buf0, lds + SL::B1, tb, x, nullptr, lane, wave);
         wstage_commit(st, lds + SL::B2, tid);
         lds_barrier();
         PHASE_MARK(SI * 8 + 5);
         wstage_issue(st, sw.wb[3], tid);
-        block_conv<S, false, 0>(buf0, buf1, lds + SL::B2, x, nullptr, lane, wave);
+        block_conv<S, false, 0>(buf0, buf1, lds + SL::B2, tb, x, nullptr, lane, wave);
         wstage_commit(st, lds + SL::B3, tid);
         lds_barrier();
         PHASE_MARK(SI * 8 + 6);
@@ -630,7 +712,7 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     {
         WStage<(SL::NEXT_SET > 0 ? SL::NEXT_SET : 1)> st;
         if constexpr (SL::NEXT_SET > 0) wstage_issue(st, next_src, tid);
-        block_conv<S, true, LAST ? 2 : 1>(buf1, buf0, lds + SL::B3, x, feat_row, lane, wave);
+        block_conv<S, true, LAST ? 2 : 1>(buf1, buf0, lds + SL::B3, tb, x, feat_row, lane, wave);
         if constexpr (SL::NEXT_SET > 0) wstage_commit(st, lds + SL::NEXT, tid);
         lds_barrier();
         PHASE_MARK(SI * 8 + 7);
@@ -676,6 +758,11 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
     const int tid = threadIdx.x;
     constexpr size_t FRAME = (size_t)S1::H * S1::W * S1::CIN;
     if ((int)blockIdx.x >= a.B) return;
+    if (tid == 0) {   // the neutral edge cell
+        bf16x4 ninf;
+        ninf[0] = ninf[1] = ninf[2] = ninf[3] = (__bf16)(-INFINITY);
+        *(bf16x4*)(lds + M::NEUTRAL) = ninf;
+    }
     {   // the resident first-layer weight set
         WStage<S1::W0_SET> s0;
         wstage_issue(s0, a.sec[0].w0, tid);
@@ -719,6 +806,11 @@ __global__ __launch_bounds__(RN_THREADS) void resnet4_bf16_kernel(TorsoArgs a)
     const int tid = threadIdx.x;
     constexpr size_t FRAME = (size_t)S1::H * S1::W * S1::CIN;
     if ((int)blockIdx.x >= a.B) return;
+    if (tid == 0) {   // the neutral edge cell
+        bf16x4 ninf;
+        ninf[0] = ninf[1] = ninf[2] = ninf[3] = (__bf16)(-INFINITY);
+        *(bf16x4*)(lds + M::NEUTRAL) = ninf;
+    }
     {
         WStage<S1::W0_SET> s0;
         wstage_issue(s0, a.sec[0].w0, tid);

@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("SEEDINF_LIB", os.path.join(_PKG, "libseedinf.so"))
 SOURCES = [os.path.join(_PKG, "csrc", f) for f in
            ("seedinf.hip", "plan.h", "kernels_fp32.h", "kernels_heads.h", "bf16_path.h", "bf16_common.h", "gemm_bf16.h", "conv_stack_bf16.h", "resnet_fused.h")]
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fno-honor-nans"]
 
 STATUS = {0: "SEED_OK", 1: "SEED_ERR_INVALID_ARG", 2: "SEED_ERR_UNSUPPORTED_ARCH", 3: "SEED_ERR_BATCH_TOO_LARGE",
           4: "SEED_ERR_ALIASING", 5: "SEED_ERR_DEVICE", 6: "SEED_ERR_OOM"}

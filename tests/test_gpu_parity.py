@@ -145,3 +145,89 @@ def test_bf16_small_ragged(orc, name, B):
     """bf16 matrix-core path, small ragged batches (fewer rows than one MFMA
     row tile; several images per persistent workgroup are covered below)."""
     run_case(orc, wl.CONFIGS[name], B, "bf16")
+
+
+def _rows(batch, idx):
+    return {k: (None if v is None else v[idx]) for k, v in batch.items()}
+
+
+def run_full(orc, cfg, B, sample=None):
+    """GPU on the full batch (the launch configuration bench.py times); oracle on all rows, or on a seeded
+    sample of rows when B is large (rows are independent, so a row's oracle value does not depend on B)."""
+    import torch
+    weights = wl.make_weights(cfg)
+    batch = wl.make_batch(cfg, B)
+    print(f"full-size {cfg['label']} B={B} sample={sample}", flush=True)
+    net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=B), weights)
+    out = net.step(**to_device(batch))
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    idx = np.arange(B) if sample is None else np.sort(np.random.default_rng(B).choice(B, sample, replace=False))
+    sub = _rows(batch, idx)
+    ref = orc.forward(oracle.make_arch(cfg), weights, sub["obs"], **{k: sub[k] for k in CORE_KEYS})
+    rep = check_against_oracle({k: v[idx] for k, v in got.items()}, ref, TOL[cfg["precision"]], sub["uniforms"])
+    print("   ", rep, flush=True)
+    # properties that hold at any size: every action in range, probabilities normalised, finite state
+    A = cfg["num_actions"]
+    assert ((got["action"] >= 0) & (got["action"] < A)).all()
+    assert np.abs(got["probs"].sum(1) - 1).max() < 1e-5
+    for k in ("logits", "value", "h", "c"):
+        if k in got:
+            assert np.isfinite(got[k]).all(), k
+    net.close()
+    return rep
+
+
+def test_full_size_c2(orc):
+    run_full(orc, wl.CONFIGS["C2"], 256)
+
+
+def test_full_size_c3(orc):
+    run_full(orc, wl.CONFIGS["C3"], 1024)
+
+
+def test_full_size_c4(orc):
+    run_full(orc, wl.CONFIGS["C4"], 2048, sample=512)
+
+
+@pytest.mark.parametrize("B,sample", [(64, None), (256, None), (4096, 256), (8192, 256)])
+def test_full_size_c5_sweep(orc, B, sample):
+    run_full(orc, wl.CONFIGS["C5"], B, sample)
+
+
+@pytest.mark.parametrize("B", [1, 257, 300])
+def test_bf16_persistent_grid_edges(orc, B):
+    """B = 1; one more image than there are compute units (one workgroup takes two); a ragged count."""
+    run_full(orc, wl.CONFIGS["C3"], B, sample=None if B == 1 else 64)
+
+
+def test_bf16_repeatable(orc):
+    import torch
+    cfg = wl.CONFIGS["C3"]
+    net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=300), wl.make_weights(cfg))
+    dev = to_device(wl.make_batch(cfg, 300))
+    o1 = {k: v.clone() for k, v in net.step(**dev).items()}
+    o2 = net.step(**dev)
+    torch.cuda.synchronize()
+    for k in o1:
+        assert torch.equal(o1[k], o2[k]), k
+    net.close()
+
+
+def test_bf16_head_and_core_variants(orc):
+    """Combinations the five configurations do not cover: conv stack without a core and with policy heads,
+    ResNet with dueling heads and greedy selection, Football torso with an LSTM core."""
+    a = dict(wl.CONFIGS["C2"], label="R2D2 torso, no core, policy heads", lstm_units=0, head=0, head_hidden=0,
+             select=1, index=21)
+    run_case(orc, a, 9, "bf16")
+    b = dict(wl.CONFIGS["C3"], label="DMLab torso, dueling greedy", head=1, head_hidden=64, select=0, index=22)
+    run_case(orc, b, 6, "bf16")
+    c = dict(wl.CONFIGS["C4"], label="Football torso + LSTM-128", lstm_units=128, index=23)
+    run_case(orc, c, 4, "bf16")
+
+
+def test_bf16_unsupported_arch_is_reported():
+    cfg = dict(wl.CONFIGS["C3"], sections=[16, 32, 64])
+    with pytest.raises(seedinf.SeedError) as e:
+        seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=2, precision="bf16"), wl.make_weights(cfg))
+    assert e.value.status == 2 and "fp32" in e.value.message
