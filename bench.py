@@ -121,6 +121,9 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the batch sweep and the other configs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=512)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference kernel for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU; --gpus must be 1 (the step shards by batch rows "
@@ -136,6 +139,13 @@ def main():
         import __graft_entry__
         __graft_entry__.build()
 
+    if args.copy_calibration:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     cfg = wl.CONFIGS["C5"]
     B = args.batch
     weights = wl.make_weights(cfg)
