@@ -33,6 +33,8 @@
 // K = 3 rows x (2 fragments of 2 pixels x 4 channels) = 48, two MFMAs per tile.
 // uint8 inputs enter as exact bf16 integers; 1/255 scales the accumulator.
 #pragma once
+#include <type_traits>
+
 #include "bf16_common.h"
 
 namespace seedinf {
@@ -101,9 +103,11 @@ struct SecCfg {
     static constexpr int IROWS = INKIND == IN_LDS ? H + 2 : (2 * SR + 1 < H ? 2 * SR + 1 : H) + 2;
     static constexpr int IPITCH = W + 2;
     static constexpr int ICELL = INKIND == IN_U8_C3 ? 8 : 16;
-    static constexpr int IPLANE = IROWS * IPITCH;
+    // plane strides are multiples of 16 cells (256 B): a ds_read_b128 whose two lane groups of a half-wave sit
+    // a non-multiple of 256 B (and more than 64 B) apart runs at about 60 % rate on this LDS
+    static constexpr int IPLANE = (IROWS * IPITCH + 15) / 16 * 16;
     static constexpr int IN_BYTES = (INKIND == IN_U8_C3 ? 1 : CIN / 8) * IPLANE * ICELL + 16;
-    static constexpr int PITCH = PW + 2, PLANE = (PH + 2) * PITCH;
+    static constexpr int PITCH = PW + 2, PLANE = ((PH + 2) * PITCH + 15) / 16 * 16;
     static constexpr int ACT_BYTES = (C / 8) * PLANE * 16;
     static constexpr int EDGE_BYTES = NCS * PH * C * 2;
     // prefetch registers for the uint8 input: items of PRE_DW dwords, PRE_N per thread
@@ -138,6 +142,33 @@ struct WStage {
     static constexpr int N = (NF * 64 + RN_THREADS - 1) / RN_THREADS;
     bf16x8 r[N];
 };
+constexpr int WSET_MAX = WSLOT_BYTES / 1024;      // chunks in the largest weight set
+// Two sets are in flight at any time: set q travels in pipe.s[q % 2] from the start of the phase that uses
+// set q-2 to the end of the phase that uses set q-1, so a layer's weights have more than a whole phase to
+// arrive from L2 before they are written to their LDS slot.
+struct WPipe {
+    WStage<WSET_MAX> s[2];
+};
+template <int NF>
+__device__ __forceinline__ void wpipe_issue(WStage<WSET_MAX>& st, const bf16x8* __restrict__ src, int tid)
+{
+    // every thread loads (out-of-range ones re-read the last chunk): loads issued under a branch would force
+    // the later commit to wait for ALL outstanding loads instead of just its own
+#pragma unroll
+    for (int j = 0; j < (NF * 64 + RN_THREADS - 1) / RN_THREADS; ++j) {
+        const int i = tid + j * RN_THREADS;
+        st.r[j] = src[i < NF * 64 ? i : NF * 64 - 1];
+    }
+}
+template <int NF>
+__device__ __forceinline__ void wpipe_commit(const WStage<WSET_MAX>& st, char* slot, int tid)
+{
+#pragma unroll
+    for (int j = 0; j < (NF * 64 + RN_THREADS - 1) / RN_THREADS; ++j) {
+        const int i = tid + j * RN_THREADS;
+        if (i < NF * 64) *(bf16x8*)(slot + i * 16) = st.r[j];
+    }
+}
 
 template <int NF>
 __device__ __forceinline__ void wstage_issue(WStage<NF>& s, const bf16x8* __restrict__ src, int tid)
@@ -232,12 +263,10 @@ __device__ __forceinline__ void prefetch_issue(Prefetch<S>& p, const uint8_t* __
             constexpr int GPR = S::W / 4;
             const int nitems = (r1 - r0 + 1) * GPR;            // real rows only (whole frame: r0 = 0, r1 = H-1)
 #pragma unroll
-            for (int j = 0; j < S::PRE_N; ++j) {
-                const int i = tid + j * RN_THREADS;
-                if (i < nitems) {
-                    const uint32_t* s = (const uint32_t*)(obs_img + (size_t)(r0 + i / GPR) * S::W * 3) + (i % GPR) * 3;
-                    p.d[j][0] = s[0]; p.d[j][1] = s[1]; p.d[j][2] = s[2];
-                }
+            for (int j = 0; j < S::PRE_N; ++j) {             // unconditional (clamped) loads, see wpipe_issue
+                const int i = min(tid + j * RN_THREADS, nitems - 1);
+                const uint32_t* s = (const uint32_t*)(obs_img + (size_t)(r0 + i / GPR) * S::W * 3) + (i % GPR) * 3;
+                p.d[j][0] = s[0]; p.d[j][1] = s[1]; p.d[j][2] = s[2];
             }
         } else {
             const int nin = r1 - r0 + 3;
@@ -246,12 +275,10 @@ __device__ __forceinline__ void prefetch_issue(Prefetch<S>& p, const uint8_t* __
                 const int i = tid + j * RN_THREADS;
                 const int ry = i / S::W, px = i % S::W;
                 const int iy = r0 - 1 + ry;
-#pragma unroll
-                for (int q = 0; q < S::PRE_DW; ++q) p.d[j][q] = 0u;
-                if (ry < nin && iy >= 0 && iy < S::H) {
-                    const uint4 v = *(const uint4*)(obs_img + ((size_t)iy * S::W + px) * S::CIN);
-                    p.d[j][0] = v.x; p.d[j][1] = v.y; p.d[j][2] = v.z; p.d[j][3] = v.w;
-                }
+                const bool inside = ry < nin && iy >= 0 && iy < S::H;
+                const uint4 v = *(const uint4*)(obs_img + ((size_t)(inside ? iy : 0) * S::W + px) * S::CIN);
+                p.d[j][0] = inside ? v.x : 0u; p.d[j][1] = inside ? v.y : 0u;
+                p.d[j][2] = inside ? v.z : 0u; p.d[j][3] = inside ? v.w : 0u;
             }
         }
     }
@@ -375,7 +402,7 @@ __device__ __forceinline__ void conv0_mma(floatx4 (&acc)[S::FT], const bf16x8 (&
 // each strip's first-column vertical maxima into `edge`.  `wslot`: conv0's staged weight set.
 // The two conv rows of pooled row py+1 are read from LDS while those of row py are multiplied.
 template <class S>
-__device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edge, const bf16x8 (&w0)[S::W0_FRAGS],
+__device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edge, char* trash, const bf16x8 (&w0)[S::W0_FRAGS],
                                            const char* wslot, int pr0, int pr1, int rbuf0, int lane, int wave)
 {
     const int g = lane >> 4, n = lane & 15;
@@ -423,12 +450,16 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
 #pragma unroll
             for (int j = 0; j < S::FT; ++j) top[j] = NEG;
         }
-        // output addresses of this unit's first pooled row; they advance by one row per pooled row
+        // Output addresses of this unit's first pooled row; they advance by one row per pooled row.  Lanes with
+        // nothing to store (odd columns; all but column 0 for the edge) store into a per-lane trash cell, which
+        // keeps the loop body free of branches.
         const int px = col >> 1;
-        int xoff = ((pb0 + 1) * S::PITCH + px + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
-        int eoff = ((cs * S::PH + pb0) * S::C + g * 4) * 2;
         const bool wr_edge = n == 0 && cs > 0;
         const bool wr_pool = live && !(n & 1);
+        char* xptr = wr_pool ? xout + ((pb0 + 1) * S::PITCH + px + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8 : trash + lane * 8;
+        char* eptr = wr_edge ? edge + ((cs * S::PH + pb0) * S::C + g * 4) * 2 : trash + lane * 8;
+        const int xstep = wr_pool ? S::PITCH * 16 : 0, estep = wr_edge ? S::C * 2 : 0;
+        const int xj = wr_pool ? 2 * S::PLANE * 16 : 0, ej = wr_edge ? 32 : 0;
 
         // rows of pooled row py: mid = 2 py - PADH + 1 (always inside the image), bot = mid + 1 (may not exist)
         auto load_pair = [&](bf16x8 (&a)[S::KC0], bf16x8 (&c)[S::KC0], int py) {
@@ -444,31 +475,29 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
             for (int j = 0; j < S::FT; ++j) {
                 floatx4 v = max4(max4(top[j], mid[j]), bot[j]) * SCALE + bv[j];
                 if (!FULL && !live) v = NEG;
-                if (wr_edge) *(bf16x4*)(edge + eoff + j * 32) = to_bf16x4(v);
+                *(bf16x4*)(eptr + j * ej) = to_bf16x4(v);
                 const floatx4 h = hmax3_row16(v);
-                if (wr_pool) *(bf16x4*)(xout + xoff + j * (2 * S::PLANE * 16)) = to_bf16x4(h);
+                *(bf16x4*)(xptr + j * xj) = to_bf16x4(h);
                 top[j] = bot[j];
             }
-            xoff += S::PITCH * 16;
-            eoff += S::C * 2;
+            xptr += xstep;
+            eptr += estep;
         };
+        int py = pb0;
         if constexpr (PIPE) {
-            load_pair(fa, fb, pb0);
+            // two pooled rows per iteration, all eight fragment loads first, no branches inside
 #pragma unroll 1
-            for (int py = pb0; py < pb1; py += 2) {
-                if (py + 1 < pb1) load_pair(ga, gb, py + 1);
-                finish_row(fa, fb);
-                if (py + 1 < pb1) {
-                    if (py + 2 < pb1) load_pair(fa, fb, py + 2);
-                    finish_row(ga, gb);
-                }
-            }
-        } else {
-#pragma unroll 1
-            for (int py = pb0; py < pb1; ++py) {
+            for (; py + 1 < pb1; py += 2) {
                 load_pair(fa, fb, py);
+                load_pair(ga, gb, py + 1);
                 finish_row(fa, fb);
+                finish_row(ga, gb);
             }
+        }
+#pragma unroll 1
+        for (; py < pb1; ++py) {
+            load_pair(fa, fb, py);
+            finish_row(fa, fb);
         }
     }
 }
@@ -531,14 +560,18 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
     // destination of this lane's four channels, tile base excluded
     char* dstl = dst + ((S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8);
 
-    bf16x8 bcur[S::KCB], bnxt[S::KCB];
+    // double-buffer the B fragments only where the registers allow it (the 16-channel section)
+    constexpr bool DBUF = S::KCB <= 5;
+    bf16x8 bcur[S::KCB], bnxt[DBUF ? S::KCB : 1];
     load_b(bcur, tb[0]);
 #pragma unroll
     for (int i = 0; i < S::NT; ++i) {
         const int t = wave + S::NWA * i;
         if (t >= S::NTILES) break;
         const bool more = i + 1 < S::NT && t + S::NWA < S::NTILES;     // uniform
-        if (more) load_b(bnxt, tb[i + 1 < S::NT ? i + 1 : i]);
+        if constexpr (DBUF) {
+            if (more) load_b(bnxt, tb[i + 1 < S::NT ? i + 1 : i]);
+        }
         floatx4 acc[S::FT];
 #pragma unroll
         for (int j = 0; j < S::FT; ++j) acc[j] = ADD_X ? x[i][j] + bv[j] : bv[j];
@@ -558,14 +591,18 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
             }
         }
         if (more) {
+            if constexpr (DBUF) {
 #pragma unroll
-            for (int kc = 0; kc < S::KCB; ++kc) bcur[kc] = bnxt[kc];
+                for (int kc = 0; kc < S::KCB; ++kc) bcur[kc] = bnxt[kc];
+            } else {
+                load_b(bcur, tb[i + 1 < S::NT ? i + 1 : i]);
+            }
         }
     }
 }
 
-// zero the halo ring of a planar map of CG planes, interior IH x IW
-template <int CG, int IH, int IW>
+// zero the halo ring of a planar map of CG planes (PLANE cells apart), interior IH x IW
+template <int CG, int IH, int IW, int PLANE>
 __device__ __forceinline__ void zero_halo(char* buf, int tid)
 {
     constexpr int PITCH = IW + 2, ROWS = IH + 2;
@@ -577,7 +614,7 @@ __device__ __forceinline__ void zero_halo(char* buf, int tid)
         if (r < PITCH) { y = 0; xx = r; }
         else if (r < 2 * PITCH) { y = ROWS - 1; xx = r - PITCH; }
         else { const int q = r - 2 * PITCH; y = 1 + (q >> 1); xx = (q & 1) ? PITCH - 1 : 0; }
-        *(bf16x8*)(buf + ((cg * ROWS + y) * PITCH + xx) * 16) = z;
+        *(bf16x8*)(buf + (cg * PLANE + y * PITCH + xx) * 16) = z;
     }
 }
 
@@ -589,7 +626,8 @@ struct LdsMap {
     static constexpr int BUF1 = r256(B0_);
     static constexpr int EDGE = BUF1 + r256(B1_);
     static constexpr int NEUTRAL = EDGE + EDGE_;                   // 8 bytes of bf16 -inf: 'no edge column'
-    static constexpr int WSA = EDGE + r256(EDGE_ + 16);
+    static constexpr int TRASH = EDGE + r256(EDGE_ + 16);         // 512 B: where lanes with nothing to store write
+    static constexpr int WSA = TRASH + 512;
     static constexpr int WSB_HI = WSA + WSLOT_BYTES;
     static constexpr int PERM = LDS_TOTAL - r256(PERM_);           // first layer's weights, resident for the whole kernel
     static constexpr int WSB_HI_CAP = PERM - WSB_HI;
@@ -598,20 +636,24 @@ struct LdsMap {
     static_assert(WSB_LO + WSLOT_BYTES <= EDGE, "low weight slot must fit in buf1's tail");
 };
 
-// Where one section finds its five layers' weight sets in LDS and what it stages for the next section.
-//   C0, B0..B3: byte offsets of the conv0 / block-layer slots.  STAGE_B0: conv0's phase stages B0.
-//   NEXT / NEXT_SET: slot and size (KiB chunks) of the set staged during the last block (0: nothing).
-template <int C0_, int B0_, int B1_, int B2_, int B3_, int NEXT_, int NEXT_SET_, bool STAGE_B0_>
-struct Slots {
-    static constexpr int C0 = C0_, B0 = B0_, B1 = B1_, B2 = B2_, B3 = B3_, NEXT = NEXT_, NEXT_SET = NEXT_SET_;
-    static constexpr bool STAGE_B0 = STAGE_B0_;
-};
+// Weight sets are numbered along one image: S1.block1.a = 0 ... (the first layer's set is resident).  Set q
+// lives in slot A when q is even, else in slot B; B is the high slot while the consuming section keeps buf1
+// full (section 1) and the low slot inside buf1's unused tail otherwise.
+template <class M, class S>
+constexpr int wslot(int q)
+{
+    return (q & 1) == 0 ? M::WSA : (S::ACT_BYTES > 36 * 1024 ? M::WSB_HI : M::WSB_LO);
+}
 
-// One section for one image.  On entry (INKIND == IN_LDS) buf0 holds the previous section's un-rectified
-// output as a planar map with halo; on exit (not LAST) buf0 holds this section's.  LAST writes ReLU(x) to
-// feat_row.  next_src: global address of the weight set SL::NEXT receives.
-template <class S, class M, class SL, bool LAST, int SI, class PreT>
-__device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, const bf16x8* __restrict__ next_src,
+// One section for one image.
+//   J0: number of this section's conv0 weight set (-1: the resident first-layer set); its blocks use J0+1..J0+4.
+//   SN / nsw: the next section (its conv0 and first block are staged from here); NSETS: sets per image.
+//   Staging rule: the phase that uses set j issues the loads of set j+2 when it starts and commits set j+1 to
+//   LDS when it ends; section 1's conv0 phase issues sets 0 and 1 and commits set 0.
+// On entry (INKIND == IN_LDS) buf0 holds the previous section's un-rectified output as a planar map with
+// halo; on exit (not LAST) buf0 holds this section's.  LAST writes ReLU(x) to feat_row.
+template <class S, class SN, class M, bool LAST, int SI, int J0, int NSETS, class PreT>
+__device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, const SecWeights& nsw, WPipe& pipe,
                                             const uint8_t* __restrict__ obs_img, PreT& pre,
                                             __bf16* __restrict__ feat_row, int tid)
 {
@@ -623,22 +665,44 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     char* buf0 = lds + M::BUF0;
     char* buf1 = lds + M::BUF1;
     char* edge = lds + M::EDGE;
-    static_assert(S::ACT_BYTES <= 36 * 1024 || (SL::C0 != M::WSB_LO && SL::B0 != M::WSB_LO && SL::B1 != M::WSB_LO &&
-                                                 SL::B2 != M::WSB_LO && SL::B3 != M::WSB_LO),
-                  "low weight slot used while buf1 is fully occupied");
+    constexpr int QB = J0 + 1;                                   // set number of block1.a
+    constexpr int SLOT_C0 = J0 < 0 ? M::PERM : wslot<M, S>(J0);
+    static_assert(S::ACT_BYTES <= 36 * 1024 || S::WB_SET * 1024 <= M::WSB_HI_CAP, "block weights do not fit the high slot");
     static_assert(S::WB_SET * 1024 <= WSLOT_BYTES && S::W0_SET * 1024 <= WSLOT_BYTES, "weight set larger than a slot");
+    static_assert(LAST || (QB + 4) % 2 == 0 || SN::ACT_BYTES <= 36 * 1024 || SN::W0_SET * 1024 <= M::WSB_HI_CAP, "next conv0 set does not fit");
+    // set q (relative to this section: 0 = block1.a ... 3 = block2.b, 4 = next conv0, 5 = next block1.a)
+    auto issue = [&](auto rel) {
+        constexpr int r = decltype(rel)::value;
+        constexpr int q = QB + r;
+        if constexpr (q < NSETS) {
+            if constexpr (r < 4) wpipe_issue<S::WB_SET>(pipe.s[q & 1], sw.wb[r], tid);
+            else if constexpr (r == 4) wpipe_issue<SN::W0_SET>(pipe.s[q & 1], nsw.w0, tid);
+            else wpipe_issue<SN::WB_SET>(pipe.s[q & 1], nsw.wb[0], tid);
+        }
+    };
+    auto commit = [&](auto rel) {
+        constexpr int r = decltype(rel)::value;
+        constexpr int q = QB + r;
+        if constexpr (q < NSETS) {
+            if constexpr (r < 4) wpipe_commit<S::WB_SET>(pipe.s[q & 1], lds + wslot<M, S>(q), tid);
+            else wpipe_commit<SN::W0_SET>(pipe.s[q & 1], lds + wslot<M, SN>(q), tid);
+        }
+    };
+    using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
+    using I4 = std::integral_constant<int, 4>; using I5 = std::integral_constant<int, 5>;
     floatx4 x[S::NT][S::FT];
     PHASE_DECL;
 
     // ---------------- conv0 + max-pool ----------------
     {
-        WStage<S::WB_SET> st;
-        if constexpr (SL::STAGE_B0) wstage_issue(st, sw.wb[0], tid);
-        zero_halo<S::C / 8, S::PH, S::PW>(buf1, tid);
+        if constexpr (J0 < 0) { issue(I0{}); issue(I1{}); }      // image start: nothing is in flight yet
+        else issue(I1{});                                        // this phase uses set J0: issue J0 + 2
+        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf1, tid);
         bf16x8 w0[S::W0_FRAGS];
         if constexpr (S::INKIND == IN_LDS) {
-            load_a_frags(w0, lds + SL::C0, lane);
-            conv0_pool<S>(buf0, buf1, edge, w0, lds + SL::C0, 0, S::PH, -1, lane, wave);
+            load_a_frags(w0, lds + SLOT_C0, lane);
+            conv0_pool<S>(buf0, buf1, edge, lds + M::TRASH, w0, lds + SLOT_C0, 0, S::PH, -1, lane, wave);
         } else {
 #pragma unroll 1
             for (int strip = 0; strip < S::NSTRIPS; ++strip) {
@@ -646,14 +710,14 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                 if (strip + 1 < S::NSTRIPS) prefetch_issue<S>(pre, obs_img, strip + 1, tid);
                 lds_barrier();
                 PHASE_MARK(SI * 8 + 0);
-                if (strip == 0) load_a_frags(w0, lds + SL::C0, lane);
+                if (strip == 0) load_a_frags(w0, lds + SLOT_C0, lane);
                 int pr0, pr1, r0, r1;
                 strip_rows<S>(strip, pr0, pr1, r0, r1);
-                conv0_pool<S>(buf0, buf1, edge, w0, lds + SL::C0, pr0, pr1, r0 - 1, lane, wave);
+                conv0_pool<S>(buf0, buf1, edge, lds + M::TRASH, w0, lds + SLOT_C0, pr0, pr1, r0 - 1, lane, wave);
                 if (strip + 1 < S::NSTRIPS) lds_barrier();
             }
         }
-        if constexpr (SL::STAGE_B0) wstage_commit(st, lds + SL::B0, tid);
+        commit(I0{});
         lds_barrier();
         PHASE_MARK(SI * 8 + 1);
     }
@@ -662,29 +726,38 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     int tb[S::NT];
     tile_table<S>(tb, lane, wave);
     {
-        WStage<S::WB_SET> st;
-        wstage_issue(st, sw.wb[1], tid);
-        zero_halo<S::C / 8, S::PH, S::PW>(buf0, tid);
+        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf0, tid);
         if (wave < S::NWA) {
             constexpr bool WHOLE = S::NPIX % 16 == 0;
             const int loff = (S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
+            bf16x4 pv[S::NT][S::FT], ev[S::NT][S::FT];
 #pragma unroll
-            for (int i = 0; i < S::NT; ++i) {
+            for (int i = 0; i < S::NT; ++i) {          // all loads first
                 const int t = wave + S::NWA * i;
                 if (t >= S::NTILES) break;
-                const int p = t * 16 + n;
                 int y, xx;
                 tile_pixel<S>(t, n, y, xx);
                 // the pooled value of a strip's last column lacks its right neighbour: it is the next strip's edge
                 // column; every other lane reads the neutral (-inf) cell instead
                 const bool fix = (xx & 7) == 7 && xx + 1 < S::PW;
                 const int eoff = fix ? M::EDGE + (((((xx + 1) >> 3) * S::PH + y) * S::C + g * 4) * 2) : M::NEUTRAL;
+                const int ejmp = fix ? 32 : 0;
                 const int off = tb[i] * 16 + loff;
 #pragma unroll
                 for (int j = 0; j < S::FT; ++j) {
-                    const bf16x4 pv = *(const bf16x4*)(buf1 + off + j * (2 * S::PLANE * 16));
-                    const bf16x4 ev = *(const bf16x4*)(lds + eoff + (fix ? j * 32 : 0));
-                    const floatx4 v = max4(to_floatx4(pv), to_floatx4(ev));
+                    pv[i][j] = *(const bf16x4*)(buf1 + off + j * (2 * S::PLANE * 16));
+                    ev[i][j] = *(const bf16x4*)(lds + eoff + j * ejmp);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < S::NT; ++i) {
+                const int t = wave + S::NWA * i;
+                if (t >= S::NTILES) break;
+                const int p = t * 16 + n;
+                const int off = tb[i] * 16 + loff;
+#pragma unroll
+                for (int j = 0; j < S::FT; ++j) {
+                    const floatx4 v = max4(to_floatx4(pv[i][j]), to_floatx4(ev[i][j]));
                     x[i][j] = v;
                     if (WHOLE || p < S::NPIX) *(bf16x4*)(buf0 + off + j * (2 * S::PLANE * 16)) = relu_bf16x4(to_bf16x4(v));
                 }
@@ -692,49 +765,30 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
         }
         lds_barrier();
         PHASE_MARK(SI * 8 + 3);
+    }
 
-        // ---------------- residual blocks ----------------
-        block_conv<S, false, 0>(buf0, buf1, lds + SL::B0, tb, x, nullptr, lane, wave);
-        wstage_commit(st, lds + SL::B1, tid);
-        lds_barrier();
-        PHASE_MARK(SI * 8 + 4);
-        wstage_issue(st, sw.wb[2], tid);
-        block_conv<S, true, 0>(buf1, buf0, lds + SL::B1, tb, x, nullptr, lane, wave);
-        wstage_commit(st, lds + SL::B2, tid);
-        lds_barrier();
-        PHASE_MARK(SI * 8 + 5);
-        wstage_issue(st, sw.wb[3], tid);
-        block_conv<S, false, 0>(buf0, buf1, lds + SL::B2, tb, x, nullptr, lane, wave);
-        wstage_commit(st, lds + SL::B3, tid);
-        lds_barrier();
-        PHASE_MARK(SI * 8 + 6);
-    }
-    {
-        WStage<(SL::NEXT_SET > 0 ? SL::NEXT_SET : 1)> st;
-        if constexpr (SL::NEXT_SET > 0) wstage_issue(st, next_src, tid);
-        block_conv<S, true, LAST ? 2 : 1>(buf1, buf0, lds + SL::B3, tb, x, feat_row, lane, wave);
-        if constexpr (SL::NEXT_SET > 0) wstage_commit(st, lds + SL::NEXT, tid);
-        lds_barrier();
-        PHASE_MARK(SI * 8 + 7);
-    }
+    // ---------------- residual blocks ----------------
+    issue(I2{});
+    block_conv<S, false, 0>(buf0, buf1, lds + wslot<M, S>(QB), tb, x, nullptr, lane, wave);
+    commit(I1{});
+    lds_barrier();
+    PHASE_MARK(SI * 8 + 4);
+    issue(I3{});
+    block_conv<S, true, 0>(buf1, buf0, lds + wslot<M, S>(QB + 1), tb, x, nullptr, lane, wave);
+    commit(I2{});
+    lds_barrier();
+    PHASE_MARK(SI * 8 + 5);
+    if constexpr (!LAST) issue(I4{});
+    block_conv<S, false, 0>(buf0, buf1, lds + wslot<M, S>(QB + 2), tb, x, nullptr, lane, wave);
+    commit(I3{});
+    lds_barrier();
+    PHASE_MARK(SI * 8 + 6);
+    if constexpr (!LAST) issue(I5{});
+    block_conv<S, true, LAST ? 2 : 1>(buf1, buf0, lds + wslot<M, S>(QB + 3), tb, x, feat_row, lane, wave);
+    if constexpr (!LAST) commit(I4{});
+    lds_barrier();
+    PHASE_MARK(SI * 8 + 7);
 }
-
-// Slot plan shared by both networks: the first layer's set is resident; every other set is staged one
-// phase before its use, alternating between slot A and slot B (B = the high slot while buf1 is full,
-// i.e. during section 1, else the low slot inside buf1's unused tail).  Section 2's conv0 is staged
-// during section 1's last block, so it must sit in A; the alternation below guarantees that.
-template <class M, class S, class SN, bool FIRST, bool HAS_NEXT>
-struct SlotPlan {
-    static constexpr int A = M::WSA;
-    static constexpr int B = S::ACT_BYTES > 36 * 1024 ? M::WSB_HI : M::WSB_LO;
-    static constexpr int BN = SN::ACT_BYTES > 36 * 1024 ? M::WSB_HI : M::WSB_LO;   // B as the next section sees it
-    static_assert(S::ACT_BYTES <= 36 * 1024 || S::WB_SET * 1024 <= M::WSB_HI_CAP, "block weights do not fit the high slot");
-    // first section: conv0 resident, blocks A B A B, next conv0 -> A
-    // later sections alternate between (conv0 A, blocks B A B A, next -> B) and (conv0 B, blocks A B A B, next -> A)
-    using First = Slots<M::PERM, A, B, A, B, A, HAS_NEXT ? SN::W0_SET : 0, true>;
-    using EvenC0A = Slots<A, B, A, B, A, BN, HAS_NEXT ? SN::W0_SET : 0, true>;
-    using OddC0B = Slots<B, A, B, A, B, A, HAS_NEXT ? SN::W0_SET : 0, true>;
-};
 
 template <class S1, class S2, class S3>
 struct Net3 {
@@ -743,9 +797,7 @@ struct Net3 {
     static constexpr int B1 = mx(mx(S1::ACT_BYTES, S2::ACT_BYTES), S3::ACT_BYTES);
     static constexpr int EDGE = mx(mx(S1::EDGE_BYTES, S2::EDGE_BYTES), S3::EDGE_BYTES);
     using M = LdsMap<B0, B1, EDGE, S1::W0_SET * 1024>;
-    using SL1 = typename SlotPlan<M, S1, S2, true, true>::First;
-    using SL2 = typename SlotPlan<M, S2, S3, false, true>::EvenC0A;
-    using SL3 = typename SlotPlan<M, S3, S3, false, false>::OddC0B;
+    static constexpr int NSETS = 14;
     static constexpr int LDS_BYTES = LDS_TOTAL;
 };
 
@@ -768,17 +820,18 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
         wstage_issue(s0, a.sec[0].w0, tid);
         wstage_commit(s0, lds + M::PERM, tid);
     }
+    WPipe pipe;
     Prefetch<S1> pre;
     prefetch_issue<S1>(pre, a.obs + FRAME * blockIdx.x, 0, tid);
     for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
-        run_section<S1, M, typename N::SL1, false, 0>(lds, a.sec[0], a.sec[1].w0, obs_img, pre, feat_row, tid);
-        // the next frame's bytes travel while sections 2 and 3 compute
-        const int nimg = img + gridDim.x;
-        if (nimg < a.B) prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
-        run_section<S2, M, typename N::SL2, false, 1>(lds, a.sec[1], a.sec[2].w0, obs_img, pre, feat_row, tid);
-        run_section<S3, M, typename N::SL3, true, 2>(lds, a.sec[2], nullptr, obs_img, pre, feat_row, tid);
+        run_section<S1, S2, M, false, 0, -1, N::NSETS>(lds, a.sec[0], a.sec[1], pipe, obs_img, pre, feat_row, tid);
+        run_section<S2, S3, M, false, 1, 4, N::NSETS>(lds, a.sec[1], a.sec[2], pipe, obs_img, pre, feat_row, tid);
+        // the next frame's bytes travel while section 3 computes
+        const int nimg = img + (int)gridDim.x < a.B ? img + (int)gridDim.x : img;   // unconditional: see wpipe_issue
+        prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
+        run_section<S3, S3, M, true, 2, 9, N::NSETS>(lds, a.sec[2], a.sec[2], pipe, obs_img, pre, feat_row, tid);
     }
 }
 
@@ -790,10 +843,7 @@ struct Net4 {
     static constexpr int B1 = mx(mx(S1::ACT_BYTES, S2::ACT_BYTES), mx(S3::ACT_BYTES, S4::ACT_BYTES));
     static constexpr int EDGE = mx(mx(S1::EDGE_BYTES, S2::EDGE_BYTES), mx(S3::EDGE_BYTES, S4::EDGE_BYTES));
     using M = LdsMap<B0, B1, EDGE, S1::W0_SET * 1024>;
-    using SL1 = typename SlotPlan<M, S1, S2, true, true>::First;
-    using SL2 = typename SlotPlan<M, S2, S3, false, true>::EvenC0A;
-    using SL3 = typename SlotPlan<M, S3, S4, false, true>::OddC0B;
-    using SL4 = typename SlotPlan<M, S4, S4, false, false>::EvenC0A;
+    static constexpr int NSETS = 19;
     static constexpr int LDS_BYTES = LDS_TOTAL;
 };
 
@@ -816,17 +866,18 @@ __global__ __launch_bounds__(RN_THREADS) void resnet4_bf16_kernel(TorsoArgs a)
         wstage_issue(s0, a.sec[0].w0, tid);
         wstage_commit(s0, lds + M::PERM, tid);
     }
+    WPipe pipe;
     Prefetch<S1> pre;
     prefetch_issue<S1>(pre, a.obs + FRAME * blockIdx.x, 0, tid);
     for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
-        run_section<S1, M, typename N::SL1, false, 0>(lds, a.sec[0], a.sec[1].w0, obs_img, pre, feat_row, tid);
-        const int nimg = img + gridDim.x;
-        if (nimg < a.B) prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
-        run_section<S2, M, typename N::SL2, false, 1>(lds, a.sec[1], a.sec[2].w0, obs_img, pre, feat_row, tid);
-        run_section<S3, M, typename N::SL3, false, 2>(lds, a.sec[2], a.sec[3].w0, obs_img, pre, feat_row, tid);
-        run_section<S4, M, typename N::SL4, true, 3>(lds, a.sec[3], nullptr, obs_img, pre, feat_row, tid);
+        run_section<S1, S2, M, false, 0, -1, N::NSETS>(lds, a.sec[0], a.sec[1], pipe, obs_img, pre, feat_row, tid);
+        run_section<S2, S3, M, false, 1, 4, N::NSETS>(lds, a.sec[1], a.sec[2], pipe, obs_img, pre, feat_row, tid);
+        run_section<S3, S4, M, false, 2, 9, N::NSETS>(lds, a.sec[2], a.sec[3], pipe, obs_img, pre, feat_row, tid);
+        const int nimg = img + (int)gridDim.x < a.B ? img + (int)gridDim.x : img;
+        prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
+        run_section<S4, S4, M, true, 3, 14, N::NSETS>(lds, a.sec[3], a.sec[3], pipe, obs_img, pre, feat_row, tid);
     }
 }
 
