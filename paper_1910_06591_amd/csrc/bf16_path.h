@@ -320,11 +320,13 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, const float* d_w
 }
 
 template <int EPI>
-inline void launch_gemm(hipStream_t st, const GemmArgs& g, int wave_groups)
+inline void launch_gemm(hipStream_t st, const GemmArgs& g, int wave_groups, int n_cu)
 {
+    // rows per wavefront (RT*16): the largest that still gives every compute unit at least two workgroups
     const int gy = (wave_groups + 3) / 4;
-    if (g.rows >= 2048) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI>), dim3((g.rows + 63) / 64, gy), dim3(256), 0, st, g);
-    else if (g.rows >= 512) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI>), dim3((g.rows + 31) / 32, gy), dim3(256), 0, st, g);
+    const long want = 2L * n_cu;
+    if ((long)((g.rows + 63) / 64) * gy >= want) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI>), dim3((g.rows + 63) / 64, gy), dim3(256), 0, st, g);
+    else if ((long)((g.rows + 31) / 32) * gy >= want) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI>), dim3((g.rows + 31) / 32, gy), dim3(256), 0, st, g);
     else hipLaunchKernelGGL((gemm_bf16_kernel<1, EPI>), dim3((g.rows + 15) / 16, gy), dim3(256), 0, st, g);
 }
 
@@ -386,7 +388,7 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
         g.x1 = s->feat; g.ld1 = s->ldf; g.kc1 = s->kc_fc; g.k2 = 0;
         g.wp = s->wp_fc; g.n_ftiles = s->ft_fc; g.rows = B; g.bias_pad = s->bias_fc;
         g.y_bf16 = s->fc_bf16; g.ldy_bf16 = s->ldfc; g.y_f32 = s->fc_f32; g.ldy_f32 = a.fc_units; g.n_out = a.fc_units;
-        launch_gemm<EPI_RELU>(st, g, (s->ft_fc + 3) / 4);
+        launch_gemm<EPI_RELU>(st, g, (s->ft_fc + 3) / 4, s->n_cu);
     }
     *core = s->fc_f32; *ld_core = a.fc_units;
     if (a.lstm_units > 0) {
@@ -396,7 +398,7 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
         g.wp = s->wp_lstm; g.n_ftiles = (a.lstm_units / 16) * 4; g.rows = B;
         g.lstm_w = d_w + p.lstm_w; g.lstm_b = d_w + p.lstm_b; g.prev_action = prev_action; g.prev_reward = prev_reward;
         g.c_in = c_in; g.h_out = h_out; g.c_out = c_out; g.F = a.fc_units; g.A = a.num_actions; g.Hn = a.lstm_units;
-        launch_gemm<EPI_LSTM>(st, g, a.lstm_units / 16);
+        launch_gemm<EPI_LSTM>(st, g, a.lstm_units / 16, s->n_cu);
         *core = h_out; *ld_core = a.lstm_units;
     }
     if (a.head == SEED_HEAD_DUELING_Q) {
@@ -405,7 +407,7 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
         else { g.x1 = s->fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->ldfc / 32; g.k2 = 0; }
         g.wp = s->wp_hid; g.n_ftiles = s->ft_hid; g.rows = B; g.bias_pad = s->bias_hid;
         g.y_bf16 = nullptr; g.y_f32 = d_hid; g.ldy_f32 = 2 * a.head_hidden; g.n_out = 2 * a.head_hidden;
-        launch_gemm<EPI_RELU>(st, g, (s->ft_hid + 3) / 4);
+        launch_gemm<EPI_RELU>(st, g, (s->ft_hid + 3) / 4, s->n_cu);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { err = std::string("kernel launch: ") + hipGetErrorString(e); return SEED_ERR_DEVICE; }

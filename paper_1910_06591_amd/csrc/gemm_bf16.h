@@ -69,37 +69,45 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
 #pragma unroll
     for (int j = 0; j < 4; ++j) wl[j] = p.wp + ((size_t)min(ft0 + j, p.n_ftiles - 1) * kct) * 64 + lane;
 
-    for (int kc = 0; kc < p.kc1; ++kc) {
-        bf16x8 a[4], b[RT];
+    // K loop, software-pipelined: the fragments of chunk kc+1 are loaded while chunk kc is multiplied
+    auto load_chunk = [&](bf16x8 (&a)[4], bf16x8 (&b)[RT], int kc) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) a[j] = wl[j][(size_t)kc * 64];
+        if (kc < p.kc1) {
 #pragma unroll
-        for (int r = 0; r < RT; ++r)
-            b[r] = *(const bf16x8*)(p.x1 + (size_t)rowi[r] * p.ld1 + kc * 32 + g * 8);
+            for (int r = 0; r < RT; ++r)
+                b[r] = *(const bf16x8*)(p.x1 + (size_t)rowi[r] * p.ld1 + kc * 32 + g * 8);
+        } else {
+            const int k = (kc - p.kc1) * 32 + g * 8;
 #pragma unroll
-        for (int r = 0; r < RT; ++r)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[r][j] = mfma16(a[j], b[r], acc[r][j]);
-    }
-    for (int kc = 0; kc < kc2; ++kc) {
-        bf16x8 a[4], b[RT];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = wl[j][(size_t)(p.kc1 + kc) * 64];
-        const int k = kc * 32 + g * 8;
-#pragma unroll
-        for (int r = 0; r < RT; ++r) {
-            floatx4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-            if (k + 8 <= p.k2) {
-                const float* s = p.x2 + (size_t)rowi[r] * p.ld2 + k;
-                lo = *(const floatx4*)s;
-                hi = *(const floatx4*)(s + 4);
+            for (int r = 0; r < RT; ++r) {
+                floatx4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+                if (k + 8 <= p.k2) {
+                    const float* s = p.x2 + (size_t)rowi[r] * p.ld2 + k;
+                    lo = *(const floatx4*)s;
+                    hi = *(const floatx4*)(s + 4);
+                }
+                b[r] = to_bf16x8(lo, hi);
             }
-            b[r] = to_bf16x8(lo, hi);
         }
+    };
+    auto mma_chunk = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[RT]) {
 #pragma unroll
         for (int r = 0; r < RT; ++r)
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[r][j] = mfma16(a[j], b[r], acc[r][j]);
+    };
+    {
+        bf16x8 a0[4], b0[RT], a1[4], b1[RT];
+        load_chunk(a0, b0, 0);
+        int kc = 0;
+        for (; kc + 2 <= kct; kc += 2) {
+            load_chunk(a1, b1, kc + 1);
+            mma_chunk(a0, b0);
+            load_chunk(a0, b0, kc + 2 < kct ? kc + 2 : kct - 1);
+            mma_chunk(a1, b1);
+        }
+        if (kc < kct) mma_chunk(a0, b0);
     }
 
     if constexpr (EPI == EPI_RELU) {

@@ -46,8 +46,20 @@ __global__ __launch_bounds__(256) void heads_select_kernel(HeadsArgs p)
     float acc = 0.0f;
     {
         const float* v = p.vec_a + (size_t)row * p.ld_a;
-        if (live)
-            for (int i = g; i < p.n; i += G) acc = fmaf(v[i], p.w_a[(size_t)i * p.A + a], acc);
+        if (live) {
+            // several independent partial sums keep many loads in flight (the loop is latency-bound otherwise);
+            // the summation order is fixed, so results stay reproducible
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            int i = g;
+            for (; i + 3 * G < p.n; i += 4 * G) {
+                s0 = fmaf(v[i], p.w_a[(size_t)i * p.A + a], s0);
+                s1 = fmaf(v[i + G], p.w_a[(size_t)(i + G) * p.A + a], s1);
+                s2 = fmaf(v[i + 2 * G], p.w_a[(size_t)(i + 2 * G) * p.A + a], s2);
+                s3 = fmaf(v[i + 3 * G], p.w_a[(size_t)(i + 3 * G) * p.A + a], s3);
+            }
+            for (; i < p.n; i += G) s0 = fmaf(v[i], p.w_a[(size_t)i * p.A + a], s0);
+            acc = (s0 + s1) + (s2 + s3);
+        }
     }
 #pragma unroll
     for (int off = P; off < 64; off <<= 1) acc += __shfl_xor(acc, off, 64);
