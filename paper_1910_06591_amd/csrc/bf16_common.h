@@ -24,12 +24,9 @@ __device__ __forceinline__ floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ bf16x4 to_bf16x4(floatx4 v)
-{
-    bf16x4 r;
-    r[0] = (__bf16)v[0]; r[1] = (__bf16)v[1]; r[2] = (__bf16)v[2]; r[3] = (__bf16)v[3];
-    return r;
-}
+// fp32 -> bf16, round to nearest even.  Converting the whole vector at once lets the compiler use the
+// packed two-at-a-time hardware conversion; element-wise casts cost a conversion and a byte permute each.
+__device__ __forceinline__ bf16x4 to_bf16x4(floatx4 v) { return __builtin_convertvector(v, bf16x4); }
 
 __device__ __forceinline__ floatx4 relu4(floatx4 v)
 {
@@ -47,12 +44,7 @@ __device__ __forceinline__ bf16x4 relu_bf16x4(bf16x4 v)
     return __builtin_bit_cast(bf16x4, __builtin_elementwise_max(__builtin_bit_cast(shortx4, v), z));
 }
 
-__device__ __forceinline__ floatx4 to_floatx4(bf16x4 v)
-{
-    floatx4 r;
-    r[0] = (float)v[0]; r[1] = (float)v[1]; r[2] = (float)v[2]; r[3] = (float)v[3];
-    return r;
-}
+__device__ __forceinline__ floatx4 to_floatx4(bf16x4 v) { return __builtin_convertvector(v, floatx4); }
 
 __device__ __forceinline__ floatx4 max4(floatx4 a, floatx4 b)
 {
@@ -64,21 +56,16 @@ __device__ __forceinline__ floatx4 max4(floatx4 a, floatx4 b)
 // 8 fp32 -> 8 bf16 (round to nearest even, the hardware conversion)
 __device__ __forceinline__ bf16x8 to_bf16x8(floatx4 lo, floatx4 hi)
 {
-    bf16x8 r;
-    r[0] = (__bf16)lo[0]; r[1] = (__bf16)lo[1]; r[2] = (__bf16)lo[2]; r[3] = (__bf16)lo[3];
-    r[4] = (__bf16)hi[0]; r[5] = (__bf16)hi[1]; r[6] = (__bf16)hi[2]; r[7] = (__bf16)hi[3];
-    return r;
+    const bf16x4 a = to_bf16x4(lo), b = to_bf16x4(hi);
+    return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 // 8 bytes (two dwords, little endian) -> 8 bf16 holding the integers 0..255 exactly
 __device__ __forceinline__ bf16x8 u8x8_to_bf16x8(uint32_t lo, uint32_t hi)
 {
-    bf16x8 r;
-    r[0] = (__bf16)(float)(lo & 0xff); r[1] = (__bf16)(float)((lo >> 8) & 0xff);
-    r[2] = (__bf16)(float)((lo >> 16) & 0xff); r[3] = (__bf16)(float)(lo >> 24);
-    r[4] = (__bf16)(float)(hi & 0xff); r[5] = (__bf16)(float)((hi >> 8) & 0xff);
-    r[6] = (__bf16)(float)((hi >> 16) & 0xff); r[7] = (__bf16)(float)(hi >> 24);
-    return r;
+    const floatx4 a = {(float)(lo & 0xff), (float)((lo >> 8) & 0xff), (float)((lo >> 16) & 0xff), (float)(lo >> 24)};
+    const floatx4 b = {(float)(hi & 0xff), (float)((hi >> 8) & 0xff), (float)((hi >> 16) & 0xff), (float)(hi >> 24)};
+    return to_bf16x8(a, b);
 }
 
 }  // namespace seedinf

@@ -162,7 +162,17 @@ inline void pack_section(std::vector<uint16_t>& pk, const float* w, const Sectio
     for (int j = 0; j < 4; ++j) {
         const float* wb = w + sec.block[j].w_off;
         off[1 + j] = pk.size();
-        pack_a(pk, S::FT, S::KCB, [&](int f, int k) -> float { return planar_weight<S::C>(wb, S::C, f, k); });
+        if constexpr (S::SLIDE) {
+            // sliding-window layout: chunk = weight fragment, lane group -> (tap, channel group) per SlideMap16
+            pack_a(pk, 1, SlideMap16::NFRAG, [&](int f, int k) -> float {
+                const int fr = k / 32, g = (k % 32) / 8, e = k % 8;
+                const int tap = SlideMap16::tap(fr, g);
+                if (tap < 0) return 0.f;
+                return wb[((size_t)tap * S::C + SlideMap16::cg(g) * 8 + e) * S::C + f];
+            });
+        } else {
+            pack_a(pk, S::FT, S::KCB, [&](int f, int k) -> float { return planar_weight<S::C>(wb, S::C, f, k); });
+        }
         pack_bias_chunk(pk, w + sec.block[j].b_off, S::C);
     }
 }

@@ -89,13 +89,16 @@ struct SecCfg {
     static constexpr int KC0 = INKIND == IN_U8_C3 ? 2 : (9 * CIN + 31) / 32;
     static constexpr int KCB = (9 * C + 31) / 32;
     static constexpr int NK0 = INKIND == IN_U8_C3 ? 2 : (CIN == 16 ? 3 : 1);   // offset registers conv0 keeps per lane
-    static constexpr int W0_FRAGS = FT * KC0, WB_FRAGS = FT * KCB;
+    static constexpr int NWA = NWA_;                        // wavefronts that own pooled tiles (x-read and blocks)
+    // 16-channel sections on the 36x48 pooled map run their block convolutions with the sliding-window
+    // scheme (block_conv_slide16): column chains of tiles, seven weight fragments per layer
+    static constexpr bool SLIDE = C == 16 && PH == 36 && PW == 48 && NWA == 8 && RN_WAVES == 8;
+    static constexpr int W0_FRAGS = FT * KC0, WB_FRAGS = SLIDE ? 7 : FT * KCB;
     // a staged weight set = the fragments + one 1 KiB chunk whose first C floats are the biases
     static constexpr int W0_SET = W0_FRAGS + 1, WB_SET = WB_FRAGS + 1;
     static constexpr int NPIX = PH * PW;
     static constexpr int NTILES = (NPIX + 15) / 16;
-    static constexpr int NWA = NWA_;                        // wavefronts that own pooled tiles (x-read and blocks)
-    static constexpr int NT = (NTILES + NWA - 1) / NWA;
+    static constexpr int NT = SLIDE ? 14 : (NTILES + NWA - 1) / NWA;
     static constexpr int NCS = (W + 15) / 16;               // 16-column strips of the conv0 output
     static constexpr int NUNITS = NCS * NB;
     static constexpr int NU = (NUNITS + RN_WAVES - 1) / RN_WAVES;
@@ -236,6 +239,41 @@ struct KMap {
     }
 };
 
+// ---- sliding-window K layout of the 16-channel block convolutions ----------------------------
+// A tile is 16 consecutive columns of one pooled row; a wavefront walks a column of tiles downwards (a
+// "chain") and keeps the B fragments that consecutive tiles share in registers.  Two kinds of fragment,
+// both addressed by buffer row (= pooled row + halo) of the source map:
+//   R(r): row r, lane group g -> kernel column g>>1 (0 or 1), channel group g&1.  The tile of pooled row y
+//         multiplies R(y), R(y+1), R(y+2) with the weight fragments 0, 1, 2 (kernel rows 0, 1, 2).
+//   E(k): kernel column 2 of the row pair (2k, 2k+1): lane groups 0,1 -> row 2k, groups 2,3 -> row 2k+1,
+//         channel group g&1.  A tile of even row y = 2k needs rows 2k, 2k+1 | 2k+2: E(k) x fragment 3
+//         (kernel rows 0 | 1) and E(k+1) x fragment 4 (kernel row 2 | zeros); a tile of odd row y = 2k+1
+//         needs rows 2k+1 | 2k+2, 2k+3: E(k) x fragment 5 (zeros | kernel row 0) and E(k+1) x fragment 6
+//         (kernel rows 1 | 2).  So the pair-aligned E fragments serve both parities and only the weights
+//         differ: per tile one new R and half a new E fragment are read instead of five fragments.
+struct SlideMap16 {
+    static constexpr int NFRAG = 7;
+    // kernel tap kh*3+kw (or -1: zero weights) of lane group g in weight fragment f
+    static constexpr int tap(int f, int g)
+    {
+        if (f < 3) return f * 3 + (g >> 1);
+        if (f == 3) return (g < 2 ? 0 : 1) * 3 + 2;
+        if (f == 4) return g < 2 ? 2 * 3 + 2 : -1;
+        if (f == 5) return g < 2 ? -1 : 0 * 3 + 2;
+        return (g < 2 ? 1 : 2) * 3 + 2;
+    }
+    static constexpr int cg(int g) { return g & 1; }
+    // Chains of the 36 x 48 pooled map (3 column strips x 36 rows = 108 tiles): every wavefront owns chain 0
+    // (8 tiles) and chain 1 (4 tiles for wavefronts 0 and 1, else 6); all chains start on an even row.
+    static constexpr int LEN0 = 8, LEN1 = 6;
+    __device__ static __forceinline__ void chain(int wave, int c, int& strip, int& row0, int& nt)
+    {
+        if (c == 0) { strip = wave >> 2; row0 = (wave & 3) * 8; nt = 8; }
+        else if (wave < 2) { strip = wave; row0 = 32; nt = 4; }
+        else { strip = 2; row0 = (wave - 2) * 6; nt = 6; }
+    }
+};
+
 // ---- uint8 frame prefetch --------------------------------------------------------
 template <class S>
 struct Prefetch {
@@ -307,10 +345,8 @@ __device__ __forceinline__ void prefetch_commit(const Prefetch<S>& p, char* buf0
                     char* d = buf0 + ((i / GPR + 1) * S::IPITCH + (i % GPR) * 4 + 1) * 8;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        bf16x4 c;
-                        c[0] = (__bf16)(float)by[q * 3]; c[1] = (__bf16)(float)by[q * 3 + 1];
-                        c[2] = (__bf16)(float)by[q * 3 + 2]; c[3] = (__bf16)0.0f;
-                        *(bf16x4*)(d + q * 8) = c;
+                        const floatx4 c = {(float)by[q * 3], (float)by[q * 3 + 1], (float)by[q * 3 + 2], 0.0f};
+                        *(bf16x4*)(d + q * 8) = to_bf16x4(c);
                     }
                 }
             }
@@ -531,6 +567,84 @@ __device__ __forceinline__ void tile_table(int (&tb)[S::NT], int lane, int wave)
     }
 }
 
+// Pooled pixel (y, xx) that lane n holds in the wavefront's tile i (clamped into the map), whether the tile
+// exists (uniform across the wavefront) and whether the lane's pixel does.
+template <class S>
+__device__ __forceinline__ void tile_ref(int wave, int i, int n, int& y, int& xx, bool& tile_ok, bool& lane_ok)
+{
+    if constexpr (S::SLIDE) {
+        const int c = i < SlideMap16::LEN0 ? 0 : 1, pos = i - (c ? SlideMap16::LEN0 : 0);
+        int strip, row0, nt;
+        SlideMap16::chain(wave, c, strip, row0, nt);
+        tile_ok = lane_ok = pos < nt;
+        y = row0 + (pos < nt ? pos : nt - 1);
+        xx = strip * 16 + n;
+    } else {
+        const int t = wave + S::NWA * i;
+        tile_ok = t < S::NTILES;
+        lane_ok = S::NPIX % 16 == 0 ? tile_ok : t * 16 + n < S::NPIX;
+        tile_pixel<S>(tile_ok ? t : S::NTILES - 1, n, y, xx);
+    }
+}
+
+// Sliding-window 3x3 SAME conv 16 -> 16 (see SlideMap16).  Tiles are taken two at a time (an even row and
+// the odd row below it) with independent accumulators, so their MFMA chains interleave; the fragments of
+// the next pair are read while the current pair is multiplied.  Tiles past the end of a short chain are
+// computed on whatever the map holds there and stored to `trash`.
+template <class S, bool ADD_X, int OUT>
+__device__ __forceinline__ void block_conv_slide16(const char* src, char* dst, char* trash, const char* wslot,
+                                                   floatx4 (&x)[S::NT][S::FT], int lane, int wave)
+{
+    static_assert(S::FT == 1 && OUT != 2, "sliding block convolution: 16 channels, LDS output");
+    using SM = SlideMap16;
+    const int g = lane >> 4, n = lane & 15;
+    bf16x8 w[SM::NFRAG];
+    load_a_frags(w, wslot, lane);
+    const floatx4 bv = *(const floatx4*)(wslot + SM::NFRAG * 1024 + g * 16);
+    constexpr int ROWB = S::PITCH * 16;                                  // bytes per map row
+    const int laneR = ((g & 1) * S::PLANE + (g >> 1) + n) * 16;
+    const int laneE = ((g & 1) * S::PLANE + (g >> 1) * S::PITCH + 2 + n) * 16;
+    const int laneD = (S::PITCH + 1 + n) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
+    auto run_chain = [&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        constexpr int LEN = c == 0 ? SM::LEN0 : SM::LEN1, I0 = c == 0 ? 0 : SM::LEN0;
+        int strip, row0, nt;
+        SM::chain(wave, c, strip, row0, nt);
+        const int cb = (row0 * S::PITCH + strip * 16) * 16;              // uniform
+        const char* pR = src + cb + laneR;
+        const char* pE = src + cb + laneE;
+        char* pD = dst + cb + laneD;
+        bf16x8 R[LEN + 2], E[LEN / 2 + 1];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) R[r] = *(const bf16x8*)(pR + r * ROWB);
+        E[0] = *(const bf16x8*)pE;
+        E[1] = *(const bf16x8*)(pE + 2 * ROWB);
+#pragma unroll
+        for (int pp = 0; pp < LEN / 2; ++pp) {
+            if (pp + 1 < LEN / 2) {
+                R[2 * pp + 4] = *(const bf16x8*)(pR + (2 * pp + 4) * ROWB);
+                R[2 * pp + 5] = *(const bf16x8*)(pR + (2 * pp + 5) * ROWB);
+                E[pp + 2] = *(const bf16x8*)(pE + (2 * pp + 4) * ROWB);
+            }
+            floatx4 a0 = ADD_X ? x[I0 + 2 * pp][0] + bv : bv;
+            floatx4 a1 = ADD_X ? x[I0 + 2 * pp + 1][0] + bv : bv;
+            a0 = mfma16(w[0], R[2 * pp], a0);      a1 = mfma16(w[0], R[2 * pp + 1], a1);
+            a0 = mfma16(w[1], R[2 * pp + 1], a0);  a1 = mfma16(w[1], R[2 * pp + 2], a1);
+            a0 = mfma16(w[2], R[2 * pp + 2], a0);  a1 = mfma16(w[2], R[2 * pp + 3], a1);
+            a0 = mfma16(w[3], E[pp], a0);          a1 = mfma16(w[5], E[pp], a1);
+            a0 = mfma16(w[4], E[pp + 1], a0);      a1 = mfma16(w[6], E[pp + 1], a1);
+            const bool ok = 2 * pp < nt;                                   // uniform; chains have even lengths
+            char* d = ok ? pD + (2 * pp) * ROWB : trash;
+            if (ADD_X) { x[I0 + 2 * pp][0] = a0; x[I0 + 2 * pp + 1][0] = a1; }
+            const bf16x4 v0 = to_bf16x4(a0), v1 = to_bf16x4(a1);
+            *(bf16x4*)d = OUT == 1 ? v0 : relu_bf16x4(v0);
+            *(bf16x4*)(d + (ok ? ROWB : 0)) = OUT == 1 ? v1 : relu_bf16x4(v1);
+        }
+    };
+    run_chain(std::integral_constant<int, 0>{});
+    run_chain(std::integral_constant<int, 1>{});
+}
+
 // 3x3 SAME conv C -> C on the section's pooled map, this wavefront's tiles.
 // src/dst: planar maps with halo.  OUT: 0 = store ReLU(v) to dst, 1 = store v
 // to dst, 2 = store ReLU(v) to the global feature row.  The B fragments of tile
@@ -723,20 +837,20 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     }
 
     // ---------------- x <- pooled map (+ edge columns); R = ReLU(x) ----------------
-    int tb[S::NT];
-    tile_table<S>(tb, lane, wave);
+    int tb[S::NT];                                     // per tile: cell index of the lane's pixel (tap (0,0), plane 0)
     {
         zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf0, tid);
         if (wave < S::NWA) {
-            constexpr bool WHOLE = S::NPIX % 16 == 0;
             const int loff = (S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
             bf16x4 pv[S::NT][S::FT], ev[S::NT][S::FT];
+            bool ok[S::NT];
 #pragma unroll
             for (int i = 0; i < S::NT; ++i) {          // all loads first
-                const int t = wave + S::NWA * i;
-                if (t >= S::NTILES) break;
                 int y, xx;
-                tile_pixel<S>(t, n, y, xx);
+                bool tile_ok;
+                tile_ref<S>(wave, i, n, y, xx, tile_ok, ok[i]);
+                tb[i] = y * S::PITCH + xx;
+                if (!S::SLIDE && !tile_ok) break;
                 // the pooled value of a strip's last column lacks its right neighbour: it is the next strip's edge
                 // column; every other lane reads the neutral (-inf) cell instead
                 const bool fix = (xx & 7) == 7 && xx + 1 < S::PW;
@@ -751,40 +865,46 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
             }
 #pragma unroll
             for (int i = 0; i < S::NT; ++i) {
-                const int t = wave + S::NWA * i;
-                if (t >= S::NTILES) break;
-                const int p = t * 16 + n;
+                if (!S::SLIDE && wave + S::NWA * i >= S::NTILES) break;
                 const int off = tb[i] * 16 + loff;
 #pragma unroll
                 for (int j = 0; j < S::FT; ++j) {
                     const floatx4 v = max4(to_floatx4(pv[i][j]), to_floatx4(ev[i][j]));
                     x[i][j] = v;
-                    if (WHOLE || p < S::NPIX) *(bf16x4*)(buf0 + off + j * (2 * S::PLANE * 16)) = relu_bf16x4(to_bf16x4(v));
+                    // a short chain's missing tiles rewrite its last tile with the same values
+                    if (S::SLIDE || ok[i]) *(bf16x4*)(buf0 + off + j * (2 * S::PLANE * 16)) = relu_bf16x4(to_bf16x4(v));
                 }
             }
         }
         lds_barrier();
         PHASE_MARK(SI * 8 + 3);
     }
+    auto conv = [&](auto add_x, auto out, const char* src, char* dst, const char* ws) {
+        constexpr bool ADD_X = decltype(add_x)::value;
+        constexpr int OUT = decltype(out)::value;
+        if constexpr (S::SLIDE) block_conv_slide16<S, ADD_X, OUT>(src, dst, lds + M::TRASH + lane * 8, ws, x, lane, wave);
+        else block_conv<S, ADD_X, OUT>(src, dst, ws, tb, x, feat_row, lane, wave);
+    };
+    using BF = std::false_type; using BT = std::true_type;
 
     // ---------------- residual blocks ----------------
     issue(I2{});
-    block_conv<S, false, 0>(buf0, buf1, lds + wslot<M, S>(QB), tb, x, nullptr, lane, wave);
+    conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB));
     commit(I1{});
     lds_barrier();
     PHASE_MARK(SI * 8 + 4);
     issue(I3{});
-    block_conv<S, true, 0>(buf1, buf0, lds + wslot<M, S>(QB + 1), tb, x, nullptr, lane, wave);
+    conv(BT{}, I0{}, buf1, buf0, lds + wslot<M, S>(QB + 1));
     commit(I2{});
     lds_barrier();
     PHASE_MARK(SI * 8 + 5);
     if constexpr (!LAST) issue(I4{});
-    block_conv<S, false, 0>(buf0, buf1, lds + wslot<M, S>(QB + 2), tb, x, nullptr, lane, wave);
+    conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB + 2));
     commit(I3{});
     lds_barrier();
     PHASE_MARK(SI * 8 + 6);
     if constexpr (!LAST) issue(I5{});
-    block_conv<S, true, LAST ? 2 : 1>(buf1, buf0, lds + wslot<M, S>(QB + 3), tb, x, feat_row, lane, wave);
+    conv(BT{}, std::integral_constant<int, LAST ? 2 : 1>{}, buf1, buf0, lds + wslot<M, S>(QB + 3));
     if constexpr (!LAST) commit(I4{});
     lds_barrier();
     PHASE_MARK(SI * 8 + 7);
@@ -823,6 +943,9 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
     WPipe pipe;
     Prefetch<S1> pre;
     prefetch_issue<S1>(pre, a.obs + FRAME * blockIdx.x, 0, tid);
+#ifdef SEEDINF_PRIO_MASK
+    if ((tid >> 6) & SEEDINF_PRIO_MASK) __builtin_amdgcn_s_setprio(2);
+#endif
     for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
@@ -869,6 +992,9 @@ __global__ __launch_bounds__(RN_THREADS) void resnet4_bf16_kernel(TorsoArgs a)
     WPipe pipe;
     Prefetch<S1> pre;
     prefetch_issue<S1>(pre, a.obs + FRAME * blockIdx.x, 0, tid);
+#ifdef SEEDINF_PRIO_MASK
+    if ((tid >> 6) & SEEDINF_PRIO_MASK) __builtin_amdgcn_s_setprio(2);
+#endif
     for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
