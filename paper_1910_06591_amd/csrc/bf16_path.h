@@ -147,12 +147,14 @@ inline void pack_section(std::vector<uint16_t>& pk, const float* w, const Sectio
     const float* w0 = w + c0.w_off;
     off[0] = pk.size();
     if constexpr (S::INKIND == IN_U8_C3) {
-        // K slot s = kchunk*4 + lanegroup: s < 6 -> kernel row s/2, pixel pair s%2; element e -> pixel e/4, channel e%4
-        pack_a(pk, S::FT, 2, [&](int f, int k) -> float {
-            int s = k / 8, e = k % 8;
-            if (s > 5) return 0.f;
-            int kh = s / 2, kw = 2 * (s % 2) + e / 4, ch = e % 4;
-            if (kw > 2 || ch > 2) return 0.f;
+        // four fragments (see conv0_pool3): lane group g -> buffer row g/2 of a row pair, pixel pair g%2; element e ->
+        // pixel e/4, channel e%4.  Fragment 0: kernel rows (0 | 1), 1: (2 | none), 2: (none | 0), 3: (1 | 2).
+        pack_a(pk, S::FT, 4, [&](int f, int k) -> float {
+            const int fr = k / 32, g = (k % 32) / 8, e = k % 8;
+            const int half = g >> 1;
+            const int kh = fr == 0 ? half : (fr == 1 ? (half ? -1 : 2) : (fr == 2 ? (half ? 0 : -1) : 1 + half));
+            const int kw = 2 * (g & 1) + e / 4, ch = e % 4;
+            if (kh < 0 || kw > 2 || ch > 2) return 0.f;
             return w0[((size_t)(kh * 3 + kw) * 3 + ch) * S::C + f];
         });
     } else {

@@ -86,7 +86,8 @@ struct SecCfg {
     static constexpr int SR = INKIND == IN_LDS ? PH : SR_;
     static constexpr int NSTRIPS = (PH + SR - 1) / SR;
     static constexpr int FT = C / 16;
-    static constexpr int KC0 = INKIND == IN_U8_C3 ? 2 : (9 * CIN + 31) / 32;
+    // conv0 weight fragments per feature tile (the 3-channel layer: two per conv-row parity, see conv0_pool3)
+    static constexpr int KC0 = INKIND == IN_U8_C3 ? 4 : (9 * CIN + 31) / 32;
     static constexpr int KCB = (9 * C + 31) / 32;
     static constexpr int NK0 = INKIND == IN_U8_C3 ? 2 : (CIN == 16 ? 3 : 1);   // offset registers conv0 keeps per lane
     static constexpr int NWA = NWA_;                        // wavefronts that own pooled tiles (x-read and blocks)
@@ -96,6 +97,9 @@ struct SecCfg {
     static constexpr int W0_FRAGS = FT * KC0, WB_FRAGS = SLIDE ? 7 : FT * KCB;
     // a staged weight set = the fragments + one 1 KiB chunk whose first C floats are the biases
     static constexpr int W0_SET = W0_FRAGS + 1, WB_SET = WB_FRAGS + 1;
+    // The 3-channel first layer pools without lane shifts (conv0_pool3): it needs no edge buffer and its
+    // pooled map is complete when the conv0 phase ends.
+    static constexpr bool POOL3 = INKIND == IN_U8_C3;
     static constexpr int NPIX = PH * PW;
     static constexpr int NTILES = (NPIX + 15) / 16;
     static constexpr int NT = SLIDE ? 14 : (NTILES + NWA - 1) / NWA;
@@ -112,7 +116,7 @@ struct SecCfg {
     static constexpr int IN_BYTES = (INKIND == IN_U8_C3 ? 1 : CIN / 8) * IPLANE * ICELL + 16;
     static constexpr int PITCH = PW + 2, PLANE = ((PH + 2) * PITCH + 15) / 16 * 16;
     static constexpr int ACT_BYTES = (C / 8) * PLANE * 16;
-    static constexpr int EDGE_BYTES = NCS * PH * C * 2;
+    static constexpr int EDGE_BYTES = POOL3 ? 0 : NCS * PH * C * 2;
     // prefetch registers for the uint8 input: items of PRE_DW dwords, PRE_N per thread
     static constexpr int PRE_DW = INKIND == IN_U8_C3 ? 3 : (INKIND == IN_U8_PLANAR ? CIN / 4 : 1);
     static constexpr int PRE_ITEMS = INKIND == IN_U8_C3 ? (IROWS - 2) * (W / 4) : (INKIND == IN_U8_PLANAR ? (IROWS - 2 + 2) * W : 0);
@@ -377,6 +381,13 @@ __device__ __forceinline__ void prefetch_commit(const Prefetch<S>& p, char* buf0
     }
 }
 
+template <bool FIRST, class A, class B>
+__device__ __forceinline__ auto& pick_ref(A& a, B& b)
+{
+    if constexpr (FIRST) return a;
+    else return b;
+}
+
 // ---- conv0 + max-pool ----------------------------------------------------------------
 // h[n] = max(v[n], v[n+1], v[n+2]) within each row of 16 lanes, for the four channels a lane holds.
 // A DPP op whose source lane lies outside the row leaves its destination untouched, so lane 14 ends
@@ -462,22 +473,25 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
     const int npr = pr1 - pr0;
     const floatx4 NEG = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 
+    // Work split: the NCS * npr (column strip, pooled row) pairs, strip-major, cut into one run per wavefront; a
+    // run that crosses a strip boundary becomes two units.  Each unit recomputes the conv row above its first
+    // pooled row, so long runs keep that overhead small.
+    const int nq = S::NCS * npr;
+    const int q0 = wave * nq / RN_WAVES, q1 = (wave + 1) * nq / RN_WAVES;
 #pragma unroll 1
-    for (int ui = 0; ui < S::NU; ++ui) {
-        const int u = wave + RN_WAVES * ui;
-        if (u >= S::NUNITS) break;
-        const int cs = u % S::NCS, b = u / S::NCS;
-        const int pb0 = pr0 + b * npr / S::NB, pb1 = pr0 + (b + 1) * npr / S::NB;
-        if (pb0 >= pb1) continue;
+    for (int q = q0; q < q1;) {
+        const int cs = q / npr, pb0 = pr0 + q % npr;
+        const int pb1 = min(pr0 + npr, pb0 + (q1 - q));
+        q += pb1 - pb0;
         const int col = cs * 16 + n;
         const bool live = FULL || col < S::W;
         const int colc = live ? col : S::W - 1;
         // cell index of conv row r, tap (0,0): (r - 1 - rbuf0) * IPITCH + colc
         const int cbase = colc - (1 + rbuf0) * S::IPITCH;
         floatx4 top[S::FT];
-        // second fragment set (software pipeline) only where the registers allow it
-        constexpr bool PIPE = S::W0_FRAGS * 4 + S::KC0 * 16 <= 128;
-        bf16x8 fa[S::KC0], fb[S::KC0], ga[PIPE ? S::KC0 : 1], gb[PIPE ? S::KC0 : 1];
+        // a second fragment set (loads a whole iteration ahead) only where the registers allow it
+        constexpr bool TWO = S::W0_FRAGS * 4 + S::KC0 * 32 <= 136;
+        bf16x8 fa[S::KC0], fb[S::KC0], ga[TWO ? S::KC0 : 1], gb[TWO ? S::KC0 : 1];
         const int rt = 2 * pb0 - S::PADH;
         if (rt >= 0) {
             conv0_load<S>(fa, in, cbase + rt * S::IPITCH, koff);
@@ -497,16 +511,18 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
         const int xstep = wr_pool ? S::PITCH * 16 : 0, estep = wr_edge ? S::C * 2 : 0;
         const int xj = wr_pool ? 2 * S::PLANE * 16 : 0, ej = wr_edge ? 32 : 0;
 
-        // rows of pooled row py: mid = 2 py - PADH + 1 (always inside the image), bot = mid + 1 (may not exist)
+        // rows of pooled row py: mid = 2 py - PADH + 1 (always inside the image), bot = mid + 1 (may not exist);
+        // py past the unit's end re-reads its last row (the fragments are then never used)
         auto load_pair = [&](bf16x8 (&a)[S::KC0], bf16x8 (&c)[S::KC0], int py) {
-            const int rm = 2 * py - S::PADH + 1;
+            const int rm = 2 * (py < pb1 ? py : pb1 - 1) - S::PADH + 1;
             conv0_load<S>(a, in, cbase + rm * S::IPITCH, koff);
             conv0_load<S>(c, in, cbase + (rm + 1 < S::H ? rm + 1 : rm) * S::IPITCH, koff);
         };
-        auto finish_row = [&](const bf16x8 (&a)[S::KC0], const bf16x8 (&c)[S::KC0]) {
-            floatx4 mid[S::FT], bot[S::FT];
+        auto mma_pair = [&](floatx4 (&mid)[S::FT], floatx4 (&bot)[S::FT], const bf16x8 (&a)[S::KC0], const bf16x8 (&c)[S::KC0]) {
             conv0_mma<S>(mid, a, w0);
             conv0_mma<S>(bot, c, w0);
+        };
+        auto pool_row = [&](const floatx4 (&mid)[S::FT], const floatx4 (&bot)[S::FT]) {
 #pragma unroll
             for (int j = 0; j < S::FT; ++j) {
                 floatx4 v = max4(max4(top[j], mid[j]), bot[j]) * SCALE + bv[j];
@@ -519,21 +535,154 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
             xptr += xstep;
             eptr += estep;
         };
-        int py = pb0;
-        if constexpr (PIPE) {
-            // two pooled rows per iteration, all eight fragment loads first, no branches inside
+        // Software pipeline over pooled rows: while row py is pooled (vector ALU), the matrix cores multiply row
+        // py+1 and LDS delivers the fragments of row py+2 (py+3 with two fragment sets).  Accumulator sets
+        // (m0, b0) / (m1, b1) and fragment sets alternate, hence two rows per iteration.
+        // (32 input and output channels: fragments, weights and two accumulator sets exceed the register file;
+        // those sections run the plain load -> multiply -> pool loop)
+        constexpr bool SWP = S::W0_FRAGS * 4 + S::KC0 * 8 + S::FT * 16 <= 160;
+        floatx4 m0[S::FT], b0[S::FT], m1[SWP ? S::FT : 1], b1[SWP ? S::FT : 1];
+        if constexpr (!SWP) {
 #pragma unroll 1
-            for (; py + 1 < pb1; py += 2) {
+            for (int py = pb0; py < pb1; ++py) {
                 load_pair(fa, fb, py);
-                load_pair(ga, gb, py + 1);
-                finish_row(fa, fb);
-                finish_row(ga, gb);
+                mma_pair(m0, b0, fa, fb);
+                pool_row(m0, b0);
             }
-        }
+        } else {
+        auto& oa = pick_ref<TWO>(ga, fa);                                    // fragments of the odd rows
+        auto& ob = pick_ref<TWO>(gb, fb);
+        constexpr int LA = TWO ? 2 : 1;
+        int py = pb0;
+        load_pair(fa, fb, py);
+        if constexpr (TWO) load_pair(ga, gb, py + 1);
+        mma_pair(m0, b0, fa, fb);
+        load_pair(fa, fb, py + LA);
 #pragma unroll 1
-        for (; py < pb1; ++py) {
-            load_pair(fa, fb, py);
-            finish_row(fa, fb);
+        for (; py + 2 < pb1; py += 2) {
+            mma_pair(m1, b1, oa, ob);
+            load_pair(oa, ob, py + 1 + LA);
+            pool_row(m0, b0);
+            mma_pair(m0, b0, fa, fb);
+            load_pair(fa, fb, py + 2 + LA);
+            pool_row(m1, b1);
+        }
+        if (py + 1 < pb1) {
+            mma_pair(m1, b1, oa, ob);
+            pool_row(m0, b0);
+            pool_row(m1, b1);
+        } else {
+            pool_row(m0, b0);
+        }
+        }
+    }
+}
+
+// conv0 + pool for the 3-channel frame, without lane shifts: lane n of a unit owns POOLED column 16 sp + n
+// and the three conv columns under its pooling window (2 px, 2 px + 1, 2 px + 2) come from three MFMA tiles
+// whose B fragments sit one frame cell apart.  The 3-maximum is then lane-wise: every lane holds a pooled
+// value, no neighbour columns are exchanged, and the map is complete when the phase ends.  Half as many
+// vector instructions per pooled value as the shifted scheme, for 1.5 x the (cheap, K = 27) MFMAs.
+// The map's last pooled column has no third conv column: its lanes read the second one twice.
+//
+// B fragments are aligned to PAIRS of frame-buffer rows: P(k) = buffer rows 2k, 2k+1; lane group g -> row
+// 2k + (g >> 1), pixel pair g & 1 (two 4-channel cells).  The whole frame is resident (buffer row 0 = image
+// row -1), so conv row r reads buffer rows r, r+1, r+2:
+//   even r = 2k:   P(k) x fragment 0 (kernel rows 0 | 1)  +  P(k+1) x fragment 1 (kernel row 2 | zeros)
+//   odd  r = 2k+1: P(k) x fragment 2 (zeros | kernel row 0)  +  P(k+1) x fragment 3 (kernel rows 1 | 2)
+// Pooled row py (conv rows 2py, 2py+1, 2py+2; PADH == 0) therefore needs P(py), P(py+1), P(py+2) and each
+// new pooled row reads ONE new pair per tile.  The pairs rotate through three register slots, hence the
+// loop over pooled rows is unrolled by three.  The bottom pooled row has no third conv row.
+template <class S>
+__device__ __forceinline__ void conv0_pool3(const char* in, char* xout, const bf16x8 (&w0)[S::W0_FRAGS], const char* wslot,
+                                            int lane, int wave)
+{
+    static_assert(S::INKIND == IN_U8_C3 && S::FT == 1 && S::W0_FRAGS == 4 && S::NSTRIPS == 1 && S::PW % 16 == 0 &&
+                      S::PADH == 0 && S::H % 2 == 0,
+                  "conv0_pool3: whole 3-channel frame, even height, pooled width a multiple of 16");
+    const int g = lane >> 4, n = lane & 15;
+    constexpr float SCALE = 1.0f / 255.0f;
+    constexpr int ROWB = S::IPITCH * 8;                     // bytes per frame row (8-byte cells)
+    const floatx4 bv = *(const floatx4*)(wslot + S::W0_FRAGS * 1024 + g * 16);
+    const int koffp = (g >> 1) * S::IPITCH + (g & 1) * 2;
+    typedef bf16x8 Pair[3];                                 // one row pair's fragments, per tile d
+    constexpr int NSP = S::PW / 16;
+    constexpr int nq = NSP * S::PH;
+    const floatx4 ZERO = {0.f, 0.f, 0.f, 0.f};
+    const int q0 = wave * nq / RN_WAVES, q1 = (wave + 1) * nq / RN_WAVES;
+#pragma unroll 1
+    for (int q = q0; q < q1;) {
+        const int sp = q / S::PH, pb0 = q % S::PH;
+        const int pb1 = min(S::PH, pb0 + (q1 - q));
+        q += pb1 - pb0;
+        const int px = sp * 16 + n;
+        // pa: tiles d = 0, 1 (d = 1 one cell further: an immediate) of the pair the pointers sit on; pa2: tile d = 2
+        const char* pa = in + (2 * pb0 * S::IPITCH + 2 * px + koffp) * 8;
+        const char* pa2 = pa + (px == S::PW - 1 ? 8 : 16);
+        int kp = pb0;                                        // pair the pointers sit on; the map's last pair is PH
+        auto load_pair = [&](Pair& f) {
+#pragma unroll
+            for (int d = 0; d < 3; ++d) {
+                const char* c = d < 2 ? pa + d * 8 : pa2;
+                const bf16x4 lo = *(const bf16x4*)c, hi = *(const bf16x4*)(c + 8);
+                f[d] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+            const bool more = kp < S::PH;                    // past the last pair: stay (those fragments are never used)
+            pa += more ? 2 * ROWB : 0;
+            pa2 += more ? 2 * ROWB : 0;
+            kp += more ? 1 : 0;
+        };
+        // horizontal maximum over the three tiles of one conv row: PAR = 0 even row, 1 odd row
+        auto conv_row = [&](auto par, const Pair& lo, const Pair& hi) {
+            constexpr int P = decltype(par)::value;
+            floatx4 acc[3];
+#pragma unroll
+            for (int d = 0; d < 3; ++d) {
+                acc[d] = mfma16(w0[2 * P], lo[d], ZERO);
+                acc[d] = mfma16(w0[2 * P + 1], hi[d], acc[d]);
+            }
+            return max4(max4(acc[0], acc[1]), acc[2]);
+        };
+        using EVEN = std::integral_constant<int, 0>;
+        using ODD = std::integral_constant<int, 1>;
+        Pair F[3];                                           // pair k lives in F[(k - pb0) % 3]
+        load_pair(F[0]);
+        load_pair(F[1]);
+        floatx4 top = conv_row(EVEN{}, F[0], F[1]);
+        load_pair(F[2]);
+        char* xptr = xout + ((pb0 + 1) * S::PITCH + px + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
+        auto store_row = [&](floatx4 v) {
+            *(bf16x4*)xptr = to_bf16x4(v * SCALE + bv);
+            xptr += S::PITCH * 16;
+        };
+        auto row_step = [&](auto jj) {                       // pooled row py = pb0 + 3 i + J
+            constexpr int J = decltype(jj)::value;
+            const floatx4 hm = conv_row(ODD{}, F[J % 3], F[(J + 1) % 3]);
+            const floatx4 hb = conv_row(EVEN{}, F[(J + 1) % 3], F[(J + 2) % 3]);
+            load_pair(F[J % 3]);                             // pair py + 3 replaces pair py
+            store_row(max4(max4(top, hm), hb));
+            top = hb;
+        };
+        auto last_step = [&](auto jj) {                      // the map's bottom row: conv rows 2py, 2py+1 only
+            constexpr int J = decltype(jj)::value;
+            store_row(max4(top, conv_row(ODD{}, F[J % 3], F[(J + 1) % 3])));
+        };
+        using J0 = std::integral_constant<int, 0>; using J1 = std::integral_constant<int, 1>; using J2 = std::integral_constant<int, 2>;
+        const int lim = min(pb1, S::PH - 1);
+        int py = pb0;
+#pragma unroll 1
+        for (; py + 3 <= lim; py += 3) {
+            row_step(J0{});
+            row_step(J1{});
+            row_step(J2{});
+        }
+        const int r = lim - py;
+        if (r >= 1) row_step(J0{});
+        if (r == 2) row_step(J1{});
+        if (pb1 == S::PH) {
+            if (r == 0) last_step(J0{});
+            else if (r == 1) last_step(J1{});
+            else last_step(J2{});
         }
     }
 }
@@ -827,7 +976,8 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                 if (strip == 0) load_a_frags(w0, lds + SLOT_C0, lane);
                 int pr0, pr1, r0, r1;
                 strip_rows<S>(strip, pr0, pr1, r0, r1);
-                conv0_pool<S>(buf0, buf1, edge, lds + M::TRASH, w0, lds + SLOT_C0, pr0, pr1, r0 - 1, lane, wave);
+                if constexpr (S::POOL3) conv0_pool3<S>(buf0, buf1, w0, lds + SLOT_C0, lane, wave);
+                else conv0_pool<S>(buf0, buf1, edge, lds + M::TRASH, w0, lds + SLOT_C0, pr0, pr1, r0 - 1, lane, wave);
                 if (strip + 1 < S::NSTRIPS) lds_barrier();
             }
         }
@@ -853,14 +1003,14 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                 if (!S::SLIDE && !tile_ok) break;
                 // the pooled value of a strip's last column lacks its right neighbour: it is the next strip's edge
                 // column; every other lane reads the neutral (-inf) cell instead
-                const bool fix = (xx & 7) == 7 && xx + 1 < S::PW;
+                const bool fix = !S::POOL3 && (xx & 7) == 7 && xx + 1 < S::PW;
                 const int eoff = fix ? M::EDGE + (((((xx + 1) >> 3) * S::PH + y) * S::C + g * 4) * 2) : M::NEUTRAL;
                 const int ejmp = fix ? 32 : 0;
                 const int off = tb[i] * 16 + loff;
 #pragma unroll
                 for (int j = 0; j < S::FT; ++j) {
                     pv[i][j] = *(const bf16x4*)(buf1 + off + j * (2 * S::PLANE * 16));
-                    ev[i][j] = *(const bf16x4*)(lds + eoff + j * ejmp);
+                    if constexpr (!S::POOL3) ev[i][j] = *(const bf16x4*)(lds + eoff + j * ejmp);
                 }
             }
 #pragma unroll
@@ -869,10 +1019,16 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                 const int off = tb[i] * 16 + loff;
 #pragma unroll
                 for (int j = 0; j < S::FT; ++j) {
-                    const floatx4 v = max4(to_floatx4(pv[i][j]), to_floatx4(ev[i][j]));
-                    x[i][j] = v;
+                    bf16x4 r;
+                    if constexpr (S::POOL3) {
+                        x[i][j] = to_floatx4(pv[i][j]);
+                        r = pv[i][j];
+                    } else {
+                        x[i][j] = max4(to_floatx4(pv[i][j]), to_floatx4(ev[i][j]));
+                        r = to_bf16x4(x[i][j]);
+                    }
                     // a short chain's missing tiles rewrite its last tile with the same values
-                    if (S::SLIDE || ok[i]) *(bf16x4*)(buf0 + off + j * (2 * S::PLANE * 16)) = relu_bf16x4(to_bf16x4(v));
+                    if (S::SLIDE || ok[i]) *(bf16x4*)(buf0 + off + j * (2 * S::PLANE * 16)) = relu_bf16x4(r);
                 }
             }
         }
