@@ -281,6 +281,7 @@ struct SlideMap16 {
 // ---- uint8 frame prefetch --------------------------------------------------------
 template <class S>
 struct Prefetch {
+    using Sec = S;
     uint32_t d[S::PRE_N][S::PRE_DW];
 };
 
@@ -969,9 +970,10 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
         } else {
 #pragma unroll 1
             for (int strip = 0; strip < S::NSTRIPS; ++strip) {
-                prefetch_commit<S>(pre, buf0, strip, tid);
+                // strip 0 is already in buf0: the previous image's last phase (or the kernel prologue) put it there
+                if (strip > 0) prefetch_commit<S>(pre, buf0, strip, tid);
                 if (strip + 1 < S::NSTRIPS) prefetch_issue<S>(pre, obs_img, strip + 1, tid);
-                lds_barrier();
+                if (strip > 0) lds_barrier();
                 PHASE_MARK(SI * 8 + 0);
                 if (strip == 0) load_a_frags(w0, lds + SLOT_C0, lane);
                 int pr0, pr1, r0, r1;
@@ -1062,6 +1064,9 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     if constexpr (!LAST) issue(I5{});
     conv(BT{}, std::integral_constant<int, LAST ? 2 : 1>{}, buf1, buf0, lds + wslot<M, S>(QB + 3));
     if constexpr (!LAST) commit(I4{});
+    // The last layer writes to global memory, so buf0 is free: the next frame's first strip (prefetched into
+    // registers before this section) is converted into it here, under this phase's barrier.
+    if constexpr (LAST) prefetch_commit<typename PreT::Sec>(pre, buf0, 0, tid);
     lds_barrier();
     PHASE_MARK(SI * 8 + 7);
 }
@@ -1099,9 +1104,8 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
     WPipe pipe;
     Prefetch<S1> pre;
     prefetch_issue<S1>(pre, a.obs + FRAME * blockIdx.x, 0, tid);
-#ifdef SEEDINF_PRIO_MASK
-    if ((tid >> 6) & SEEDINF_PRIO_MASK) __builtin_amdgcn_s_setprio(2);
-#endif
+    prefetch_commit<S1>(pre, lds + M::BUF0, 0, tid);
+    lds_barrier();
     for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
@@ -1148,9 +1152,8 @@ __global__ __launch_bounds__(RN_THREADS) void resnet4_bf16_kernel(TorsoArgs a)
     WPipe pipe;
     Prefetch<S1> pre;
     prefetch_issue<S1>(pre, a.obs + FRAME * blockIdx.x, 0, tid);
-#ifdef SEEDINF_PRIO_MASK
-    if ((tid >> 6) & SEEDINF_PRIO_MASK) __builtin_amdgcn_s_setprio(2);
-#endif
+    prefetch_commit<S1>(pre, lds + M::BUF0, 0, tid);
+    lds_barrier();
     for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
