@@ -332,14 +332,28 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, const float* d_w
 }
 
 template <int EPI>
-inline void launch_gemm(hipStream_t st, const GemmArgs& g, int wave_groups, int n_cu)
+inline void launch_gemm(hipStream_t st, const GemmArgs& g, int tile_groups, int n_cu)
 {
-    // rows per wavefront (RT*16): the largest that still gives every compute unit at least two workgroups
-    const int gy = (wave_groups + 3) / 4;
+    // RT (row tiles of 16 per wavefront / block): the largest that still gives every compute unit two blocks
     const long want = 2L * n_cu;
-    if ((long)((g.rows + 63) / 64) * gy >= want) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI>), dim3((g.rows + 63) / 64, gy), dim3(256), 0, st, g);
-    else if ((long)((g.rows + 31) / 32) * gy >= want) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI>), dim3((g.rows + 31) / 32, gy), dim3(256), 0, st, g);
-    else hipLaunchKernelGGL((gemm_bf16_kernel<1, EPI>), dim3((g.rows + 15) / 16, gy), dim3(256), 0, st, g);
+    const int kct = g.kc1 + (g.k2 + 31) / 32;
+    if (kct >= 32) {
+        // long K: one block per (RT*16 rows, 4 feature tiles), K split over its wavefronts
+        const int gy = tile_groups;
+        auto go = [&](auto rt) {
+            constexpr int RT = decltype(rt)::value;
+            hipLaunchKernelGGL((gemm_bf16_splitk_kernel<RT, EPI>), dim3((g.rows + RT * 16 - 1) / (RT * 16), gy), dim3(256),
+                               4 * RT * 4 * 64 * sizeof(floatx4), st, g);
+        };
+        if ((long)((g.rows + 63) / 64) * gy >= want) go(std::integral_constant<int, 4>{});
+        else if ((long)((g.rows + 31) / 32) * gy >= want) go(std::integral_constant<int, 2>{});
+        else go(std::integral_constant<int, 1>{});
+    } else {
+        const int gy = (tile_groups + 3) / 4;
+        if ((long)((g.rows + 63) / 64) * gy >= want) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI>), dim3((g.rows + 63) / 64, gy), dim3(256), 0, st, g);
+        else if ((long)((g.rows + 31) / 32) * gy >= want) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI>), dim3((g.rows + 31) / 32, gy), dim3(256), 0, st, g);
+        else hipLaunchKernelGGL((gemm_bf16_kernel<1, EPI>), dim3((g.rows + 15) / 16, gy), dim3(256), 0, st, g);
+    }
 }
 
 template <int FT, bool U8>

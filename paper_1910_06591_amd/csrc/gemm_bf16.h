@@ -5,12 +5,21 @@
 //   k = kchunk*32 + 8*(lane/16) + e; padded with zeros to whole tiles/chunks.
 // Activations are read straight from their row-major bf16 (or fp32, converted
 // on load) buffer as B-operand fragments: 16 bytes per lane.
-// One wavefront owns 4 feature tiles x RT row tiles; a block is 4 wavefronts
-// that differ in their feature tiles.  K is walked in chunks of 32.
+// Two kernels, chosen by the length of K:
+//   gemm_bf16_kernel (short K, the recurrent core): a wavefront owns 4 feature
+//     tiles x RT row tiles and walks all of K; the block's 4 wavefronts differ
+//     in their feature tiles.
+//   gemm_bf16_splitk_kernel (long K, the linear layer after the torso): the
+//     block's 4 wavefronts share ONE output tile of RT*16 rows x 64 features
+//     and split K between them.  That layer has few outputs and a long K, so
+//     splitting rows or features further would have every compute unit re-read
+//     the whole weight matrix.  Each wavefront walks its quarter of K with three
+//     chunks of loads in flight, the partial sums meet in LDS, and wavefront r
+//     finishes row tile r.
 //
 // Epilogues:
 //   EPI_RELU : y = max(acc + bias, 0) stored as bf16 and/or fp32
-//   EPI_LSTM : the wavefront's 4 feature tiles are the i, f, g, o gates of the
+//   EPI_LSTM : the 4 feature tiles of a group are the i, f, g, o gates of the
 //              same 16 units; adds bias, the gathered previous-action row and
 //              reward * reward-row (all fp32), then the LSTM cell update
 //              (Appendix A.3.1: the core also sees the one-hot previous action
@@ -42,74 +51,12 @@ struct GemmArgs {
 
 __device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
 
+// Epilogue of one block tile: row tiles r with (only_r < 0 || r == only_r); wt = the tile group along features.
 template <int RT, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, floatx4 (&acc)[RT][4], int only_r, int wt, int r0, int lane)
 {
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
     const int g = lane >> 4, n = lane & 15;
-    const int wt = blockIdx.y * 4 + wave;              // wavefront's tile group along features
     const int ft0 = wt * 4;
-    if (ft0 >= p.n_ftiles) return;                     // uniform per wavefront
-    const int r0 = blockIdx.x * (RT * 16);
-    const int kc2 = (p.k2 + 31) >> 5;
-    const int kct = p.kc1 + kc2;
-
-    floatx4 acc[RT][4];
-#pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[r][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-    int rowi[RT];
-#pragma unroll
-    for (int r = 0; r < RT; ++r) rowi[r] = min(r0 + r * 16 + n, p.rows - 1);
-
-    const bf16x8* wl[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) wl[j] = p.wp + ((size_t)min(ft0 + j, p.n_ftiles - 1) * kct) * 64 + lane;
-
-    // K loop, software-pipelined: the fragments of chunk kc+1 are loaded while chunk kc is multiplied
-    auto load_chunk = [&](bf16x8 (&a)[4], bf16x8 (&b)[RT], int kc) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = wl[j][(size_t)kc * 64];
-        if (kc < p.kc1) {
-#pragma unroll
-            for (int r = 0; r < RT; ++r)
-                b[r] = *(const bf16x8*)(p.x1 + (size_t)rowi[r] * p.ld1 + kc * 32 + g * 8);
-        } else {
-            const int k = (kc - p.kc1) * 32 + g * 8;
-#pragma unroll
-            for (int r = 0; r < RT; ++r) {
-                floatx4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-                if (k + 8 <= p.k2) {
-                    const float* s = p.x2 + (size_t)rowi[r] * p.ld2 + k;
-                    lo = *(const floatx4*)s;
-                    hi = *(const floatx4*)(s + 4);
-                }
-                b[r] = to_bf16x8(lo, hi);
-            }
-        }
-    };
-    auto mma_chunk = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[RT]) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[r][j] = mfma16(a[j], b[r], acc[r][j]);
-    };
-    {
-        bf16x8 a0[4], b0[RT], a1[4], b1[RT];
-        load_chunk(a0, b0, 0);
-        int kc = 0;
-        for (; kc + 2 <= kct; kc += 2) {
-            load_chunk(a1, b1, kc + 1);
-            mma_chunk(a0, b0);
-            load_chunk(a0, b0, kc + 2 < kct ? kc + 2 : kct - 1);
-            mma_chunk(a1, b1);
-        }
-        if (kc < kct) mma_chunk(a0, b0);
-    }
-
     if constexpr (EPI == EPI_RELU) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -119,7 +66,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
 #pragma unroll
             for (int r = 0; r < RT; ++r) {
                 const int row = r0 + r * 16 + n;
-                if (row >= p.rows) continue;
+                if ((only_r >= 0 && r != only_r) || row >= p.rows) continue;
                 floatx4 v = relu4(acc[r][j] + bv);
                 if (p.y_bf16) *(bf16x4*)(p.y_bf16 + (size_t)row * p.ldy_bf16 + f) = to_bf16x4(v);
                 if (p.y_f32) {
@@ -132,7 +79,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
             }
         }
     } else {
-        // wavefront wt = unit tile; feature tile j = gate j of units wt*16 .. wt*16+15
+        // tile group wt = unit tile; feature tile j = gate j of units wt*16 .. wt*16+15
         const int Hn = p.Hn, G4 = 4 * p.Hn;
         const int u = wt * 16 + g * 4;                  // this lane's 4 consecutive units
         floatx4 bg[4], wr[4];
@@ -144,7 +91,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
 #pragma unroll
         for (int r = 0; r < RT; ++r) {
             const int row = r0 + r * 16 + n;
-            if (row >= p.rows) continue;
+            if ((only_r >= 0 && r != only_r) || row >= p.rows) continue;
             const int a = p.prev_action[row];
             const float rew = p.prev_reward[row];
             floatx4 pre[4];
@@ -164,6 +111,167 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
             *(floatx4*)(p.h_out + (size_t)row * Hn + u) = hn;
         }
     }
+}
+
+// K loop over the chunks [kb, ke) of one source segment, branch-free inside: NST rotating fragment sets keep
+// NST-1 stages of loads in flight while one is multiplied (these loops are bound by load latency and L1
+// capacity, so bytes in flight and whole cache lines are what counts).  A stage is CPS consecutive chunks: with
+// bf16 rows a chunk is 64 bytes of a row, so CPS = 2 (and an even kb) makes every activation load pair use a
+// whole 128-byte line while it is in L1.  F32: the activations of this segment are fp32 rows (converted when
+// multiplied; one chunk is a whole line), chunk numbering inside the segment starts at `seg0`, and only columns
+// < kvalid exist.
+template <int RT, int NST, int CPS, bool F32>
+__device__ __forceinline__ void gemm_k_loop(floatx4 (&acc)[RT][4], const bf16x8* const (&wl)[4], const void* xbase, int ld,
+                                            const int (&rowi)[RT], int kb, int ke, int seg0, int kvalid, int g)
+{
+    if (kb >= ke) return;
+    struct Stage {
+        bf16x8 a[CPS][4];
+        bf16x8 b[CPS][F32 ? 1 : RT];
+        floatx4 f[CPS][F32 ? RT : 1][2];
+    };
+    Stage st[NST];
+    auto load = [&](Stage& s, int k0) {                // chunks k0 .. k0+CPS-1; past the end: the last chunk again
+#pragma unroll
+        for (int c = 0; c < CPS; ++c) {
+            const int kc = k0 + c < ke ? k0 + c : ke - 1;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s.a[c][j] = wl[j][(size_t)kc * 64];
+            if constexpr (!F32) {
+                const __bf16* x = (const __bf16*)xbase;
+#pragma unroll
+                for (int r = 0; r < RT; ++r)
+                    s.b[c][r] = *(const bf16x8*)(x + (size_t)rowi[r] * ld + (kc - seg0) * 32 + g * 8);
+            } else {
+                const float* x = (const float*)xbase;
+                int k = (kc - seg0) * 32 + g * 8;
+                k = k + 8 <= kvalid ? k : 0;           // columns past the end: any valid address, zeroed when used
+#pragma unroll
+                for (int r = 0; r < RT; ++r) {
+                    const float* q = x + (size_t)rowi[r] * ld + k;
+                    s.f[c][r][0] = *(const floatx4*)q;
+                    s.f[c][r][1] = *(const floatx4*)(q + 4);
+                }
+            }
+        }
+    };
+    auto mma1 = [&](const Stage& s, int c, int kc) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            bf16x8 b;
+            if constexpr (!F32) {
+                b = s.b[c][r];
+            } else {
+                const bool ok = (kc - seg0) * 32 + g * 8 + 8 <= kvalid;
+                const floatx4 z = {0.f, 0.f, 0.f, 0.f};
+                b = to_bf16x8(ok ? s.f[c][r][0] : z, ok ? s.f[c][r][1] : z);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[r][j] = mfma16(s.a[c][j], b, acc[r][j]);
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < NST - 1; ++i) load(st[i], kb + i * CPS);
+    int kc = kb;
+    for (; kc + NST * CPS <= ke; kc += NST * CPS) {
+#pragma unroll
+        for (int i = 0; i < NST; ++i) {
+            load(st[(i + NST - 1) % NST], kc + (i + NST - 1) * CPS);
+#pragma unroll
+            for (int c = 0; c < CPS; ++c) mma1(st[i], c, kc + i * CPS + c);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NST - 1; ++i)                  // the last (fewer than NST) stages are already loaded
+#pragma unroll
+        for (int c = 0; c < CPS; ++c)
+            if (kc + i * CPS + c < ke) mma1(st[i], c, kc + i * CPS + c);
+}
+
+// ---- short K: the block's 4 wavefronts take different feature-tile groups, each walks all of K ----
+template <int RT, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, n = lane & 15;
+    const int wt = blockIdx.y * 4 + wave;              // wavefront's tile group along features
+    const int ft0 = wt * 4;
+    if (ft0 >= p.n_ftiles) return;                     // uniform per wavefront
+    const int r0 = blockIdx.x * (RT * 16);
+    const int kc2 = (p.k2 + 31) >> 5;
+    const int kct = p.kc1 + kc2;
+
+    floatx4 acc[RT][4];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[r][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    int rowi[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) rowi[r] = min(r0 + r * 16 + n, p.rows - 1);
+    const bf16x8* wl[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wl[j] = p.wp + ((size_t)min(ft0 + j, p.n_ftiles - 1) * kct) * 64 + lane;
+
+    gemm_k_loop<RT, 3, 2, false>(acc, wl, p.x1, p.ld1, rowi, 0, p.kc1, 0, 0, g);
+    gemm_k_loop<RT, 3, 1, true>(acc, wl, p.x2, p.ld2, rowi, p.kc1, kct, p.kc1, p.k2, g);
+    gemm_epilogue<RT, EPI>(p, acc, -1, wt, r0, lane);
+}
+
+// ---- long K: the block's 4 wavefronts share one output tile and split K ----
+template <int RT, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_splitk_kernel(GemmArgs p)
+{
+    extern __shared__ __attribute__((aligned(16))) char gemm_lds[];     // partial sums [wave][row tile][feature tile][lane]
+    floatx4* part = (floatx4*)gemm_lds;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, n = lane & 15;
+    const int wt = blockIdx.y;                         // the block's tile group along features
+    const int ft0 = wt * 4;
+    const int r0 = blockIdx.x * (RT * 16);
+    const int kc2 = (p.k2 + 31) >> 5;
+    const int kct = p.kc1 + kc2;
+    // this wavefront's K chunks: quarters of K cut at even chunks (whole 128-byte lines of the bf16 rows)
+    const int kpairs = (kct + 1) / 2;
+    const int k0 = 2 * (wave * kpairs / 4), k1 = min(2 * ((wave + 1) * kpairs / 4), kct);
+
+    floatx4 acc[RT][4];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[r][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    int rowi[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) rowi[r] = min(r0 + r * 16 + n, p.rows - 1);
+    const bf16x8* wl[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wl[j] = p.wp + ((size_t)min(ft0 + j, p.n_ftiles - 1) * kct) * 64 + lane;
+
+    gemm_k_loop<RT, 3, 2, false>(acc, wl, p.x1, p.ld1, rowi, k0, min(k1, p.kc1), 0, 0, g);
+    gemm_k_loop<RT, 3, 1, true>(acc, wl, p.x2, p.ld2, rowi, max(k0, p.kc1), k1, p.kc1, p.k2, g);
+
+    // K reduction: wavefront r keeps row tile r, the others hand theirs over through LDS
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        if (r == wave) continue;                       // uniform
+#pragma unroll
+        for (int j = 0; j < 4; ++j) part[((wave * RT + r) * 4 + j) * 64 + lane] = acc[r][j];
+    }
+    __syncthreads();
+    if (wave >= RT) return;
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        if (r != wave) continue;                       // uniform
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+            if (w2 == r) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[r][j] += part[((w2 * RT + r) * 4 + j) * 64 + lane];
+        }
+    }
+    gemm_epilogue<RT, EPI>(p, acc, wave, wt, r0, lane);
 }
 
 // bf16 rows -> fp32 rows (diagnostic tap)
