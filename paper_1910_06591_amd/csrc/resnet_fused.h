@@ -433,11 +433,13 @@ __device__ __forceinline__ void conv0_load(bf16x8 (&b)[S::KC0], const char* in, 
     }
 }
 
+// acc = init + W * b: `init` carries the bias (divided by the input scale), so the epilogue has no bias add
 template <class S>
-__device__ __forceinline__ void conv0_mma(floatx4 (&acc)[S::FT], const bf16x8 (&b)[S::KC0], const bf16x8 (&w0)[S::W0_FRAGS])
+__device__ __forceinline__ void conv0_mma(floatx4 (&acc)[S::FT], const bf16x8 (&b)[S::KC0], const bf16x8 (&w0)[S::W0_FRAGS],
+                                          const floatx4 (&init)[S::FT])
 {
 #pragma unroll
-    for (int j = 0; j < S::FT; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < S::FT; ++j) acc[j] = init[j];
 #pragma unroll
     for (int kc = 0; kc < S::KC0; ++kc)
 #pragma unroll
@@ -458,7 +460,7 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
     constexpr bool FULL = S::W % 16 == 0;                 // no partial column strip
     floatx4 bv[S::FT];
 #pragma unroll
-    for (int j = 0; j < S::FT; ++j) bv[j] = *(const floatx4*)(wslot + S::W0_FRAGS * 1024 + (j * 4 + g) * 16);
+    for (int j = 0; j < S::FT; ++j) bv[j] = *(const floatx4*)(wslot + S::W0_FRAGS * 1024 + (j * 4 + g) * 16) * (1.0f / SCALE);
     int koff[S::NK0];                                     // 3-channel frame: per-chunk offsets; planar: lane bases
     if constexpr (S::INKIND == IN_U8_C3) {
         // K slot s = kc*4 + g -> (kernel row s/2, pixel pair s%2); 8-byte cells
@@ -496,7 +498,7 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
         const int rt = 2 * pb0 - S::PADH;
         if (rt >= 0) {
             conv0_load<S>(fa, in, cbase + rt * S::IPITCH, koff);
-            conv0_mma<S>(top, fa, w0);
+            conv0_mma<S>(top, fa, w0, bv);
         } else {
 #pragma unroll
             for (int j = 0; j < S::FT; ++j) top[j] = NEG;
@@ -520,13 +522,14 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
             conv0_load<S>(c, in, cbase + (rm + 1 < S::H ? rm + 1 : rm) * S::IPITCH, koff);
         };
         auto mma_pair = [&](floatx4 (&mid)[S::FT], floatx4 (&bot)[S::FT], const bf16x8 (&a)[S::KC0], const bf16x8 (&c)[S::KC0]) {
-            conv0_mma<S>(mid, a, w0);
-            conv0_mma<S>(bot, c, w0);
+            conv0_mma<S>(mid, a, w0, bv);
+            conv0_mma<S>(bot, c, w0, bv);
         };
         auto pool_row = [&](const floatx4 (&mid)[S::FT], const floatx4 (&bot)[S::FT]) {
 #pragma unroll
             for (int j = 0; j < S::FT; ++j) {
-                floatx4 v = max4(max4(top[j], mid[j]), bot[j]) * SCALE + bv[j];
+                floatx4 v = max4(max4(top[j], mid[j]), bot[j]);
+                if (SCALE != 1.0f) v = v * SCALE;
                 if (!FULL && !live) v = NEG;
                 *(bf16x4*)(eptr + j * ej) = to_bf16x4(v);
                 const floatx4 h = hmax3_row16(v);
@@ -703,18 +706,6 @@ __device__ __forceinline__ void tile_pixel(int t, int n, int& y, int& xx)
     for (int k = 0; k < (15 + S::PW - 1) / S::PW; ++k)
         if (xx >= S::PW) { xx -= S::PW; ++y; }
     if (S::NPIX % 16 != 0 && y >= S::PH) { y = S::PH - 1; xx = S::PW - 1; }
-}
-
-template <class S>
-__device__ __forceinline__ void tile_table(int (&tb)[S::NT], int lane, int wave)
-{
-    const int n = lane & 15;
-#pragma unroll
-    for (int i = 0; i < S::NT; ++i) {
-        int y, xx;
-        tile_pixel<S>(wave + S::NWA * i, n, y, xx);
-        tb[i] = y * S::PITCH + xx;
-    }
 }
 
 // Pooled pixel (y, xx) that lane n holds in the wavefront's tile i (clamped into the map), whether the tile
