@@ -338,16 +338,19 @@ inline void launch_gemm(hipStream_t st, const GemmArgs& g, int tile_groups, int 
     const long want = 2L * n_cu;
     const int kct = g.kc1 + (g.k2 + 31) / 32;
     if (kct >= 32) {
-        // long K: one block per (RT*16 rows, 4 feature tiles), K split over its wavefronts
+        // long K: one block per (RT*16 rows, 4 feature tiles), K split over its wavefronts.  The loop is bound by
+        // the load instructions each compute unit issues, so the largest tile that still gives every compute
+        // unit a block wins, with 8 wavefronts to keep enough loads in flight.
         const int gy = tile_groups;
-        auto go = [&](auto rt) {
-            constexpr int RT = decltype(rt)::value;
-            hipLaunchKernelGGL((gemm_bf16_splitk_kernel<RT, EPI>), dim3((g.rows + RT * 16 - 1) / (RT * 16), gy), dim3(256),
+        auto go = [&](auto rt, auto nw) {
+            constexpr int RT = decltype(rt)::value, NW = decltype(nw)::value;
+            hipLaunchKernelGGL((gemm_bf16_splitk_kernel<RT, EPI, NW>), dim3((g.rows + RT * 16 - 1) / (RT * 16), gy), dim3(NW * 64),
                                4 * RT * 4 * 64 * sizeof(floatx4), st, g);
         };
-        if ((long)((g.rows + 63) / 64) * gy >= want) go(std::integral_constant<int, 4>{});
-        else if ((long)((g.rows + 31) / 32) * gy >= want) go(std::integral_constant<int, 2>{});
-        else go(std::integral_constant<int, 1>{});
+        using W4 = std::integral_constant<int, 4>; using W8 = std::integral_constant<int, 8>;
+        if ((long)((g.rows + 63) / 64) * gy >= n_cu) go(std::integral_constant<int, 4>{}, W8{});
+        else if ((long)((g.rows + 31) / 32) * gy >= n_cu) go(std::integral_constant<int, 2>{}, W8{});
+        else go(std::integral_constant<int, 1>{}, W4{});
     } else {
         const int gy = (tile_groups + 3) / 4;
         if ((long)((g.rows + 63) / 64) * gy >= want) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI>), dim3((g.rows + 63) / 64, gy), dim3(256), 0, st, g);

@@ -13,9 +13,9 @@
 //     block's 4 wavefronts share ONE output tile of RT*16 rows x 64 features
 //     and split K between them.  That layer has few outputs and a long K, so
 //     splitting rows or features further would have every compute unit re-read
-//     the whole weight matrix.  Each wavefront walks its quarter of K with three
-//     chunks of loads in flight, the partial sums meet in LDS, and wavefront r
-//     finishes row tile r.
+//     the whole weight matrix.  4 or 8 wavefronts per block: each walks its
+//     share of K with three stages of loads in flight, the partial sums meet
+//     in LDS, and wavefront r finishes row tile r.
 //
 // Epilogues:
 //   EPI_RELU : y = max(acc + bias, 0) stored as bf16 and/or fp32
@@ -220,9 +220,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
 }
 
 // ---- long K: the block's 4 wavefronts share one output tile and split K ----
-template <int RT, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_splitk_kernel(GemmArgs p)
+template <int RT, int EPI, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
 {
+    static_assert(NW == 4 || NW == 8, "4 or 8 wavefronts share the output tile");
     extern __shared__ __attribute__((aligned(16))) char gemm_lds[];     // partial sums [wave][row tile][feature tile][lane]
     floatx4* part = (floatx4*)gemm_lds;
     const int lane = threadIdx.x & 63;
@@ -233,9 +234,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_splitk_kernel(GemmArgs p)
     const int r0 = blockIdx.x * (RT * 16);
     const int kc2 = (p.k2 + 31) >> 5;
     const int kct = p.kc1 + kc2;
-    // this wavefront's K chunks: quarters of K cut at even chunks (whole 128-byte lines of the bf16 rows)
+    // this wavefront's K chunks: an NW-th of K cut at even chunks (whole 128-byte lines of the bf16 rows)
     const int kpairs = (kct + 1) / 2;
-    const int k0 = 2 * (wave * kpairs / 4), k1 = min(2 * ((wave + 1) * kpairs / 4), kct);
+    const int k0 = 2 * (wave * kpairs / NW), k1 = min(2 * ((wave + 1) * kpairs / NW), kct);
 
     floatx4 acc[RT][4];
 #pragma unroll
@@ -252,7 +253,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_splitk_kernel(GemmArgs p)
     gemm_k_loop<RT, 3, 2, false>(acc, wl, p.x1, p.ld1, rowi, k0, min(k1, p.kc1), 0, 0, g);
     gemm_k_loop<RT, 3, 1, true>(acc, wl, p.x2, p.ld2, rowi, max(k0, p.kc1), k1, p.kc1, p.k2, g);
 
-    // K reduction: wavefront r keeps row tile r, the others hand theirs over through LDS
+    // K reduction through LDS.  With 8 wavefronts the upper four first hand everything to the lower four.
+    if constexpr (NW == 8) {
+        if (wave >= 4) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) part[(((wave - 4) * RT + r) * 4 + j) * 64 + lane] = acc[r][j];
+        }
+        __syncthreads();
+        if (wave >= 4) return;
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[r][j] += part[((wave * RT + r) * 4 + j) * 64 + lane];
+        // (wavefront w has read only region w of the buffer, the region it writes next; the barrier below
+        // counts the four wavefronts that are still alive)
+    }
+    // Wavefront r keeps row tile r, the others hand theirs over
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
         if (r == wave) continue;                       // uniform
