@@ -200,10 +200,25 @@ class Oracle:
     def torso_features(self, arch: Arch) -> int:
         return int(self.lib.oracle_torso_features(C.byref(arch)))
 
+    def episode_state(self, done, h_in, c_in):
+        h_in, c_in = self._r(h_in), self._r(c_in)
+        h0, c0 = np.empty_like(h_in), np.empty_like(c_in)
+        self.lib.oracle_episode_state(int(done), self._p(h_in), self._p(c_in), h_in.size, self._p(h0), self._p(c0))
+        return h0, c0
+
+    def epsilon_greedy(self, selected, A, eps, u0, u1):
+        r = self.dtype.type if hasattr(self.dtype, "type") else self.dtype
+        ct = C.c_double if np.dtype(self.dtype) == np.float64 else C.c_float
+        self.lib.oracle_epsilon_greedy.restype = C.c_int
+        return int(self.lib.oracle_epsilon_greedy(int(selected), int(A), ct(float(r(eps))), ct(float(r(u0))), ct(float(r(u1)))))
+
     def forward(self, arch: Arch, weights, obs, prev_action=None, prev_reward=None,
-                h_in=None, c_in=None, uniforms=None, want_intermediates=False):
+                h_in=None, c_in=None, uniforms=None, want_intermediates=False,
+                done=None, epsilon=None, explore_u=None):
         """Returns a dict of numpy arrays: action, logits, value, probs, margin
-        and, with a recurrent core, h and c; plus torso_feat / fc_act on request."""
+        and, with a recurrent core, h and c; plus torso_feat / fc_act on request.
+        done [B] uint8, epsilon [B] and explore_u [B, 2] are optional (episode
+        flags and epsilon-greedy exploration)."""
         obs = np.ascontiguousarray(obs, dtype=np.uint8)
         B = obs.shape[0]
         A, Hn = arch.num_actions, arch.lstm_units
@@ -231,9 +246,16 @@ class Oracle:
         if want_intermediates:
             out["torso_feat"] = np.empty((B, self.torso_features(arch)), self.dtype)
             out["fc_act"] = np.empty((B, arch.fc_units), self.dtype)
-        rc = self.lib.oracle_forward(
+        dn = ep = eu = None
+        if done is not None:
+            dn = np.ascontiguousarray(done, dtype=np.uint8)
+            assert dn.shape == (B,) and Hn > 0
+        if epsilon is not None:
+            ep, eu = self._r(epsilon), self._r(explore_u)
+            assert ep.shape == (B,) and eu.shape == (B, 2)
+        rc = self.lib.oracle_forward_ext(
             C.byref(arch), self._p(weights), B, self._p(obs), self._p(pa), self._p(pr),
-            self._p(hi), self._p(ci), self._p(un),
+            self._p(hi), self._p(ci), self._p(un), self._p(dn), self._p(ep), self._p(eu),
             self._p(out["action"]), self._p(out["logits"]), self._p(out["value"]),
             self._p(out.get("h")), self._p(out.get("c")), self._p(out["probs"]),
             self._p(out["margin"]), self._p(out.get("torso_feat")), self._p(out.get("fc_act")))

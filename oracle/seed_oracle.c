@@ -402,6 +402,34 @@ int64_t oracle_torso_features(const oracle_arch *a)
     return (int64_t)H * W * C;
 }
 
+/* ------------------------------------------- episode boundary, exploration */
+
+/* Episode termination flags reach the inference thread together with the
+ * observations (Section 3, "Detailed Learner architecture"): a row whose flag
+ * is set starts a new episode, so its recurrent core runs from the zero state
+ * instead of the stored one.  Writes the state the core must use. */
+void oracle_episode_state(int done, const real *h_in, const real *c_in, int Hn, real *h0, real *c0)
+{
+    for (int i = 0; i < Hn; ++i) {
+        h0[i] = done ? (real)0 : h_in[i];
+        c0[i] = done ? (real)0 : c_in[i];
+    }
+}
+
+/* epsilon-greedy exploration (Appendix A.3.1: actor i of N acts epsilon-greedily
+ * with epsilon_i = 0.4^(1 + 7 i / (N - 1))): with probability eps the action is
+ * drawn uniformly from the A actions, otherwise the selected action is kept.
+ * Both draws are caller uniforms in [0, 1): explore iff u0 < eps; the random
+ * action is floor(u1 * A), clamped to A - 1. */
+int oracle_epsilon_greedy(int selected, int A, real eps, real u0, real u1)
+{
+    if (!(u0 < eps)) return selected;
+    int r = (int)floor((double)u1 * (double)A);
+    if (r < 0) r = 0;
+    if (r > A - 1) r = A - 1;
+    return r;
+}
+
 /* -------------------------------------------------------------- forward */
 
 static void forward_row(const oracle_arch *a, const real *w, const uint8_t *obs,
@@ -494,11 +522,33 @@ static void forward_row(const oracle_arch *a, const real *w, const uint8_t *obs,
  * Optional outputs (may be NULL): probs [B,A], margin [B] (top1 - top2 of
  * what the selection compared), torso_feat [B, H*W*C] (ReLU'd, flattened
  * torso output), fc_act [B, fc_units].  Returns 0, or -1 on a bad arch. */
+int oracle_forward_ext(const oracle_arch *a, const real *weights, int B,
+                       const uint8_t *obs, const int32_t *prev_action, const real *prev_reward,
+                       const real *h_in, const real *c_in, const real *uniforms,
+                       const uint8_t *done, const real *epsilon, const real *explore_u,
+                       int32_t *action, real *logits, real *value, real *h_out, real *c_out,
+                       real *probs, real *margin, real *torso_feat, real *fc_act);
+
 int oracle_forward(const oracle_arch *a, const real *weights, int B,
                    const uint8_t *obs, const int32_t *prev_action, const real *prev_reward,
                    const real *h_in, const real *c_in, const real *uniforms,
                    int32_t *action, real *logits, real *value, real *h_out, real *c_out,
                    real *probs, real *margin, real *torso_feat, real *fc_act)
+{
+    return oracle_forward_ext(a, weights, B, obs, prev_action, prev_reward, h_in, c_in, uniforms, NULL, NULL, NULL,
+                              action, logits, value, h_out, c_out, probs, margin, torso_feat, fc_act);
+}
+
+/* The step with episode flags and epsilon-greedy exploration (each optional):
+ * done [B] uint8 (non-zero: the row's core starts from the zero state),
+ * epsilon [B] and explore_u [B,2] (see oracle_epsilon_greedy; applied after
+ * the greedy / Gumbel-max selection, logits and values are unaffected). */
+int oracle_forward_ext(const oracle_arch *a, const real *weights, int B,
+                       const uint8_t *obs, const int32_t *prev_action, const real *prev_reward,
+                       const real *h_in, const real *c_in, const real *uniforms,
+                       const uint8_t *done, const real *epsilon, const real *explore_u,
+                       int32_t *action, real *logits, real *value, real *h_out, real *c_out,
+                       real *probs, real *margin, real *torso_feat, real *fc_act)
 {
     int64_t flat = oracle_torso_features(a);
     if (flat <= 0 || oracle_weight_count(a) <= 0) return -1;
@@ -507,10 +557,15 @@ int oracle_forward(const oracle_arch *a, const real *weights, int B,
 #pragma omp parallel for schedule(dynamic, 1)
     for (int b = 0; b < B; ++b) {
         real m = 0;
+        real *h0 = NULL, *c0 = NULL;
+        if (Hn > 0) {
+            h0 = (real *)malloc(sizeof(real) * (size_t)Hn);
+            c0 = (real *)malloc(sizeof(real) * (size_t)Hn);
+            oracle_episode_state(done ? done[b] : 0, h_in + (int64_t)Hn * b, c_in + (int64_t)Hn * b, Hn, h0, c0);
+        }
         forward_row(a, weights, obs + frame * b,
                     Hn > 0 ? prev_action[b] : 0, Hn > 0 ? prev_reward[b] : (real)0,
-                    Hn > 0 ? h_in + (int64_t)Hn * b : NULL,
-                    Hn > 0 ? c_in + (int64_t)Hn * b : NULL,
+                    h0, c0,
                     a->select ? uniforms + (int64_t)A * b : NULL,
                     action + b, logits + (int64_t)A * b, value + b,
                     Hn > 0 ? h_out + (int64_t)Hn * b : NULL,
@@ -518,7 +573,10 @@ int oracle_forward(const oracle_arch *a, const real *weights, int B,
                     probs ? probs + (int64_t)A * b : NULL, &m,
                     torso_feat ? torso_feat + flat * b : NULL,
                     fc_act ? fc_act + (int64_t)a->fc_units * b : NULL);
+        if (epsilon) action[b] = oracle_epsilon_greedy(action[b], A, epsilon[b], explore_u[2 * b], explore_u[2 * b + 1]);
         if (margin) margin[b] = m;
+        free(h0);
+        free(c0);
     }
     return 0;
 }

@@ -197,6 +197,27 @@ def make_uniforms(cfg, batch=None, seed=None):
     return np.clip(u, np.float32(1e-7), np.float32(1.0 - 6e-8))
 
 
+def epsilon_schedule(n_actors: int) -> np.ndarray:
+    """Exploration rate of each of N training actors (Appendix A.3.1, agent hyperparameter table):
+    epsilon_i = 0.4 ** (1 + 7 i / (N - 1)); evaluation uses 1e-3."""
+    i = np.arange(n_actors, dtype=np.float64)
+    return (0.4 ** (1.0 + 7.0 * i / max(n_actors - 1, 1))).astype(np.float32)
+
+
+def make_episode_inputs(cfg, batch=None, seed=None, done_rate=0.05):
+    """Episode flags and exploration inputs of one step: done [B] uint8 (a row starts a new episode with
+    probability done_rate), epsilon [B] (the training schedule over B actors) and explore_u [B, 2] uniforms.
+    Seed 3500 + config index."""
+    B = cfg["batch"] if batch is None else batch
+    if seed is None:
+        seed = 3500 + cfg["index"]
+    rng = np.random.default_rng(seed)
+    done = (rng.random(B) < done_rate).astype(np.uint8)
+    eps = epsilon_schedule(B)
+    u = rng.random((B, 2), dtype=np.float32)
+    return done, eps, u
+
+
 def make_batch(cfg, batch=None, seed_shift=0):
     """All step inputs for one batch as a dict of numpy arrays."""
     B = cfg["batch"] if batch is None else batch

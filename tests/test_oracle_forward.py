@@ -20,7 +20,8 @@ def read_golden():
         line = line.split("#")[0].strip()
         if "=" in line:
             k, v = (t.strip() for t in line.split("="))
-            d[k] = [int(t) for t in v.split(",")] if "," in v else int(v)
+            num = lambda t: int(t) if t.lstrip("-").isdigit() else float(t)
+            d[k] = [num(t) for t in v.split(",")] if "," in v else num(v)
     return d
 
 
