@@ -82,6 +82,44 @@ def time_config(cfg, B, steps, warmup, weights=None, profile=True):
     return res
 
 
+def time_extensions(cfg, B, weights):
+    """The step with episode flags + epsilon-greedy, and the weight hot-swap between steps (extras, not `value`)."""
+    import numpy as np
+    import torch
+    from paper_1910_06591_amd import seedinf, workloads as wl
+
+    batch = wl.make_batch(cfg, B)
+    dev = {k: (None if v is None else torch.from_numpy(v).cuda()) for k, v in batch.items()}
+    done, eps, eu = wl.make_episode_inputs(cfg, B)
+    ext = dict(done=torch.from_numpy(done).cuda(), epsilon=torch.from_numpy(eps).cuda(),
+               explore_uniforms=torch.from_numpy(eu).cuda())
+    net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=B), weights)
+    out = net.step(**dev, **ext)
+    torch.cuda.synchronize()
+
+    def p50(fn, n=40):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in evs:
+            a.record(); fn(); b.record()
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(b) for a, b in evs]))
+
+    res = {"step_ext_p50_ms": p50(lambda: net.step(out=out, **dev, **ext))}
+    # weight refresh: host time of the call (repack + enqueue) and a step issued right behind it
+    t = []
+    for _ in range(5):
+        t0 = time.perf_counter()
+        net.set_weights(weights)
+        t.append((time.perf_counter() - t0) * 1e3)
+        net.step(out=out, **dev)
+    torch.cuda.synchronize()
+    res["set_weights_host_ms"] = float(np.median(t))
+    res["step_after_set_weights_p50_ms"] = p50(lambda: (net.set_weights(weights), net.step(out=out, **dev)), n=5)
+    res["weights_mb"] = weights.size * 4 / 1e6
+    net.close()
+    return res
+
+
 def cpu_baseline(cfg, rows):
     """The CPU oracle as it stands, on `rows` rows of the same workload."""
     import oracle
@@ -185,6 +223,7 @@ def main():
                            "frames_per_s": c["batch"] / (s["p50_ms"] * 1e-3), "p50_ms": s["p50_ms"],
                            "tflops": 2.0 * wl.macs_per_frame(c) * c["batch"] / (s["p50_ms"] * 1e-3) / 1e12})
         line["other_workloads"] = others
+        line["extensions"] = time_extensions(cfg, B, weights)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(cfg, args.cpu_rows)
     print(json.dumps(line))

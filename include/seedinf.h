@@ -163,6 +163,68 @@ seed_status_t seed_infer_step(seed_infer_t* handle, int32_t B,
                               void* hip_stream);
 
 /*
+ * The step with episode boundaries and epsilon-greedy exploration.
+ *
+ * Section 3 ("Detailed Learner architecture"): the inference thread receives
+ * episode termination flags with the observations; Appendix A.3.1 (agent
+ * hyperparameters): training actor i of N acts epsilon-greedily with
+ * epsilon_i = 0.4^(1 + 7 i / (N - 1)), evaluation uses 1e-3.  `ext` carries the
+ * extra inputs, all device pointers, each optional (NULL = absent; ext == NULL
+ * or all fields NULL makes this call identical to seed_infer_step):
+ *
+ *   done              [B] uint8; a non-zero flag means the row starts a new
+ *                     episode: its recurrent core runs from the zero state and
+ *                     h_in / c_in of that row are not read.  prev_action and
+ *                     prev_reward are used as given.  Recurrent archs only
+ *                     (SEED_ERR_INVALID_ARG otherwise).
+ *   epsilon           [B] fp32 exploration rates, with
+ *   explore_uniforms  [B, 2] fp32 uniforms in [0, 1): after the greedy /
+ *                     Gumbel-max selection, a row with u0 < epsilon takes the
+ *                     action min(floor(u1 * num_actions), num_actions - 1)
+ *                     instead.  logits_out, value_out and probs_out are
+ *                     unaffected.  The two must be given together.
+ *
+ * Set struct_size = sizeof(seed_step_ext_t).  Everything else (arguments,
+ * stream behaviour, error returns) is as for seed_infer_step.
+ */
+typedef struct seed_step_ext {
+    uint32_t struct_size;
+    const uint8_t* done;
+    const float* epsilon;
+    const float* explore_uniforms;
+} seed_step_ext_t;
+
+seed_status_t seed_infer_step_ext(seed_infer_t* handle, int32_t B,
+                                  const uint8_t* obs,
+                                  const int32_t* prev_action, const float* prev_reward,
+                                  const float* h_in, const float* c_in,
+                                  const float* uniforms, const seed_step_ext_t* ext,
+                                  int32_t* action_out, float* logits_out, float* value_out,
+                                  float* h_out, float* c_out, float* probs_out,
+                                  void* hip_stream);
+
+/*
+ * Replace the weights of a live handle (Section 3: the learner holds the only
+ * copy of the model and the inference threads always use the latest one, so
+ * every training step is followed by a weight refresh of the inference path).
+ *
+ *   weights_host  host pointer, the same flat layout and count as at creation;
+ *                 copied (and repacked for the matrix-core kernels) before the
+ *                 call returns: the caller may reuse the buffer at once.
+ *
+ * The handle keeps two device copies of its weights.  The call fills the idle
+ * copy with asynchronous copies enqueued on `hip_stream` and then makes it the
+ * active one: steps enqueued afterwards use the new weights, steps enqueued
+ * before keep the old ones, and no step waits for the upload.  Steps and
+ * updates must be enqueued on the same stream (or be ordered by the caller):
+ * the update after next overwrites the copy that steps enqueued before this
+ * call are still reading.  Allocates nothing.  SEED_ERR_INVALID_ARG on a null
+ * pointer or a wrong count; the active weights are then unchanged.
+ */
+seed_status_t seed_infer_set_weights(seed_infer_t* handle, const float* weights_host,
+                                     size_t n_weights, void* hip_stream);
+
+/*
  * Test/diagnostic tap: copy an intermediate of the most recent step into a
  * device buffer as fp32 (converted from the internal storage type), enqueued
  * on `hip_stream` after the step's work.  which = 0: the rectified, flattened

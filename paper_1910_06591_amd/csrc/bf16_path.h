@@ -86,17 +86,38 @@ inline void pack_a(std::vector<uint16_t>& out, int n_ftiles, int kchunks, F valu
 
 struct ConvStackLayerDev { size_t wp_off; size_t koff_off; int kchunks; };
 
+// Device pointers into one uploaded copy of the packed weights.
+struct Bf16WeightSet {
+    const bf16x8* wp_fc = nullptr; const float* bias_fc = nullptr;
+    const bf16x8* wp_lstm = nullptr;
+    const bf16x8* wp_hid = nullptr; const float* bias_hid = nullptr;
+    const bf16x8* wp_conv = nullptr;
+    SecWeights sec[4];
+};
+
+// Host-side result of packing one set of weights; the offsets depend on the arch only.
+struct Bf16Packed {
+    std::vector<uint16_t> pk;                  // all packed bf16 weights
+    std::vector<float> fb;                     // padded fp32 biases
+    std::vector<int> ko;                       // conv-stack offset tables (weight-independent)
+    size_t sec_off[4][5] = {};
+    size_t off_fc = 0, off_bfc = 0, off_lstm = 0, off_hid = 0, off_bhid = 0;
+    std::vector<ConvStackLayerDev> stack;
+    int kc_fc = 0, ft_fc = 0, kc1_lstm = 0, ft_hid = 0;
+};
+
 struct Bf16State {
     int torso_kind = TORSO_NONE;
     int n_cu = 256;
     char* arena = nullptr;
-    // packed weights (byte offsets into arena resolved to pointers)
-    const bf16x8* wp_fc = nullptr; const float* bias_fc = nullptr; int kc_fc = 0, ft_fc = 0;
-    const bf16x8* wp_lstm = nullptr; int kc1_lstm = 0;
-    const bf16x8* wp_hid = nullptr; const float* bias_hid = nullptr; int ft_hid = 0;
+    // two copies of the packed weights: steps read ws[active]; a weight update fills the other and flips
+    Bf16WeightSet ws[2];
+    int active = 0;
+    size_t o_pk[2] = {0, 0}, o_fb[2] = {0, 0};
+    size_t pk_bytes = 0, fb_bytes = 0;
+    int kc_fc = 0, ft_fc = 0, kc1_lstm = 0, ft_hid = 0;
     std::vector<ConvStackLayerDev> stack;
-    const bf16x8* wp_conv = nullptr; const int* koff = nullptr;
-    SecWeights sec[4];
+    const int* koff = nullptr;
     // activations
     __bf16* act[2] = {nullptr, nullptr};
     __bf16* feat = nullptr; int ldf = 0;
@@ -179,26 +200,16 @@ inline void pack_section(std::vector<uint16_t>& pk, const float* w, const Sectio
     }
 }
 
-inline seed_status_t bf16_create(const Plan& p, const float* w, const float* d_w, Bf16State** out, std::string& err)
+// Packs every layer's weights for the bf16 kernels (host side; `w` = canonical flat fp32 weights).
+inline void bf16_pack(const Plan& p, int torso_kind, int ldf_, int ldfc_, const float* w, Bf16Packed& o)
 {
     const seed_arch_t& a = p.arch;
-    Bf16State* s = new Bf16State;
-    *out = s;                                  // owned by the handle from here on (freed on any failure by the caller)
-    int dev = 0;
-    BF_TRY(hipGetDevice(&dev));
-    hipDeviceProp_t prop;
-    BF_TRY(hipGetDeviceProperties(&prop, dev));
-    s->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    s->torso_kind = match_resnet(a);
-    s->ldf = round_up((int)p.flat, 32);
-    s->ldfc = round_up(a.fc_units, 32);
-
-    std::vector<uint16_t> pk;                  // all packed bf16 weights
-    std::vector<float> fb;                     // padded fp32 biases
-    std::vector<int> ko;                       // conv-stack offset tables
-    size_t sec_off[4][5];
+    std::vector<uint16_t>& pk = o.pk;
+    std::vector<float>& fb = o.fb;
+    std::vector<int>& ko = o.ko;
+    size_t (&sec_off)[4][5] = o.sec_off;
     if (a.torso == SEED_TORSO_RESNET) {
-        if (s->torso_kind == TORSO_DMLAB) {
+        if (torso_kind == TORSO_DMLAB) {
             pack_section<DmS1>(pk, w, p.sections[0], sec_off[0]);
             pack_section<DmS2>(pk, w, p.sections[1], sec_off[1]);
             pack_section<DmS3>(pk, w, p.sections[2], sec_off[2]);
@@ -223,31 +234,30 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, const float* d_w
                     int kh = k0 / (c.k * c.Cin), rem = k0 % (c.k * c.Cin);
                     ko.push_back(kh * c.W * c.Cin + rem);
                 }
-            s->stack.push_back(d);
+            o.stack.push_back(d);
         }
     }
     // linear layer: K = ldf (zero rows past flat), features padded to whole tiles
     const int F = a.fc_units;
-    s->ft_fc = (F + 15) / 16;
-    s->kc_fc = s->ldf / 32;
-    const size_t off_fc = pk.size();
+    o.ft_fc = (F + 15) / 16;
+    o.kc_fc = ldf_ / 32;
+    o.off_fc = pk.size();
     {
         const float* wf = w + p.fc_w;
         const int flat = (int)p.flat;
-        pack_a(pk, s->ft_fc, s->kc_fc, [&](int f, int k) -> float { return (k < flat && f < F) ? wf[(size_t)k * F + f] : 0.f; });
+        pack_a(pk, o.ft_fc, o.kc_fc, [&](int f, int k) -> float { return (k < flat && f < F) ? wf[(size_t)k * F + f] : 0.f; });
     }
-    const size_t off_bfc = fb.size();
-    for (int f = 0; f < s->ft_fc * 16; ++f) fb.push_back(f < F ? w[p.fc_b + f] : 0.f);
+    o.off_bfc = fb.size();
+    for (int f = 0; f < o.ft_fc * 16; ++f) fb.push_back(f < F ? w[p.fc_b + f] : 0.f);
     // LSTM: K = [ldfc feature columns | h columns]; feature tile (ut, gate)
-    size_t off_lstm = 0;
     const int Hn = a.lstm_units;
     if (Hn > 0) {
-        off_lstm = pk.size();
-        s->kc1_lstm = s->ldfc / 32;
+        o.off_lstm = pk.size();
+        o.kc1_lstm = ldfc_ / 32;
         const int kc2 = (Hn + 31) / 32;
         const float* wl = w + p.lstm_w;
-        const int G4 = 4 * Hn, ldfc = s->ldfc, A = a.num_actions;
-        pack_a(pk, (Hn / 16) * 4, s->kc1_lstm + kc2, [&](int f, int k) -> float {
+        const int G4 = 4 * Hn, ldfc = ldfc_, A = a.num_actions;
+        pack_a(pk, (Hn / 16) * 4, o.kc1_lstm + kc2, [&](int f, int k) -> float {
             int ft = f / 16, m = f % 16;
             int col = (ft % 4) * Hn + (ft / 4) * 16 + m;
             if (k < ldfc) return k < F ? wl[(size_t)k * G4 + col] : 0.f;
@@ -256,30 +266,76 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, const float* d_w
         });
     }
     // dueling hidden layers: features [value stream | advantage stream]
-    size_t off_hid = 0, off_bhid = 0;
     if (a.head == SEED_HEAD_DUELING_Q) {
         const int hid = a.head_hidden, core = p.core;
-        const int kc = Hn > 0 ? (core + 31) / 32 : s->ldfc / 32;
-        s->ft_hid = 2 * hid / 16;
-        off_hid = pk.size();
+        const int kc = Hn > 0 ? (core + 31) / 32 : ldfc_ / 32;
+        o.ft_hid = 2 * hid / 16;
+        o.off_hid = pk.size();
         const float* wv = w + p.v1_w;
         const float* wa = w + p.a1_w;
-        pack_a(pk, s->ft_hid, kc, [&](int f, int k) -> float {
+        pack_a(pk, o.ft_hid, kc, [&](int f, int k) -> float {
             if (k >= core) return 0.f;
             return f < hid ? wv[(size_t)k * hid + f] : wa[(size_t)k * hid + (f - hid)];
         });
-        off_bhid = fb.size();
+        o.off_bhid = fb.size();
         for (int f = 0; f < hid; ++f) fb.push_back(w[p.v1_b + f]);
         for (int f = 0; f < hid; ++f) fb.push_back(w[p.a1_b + f]);
     }
 
+}
+
+// Resolves the pointers of weight set `set` from the packing offsets.
+inline void bf16_bind(Bf16State* s, const Plan& p, const Bf16Packed& o, int set)
+{
+    const seed_arch_t& a = p.arch;
+    Bf16WeightSet& W = s->ws[set];
+    const uint16_t* dpk = (const uint16_t*)(s->arena + s->o_pk[set]);
+    auto frag = [&](size_t off) { return (const bf16x8*)(dpk + off); };
+    const float* dfb = (const float*)(s->arena + s->o_fb[set]);
+    W.wp_fc = frag(o.off_fc); W.bias_fc = dfb + o.off_bfc;
+    if (a.lstm_units > 0) W.wp_lstm = frag(o.off_lstm);
+    if (a.head == SEED_HEAD_DUELING_Q) { W.wp_hid = frag(o.off_hid); W.bias_hid = dfb + o.off_bhid; }
+    W.wp_conv = frag(0);
+    if (a.torso == SEED_TORSO_RESNET) {
+        for (size_t si = 0; si < p.sections.size(); ++si) {
+            SecWeights& sw = W.sec[si];
+            sw.w0 = frag(o.sec_off[si][0]);
+            for (int j = 0; j < 4; ++j) sw.wb[j] = frag(o.sec_off[si][1 + j]);
+        }
+    }
+}
+
+inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out, std::string& err)
+{
+    const seed_arch_t& a = p.arch;
+    Bf16State* s = new Bf16State;
+    *out = s;                                  // owned by the handle from here on (freed on any failure by the caller)
+    int dev = 0;
+    BF_TRY(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    BF_TRY(hipGetDeviceProperties(&prop, dev));
+    s->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    s->torso_kind = match_resnet(a);
+    s->ldf = round_up((int)p.flat, 32);
+    s->ldfc = round_up(a.fc_units, 32);
+
+    Bf16Packed o;
+    bf16_pack(p, s->torso_kind, s->ldf, s->ldfc, w, o);
+    s->kc_fc = o.kc_fc; s->ft_fc = o.ft_fc; s->kc1_lstm = o.kc1_lstm; s->ft_hid = o.ft_hid;
+    s->stack = o.stack;
+    s->pk_bytes = o.pk.size() * 2;
+    s->fb_bytes = o.fb.size() * 4;
+    const int F = a.fc_units;
+
     // arena layout
     auto al = [](size_t v) { return (v + 255) / 256 * 256; };
     const size_t mb = (size_t)a.max_batch;
-    size_t o = 0;
-    const size_t o_pk = o; o += al(pk.size() * 2);
-    const size_t o_fb = o; o += al(fb.size() * 4 + 16);
-    const size_t o_ko = o; o += al(ko.size() * 4 + 16);
+    size_t off = 0;
+    for (int set = 0; set < 2; ++set) {
+        s->o_pk[set] = off; off += al(s->pk_bytes);
+        s->o_fb[set] = off; off += al(s->fb_bytes + 16);
+    }
+    const size_t o_ko = off; off += al(o.ko.size() * 4 + 16);
     size_t o_act[2] = {0, 0};
     if (a.torso == SEED_TORSO_CONV_STACK && p.convs.size() > 1) {
         size_t m = 0;
@@ -287,33 +343,21 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, const float* d_w
             size_t n = (size_t)p.convs[l].OH * p.convs[l].OW * p.convs[l].Cout;
             if (n > m) m = n;
         }
-        o_act[0] = o; o += al(mb * m * 2);
-        o_act[1] = o; o += al(mb * m * 2);
+        o_act[0] = off; off += al(mb * m * 2);
+        o_act[1] = off; off += al(mb * m * 2);
     }
-    const size_t o_feat = o; o += al(mb * s->ldf * 2);
-    const size_t o_fcb = o; o += al(mb * s->ldfc * 2);
-    const size_t o_fcf = o; o += al(mb * F * 4);
-    BF_TRY(hipMalloc((void**)&s->arena, o));
-    BF_TRY(hipMemset(s->arena, 0, o));        // padding columns of feat / fc stay zero for ever
-    BF_TRY(hipMemcpy(s->arena + o_pk, pk.data(), pk.size() * 2, hipMemcpyHostToDevice));
-    if (!fb.empty()) BF_TRY(hipMemcpy(s->arena + o_fb, fb.data(), fb.size() * 4, hipMemcpyHostToDevice));
-    if (!ko.empty()) BF_TRY(hipMemcpy(s->arena + o_ko, ko.data(), ko.size() * 4, hipMemcpyHostToDevice));
-
-    const uint16_t* dpk = (const uint16_t*)(s->arena + o_pk);
-    auto frag = [&](size_t off) { return (const bf16x8*)(dpk + off); };
-    const float* dfb = (const float*)(s->arena + o_fb);
-    s->wp_fc = frag(off_fc); s->bias_fc = dfb + off_bfc;
-    if (Hn > 0) s->wp_lstm = frag(off_lstm);
-    if (a.head == SEED_HEAD_DUELING_Q) { s->wp_hid = frag(off_hid); s->bias_hid = dfb + off_bhid; }
-    s->wp_conv = frag(0);
+    const size_t o_feat = off; off += al(mb * s->ldf * 2);
+    const size_t o_fcb = off; off += al(mb * s->ldfc * 2);
+    const size_t o_fcf = off; off += al(mb * F * 4);
+    BF_TRY(hipMalloc((void**)&s->arena, off));
+    BF_TRY(hipMemset(s->arena, 0, off));      // padding columns of feat / fc stay zero for ever
+    BF_TRY(hipMemcpy(s->arena + s->o_pk[0], o.pk.data(), s->pk_bytes, hipMemcpyHostToDevice));
+    if (!o.fb.empty()) BF_TRY(hipMemcpy(s->arena + s->o_fb[0], o.fb.data(), s->fb_bytes, hipMemcpyHostToDevice));
+    if (!o.ko.empty()) BF_TRY(hipMemcpy(s->arena + o_ko, o.ko.data(), o.ko.size() * 4, hipMemcpyHostToDevice));
+    bf16_bind(s, p, o, 0);
+    bf16_bind(s, p, o, 1);
+    s->active = 0;
     s->koff = (const int*)(s->arena + o_ko);
-    if (a.torso == SEED_TORSO_RESNET) {
-        for (size_t si = 0; si < p.sections.size(); ++si) {
-            SecWeights& sw = s->sec[si];
-            sw.w0 = frag(sec_off[si][0]);
-            for (int j = 0; j < 4; ++j) sw.wb[j] = frag(sec_off[si][1 + j]);
-        }
-    }
     s->act[0] = (__bf16*)(s->arena + o_act[0]);
     s->act[1] = (__bf16*)(s->arena + o_act[1]);
     s->feat = (__bf16*)(s->arena + o_feat);
@@ -372,16 +416,17 @@ inline void launch_conv_stack(hipStream_t st, const ConvStackArgs& c)
 // return *core / *ld_core name the fp32 rows the output heads read.
 inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hipStream_t st, int B, const uint8_t* obs,
                                const int32_t* prev_action, const float* prev_reward, const float* h_in,
-                               const float* c_in, float* h_out, float* c_out, float* d_hid, const float** core,
-                               int* ld_core, hipEvent_t ev0, hipEvent_t ev1, std::string& err)
+                               const float* c_in, const uint8_t* done, float* h_out, float* c_out, float* d_hid,
+                               const float** core, int* ld_core, hipEvent_t ev0, hipEvent_t ev1, std::string& err)
 {
     const seed_arch_t& a = p.arch;
     (void)err;
+    const Bf16WeightSet& W = s->ws[s->active];
     if (ev0) (void)hipEventRecord(ev0, st);
     if (a.torso == SEED_TORSO_RESNET) {
         TorsoArgs t{};
         t.obs = obs; t.feat = s->feat; t.ldf = s->ldf; t.B = B;
-        for (int i = 0; i < 4; ++i) t.sec[i] = s->sec[i];
+        for (int i = 0; i < 4; ++i) t.sec[i] = W.sec[i];
         const int grid = B < s->n_cu ? B : s->n_cu;
         constexpr int LDS_DM = Net3<DmS1, DmS2, DmS3>::LDS_BYTES;
         constexpr int LDS_FB = Net4<FbS1, DmS2, DmS3, FbS4>::LDS_BYTES;
@@ -396,7 +441,7 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
             const ConvLayer& c = p.convs[l];
             const bool last = l + 1 == p.convs.size();
             ConvStackArgs ca{};
-            ca.x = x; ca.wp = s->wp_conv + s->stack[l].wp_off / 8; ca.bias = d_w + c.b_off;
+            ca.x = x; ca.wp = W.wp_conv + s->stack[l].wp_off / 8; ca.bias = d_w + c.b_off;
             ca.koff = s->koff + s->stack[l].koff_off; ca.y = last ? s->feat : s->act[l & 1];
             ca.B = B; ca.H = c.H; ca.W = c.W; ca.Cin = c.Cin; ca.OH = c.OH; ca.OW = c.OW; ca.Cout = c.Cout;
             ca.stride = c.stride; ca.kchunks = s->stack[l].kchunks; ca.scale = l == 0 ? 1.0f / 255.0f : 1.0f;
@@ -415,7 +460,7 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
     {
         GemmArgs g{};
         g.x1 = s->feat; g.ld1 = s->ldf; g.kc1 = s->kc_fc; g.k2 = 0;
-        g.wp = s->wp_fc; g.n_ftiles = s->ft_fc; g.rows = B; g.bias_pad = s->bias_fc;
+        g.wp = W.wp_fc; g.n_ftiles = s->ft_fc; g.rows = B; g.bias_pad = W.bias_fc;
         g.y_bf16 = s->fc_bf16; g.ldy_bf16 = s->ldfc; g.y_f32 = s->fc_f32; g.ldy_f32 = a.fc_units; g.n_out = a.fc_units;
         launch_gemm<EPI_RELU>(st, g, (s->ft_fc + 3) / 4, s->n_cu);
     }
@@ -424,9 +469,10 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
         GemmArgs g{};
         g.x1 = s->fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->kc1_lstm;
         g.x2 = h_in; g.ld2 = a.lstm_units; g.k2 = a.lstm_units;
-        g.wp = s->wp_lstm; g.n_ftiles = (a.lstm_units / 16) * 4; g.rows = B;
+        g.wp = W.wp_lstm; g.n_ftiles = (a.lstm_units / 16) * 4; g.rows = B;
         g.lstm_w = d_w + p.lstm_w; g.lstm_b = d_w + p.lstm_b; g.prev_action = prev_action; g.prev_reward = prev_reward;
         g.c_in = c_in; g.h_out = h_out; g.c_out = c_out; g.F = a.fc_units; g.A = a.num_actions; g.Hn = a.lstm_units;
+        g.done = done;
         launch_gemm<EPI_LSTM>(st, g, a.lstm_units / 16, s->n_cu);
         *core = h_out; *ld_core = a.lstm_units;
     }
@@ -434,7 +480,7 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
         GemmArgs g{};
         if (a.lstm_units > 0) { g.kc1 = 0; g.x1 = s->fc_bf16; g.ld1 = s->ldfc; g.x2 = h_out; g.ld2 = a.lstm_units; g.k2 = a.lstm_units; }
         else { g.x1 = s->fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->ldfc / 32; g.k2 = 0; }
-        g.wp = s->wp_hid; g.n_ftiles = s->ft_hid; g.rows = B; g.bias_pad = s->bias_hid;
+        g.wp = W.wp_hid; g.n_ftiles = s->ft_hid; g.rows = B; g.bias_pad = W.bias_hid;
         g.y_bf16 = nullptr; g.y_f32 = d_hid; g.ldy_f32 = 2 * a.head_hidden; g.n_out = 2 * a.head_hidden;
         launch_gemm<EPI_RELU>(st, g, (s->ft_hid + 3) / 4, s->n_cu);
     }

@@ -47,6 +47,7 @@ struct GemmArgs {
     const int32_t* prev_action; const float* prev_reward;
     const float* c_in; float* h_out; float* c_out;
     int F, A, Hn;
+    const uint8_t* done;                     // [rows] or nullptr: non-zero = the row's cell starts from the zero state
 };
 
 __device__ __forceinline__ float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
@@ -100,7 +101,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, floatx4 (&acc)[
                 pre[j] = acc[r][j] + bg[j] + rew * wr[j];
                 if (a >= 0 && a < p.A) pre[j] += *(const floatx4*)(p.lstm_w + (size_t)(p.F + a) * G4 + j * Hn + u);
             }
-            const floatx4 c0 = *(const floatx4*)(p.c_in + (size_t)row * Hn + u);
+            floatx4 c0 = *(const floatx4*)(p.c_in + (size_t)row * Hn + u);
+            if (p.done && p.done[row]) c0 = floatx4{0.f, 0.f, 0.f, 0.f};
             floatx4 cn, hn;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -122,7 +124,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, floatx4 (&acc)[
 // < kvalid exist.
 template <int RT, int NST, int CPS, bool F32>
 __device__ __forceinline__ void gemm_k_loop(floatx4 (&acc)[RT][4], const bf16x8* const (&wl)[4], const void* xbase, int ld,
-                                            const int (&rowi)[RT], int kb, int ke, int seg0, int kvalid, int g)
+                                            const int (&rowi)[RT], int kb, int ke, int seg0, int kvalid, int g,
+                                            const bool (&zero_row)[RT])
 {
     if (kb >= ke) return;
     struct Stage {
@@ -162,7 +165,7 @@ __device__ __forceinline__ void gemm_k_loop(floatx4 (&acc)[RT][4], const bf16x8*
             if constexpr (!F32) {
                 b = s.b[c][r];
             } else {
-                const bool ok = (kc - seg0) * 32 + g * 8 + 8 <= kvalid;
+                const bool ok = (kc - seg0) * 32 + g * 8 + 8 <= kvalid && !zero_row[r];
                 const floatx4 z = {0.f, 0.f, 0.f, 0.f};
                 b = to_bf16x8(ok ? s.f[c][r][0] : z, ok ? s.f[c][r][1] : z);
             }
@@ -214,8 +217,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
 #pragma unroll
     for (int j = 0; j < 4; ++j) wl[j] = p.wp + ((size_t)min(ft0 + j, p.n_ftiles - 1) * kct) * 64 + lane;
 
-    gemm_k_loop<RT, 3, 2, false>(acc, wl, p.x1, p.ld1, rowi, 0, p.kc1, 0, 0, g);
-    gemm_k_loop<RT, 3, 1, true>(acc, wl, p.x2, p.ld2, rowi, p.kc1, kct, p.kc1, p.k2, g);
+    // rows that start a new episode contribute no recurrent input (the fp32 segment is the previous h)
+    bool fresh[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) fresh[r] = EPI == EPI_LSTM && p.done && p.done[rowi[r]];
+    gemm_k_loop<RT, 3, 2, false>(acc, wl, p.x1, p.ld1, rowi, 0, p.kc1, 0, 0, g, fresh);
+    gemm_k_loop<RT, 3, 1, true>(acc, wl, p.x2, p.ld2, rowi, p.kc1, kct, p.kc1, p.k2, g, fresh);
     gemm_epilogue<RT, EPI>(p, acc, -1, wt, r0, lane);
 }
 
@@ -250,8 +257,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
 #pragma unroll
     for (int j = 0; j < 4; ++j) wl[j] = p.wp + ((size_t)min(ft0 + j, p.n_ftiles - 1) * kct) * 64 + lane;
 
-    gemm_k_loop<RT, 3, 2, false>(acc, wl, p.x1, p.ld1, rowi, k0, min(k1, p.kc1), 0, 0, g);
-    gemm_k_loop<RT, 3, 1, true>(acc, wl, p.x2, p.ld2, rowi, max(k0, p.kc1), k1, p.kc1, p.k2, g);
+    bool fresh[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) fresh[r] = EPI == EPI_LSTM && p.done && p.done[rowi[r]];
+    gemm_k_loop<RT, 3, 2, false>(acc, wl, p.x1, p.ld1, rowi, k0, min(k1, p.kc1), 0, 0, g, fresh);
+    gemm_k_loop<RT, 3, 1, true>(acc, wl, p.x2, p.ld2, rowi, max(k0, p.kc1), k1, p.kc1, p.k2, g, fresh);
 
     // K reduction through LDS.  With 8 wavefronts the upper four first hand everything to the lower four.
     if constexpr (NW == 8) {

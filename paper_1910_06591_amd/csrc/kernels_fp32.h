@@ -119,11 +119,14 @@ __global__ __launch_bounds__(256) void lstm_f32_kernel(
     const float* __restrict__ feat, const int32_t* __restrict__ prev_action,
     const float* __restrict__ prev_reward, const float* __restrict__ h_in,
     const float* __restrict__ c_in, const float* __restrict__ w, const float* __restrict__ bias,
-    float* __restrict__ h_out, float* __restrict__ c_out, int B, int F, int A, int Hn)
+    float* __restrict__ h_out, float* __restrict__ c_out, int B, int F, int A, int Hn,
+    const uint8_t* __restrict__ done)
 {
     int j = blockIdx.y * blockDim.x + threadIdx.x;
     int b = blockIdx.x;
     if (j >= Hn) return;
+    // a row that starts a new episode runs the cell from the zero state (Section 3: termination flags)
+    const bool fresh = done && done[b];
     const int G = 4 * Hn;
     float gi = bias[j], gf = bias[Hn + j], gg = bias[2 * Hn + j], go = bias[3 * Hn + j];
     const float* fr = feat + (size_t)b * F;
@@ -143,12 +146,12 @@ __global__ __launch_bounds__(256) void lstm_f32_kernel(
         gi = fmaf(r, wr[0], gi); gf = fmaf(r, wr[Hn], gf); gg = fmaf(r, wr[2 * Hn], gg); go = fmaf(r, wr[3 * Hn], go);
     }
     const float* hr = h_in + (size_t)b * Hn;
-    for (int i = 0; i < Hn; ++i) {
+    for (int i = 0; i < Hn && !fresh; ++i) {
         float v = hr[i];
         const float* wr = w + (size_t)(F + A + 1 + i) * G + j;
         gi = fmaf(v, wr[0], gi); gf = fmaf(v, wr[Hn], gf); gg = fmaf(v, wr[2 * Hn], gg); go = fmaf(v, wr[3 * Hn], go);
     }
-    float cn = sigmoid_f32(gf) * c_in[(size_t)b * Hn + j] + sigmoid_f32(gi) * tanhf(gg);
+    float cn = sigmoid_f32(gf) * (fresh ? 0.0f : c_in[(size_t)b * Hn + j]) + sigmoid_f32(gi) * tanhf(gg);
     c_out[(size_t)b * Hn + j] = cn;
     h_out[(size_t)b * Hn + j] = sigmoid_f32(go) * tanhf(cn);
 }

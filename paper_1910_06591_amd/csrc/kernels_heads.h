@@ -23,6 +23,8 @@ struct HeadsArgs {
     const float* w_v;                // [n]
     const float* b_v;                // [1]
     const float* uniforms;           // [B, A] or nullptr (greedy)
+    const float* epsilon;            // [B] or nullptr: epsilon-greedy exploration (Appendix A.3.1)
+    const float* explore_u;          // [B, 2] uniforms in [0,1): explore iff u0 < epsilon, action floor(u1 * A)
     int32_t* action;                 // [B]
     float* logits;                   // [B, A]
     float* value;                    // [B]
@@ -110,7 +112,13 @@ __global__ __launch_bounds__(256) void heads_select_kernel(HeadsArgs p)
         int ob = __shfl_xor(best, off, 64);
         if (ok > key || (ok == key && ob < best)) { key = ok; best = ob; }
     }
-    if (lane == 0) p.action[row] = best;
+    if (lane == 0) {
+        if (p.epsilon && p.explore_u[2 * (size_t)row] < p.epsilon[row]) {
+            const int r = (int)floorf(p.explore_u[2 * (size_t)row + 1] * (float)p.A);
+            best = r < 0 ? 0 : (r > p.A - 1 ? p.A - 1 : r);
+        }
+        p.action[row] = best;
+    }
 }
 
 }  // namespace seedinf

@@ -20,7 +20,12 @@ using namespace seedinf;
 struct seed_infer {
     Plan plan;
     int device = -1;
-    float* d_w = nullptr;          // canonical flat fp32 weights
+    float* d_w = nullptr;          // canonical flat fp32 weights the steps read: d_w_set[active]
+    float* d_w_set[2] = {nullptr, nullptr};   // two copies: a weight update fills the idle one and flips
+    int active = 0;
+    char* staging = nullptr;       // pinned host buffer a weight update is staged in
+    size_t staging_bytes = 0;
+    hipEvent_t staged = nullptr;   // recorded after the copies that read `staging`
     float* d_act[2] = {nullptr, nullptr};   // fp32 ping-pong activations (fp32 mode)
     float* d_fc = nullptr;         // [max_batch, fc_units] fp32 (fp32 mode)
     float* d_hid = nullptr;        // [max_batch, 2*head_hidden] dueling hidden, fp32
@@ -83,7 +88,10 @@ static void free_all(seed_infer* h)
     if (!h) return;
     if (h->bf) { bf16_destroy(h->bf); h->bf = nullptr; }
     for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
-    if (h->d_w) (void)hipFree(h->d_w);
+    if (h->staged) (void)hipEventDestroy(h->staged);
+    if (h->staging) (void)hipHostFree(h->staging);
+    if (h->d_w_set[0]) (void)hipFree(h->d_w_set[0]);
+    if (h->d_w_set[1]) (void)hipFree(h->d_w_set[1]);
     if (h->d_act[0]) (void)hipFree(h->d_act[0]);
     if (h->d_act[1]) (void)hipFree(h->d_act[1]);
     if (h->d_fc) (void)hipFree(h->d_fc);
@@ -98,7 +106,9 @@ static seed_status_t create_impl(seed_infer* h, const float* weights_host)
     const Plan& p = h->plan;
     const seed_arch_t& a = p.arch;
     HIP_TRY(h, hipGetDevice(&h->device));
-    HIP_TRY(h, hipMalloc(&h->d_w, p.n_weights * sizeof(float)));
+    HIP_TRY(h, hipMalloc(&h->d_w_set[0], p.n_weights * sizeof(float)));
+    HIP_TRY(h, hipMalloc(&h->d_w_set[1], p.n_weights * sizeof(float)));
+    h->d_w = h->d_w_set[0];
     HIP_TRY(h, hipMemcpy(h->d_w, weights_host, p.n_weights * sizeof(float), hipMemcpyHostToDevice));
     const size_t mb = (size_t)a.max_batch;
     if (a.head == SEED_HEAD_DUELING_Q) HIP_TRY(h, hipMalloc(&h->d_hid, mb * 2 * a.head_hidden * sizeof(float)));
@@ -107,9 +117,13 @@ static seed_status_t create_impl(seed_infer* h, const float* weights_host)
         HIP_TRY(h, hipMalloc(&h->d_act[1], mb * p.max_act * sizeof(float)));
         HIP_TRY(h, hipMalloc(&h->d_fc, mb * a.fc_units * sizeof(float)));
     } else {
-        seed_status_t st = bf16_create(p, weights_host, h->d_w, &h->bf, h->err);
+        seed_status_t st = bf16_create(p, weights_host, &h->bf, h->err);
         if (st != SEED_OK) return st;
     }
+    // staging for weight updates, allocated here so that seed_infer_set_weights allocates nothing
+    h->staging_bytes = p.n_weights * sizeof(float) + (h->bf ? h->bf->pk_bytes + h->bf->fb_bytes : 0);
+    HIP_TRY(h, hipHostMalloc((void**)&h->staging, h->staging_bytes, hipHostMallocDefault));
+    HIP_TRY(h, hipEventCreateWithFlags(&h->staged, hipEventDisableTiming));
     HIP_TRY(h, hipDeviceSynchronize());
     return SEED_OK;
 }
@@ -220,6 +234,17 @@ extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8
                                          int32_t* action_out, float* logits_out, float* value_out,
                                          float* h_out, float* c_out, float* probs_out, void* hip_stream)
 {
+    return seed_infer_step_ext(h, B, obs, prev_action, prev_reward, h_in, c_in, uniforms, nullptr, action_out, logits_out,
+                               value_out, h_out, c_out, probs_out, hip_stream);
+}
+
+extern "C" seed_status_t seed_infer_step_ext(seed_infer_t* h, int32_t B, const uint8_t* obs,
+                                             const int32_t* prev_action, const float* prev_reward,
+                                             const float* h_in, const float* c_in, const float* uniforms,
+                                             const seed_step_ext_t* ext,
+                                             int32_t* action_out, float* logits_out, float* value_out,
+                                             float* h_out, float* c_out, float* probs_out, void* hip_stream)
+{
     if (!h) return SEED_ERR_INVALID_ARG;
     const Plan& p = h->plan;
     const seed_arch_t& a = p.arch;
@@ -235,6 +260,15 @@ extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8
         return fail(SEED_ERR_INVALID_ARG, "a feed-forward arch takes no recurrent arguments (pass NULL)");
     if (a.select == SEED_SELECT_GUMBEL && !uniforms) return fail(SEED_ERR_INVALID_ARG, "Gumbel-max selection needs uniforms");
     if (a.select == SEED_SELECT_GREEDY && uniforms) return fail(SEED_ERR_INVALID_ARG, "greedy selection takes no uniforms (pass NULL)");
+    const uint8_t* done = nullptr;
+    const float* epsilon = nullptr;
+    const float* explore_u = nullptr;
+    if (ext) {
+        if (ext->struct_size != sizeof(seed_step_ext_t)) return fail(SEED_ERR_INVALID_ARG, "ext->struct_size is not sizeof(seed_step_ext_t)");
+        done = ext->done; epsilon = ext->epsilon; explore_u = ext->explore_uniforms;
+        if (done && !rec) return fail(SEED_ERR_INVALID_ARG, "done flags need a recurrent arch");
+        if ((epsilon == nullptr) != (explore_u == nullptr)) return fail(SEED_ERR_INVALID_ARG, "epsilon and explore_uniforms must be given together");
+    }
     if (rec) {
         size_t nb = (size_t)B * a.lstm_units * sizeof(float);
         if (overlaps(h_out, nb, h_in, nb) || overlaps(h_out, nb, c_in, nb) || overlaps(c_out, nb, h_in, nb) ||
@@ -261,7 +295,7 @@ extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8
         if (rec) {
             hipLaunchKernelGGL(lstm_f32_kernel, dim3(B, (a.lstm_units + 255) / 256), dim3(256), 0, s, h->d_fc, prev_action,
                                prev_reward, h_in, c_in, w + p.lstm_w, w + p.lstm_b, h_out, c_out, B, a.fc_units,
-                               a.num_actions, a.lstm_units);
+                               a.num_actions, a.lstm_units, done);
             core = h_out;
         }
         if (a.head == SEED_HEAD_DUELING_Q) {
@@ -272,14 +306,14 @@ extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8
                                h->d_hid + hid, p.core, hid, ld_core, 2 * hid, 1);
         }
     } else {
-        seed_status_t st = bf16_step(h->bf, p, w, s, B, obs, prev_action, prev_reward, h_in, c_in, h_out, c_out,
+        seed_status_t st = bf16_step(h->bf, p, w, s, B, obs, prev_action, prev_reward, h_in, c_in, done, h_out, c_out,
                                      h->d_hid, &core, &ld_core, ev0, ev1, h->err);
         if (st != SEED_OK) return st;
     }
 
     HeadsArgs ha{};
     ha.n = p.core; ha.A = a.num_actions; ha.B = B;
-    ha.uniforms = uniforms; ha.action = action_out; ha.logits = logits_out; ha.value = value_out; ha.probs = probs_out;
+    ha.uniforms = uniforms; ha.epsilon = epsilon; ha.explore_u = explore_u; ha.action = action_out; ha.logits = logits_out; ha.value = value_out; ha.probs = probs_out;
     if (a.head == SEED_HEAD_POLICY_VALUE) {
         ha.vec_a = core; ha.ld_a = ld_core; ha.vec_v = core; ha.ld_v = ld_core;
         ha.w_a = w + p.pol_w; ha.b_a = w + p.pol_b; ha.w_v = w + p.val_w; ha.b_v = w + p.val_b;
@@ -293,6 +327,43 @@ extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8
     }
     launch_heads(s, ha);
     HIP_TRY(h, hipGetLastError());
+    return SEED_OK;
+}
+
+extern "C" seed_status_t seed_infer_set_weights(seed_infer_t* h, const float* weights_host, size_t n_weights,
+                                                void* hip_stream)
+{
+    if (!h) return SEED_ERR_INVALID_ARG;
+    const Plan& p = h->plan;
+    auto fail = [&](seed_status_t st, const char* m) { h->err = m; return st; };
+    if (!weights_host) return fail(SEED_ERR_INVALID_ARG, "weights_host is NULL");
+    if (n_weights != p.n_weights) return fail(SEED_ERR_INVALID_ARG, "n_weights does not match the handle's arch");
+    int dev = -1;
+    HIP_TRY(h, hipGetDevice(&dev));
+    if (dev != h->device) return fail(SEED_ERR_INVALID_ARG, "current HIP device differs from the handle's device");
+    hipStream_t s = (hipStream_t)hip_stream;
+    // the previous update's copies may still be reading the staging buffer
+    HIP_TRY(h, hipEventSynchronize(h->staged));
+    const int idle = 1 - h->active;
+    const size_t wb = p.n_weights * sizeof(float);
+    memcpy(h->staging, weights_host, wb);
+    HIP_TRY(h, hipMemcpyAsync(h->d_w_set[idle], h->staging, wb, hipMemcpyHostToDevice, s));
+    if (h->bf) {
+        Bf16State* b = h->bf;
+        Bf16Packed o;
+        bf16_pack(p, b->torso_kind, b->ldf, b->ldfc, weights_host, o);
+        if (o.pk.size() * 2 != b->pk_bytes || o.fb.size() * 4 != b->fb_bytes) return fail(SEED_ERR_DEVICE, "packed weight size changed");
+        char* st_pk = h->staging + wb;
+        char* st_fb = st_pk + b->pk_bytes;
+        memcpy(st_pk, o.pk.data(), b->pk_bytes);
+        if (b->fb_bytes) memcpy(st_fb, o.fb.data(), b->fb_bytes);
+        HIP_TRY(h, hipMemcpyAsync(b->arena + b->o_pk[idle], st_pk, b->pk_bytes, hipMemcpyHostToDevice, s));
+        if (b->fb_bytes) HIP_TRY(h, hipMemcpyAsync(b->arena + b->o_fb[idle], st_fb, b->fb_bytes, hipMemcpyHostToDevice, s));
+        b->active = idle;
+    }
+    HIP_TRY(h, hipEventRecord(h->staged, s));
+    h->active = idle;
+    h->d_w = h->d_w_set[idle];
     return SEED_OK;
 }
 

@@ -23,8 +23,15 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 STATUS = {0: "SEED_OK", 1: "SEED_ERR_INVALID_ARG", 2: "SEED_ERR_UNSUPPORTED_ARCH", 3: "SEED_ERR_BATCH_TOO_LARGE",
           4: "SEED_ERR_ALIASING", 5: "SEED_ERR_DEVICE", 6: "SEED_ERR_OOM"}
 EXPORTS = ["seed_infer_weight_count", "seed_infer_validate", "seed_infer_create", "seed_infer_step",
+           "seed_infer_step_ext", "seed_infer_set_weights",
            "seed_infer_read_intermediate", "seed_infer_torso_features", "seed_infer_last_error",
            "seed_infer_destroy", "seed_infer_set_profiling", "seed_infer_profile_read"]
+
+
+class SeedStepExt(C.Structure):
+    """seed_step_ext_t: optional inputs of seed_infer_step_ext (device pointers, 0 = absent)."""
+    _fields_ = [("struct_size", C.c_uint32), ("done", C.c_void_p), ("epsilon", C.c_void_p),
+                ("explore_uniforms", C.c_void_p)]
 
 
 class SeedError(RuntimeError):
@@ -84,6 +91,10 @@ def load_library():
     lib.seed_infer_step.restype = C.c_int
     lib.seed_infer_step.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 13
     lib.seed_infer_read_intermediate.restype = C.c_int
+    lib.seed_infer_step_ext.restype = C.c_int
+    lib.seed_infer_step_ext.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 6 + [C.POINTER(SeedStepExt)] + [C.c_void_p] * 7
+    lib.seed_infer_set_weights.restype = C.c_int
+    lib.seed_infer_set_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.seed_infer_read_intermediate.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.seed_infer_last_error.restype = C.c_char_p
     lib.seed_infer_last_error.argtypes = [C.c_void_p]
@@ -180,10 +191,30 @@ class SeedInfer:
                                       logits, value, h_out, c_out, probs, stream)
         return st, self.lib.seed_infer_last_error(self._h).decode()
 
+    def step_ext_raw(self, B, obs, prev_action, prev_reward, h_in, c_in, uniforms, ext, action, logits, value,
+                     h_out, c_out, probs, stream=0):
+        """Direct call of seed_infer_step_ext with raw pointers/ints; `ext` is a SeedStepExt or None."""
+        st = self.lib.seed_infer_step_ext(self._h, B, obs, prev_action, prev_reward, h_in, c_in, uniforms,
+                                          C.byref(ext) if ext is not None else None, action, logits, value,
+                                          h_out, c_out, probs, stream)
+        return st, self.lib.seed_infer_last_error(self._h).decode()
+
+    def set_weights(self, weights, stream=None):
+        """Replace the handle's weights (host numpy array, same layout as at creation); steps enqueued
+        afterwards on the same stream use them."""
+        import torch
+        w = np.ascontiguousarray(weights, dtype=np.float32)
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        st = self.lib.seed_infer_set_weights(self._h, w.ctypes.data_as(C.c_void_p), w.size, C.c_void_p(s))
+        if st != 0:
+            raise SeedError(st, self.lib.seed_infer_last_error(self._h).decode())
+
     def step(self, obs, prev_action=None, prev_reward=None, h_in=None, c_in=None, uniforms=None,
-             want_probs=True, out=None, stream=None):
+             want_probs=True, out=None, stream=None, done=None, epsilon=None, explore_uniforms=None):
         """Run one inference step on device tensors; returns a dict of device
-        tensors (allocated here with torch unless `out` supplies them)."""
+        tensors (allocated here with torch unless `out` supplies them).  done [B] uint8,
+        epsilon [B] and explore_uniforms [B, 2] are the optional episode flags and
+        epsilon-greedy inputs (seed_infer_step_ext)."""
         import torch
         a = self.arch
         B = obs.shape[0]
@@ -198,7 +229,14 @@ class SeedInfer:
             if want_probs:
                 out["probs"] = torch.empty(B, self.A, dtype=torch.float32, device=dev)
         s = torch.cuda.current_stream(dev).cuda_stream if stream is None else stream
-        st = self.lib.seed_infer_step(
+        ext = None
+        if done is not None or epsilon is not None or explore_uniforms is not None:
+            addr = lambda p_: None if p_ is None else p_.value
+            ext = SeedStepExt(C.sizeof(SeedStepExt),
+                              addr(_ptr(done, torch.uint8, (B,), "done")),
+                              addr(_ptr(epsilon, torch.float32, (B,), "epsilon")),
+                              addr(_ptr(explore_uniforms, torch.float32, (B, 2), "explore_uniforms")))
+        st = self.lib.seed_infer_step_ext(
             self._h, B,
             _ptr(obs, torch.uint8, (B, a.obs_h, a.obs_w, a.obs_c), "obs"),
             _ptr(prev_action, torch.int32, (B,), "prev_action"),
@@ -206,6 +244,7 @@ class SeedInfer:
             _ptr(h_in, torch.float32, (B, self.Hn), "h_in"),
             _ptr(c_in, torch.float32, (B, self.Hn), "c_in"),
             _ptr(uniforms, torch.float32, (B, self.A), "uniforms"),
+            C.byref(ext) if ext is not None else None,
             _ptr(out["action"], torch.int32, (B,), "action"),
             _ptr(out["logits"], torch.float32, (B, self.A), "logits"),
             _ptr(out["value"], torch.float32, (B,), "value"),

@@ -1,0 +1,156 @@
+"""GPU parity for the step with episode flags and epsilon-greedy exploration (seed_infer_step_ext) and for the
+weight hot-swap (seed_infer_set_weights), against the CPU oracle."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1910_06591_amd import seedinf, workloads as wl
+from tests.parity import check_against_oracle, to_device
+
+pytestmark = pytest.mark.gpu
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+CORE_KEYS = ("prev_action", "prev_reward", "h_in", "c_in", "uniforms")
+
+
+def ext_case(orc, cfg, B, precision, done_rate=0.3, use_done=True, use_eps=True):
+    import torch
+    w = wl.make_weights(cfg, bf16_representable=(precision == "bf16"))
+    batch = wl.make_batch(cfg, B)
+    done, eps, eu = wl.make_episode_inputs(cfg, B, done_rate=done_rate)
+    eps = np.minimum(eps * 1.5, 1.0).astype(np.float32)            # more explored rows than the training schedule
+    rec = cfg["lstm_units"] > 0
+    kw_o = {}
+    kw_g = {}
+    if use_done and rec:
+        kw_o["done"] = done
+        kw_g["done"] = torch.from_numpy(done).cuda()
+    if use_eps:
+        kw_o.update(epsilon=eps, explore_u=eu)
+        kw_g.update(epsilon=torch.from_numpy(eps).cuda(), explore_uniforms=torch.from_numpy(eu).cuda())
+    print(f"ext case {cfg['label']} B={B} {precision} done={use_done and rec} eps={use_eps}", flush=True)
+    net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=B, precision=precision), w)
+    # poison the state rows of finished episodes: they must not be read
+    dev = to_device(batch)
+    if use_done and rec:
+        flagged = torch.from_numpy(done != 0).cuda()
+        dev["h_in"] = dev["h_in"].clone()
+        dev["c_in"] = dev["c_in"].clone()
+        dev["h_in"][flagged] = float("nan")
+        dev["c_in"][flagged] = float("nan")
+    out = net.step(**dev, **kw_g)
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    ref = orc.forward(oracle.make_arch(cfg), w, batch["obs"], **{k: batch[k] for k in CORE_KEYS}, **kw_o)
+    # rows that explored take exactly the oracle's random action; the others follow the usual action rule
+    explored = (eu[:, 0] < eps) if use_eps else np.zeros(B, bool)
+    assert np.array_equal(got["action"][explored], ref["action"][explored])
+    keep = ~explored
+    sub = lambda d: {k: v[keep] for k, v in d.items()}
+    rep = check_against_oracle(sub(got), sub(ref), TOL[precision], None if batch["uniforms"] is None else batch["uniforms"][keep])
+    print("   ", rep, "explored", int(explored.sum()), "done", int((done != 0).sum()), flush=True)
+    net.close()
+    return rep
+
+
+@pytest.mark.parametrize("name,B", [("C2", 37), ("C3", 41), ("C4", 19)])
+def test_ext_fp32(orc, name, B):
+    ext_case(orc, wl.CONFIGS[name], B, "fp32")
+
+
+@pytest.mark.parametrize("name,B", [("C2", 70), ("C3", 300), ("C4", 33)])
+def test_ext_bf16(orc, name, B):
+    ext_case(orc, wl.CONFIGS[name], B, "bf16")
+
+
+def test_ext_parts_alone_and_absent(orc):
+    cfg = wl.CONFIGS["C3"]
+    ext_case(orc, cfg, 48, "bf16", use_done=True, use_eps=False)
+    ext_case(orc, cfg, 48, "bf16", use_done=False, use_eps=True)
+    ext_case(orc, cfg, 48, "bf16", done_rate=1.0)              # every row starts an episode
+    # an all-NULL ext equals the plain step, bit for bit
+    import torch
+    w = wl.make_weights(cfg, bf16_representable=True)
+    batch = to_device(wl.make_batch(cfg, 48))
+    net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=48, precision="bf16"), w)
+    a = net.step(**batch)
+    ext = seedinf.SeedStepExt(C.sizeof(seedinf.SeedStepExt), None, None, None)
+    b = {k: torch.empty_like(v) for k, v in a.items()}
+    p = lambda t: C.c_void_p(t.data_ptr())
+    st, msg = net.step_ext_raw(48, p(batch["obs"]), p(batch["prev_action"]), p(batch["prev_reward"]), p(batch["h_in"]),
+                               p(batch["c_in"]), p(batch["uniforms"]), ext, p(b["action"]), p(b["logits"]), p(b["value"]),
+                               p(b["h"]), p(b["c"]), p(b["probs"]))
+    assert st == 0, msg
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    net.close()
+
+
+def test_ext_error_paths(orc):
+    import torch
+    cfg = wl.CONFIGS["C4"]                                       # feed-forward: done flags make no sense
+    B = 4
+    w = wl.make_weights(cfg, bf16_representable=True)
+    batch = to_device(wl.make_batch(cfg, B))
+    net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=B, precision="bf16"), w)
+    out = {"action": torch.full((B,), -7, dtype=torch.int32, device="cuda"),
+           "logits": torch.empty(B, cfg["num_actions"], device="cuda"), "value": torch.empty(B, device="cuda")}
+    p = lambda t: C.c_void_p(t.data_ptr())
+    done = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    eps = torch.ones(B, device="cuda")
+    call = lambda ext: net.step_ext_raw(B, p(batch["obs"]), None, None, None, None, p(batch["uniforms"]), ext,
+                                        p(out["action"]), p(out["logits"]), p(out["value"]), None, None, None)
+    size = C.sizeof(seedinf.SeedStepExt)
+    st, msg = call(seedinf.SeedStepExt(size, done.data_ptr(), None, None))
+    assert st == 1 and "recurrent" in msg
+    st, msg = call(seedinf.SeedStepExt(size, None, eps.data_ptr(), None))
+    assert st == 1 and "together" in msg
+    st, msg = call(seedinf.SeedStepExt(size - 4, None, None, None))
+    assert st == 1 and "struct_size" in msg
+    torch.cuda.synchronize()
+    assert (out["action"] == -7).all()                           # nothing was written on the error returns
+    net.close()
+
+
+@pytest.mark.parametrize("name,precision,B", [("C3", "bf16", 64), ("C2", "bf16", 32), ("C3", "fp32", 9), ("C4", "bf16", 40)])
+def test_set_weights_swaps_and_restores(orc, name, precision, B):
+    """After an update the step must equal a fresh handle built on the new weights (bit for bit: same kernels,
+    same packed layout) and match the oracle run on them; going back restores the first outputs."""
+    import torch
+    cfg = wl.CONFIGS[name]
+    bf = precision == "bf16"
+    w1 = wl.make_weights(cfg, bf16_representable=bf)
+    w2 = wl.make_weights(cfg, seed=7777, bf16_representable=bf)
+    batch_np = wl.make_batch(cfg, B)
+    batch = to_device(batch_np)
+    arch = seedinf.make_arch(cfg, max_batch=B, precision=precision)
+    net = seedinf.SeedInfer(arch, w1)
+    o1 = {k: v.clone() for k, v in net.step(**batch).items()}
+    net.set_weights(w2)
+    o2 = {k: v.clone() for k, v in net.step(**batch).items()}
+    net.set_weights(w1)
+    o3 = {k: v.clone() for k, v in net.step(**batch).items()}
+    net.set_weights(w2)                                          # a third update reuses the first copy
+    o4 = {k: v.clone() for k, v in net.step(**batch).items()}
+    torch.cuda.synchronize()
+    fresh = seedinf.SeedInfer(arch, w2)
+    f2 = fresh.step(**batch)
+    torch.cuda.synchronize()
+    for k in o1:
+        assert torch.equal(o1[k], o3[k]), k
+        assert torch.equal(o2[k], f2[k]), k
+        assert torch.equal(o2[k], o4[k]), k
+    assert not torch.equal(o1["logits"], o2["logits"])
+    ref = orc.forward(oracle.make_arch(cfg), w2, batch_np["obs"], **{k: batch_np[k] for k in CORE_KEYS})
+    check_against_oracle({k: v.cpu().numpy() for k, v in o2.items()}, ref, TOL[precision], batch_np["uniforms"])
+    # error paths leave the active weights alone
+    wbad = np.zeros(w1.size - 1, np.float32)
+    with pytest.raises(seedinf.SeedError):
+        net.set_weights(wbad)
+    o5 = net.step(**batch)
+    torch.cuda.synchronize()
+    assert torch.equal(o5["logits"], o2["logits"])
+    net.close()
+    fresh.close()
