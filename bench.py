@@ -98,6 +98,8 @@ def time_extensions(cfg, B, weights):
     torch.cuda.synchronize()
 
     def p50(fn, n=40):
+        for _ in range(5):
+            fn()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
         for a, b in evs:
             a.record(); fn(); b.record()
