@@ -106,7 +106,8 @@ def time_extensions(cfg, B, weights):
         torch.cuda.synchronize()
         return float(np.median([a.elapsed_time(b) for a, b in evs]))
 
-    res = {"step_ext_p50_ms": p50(lambda: net.step(out=out, **dev, **ext))}
+    res = {"step_plain_p50_ms": p50(lambda: net.step(out=out, **dev)),
+           "step_ext_p50_ms": p50(lambda: net.step(out=out, **dev, **ext))}
     # weight refresh: host time of the call (repack + enqueue) and a step issued right behind it
     t = []
     for _ in range(5):
@@ -226,6 +227,20 @@ def main():
                            "tflops": 2.0 * wl.macs_per_frame(c) * c["batch"] / (s["p50_ms"] * 1e-3) / 1e12})
         line["other_workloads"] = others
         line["extensions"] = time_extensions(cfg, B, weights)
+        # model-size variants (Section 4.1: filters x2 / x4; Section 4.2: medium and large minimaps; Atari without
+        # frame stacking): no fused kernel, layer-by-layer bf16 path (fp32 where bf16 mode has no kernels)
+        variants = []
+        c3, c4, c2 = wl.CONFIGS["C3"], wl.CONFIGS["C4"], wl.CONFIGS["C2"]
+        for label, c, b in (("DMLab filters x2", dict(c3, sections=[32, 64, 64]), 1024),
+                            ("DMLab filters x4", dict(c3, sections=[64, 128, 128]), 1024),
+                            ("Football map 120x90", dict(c4, obs_h=90, obs_w=120), 1024),
+                            ("Football map 144x108", dict(c4, obs_h=108, obs_w=144), 1024),
+                            ("Atari without frame stacking (fp32 mode)", dict(c2, obs_c=1, precision="fp32"), 256)):
+            c = dict(c, label=label, index=40)
+            s = time_config(c, b, 20, 3, profile=False)
+            variants.append({"config": label, "batch": b, "dtype": c["precision"], "frames_per_s": b / (s["p50_ms"] * 1e-3),
+                             "p50_ms": s["p50_ms"], "tflops": 2.0 * wl.macs_per_frame(c) * b / (s["p50_ms"] * 1e-3) / 1e12})
+        line["model_variants"] = variants
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(cfg, args.cpu_rows)
     print(json.dumps(line))

@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -12,6 +13,7 @@
 #include "gemm_bf16.h"
 #include "conv_stack_bf16.h"
 #include "resnet_fused.h"
+#include "resnet_layerwise.h"
 
 namespace seedinf {
 
@@ -44,8 +46,10 @@ inline seed_status_t bf16_supported(const Plan& p, std::string& err)
     const seed_arch_t& a = p.arch;
     auto no = [&](const char* m) { err = std::string("bf16 mode: ") + m + " (fp32 mode supports every valid arch)"; return SEED_ERR_UNSUPPORTED_ARCH; };
     if (a.torso == SEED_TORSO_RESNET) {
+        // shapes without a fused kernel run layer by layer; that path needs whole 16-channel tiles
         if (match_resnet(a) == TORSO_NONE)
-            return no("fused ResNet kernels exist for 72x96x3 frames with sections 16/32/32 and 72x96x16 frames with sections 16/32/32/32");
+            for (int i = 0; i < a.n_sections; ++i)
+                if (a.section_ch[i] % 16) return no("ResNet section channels must be multiples of 16");
     } else {
         for (size_t l = 0; l < p.convs.size(); ++l) {
             const ConvLayer& c = p.convs[l];
@@ -85,6 +89,7 @@ inline void pack_a(std::vector<uint16_t>& out, int n_ftiles, int kchunks, F valu
 }
 
 struct ConvStackLayerDev { size_t wp_off; size_t koff_off; int kchunks; };
+struct LwLayerDev { size_t wp_off; size_t ktab_off; int kchunks; };       // layer-by-layer ResNet: one 3x3 convolution
 
 // Device pointers into one uploaded copy of the packed weights.
 struct Bf16WeightSet {
@@ -103,6 +108,7 @@ struct Bf16Packed {
     size_t sec_off[4][5] = {};
     size_t off_fc = 0, off_bfc = 0, off_lstm = 0, off_hid = 0, off_bhid = 0;
     std::vector<ConvStackLayerDev> stack;
+    std::vector<LwLayerDev> lw;                // per section: conv0, block1.a, block1.b, block2.a, block2.b
     int kc_fc = 0, ft_fc = 0, kc1_lstm = 0, ft_hid = 0;
 };
 
@@ -117,7 +123,10 @@ struct Bf16State {
     size_t pk_bytes = 0, fb_bytes = 0;
     int kc_fc = 0, ft_fc = 0, kc1_lstm = 0, ft_hid = 0;
     std::vector<ConvStackLayerDev> stack;
+    std::vector<LwLayerDev> lw;
     const int* koff = nullptr;
+    // layer-by-layer ResNet workspace: conv0 output at input resolution; R / U conv inputs; x residual stream
+    __bf16* lw_c0 = nullptr; __bf16* lw_r = nullptr; __bf16* lw_u = nullptr; float* lw_x = nullptr;
     // activations
     __bf16* act[2] = {nullptr, nullptr};
     __bf16* feat = nullptr; int ldf = 0;
@@ -208,7 +217,31 @@ inline void bf16_pack(const Plan& p, int torso_kind, int ldf_, int ldfc_, const 
     std::vector<float>& fb = o.fb;
     std::vector<int>& ko = o.ko;
     size_t (&sec_off)[4][5] = o.sec_off;
-    if (a.torso == SEED_TORSO_RESNET) {
+    if (a.torso == SEED_TORSO_RESNET && torso_kind == TORSO_NONE) {
+        auto pack_conv = [&](const ConvLayer& c) {
+            LwLayerDev d;
+            const int K = 9 * c.Cin;
+            d.kchunks = (K + 31) / 32;
+            d.wp_off = pk.size();
+            const float* wl = w + c.w_off;
+            pack_a(pk, c.Cout / 16, d.kchunks, [&](int f, int k) -> float { return k < K ? wl[(size_t)k * c.Cout + f] : 0.f; });
+            if (ko.size() & 1) ko.push_back(0);            // the table is read as int2
+            d.ktab_off = ko.size();
+            for (int kc = 0; kc < d.kchunks; ++kc)
+                for (int g = 0; g < 4; ++g) {
+                    const int k0 = kc * 32 + g * 8;
+                    if (k0 >= K || (c.Cin & 7)) { ko.push_back(0); ko.push_back(-1); continue; }
+                    const int tap = k0 / c.Cin, dy = tap / 3 - 1, dx = tap % 3 - 1;
+                    ko.push_back((dy * c.W + dx) * c.Cin + k0 % c.Cin);
+                    ko.push_back((dy + 1) | ((dx + 1) << 8));
+                }
+            o.lw.push_back(d);
+        };
+        for (const Section& sec : p.sections) {
+            pack_conv(sec.conv0);
+            for (int j = 0; j < 4; ++j) pack_conv(sec.block[j]);
+        }
+    } else if (a.torso == SEED_TORSO_RESNET) {
         if (torso_kind == TORSO_DMLAB) {
             pack_section<DmS1>(pk, w, p.sections[0], sec_off[0]);
             pack_section<DmS2>(pk, w, p.sections[1], sec_off[1]);
@@ -296,7 +329,7 @@ inline void bf16_bind(Bf16State* s, const Plan& p, const Bf16Packed& o, int set)
     if (a.lstm_units > 0) W.wp_lstm = frag(o.off_lstm);
     if (a.head == SEED_HEAD_DUELING_Q) { W.wp_hid = frag(o.off_hid); W.bias_hid = dfb + o.off_bhid; }
     W.wp_conv = frag(0);
-    if (a.torso == SEED_TORSO_RESNET) {
+    if (a.torso == SEED_TORSO_RESNET && s->torso_kind != TORSO_NONE) {
         for (size_t si = 0; si < p.sections.size(); ++si) {
             SecWeights& sw = W.sec[si];
             sw.w0 = frag(o.sec_off[si][0]);
@@ -323,6 +356,7 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     bf16_pack(p, s->torso_kind, s->ldf, s->ldfc, w, o);
     s->kc_fc = o.kc_fc; s->ft_fc = o.ft_fc; s->kc1_lstm = o.kc1_lstm; s->ft_hid = o.ft_hid;
     s->stack = o.stack;
+    s->lw = o.lw;
     s->pk_bytes = o.pk.size() * 2;
     s->fb_bytes = o.fb.size() * 4;
     const int F = a.fc_units;
@@ -346,6 +380,18 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
         o_act[0] = off; off += al(mb * m * 2);
         o_act[1] = off; off += al(mb * m * 2);
     }
+    size_t o_lw[4] = {0, 0, 0, 0};
+    if (a.torso == SEED_TORSO_RESNET && s->torso_kind == TORSO_NONE) {
+        size_t m0 = 0, m1 = 0;
+        for (const Section& sec : p.sections) {
+            m0 = std::max(m0, (size_t)sec.conv0.OH * sec.conv0.OW * sec.conv0.Cout);
+            m1 = std::max(m1, (size_t)sec.PH * sec.PW * sec.conv0.Cout);
+        }
+        o_lw[0] = off; off += al(mb * m0 * 2);
+        o_lw[1] = off; off += al(mb * m1 * 2);
+        o_lw[2] = off; off += al(mb * m1 * 2);
+        o_lw[3] = off; off += al(mb * m1 * 4);
+    }
     const size_t o_feat = off; off += al(mb * s->ldf * 2);
     const size_t o_fcb = off; off += al(mb * s->ldfc * 2);
     const size_t o_fcf = off; off += al(mb * F * 4);
@@ -360,6 +406,10 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     s->koff = (const int*)(s->arena + o_ko);
     s->act[0] = (__bf16*)(s->arena + o_act[0]);
     s->act[1] = (__bf16*)(s->arena + o_act[1]);
+    s->lw_c0 = (__bf16*)(s->arena + o_lw[0]);
+    s->lw_r = (__bf16*)(s->arena + o_lw[1]);
+    s->lw_u = (__bf16*)(s->arena + o_lw[2]);
+    s->lw_x = (float*)(s->arena + o_lw[3]);
     s->feat = (__bf16*)(s->arena + o_feat);
     s->fc_bf16 = (__bf16*)(s->arena + o_fcb);
     s->fc_f32 = (float*)(s->arena + o_fcf);
@@ -412,6 +462,28 @@ inline void launch_conv_stack(hipStream_t st, const ConvStackArgs& c)
     else hipLaunchKernelGGL((conv_stack_bf16_kernel<FT, 1, U8>), dim3((unsigned)((npix + 63) / 64), gy), dim3(256), 0, st, c);
 }
 
+inline void launch_lw_conv(hipStream_t st, const LwConvArgs& c, int ft, bool u8)
+{
+    const long npix = (long)c.B * c.H * c.W;
+    const int gy = c.Cout / (16 * ft);
+    auto go = [&](auto ftc, auto rtc, auto u8c) {
+        constexpr int FT = decltype(ftc)::value, RT = decltype(rtc)::value;
+        constexpr bool U8 = decltype(u8c)::value;
+        hipLaunchKernelGGL((conv3x3_lw_kernel<FT, RT, U8>), dim3((unsigned)((npix + 64 * RT - 1) / (64 * RT)), gy), dim3(256), 0, st, c);
+    };
+    auto by_rt = [&](auto ftc, auto u8c) {
+        if (npix >= 65536) go(ftc, std::integral_constant<int, 2>{}, u8c);
+        else go(ftc, std::integral_constant<int, 1>{}, u8c);
+    };
+    auto by_ft = [&](auto u8c) {
+        if (ft == 4) by_rt(std::integral_constant<int, 4>{}, u8c);
+        else if (ft == 2) by_rt(std::integral_constant<int, 2>{}, u8c);
+        else by_rt(std::integral_constant<int, 1>{}, u8c);
+    };
+    if (u8) by_ft(std::true_type{});
+    else by_ft(std::false_type{});
+}
+
 // Runs torso, linear layer, recurrent core and dueling hidden layers.  On
 // return *core / *ld_core name the fp32 rows the output heads read.
 inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hipStream_t st, int B, const uint8_t* obs,
@@ -423,7 +495,41 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
     (void)err;
     const Bf16WeightSet& W = s->ws[s->active];
     if (ev0) (void)hipEventRecord(ev0, st);
-    if (a.torso == SEED_TORSO_RESNET) {
+    if (a.torso == SEED_TORSO_RESNET && s->torso_kind == TORSO_NONE) {
+        // layer by layer: conv0 -> pool -> (conv_a, conv_b) x 2 per section, activations in HBM
+        const void* in = obs;
+        size_t li = 0;
+        for (size_t si = 0; si < p.sections.size(); ++si) {
+            const Section& sec = p.sections[si];
+            const bool last_sec = si + 1 == p.sections.size();
+            auto conv = [&](const ConvLayer& c, const void* src, bool u8, const float* x_in, float* x_out, __bf16* y, int y_relu,
+                            int ldy) {
+                const LwLayerDev& d = s->lw[li++];
+                LwConvArgs ca{};
+                ca.in = src; ca.wp = W.wp_conv + d.wp_off / 8; ca.bias = d_w + c.b_off;
+                ca.ktab = (const int2*)(s->koff + d.ktab_off);
+                ca.x_in = x_in; ca.x_out = x_out; ca.y = y; ca.y_relu = y_relu; ca.ldy = ldy;
+                ca.B = B; ca.H = c.H; ca.W = c.W; ca.Cin = c.Cin; ca.Cout = c.Cout; ca.kchunks = d.kchunks;
+                ca.scale = u8 ? 1.0f / 255.0f : 1.0f;
+                const int nft = c.Cout / 16;
+                const int ft = nft % 4 == 0 ? 4 : (nft % 2 == 0 ? 2 : 1);
+                launch_lw_conv(st, ca, ft, u8);
+            };
+            conv(sec.conv0, in, si == 0, nullptr, nullptr, s->lw_c0, 0, 0);
+            const int C = sec.conv0.Cout;
+            const long total = (long)B * sec.PH * sec.PW * (C / 4);
+            hipLaunchKernelGGL(pool3x3s2_lw_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s->lw_c0, s->lw_x,
+                               s->lw_r, B, sec.conv0.OH, sec.conv0.OW, C, sec.PH, sec.PW, sec.pool_pad_h, sec.pool_pad_w);
+            for (int blk = 0; blk < 2; ++blk) {
+                conv(sec.block[2 * blk], s->lw_r, false, nullptr, nullptr, s->lw_u, 1, 0);
+                const bool closing = last_sec && blk == 1;          // the torso's last layer writes the rectified features
+                const bool to_next = !last_sec && blk == 1;         // the next section's conv0 takes x un-rectified
+                conv(sec.block[2 * blk + 1], s->lw_u, false, s->lw_x, s->lw_x, closing ? s->feat : s->lw_r,
+                     to_next ? 0 : 1, closing ? s->ldf : 0);
+            }
+            in = s->lw_r;
+        }
+    } else if (a.torso == SEED_TORSO_RESNET) {
         TorsoArgs t{};
         t.obs = obs; t.feat = s->feat; t.ldf = s->ldf; t.B = B;
         for (int i = 0; i < 4; ++i) t.sec[i] = W.sec[i];

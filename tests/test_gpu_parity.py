@@ -226,8 +226,25 @@ def test_bf16_head_and_core_variants(orc):
     run_case(orc, c, 4, "bf16")
 
 
+@pytest.mark.parametrize("label,over,B", [
+    ("DMLab torso, filters x2", dict(sections=[32, 64, 64]), 5),
+    ("DMLab torso, filters x4", dict(sections=[64, 128, 128]), 3),
+    ("Football torso, medium map 120x90", dict(obs_h=90, obs_w=120), 4),
+    ("Football torso, large map 144x108", dict(obs_h=108, obs_w=144), 2),
+    ("odd frame 50x70x3, two sections, 48 channels", dict(obs_h=50, obs_w=70, sections=[16, 48]), 7),
+    ("4-plane minimap 72x96x4", dict(obs_c=4, sections=[16, 32, 32, 32]), 6),
+])
+def test_bf16_model_size_variants_run_layer_by_layer(orc, label, over, B):
+    """Model-size variants (Section 4.1: wider filters; Section 4.2: larger minimaps) have no fused kernel and
+    take the layer-by-layer bf16 path; same tolerance as the fused torso."""
+    base = wl.CONFIGS["C4"] if "Football" in label or "minimap" in label else wl.CONFIGS["C3"]
+    cfg = dict(base, label=label, index=31, **over)
+    got, ref, rep = run_case(orc, cfg, B, "bf16")
+    assert rep["max_rel_err"] <= 2e-2
+
+
 def test_bf16_unsupported_arch_is_reported():
-    cfg = dict(wl.CONFIGS["C3"], sections=[16, 32, 64])
+    cfg = dict(wl.CONFIGS["C3"], sections=[16, 32, 40])
     with pytest.raises(seedinf.SeedError) as e:
         seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=2, precision="bf16"), wl.make_weights(cfg))
     assert e.value.status == 2 and "fp32" in e.value.message
