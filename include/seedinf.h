@@ -260,6 +260,75 @@ const char* seed_infer_last_error(const seed_infer_t* handle);
  * have synchronised every stream the handle was used on. */
 void seed_infer_destroy(seed_infer_t* handle);
 
+/* ------------------------------------------------------------------------
+ * Host batching front-end (Section 3: a batching module gathers the actors'
+ * inference calls into one batch; the inference thread holds the recurrent
+ * states of all actors on the learner and returns only the actions).
+ *
+ * A batcher belongs to one seed_infer handle and one host thread.  It owns,
+ * on the device, the recurrent state (h, c, zero at creation) and the last
+ * action (0 at creation) of every actor, two pinned host staging sets and
+ * their device mirrors, a copy stream and a compute stream (default
+ * priority).  One round:
+ *
+ *   seed_batcher_add     once per actor call: copies the frame (host pointer,
+ *                        obs_h*obs_w*obs_c bytes), the reward that followed the
+ *                        actor's previous action and its episode flag into the
+ *                        next row of the staging set being filled.  Errors:
+ *                        actor out of [0, n_actors), the same actor twice in
+ *                        one batch, more than max_batch rows.
+ *   seed_batcher_submit  closes the batch (rows in the order they were added):
+ *                        host->device copies on the copy stream, then on the
+ *                        compute stream: gather the rows' states by actor,
+ *                        seed_infer_step_ext (done flags reset states; epsilon
+ *                        optional), scatter the new states and actions back,
+ *                        copy the actions to pinned host memory.  Returns at
+ *                        once with a ticket; the other staging set can be
+ *                        filled while this batch is in flight (the call waits
+ *                        only if that set's own earlier batch is unfinished).
+ *                        uniforms [rows, num_actions] (host) is required iff
+ *                        select is SEED_SELECT_GUMBEL; epsilon [rows] and
+ *                        explore_uniforms [rows, 2] (host) are optional, given
+ *                        together.  An empty batch is SEED_ERR_INVALID_ARG.
+ *   seed_batcher_wait    blocks until the ticket's batch has finished and
+ *                        copies its actions (row order) into actions_out
+ *                        [capacity >= rows]; *n_rows receives the row count.
+ *                        Only the two most recent tickets can be waited for.
+ *
+ * seed_batcher_read_state copies one actor's h and c ([lstm_units] each, host
+ * pointers) after synchronising the compute stream (diagnostic).  Feed-forward
+ * archs have no state: the call returns SEED_ERR_INVALID_ARG.
+ * The handle must outlive the batcher; seed_infer_set_weights may be called
+ * between rounds with the stream returned by seed_batcher_stream.
+ */
+typedef struct seed_batcher seed_batcher_t;
+
+seed_status_t seed_batcher_create(seed_infer_t* handle, int32_t n_actors, seed_batcher_t** out);
+seed_status_t seed_batcher_add(seed_batcher_t* b, int32_t actor, const uint8_t* obs_host,
+                               float prev_reward, uint8_t done);
+/* seed_batcher_add without the frame copy: *obs_slot receives the address of the row's frame in the pinned
+ * staging set, for the caller (e.g. the RPC layer) to write obs_h*obs_w*obs_c bytes into before
+ * seed_batcher_submit.  Same errors as seed_batcher_add. */
+seed_status_t seed_batcher_reserve(seed_batcher_t* b, int32_t actor, float prev_reward, uint8_t done,
+                                   uint8_t** obs_slot);
+/* n calls of seed_batcher_add: actors [n], obs_host n contiguous frames, prev_rewards [n], dones [n] (host).
+ * Stops at the first row that fails; the rows before it stay in the batch. */
+seed_status_t seed_batcher_add_many(seed_batcher_t* b, int32_t n, const int32_t* actors,
+                                    const uint8_t* obs_host, const float* prev_rewards,
+                                    const uint8_t* dones);
+seed_status_t seed_batcher_submit(seed_batcher_t* b, const float* uniforms_host,
+                                  const float* epsilon_host, const float* explore_uniforms_host,
+                                  int32_t* ticket);
+seed_status_t seed_batcher_wait(seed_batcher_t* b, int32_t ticket, int32_t* actions_out,
+                                int32_t capacity, int32_t* n_rows);
+seed_status_t seed_batcher_read_state(seed_batcher_t* b, int32_t actor, float* h_host, float* c_host);
+/* The compute stream (a hipStream_t) the batcher enqueues its steps on. */
+void* seed_batcher_stream(seed_batcher_t* b);
+/* Text of the batcher's most recent error; never NULL. */
+const char* seed_batcher_last_error(const seed_batcher_t* b);
+/* Waits for work in flight and frees the batcher.  NULL is allowed. */
+void seed_batcher_destroy(seed_batcher_t* b);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,6 +7,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/seedinf.h"
@@ -423,3 +424,4 @@ extern "C" seed_status_t seed_infer_profile_read(seed_infer_t* h, float* torso_m
     h->ev_used = 0;
     return SEED_OK;
 }
+#include "batcher.h"

@@ -24,6 +24,8 @@ STATUS = {0: "SEED_OK", 1: "SEED_ERR_INVALID_ARG", 2: "SEED_ERR_UNSUPPORTED_ARCH
           4: "SEED_ERR_ALIASING", 5: "SEED_ERR_DEVICE", 6: "SEED_ERR_OOM"}
 EXPORTS = ["seed_infer_weight_count", "seed_infer_validate", "seed_infer_create", "seed_infer_step",
            "seed_infer_step_ext", "seed_infer_set_weights",
+           "seed_batcher_create", "seed_batcher_add", "seed_batcher_reserve", "seed_batcher_add_many", "seed_batcher_submit", "seed_batcher_wait",
+           "seed_batcher_read_state", "seed_batcher_stream", "seed_batcher_last_error", "seed_batcher_destroy",
            "seed_infer_read_intermediate", "seed_infer_torso_features", "seed_infer_last_error",
            "seed_infer_destroy", "seed_infer_set_profiling", "seed_infer_profile_read"]
 
@@ -95,6 +97,26 @@ def load_library():
     lib.seed_infer_step_ext.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 6 + [C.POINTER(SeedStepExt)] + [C.c_void_p] * 7
     lib.seed_infer_set_weights.restype = C.c_int
     lib.seed_infer_set_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.seed_batcher_create.restype = C.c_int
+    lib.seed_batcher_create.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)]
+    lib.seed_batcher_add.restype = C.c_int
+    lib.seed_batcher_add.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_float, C.c_uint8]
+    lib.seed_batcher_reserve.restype = C.c_int
+    lib.seed_batcher_reserve.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_uint8, C.POINTER(C.c_void_p)]
+    lib.seed_batcher_add_many.restype = C.c_int
+    lib.seed_batcher_add_many.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.seed_batcher_submit.restype = C.c_int
+    lib.seed_batcher_submit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+    lib.seed_batcher_wait.restype = C.c_int
+    lib.seed_batcher_wait.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+    lib.seed_batcher_read_state.restype = C.c_int
+    lib.seed_batcher_read_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.seed_batcher_stream.restype = C.c_void_p
+    lib.seed_batcher_stream.argtypes = [C.c_void_p]
+    lib.seed_batcher_last_error.restype = C.c_char_p
+    lib.seed_batcher_last_error.argtypes = [C.c_void_p]
+    lib.seed_batcher_destroy.restype = None
+    lib.seed_batcher_destroy.argtypes = [C.c_void_p]
     lib.seed_infer_read_intermediate.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.seed_infer_last_error.restype = C.c_char_p
     lib.seed_infer_last_error.argtypes = [C.c_void_p]
@@ -280,3 +302,80 @@ class SeedInfer:
         if st != 0:
             raise SeedError(st, self.lib.seed_infer_last_error(self._h).decode())
         return dst
+
+
+class Batcher:
+    """Host batching front-end of one SeedInfer handle (seed_batcher_*): numpy in, numpy out."""
+
+    def __init__(self, net: SeedInfer, n_actors: int):
+        self.net, self.lib = net, net.lib
+        self.A, self.Hn = net.A, net.Hn
+        self.max_rows = net.arch.max_batch
+        h = C.c_void_p()
+        st = self.lib.seed_batcher_create(net._h, n_actors, C.byref(h))
+        if st != 0:
+            raise SeedError(st, self.lib.seed_batcher_last_error(None).decode())
+        self._b = h
+
+    def _check(self, st):
+        if st != 0:
+            raise SeedError(st, self.lib.seed_batcher_last_error(self._b).decode())
+
+    def add(self, actor: int, obs: np.ndarray, prev_reward: float = 0.0, done: bool = False):
+        obs = np.ascontiguousarray(obs, dtype=np.uint8)
+        a = self.net.arch
+        assert obs.shape == (a.obs_h, a.obs_w, a.obs_c), obs.shape
+        self._check(self.lib.seed_batcher_add(self._b, actor, obs.ctypes.data_as(C.c_void_p), float(prev_reward), int(bool(done))))
+
+    def reserve(self, actor: int, prev_reward: float = 0.0, done: bool = False) -> np.ndarray:
+        """Adds a row and returns a writable uint8 view of its frame slot in the pinned staging memory."""
+        slot = C.c_void_p()
+        self._check(self.lib.seed_batcher_reserve(self._b, actor, float(prev_reward), int(bool(done)), C.byref(slot)))
+        a = self.net.arch
+        n = a.obs_h * a.obs_w * a.obs_c
+        buf = (C.c_uint8 * n).from_address(slot.value)
+        return np.frombuffer(buf, dtype=np.uint8).reshape(a.obs_h, a.obs_w, a.obs_c)
+
+    def add_many(self, actors, obs, prev_rewards, dones):
+        actors = np.ascontiguousarray(actors, dtype=np.int32)
+        obs = np.ascontiguousarray(obs, dtype=np.uint8)
+        rew = np.ascontiguousarray(prev_rewards, dtype=np.float32)
+        dn = np.ascontiguousarray(dones, dtype=np.uint8)
+        a = self.net.arch
+        n = actors.size
+        assert obs.shape == (n, a.obs_h, a.obs_w, a.obs_c) and rew.shape == (n,) and dn.shape == (n,)
+        p = lambda x: x.ctypes.data_as(C.c_void_p)
+        self._check(self.lib.seed_batcher_add_many(self._b, n, p(actors), p(obs), p(rew), p(dn)))
+
+    def submit(self, uniforms=None, epsilon=None, explore_uniforms=None) -> int:
+        keep = [None if x is None else np.ascontiguousarray(x, dtype=np.float32) for x in (uniforms, epsilon, explore_uniforms)]
+        ptr = [None if x is None else x.ctypes.data_as(C.c_void_p) for x in keep]
+        t = C.c_int32()
+        self._check(self.lib.seed_batcher_submit(self._b, ptr[0], ptr[1], ptr[2], C.byref(t)))
+        return t.value
+
+    def wait(self, ticket: int) -> np.ndarray:
+        out = np.empty(self.max_rows, np.int32)
+        n = C.c_int32()
+        self._check(self.lib.seed_batcher_wait(self._b, ticket, out.ctypes.data_as(C.c_void_p), out.size, C.byref(n)))
+        return out[:n.value].copy()
+
+    def read_state(self, actor: int):
+        h, c = np.empty(self.Hn, np.float32), np.empty(self.Hn, np.float32)
+        self._check(self.lib.seed_batcher_read_state(self._b, actor, h.ctypes.data_as(C.c_void_p), c.ctypes.data_as(C.c_void_p)))
+        return h, c
+
+    @property
+    def stream(self) -> int:
+        return self.lib.seed_batcher_stream(self._b) or 0
+
+    def close(self):
+        if getattr(self, "_b", None):
+            self.lib.seed_batcher_destroy(self._b)
+            self._b = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

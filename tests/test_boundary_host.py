@@ -20,7 +20,7 @@ def lib():
 
 def test_exports_match_header(lib):
     hdr = open(os.path.join(ROOT, "include", "seedinf.h")).read()
-    declared = set(re.findall(r"\b(seed_infer_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(seed_(?:infer|batcher)_[a-z_]+)\s*\(", hdr))
     assert declared == set(seedinf.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
