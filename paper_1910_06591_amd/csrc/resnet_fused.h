@@ -143,57 +143,27 @@ struct TorsoArgs {
     int B;
 };
 
-// ---- weight staging: global -> registers (issue) -> LDS slot (commit) -> A fragments ----
-template <int NF>
-struct WStage {
-    static constexpr int N = (NF * 64 + RN_THREADS - 1) / RN_THREADS;
-    bf16x8 r[N];
-};
-constexpr int WSET_MAX = WSLOT_BYTES / 1024;      // chunks in the largest weight set
-// Two sets are in flight at any time: set q travels in pipe.s[q % 2] from the start of the phase that uses
-// set q-2 to the end of the phase that uses set q-1, so a layer's weights have more than a whole phase to
-// arrive from L2 before they are written to their LDS slot.
-struct WPipe {
-    WStage<WSET_MAX> s[2];
-};
-template <int NF>
-__device__ __forceinline__ void wpipe_issue(WStage<WSET_MAX>& st, const bf16x8* __restrict__ src, int tid)
+// ---- weight staging: global -> LDS slot (asynchronous, no registers) -> A fragments ----
+// A set is NF chunks of 1 KiB; chunk c is moved by wavefront c % RN_WAVES with one global_load_lds_dwordx4:
+// lane l's 16 bytes land at (wave-uniform LDS base in M0) + 16 * l.  The load is written as inline assembly
+// because the compiler would otherwise wait for it before the next LDS access of any kind; here it stays in
+// flight for the whole phase and stage_wait() (before the phase's closing barrier) collects it.
+__device__ __forceinline__ void g2lds16(const void* gptr, uint32_t lds_base)
 {
-    // every thread loads (out-of-range ones re-read the last chunk): loads issued under a branch would force
-    // the later commit to wait for ALL outstanding loads instead of just its own
-#pragma unroll
-    for (int j = 0; j < (NF * 64 + RN_THREADS - 1) / RN_THREADS; ++j) {
-        const int i = tid + j * RN_THREADS;
-        st.r[j] = src[i < NF * 64 ? i : NF * 64 - 1];
-    }
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void stage_wait()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 template <int NF>
-__device__ __forceinline__ void wpipe_commit(const WStage<WSET_MAX>& st, char* slot, int tid)
+__device__ __forceinline__ void stage_set(const bf16x8* __restrict__ src, char* slot, int lane, int wave)
 {
+    const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)slot;
 #pragma unroll
-    for (int j = 0; j < (NF * 64 + RN_THREADS - 1) / RN_THREADS; ++j) {
-        const int i = tid + j * RN_THREADS;
-        if (i < NF * 64) *(bf16x8*)(slot + i * 16) = st.r[j];
-    }
-}
-
-template <int NF>
-__device__ __forceinline__ void wstage_issue(WStage<NF>& s, const bf16x8* __restrict__ src, int tid)
-{
-#pragma unroll
-    for (int j = 0; j < WStage<NF>::N; ++j) {
-        const int i = tid + j * RN_THREADS;
-        if (i < NF * 64) s.r[j] = src[i];
-    }
-}
-
-template <int NF>
-__device__ __forceinline__ void wstage_commit(const WStage<NF>& s, char* slot, int tid)
-{
-#pragma unroll
-    for (int j = 0; j < WStage<NF>::N; ++j) {
-        const int i = tid + j * RN_THREADS;
-        if (i < NF * 64) *(bf16x8*)(slot + i * 16) = s.r[j];
+    for (int j = 0; j < (NF + RN_WAVES - 1) / RN_WAVES; ++j) {
+        const int c = wave + j * RN_WAVES;                       // wave-uniform
+        if ((j + 1) * RN_WAVES <= NF || c < NF) g2lds16(src + c * 64 + lane, base + c * 1024);
     }
 }
 
@@ -306,7 +276,7 @@ __device__ __forceinline__ void prefetch_issue(Prefetch<S>& p, const uint8_t* __
             constexpr int GPR = S::W / 4;
             const int nitems = (r1 - r0 + 1) * GPR;            // real rows only (whole frame: r0 = 0, r1 = H-1)
 #pragma unroll
-            for (int j = 0; j < S::PRE_N; ++j) {             // unconditional (clamped) loads, see wpipe_issue
+            for (int j = 0; j < S::PRE_N; ++j) {             // unconditional (clamped) loads: under a branch the later wait would cover ALL outstanding loads
                 const int i = min(tid + j * RN_THREADS, nitems - 1);
                 const uint32_t* s = (const uint32_t*)(obs_img + (size_t)(r0 + i / GPR) * S::W * 3) + (i % GPR) * 3;
                 p.d[j][0] = s[0]; p.d[j][1] = s[1]; p.d[j][2] = s[2];
@@ -902,13 +872,13 @@ constexpr int wslot(int q)
 
 // One section for one image.
 //   J0: number of this section's conv0 weight set (-1: the resident first-layer set); its blocks use J0+1..J0+4.
-//   SN / nsw: the next section (its conv0 and first block are staged from here); NSETS: sets per image.
-//   Staging rule: the phase that uses set j issues the loads of set j+2 when it starts and commits set j+1 to
-//   LDS when it ends; section 1's conv0 phase issues sets 0 and 1 and commits set 0.
+//   SN / nsw: the next section (its conv0 set is staged from here); NSETS: sets per image.
+//   Staging rule: the phase that uses set j starts the asynchronous load of set j+1 into the other slot and
+//   waits for it just before its closing barrier (the x-read phase uses no set and stages nothing).
 // On entry (INKIND == IN_LDS) buf0 holds the previous section's un-rectified output as a planar map with
 // halo; on exit (not LAST) buf0 holds this section's.  LAST writes ReLU(x) to feat_row.
 template <class S, class SN, class M, bool LAST, int SI, int J0, int NSETS, class PreT>
-__device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, const SecWeights& nsw, WPipe& pipe,
+__device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, const SecWeights& nsw,
                                             const uint8_t* __restrict__ obs_img, PreT& pre,
                                             __bf16* __restrict__ feat_row, int tid)
 {
@@ -925,34 +895,24 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     static_assert(S::ACT_BYTES <= 36 * 1024 || S::WB_SET * 1024 <= M::WSB_HI_CAP, "block weights do not fit the high slot");
     static_assert(S::WB_SET * 1024 <= WSLOT_BYTES && S::W0_SET * 1024 <= WSLOT_BYTES, "weight set larger than a slot");
     static_assert(LAST || (QB + 4) % 2 == 0 || SN::ACT_BYTES <= 36 * 1024 || SN::W0_SET * 1024 <= M::WSB_HI_CAP, "next conv0 set does not fit");
-    // set q (relative to this section: 0 = block1.a ... 3 = block2.b, 4 = next conv0, 5 = next block1.a)
-    auto issue = [&](auto rel) {
+    // set q (relative to this section: 0 = block1.a ... 3 = block2.b, 4 = next conv0)
+    auto stage = [&](auto rel) {
         constexpr int r = decltype(rel)::value;
         constexpr int q = QB + r;
         if constexpr (q < NSETS) {
-            if constexpr (r < 4) wpipe_issue<S::WB_SET>(pipe.s[q & 1], sw.wb[r], tid);
-            else if constexpr (r == 4) wpipe_issue<SN::W0_SET>(pipe.s[q & 1], nsw.w0, tid);
-            else wpipe_issue<SN::WB_SET>(pipe.s[q & 1], nsw.wb[0], tid);
-        }
-    };
-    auto commit = [&](auto rel) {
-        constexpr int r = decltype(rel)::value;
-        constexpr int q = QB + r;
-        if constexpr (q < NSETS) {
-            if constexpr (r < 4) wpipe_commit<S::WB_SET>(pipe.s[q & 1], lds + wslot<M, S>(q), tid);
-            else wpipe_commit<SN::W0_SET>(pipe.s[q & 1], lds + wslot<M, SN>(q), tid);
+            if constexpr (r < 4) stage_set<S::WB_SET>(sw.wb[r], lds + wslot<M, S>(q), lane, wave);
+            else stage_set<SN::W0_SET>(nsw.w0, lds + wslot<M, SN>(q), lane, wave);
         }
     };
     using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
     using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
-    using I4 = std::integral_constant<int, 4>; using I5 = std::integral_constant<int, 5>;
+    using I4 = std::integral_constant<int, 4>;
     floatx4 x[S::NT][S::FT];
     PHASE_DECL;
 
     // ---------------- conv0 + max-pool ----------------
     {
-        if constexpr (J0 < 0) { issue(I0{}); issue(I1{}); }      // image start: nothing is in flight yet
-        else issue(I1{});                                        // this phase uses set J0: issue J0 + 2
+        stage(I0{});                                             // this phase uses set J0: stage J0 + 1
         zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf1, tid);
         bf16x8 w0[S::W0_FRAGS];
         if constexpr (S::INKIND == IN_LDS) {
@@ -974,7 +934,7 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                 if (strip + 1 < S::NSTRIPS) lds_barrier();
             }
         }
-        commit(I0{});
+        stage_wait();
         lds_barrier();
         PHASE_MARK(SI * 8 + 1);
     }
@@ -1037,27 +997,27 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     using BF = std::false_type; using BT = std::true_type;
 
     // ---------------- residual blocks ----------------
-    issue(I2{});
+    stage(I1{});
     conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB));
-    commit(I1{});
+    stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 4);
-    issue(I3{});
+    stage(I2{});
     conv(BT{}, I0{}, buf1, buf0, lds + wslot<M, S>(QB + 1));
-    commit(I2{});
+    stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 5);
-    if constexpr (!LAST) issue(I4{});
+    stage(I3{});
     conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB + 2));
-    commit(I3{});
+    stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 6);
-    if constexpr (!LAST) issue(I5{});
+    if constexpr (!LAST) stage(I4{});
     conv(BT{}, std::integral_constant<int, LAST ? 2 : 1>{}, buf1, buf0, lds + wslot<M, S>(QB + 3));
-    if constexpr (!LAST) commit(I4{});
     // The last layer writes to global memory, so buf0 is free: the next frame's first strip (prefetched into
     // registers before this section) is converted into it here, under this phase's barrier.
     if constexpr (LAST) prefetch_commit<typename PreT::Sec>(pre, buf0, 0, tid);
+    stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 7);
 }
@@ -1087,25 +1047,22 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
         ninf[0] = ninf[1] = ninf[2] = ninf[3] = (__bf16)(-INFINITY);
         *(bf16x4*)(lds + M::NEUTRAL) = ninf;
     }
-    {   // the resident first-layer weight set
-        WStage<S1::W0_SET> s0;
-        wstage_issue(s0, a.sec[0].w0, tid);
-        wstage_commit(s0, lds + M::PERM, tid);
-    }
-    WPipe pipe;
+    // the resident first-layer weight set
+    stage_set<S1::W0_SET>(a.sec[0].w0, lds + M::PERM, tid & 63, __builtin_amdgcn_readfirstlane(tid >> 6));
     Prefetch<S1> pre;
     prefetch_issue<S1>(pre, a.obs + FRAME * blockIdx.x, 0, tid);
     prefetch_commit<S1>(pre, lds + M::BUF0, 0, tid);
+    stage_wait();
     lds_barrier();
     for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
-        run_section<S1, S2, M, false, 0, -1, N::NSETS>(lds, a.sec[0], a.sec[1], pipe, obs_img, pre, feat_row, tid);
-        run_section<S2, S3, M, false, 1, 4, N::NSETS>(lds, a.sec[1], a.sec[2], pipe, obs_img, pre, feat_row, tid);
+        run_section<S1, S2, M, false, 0, -1, N::NSETS>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
+        run_section<S2, S3, M, false, 1, 4, N::NSETS>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
         // the next frame's bytes travel while section 3 computes
-        const int nimg = img + (int)gridDim.x < a.B ? img + (int)gridDim.x : img;   // unconditional: see wpipe_issue
+        const int nimg = img + (int)gridDim.x < a.B ? img + (int)gridDim.x : img;   // unconditional load address
         prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
-        run_section<S3, S3, M, true, 2, 9, N::NSETS>(lds, a.sec[2], a.sec[2], pipe, obs_img, pre, feat_row, tid);
+        run_section<S3, S3, M, true, 2, 9, N::NSETS>(lds, a.sec[2], a.sec[2], obs_img, pre, feat_row, tid);
     }
 }
 
@@ -1135,25 +1092,21 @@ __global__ __launch_bounds__(RN_THREADS) void resnet4_bf16_kernel(TorsoArgs a)
         ninf[0] = ninf[1] = ninf[2] = ninf[3] = (__bf16)(-INFINITY);
         *(bf16x4*)(lds + M::NEUTRAL) = ninf;
     }
-    {
-        WStage<S1::W0_SET> s0;
-        wstage_issue(s0, a.sec[0].w0, tid);
-        wstage_commit(s0, lds + M::PERM, tid);
-    }
-    WPipe pipe;
+    stage_set<S1::W0_SET>(a.sec[0].w0, lds + M::PERM, tid & 63, __builtin_amdgcn_readfirstlane(tid >> 6));
     Prefetch<S1> pre;
     prefetch_issue<S1>(pre, a.obs + FRAME * blockIdx.x, 0, tid);
     prefetch_commit<S1>(pre, lds + M::BUF0, 0, tid);
+    stage_wait();
     lds_barrier();
     for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
-        run_section<S1, S2, M, false, 0, -1, N::NSETS>(lds, a.sec[0], a.sec[1], pipe, obs_img, pre, feat_row, tid);
-        run_section<S2, S3, M, false, 1, 4, N::NSETS>(lds, a.sec[1], a.sec[2], pipe, obs_img, pre, feat_row, tid);
-        run_section<S3, S4, M, false, 2, 9, N::NSETS>(lds, a.sec[2], a.sec[3], pipe, obs_img, pre, feat_row, tid);
+        run_section<S1, S2, M, false, 0, -1, N::NSETS>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
+        run_section<S2, S3, M, false, 1, 4, N::NSETS>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
+        run_section<S3, S4, M, false, 2, 9, N::NSETS>(lds, a.sec[2], a.sec[3], obs_img, pre, feat_row, tid);
         const int nimg = img + (int)gridDim.x < a.B ? img + (int)gridDim.x : img;
         prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
-        run_section<S4, S4, M, true, 3, 14, N::NSETS>(lds, a.sec[3], a.sec[3], pipe, obs_img, pre, feat_row, tid);
+        run_section<S4, S4, M, true, 3, 14, N::NSETS>(lds, a.sec[3], a.sec[3], obs_img, pre, feat_row, tid);
     }
 }
 
