@@ -52,7 +52,11 @@ __device__ unsigned long long seed_phase_cycles[32];
         }                                                                               \
     } while (0)
 #define PHASE_DECL unsigned long long phase_last_ = clock64()
+#define DETAIL_T0 unsigned long long dt_[4]; dt_[0] = clock64()
+#define DETAIL_MARK(k) do { dt_[k + 1] = clock64(); if (k == 2 && SI == DETAIL_SEC && (tid & 63) == 0 && (tid >> 6) == DETAIL_WAVE) { for (int q_ = 0; q_ < 3; ++q_) atomicAdd(&seed_phase_cycles[24 + q_], dt_[q_ + 1] - dt_[q_]); } } while (0)
 #else
+#define DETAIL_T0 do { } while (0)
+#define DETAIL_MARK(k) do { } while (0)
 #define PHASE_MARK(id) do { } while (0)
 #define PHASE_DECL do { } while (0)
 #endif
@@ -100,6 +104,11 @@ struct SecCfg {
     // The 3-channel first layer pools without lane shifts (conv0_pool3): it needs no edge buffer and its
     // pooled map is complete when the conv0 phase ends.
     static constexpr bool POOL3 = INKIND == IN_U8_C3;
+    // Small 32 -> 32 channel sections write conv0's full-resolution output to LDS as a planar map (conv_map)
+    // and pool it while the residual stream is read: on a map this narrow the strip scheme wastes half of its
+    // second column strip and its per-row pooling costs more than the extra LDS round trip.
+    static constexpr int CM_BYTES = (C / 8) * (((H + 2) * (W + 2) + 15) / 16 * 16) * 16;
+    static constexpr bool CONVMAP = INKIND == IN_LDS && CIN == 32 && C == 32 && CM_BYTES <= 36 * 1024;
     static constexpr int NPIX = PH * PW;
     static constexpr int NTILES = (NPIX + 15) / 16;
     static constexpr int NT = SLIDE ? 14 : (NTILES + NWA - 1) / NWA;
@@ -116,7 +125,7 @@ struct SecCfg {
     static constexpr int IN_BYTES = (INKIND == IN_U8_C3 ? 1 : CIN / 8) * IPLANE * ICELL + 16;
     static constexpr int PITCH = PW + 2, PLANE = ((PH + 2) * PITCH + 15) / 16 * 16;
     static constexpr int ACT_BYTES = (C / 8) * PLANE * 16;
-    static constexpr int EDGE_BYTES = POOL3 ? 0 : NCS * PH * C * 2;
+    static constexpr int EDGE_BYTES = POOL3 || CONVMAP ? 0 : NCS * PH * C * 2;
     // prefetch registers for the uint8 input: items of PRE_DW dwords, PRE_N per thread
     static constexpr int PRE_DW = INKIND == IN_U8_C3 ? 3 : (INKIND == IN_U8_PLANAR ? CIN / 4 : 1);
     static constexpr int PRE_ITEMS = INKIND == IN_U8_C3 ? (IROWS - 2) * (W / 4) : (INKIND == IN_U8_PLANAR ? (IROWS - 2 + 2) * W : 0);
@@ -826,6 +835,54 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
     }
 }
 
+// conv0 of a CONVMAP section in block_conv's terms: a 3x3 SAME conv C -> C over the section's H x W input map,
+// all wavefronts, output = the un-pooled, un-rectified conv map (planar, same geometry as the input).
+template <class S>
+struct ConvMapCfg {
+    static constexpr int C = S::C, FT = S::FT, KCB = S::KC0, WB_FRAGS = S::W0_FRAGS;
+    static constexpr int PH = S::H, PW = S::W, NPIX = PH * PW, NTILES = (NPIX + 15) / 16;
+    static constexpr int NWA = RN_WAVES, NT = (NTILES + NWA - 1) / NWA;
+    static constexpr int PITCH = S::IPITCH, PLANE = S::IPLANE;
+    static_assert(S::CONVMAP && S::IROWS == S::H + 2 && PLANE * (C / 8) * 16 == S::CM_BYTES, "conv map geometry");
+};
+
+template <class S>
+__device__ __forceinline__ void conv_map(const char* in, char* out, const char* wslot, int lane, int wave)
+{
+    using CM = ConvMapCfg<S>;
+    int tb[CM::NT];
+#pragma unroll
+    for (int i = 0; i < CM::NT; ++i) {
+        const int t = wave + CM::NWA * i;
+        int y, xx;
+        tile_pixel<CM>(t < CM::NTILES ? t : CM::NTILES - 1, lane & 15, y, xx);
+        tb[i] = y * CM::PITCH + xx;
+    }
+    floatx4 unused[CM::NT][CM::FT];                        // block_conv reads x only when it adds it
+    block_conv<CM, false, 1>(in, out, wslot, tb, unused, nullptr, lane, wave);
+}
+
+// 3x3 / stride-2 maximum of a CONVMAP section's conv map at pooled pixel (y, xx) for the lane's four channels of
+// feature tile j.  Window rows and columns that fall outside the map are clamped onto it (a repeated value
+// does not change a maximum), which is the SAME padding of max-pooling.
+template <class S>
+__device__ __forceinline__ void pool_window(const char* cmap, int y, int xx, int g, bf16x4 (&v)[S::FT][9])
+{
+    using CM = ConvMapCfg<S>;
+    int ro[3], co[3];
+#pragma unroll
+    for (int d = 0; d < 3; ++d) {
+        const int r = 2 * y - S::PADH + d, c = 2 * xx + d;
+        ro[d] = ((r < 0 ? 0 : (r > S::H - 1 ? S::H - 1 : r)) + 1) * CM::PITCH;
+        co[d] = (c > S::W - 1 ? S::W - 1 : c) + 1;
+    }
+    const char* base = cmap + (g >> 1) * (CM::PLANE * 16) + (g & 1) * 8;
+#pragma unroll
+    for (int j = 0; j < S::FT; ++j)
+#pragma unroll
+        for (int d = 0; d < 9; ++d) v[j][d] = *(const bf16x4*)(base + (ro[d / 3] + co[d % 3]) * 16 + j * (2 * CM::PLANE * 16));
+}
+
 // zero the halo ring of a planar map of CG planes (PLANE cells apart), interior IH x IW
 template <int CG, int IH, int IW, int PLANE>
 __device__ __forceinline__ void zero_halo(char* buf, int tid)
@@ -913,9 +970,11 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     // ---------------- conv0 + max-pool ----------------
     {
         stage(I0{});                                             // this phase uses set J0: stage J0 + 1
-        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf1, tid);
-        bf16x8 w0[S::W0_FRAGS];
-        if constexpr (S::INKIND == IN_LDS) {
+        if constexpr (!S::CONVMAP) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf1, tid);
+        bf16x8 w0[S::CONVMAP ? 1 : S::W0_FRAGS];
+        if constexpr (S::CONVMAP) {
+            conv_map<S>(buf0, buf1, lds + SLOT_C0, lane, wave);     // buf1 <- the full-resolution conv map
+        } else if constexpr (S::INKIND == IN_LDS) {
             load_a_frags(w0, lds + SLOT_C0, lane);
             conv0_pool<S>(buf0, buf1, edge, lds + M::TRASH, w0, lds + SLOT_C0, 0, S::PH, -1, lane, wave);
         } else {
@@ -943,7 +1002,34 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     int tb[S::NT];                                     // per tile: cell index of the lane's pixel (tap (0,0), plane 0)
     {
         zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf0, tid);
-        if (wave < S::NWA) {
+        if constexpr (S::CONVMAP) {
+            if (wave < S::NWA) {                       // x = 3x3/2 maximum of the conv map in buf1
+                const int loff = (S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
+                bf16x4 wv[S::NT][S::FT][9];
+                bool ok[S::NT];
+#pragma unroll
+                for (int i = 0; i < S::NT; ++i) {      // all loads first
+                    int y, xx;
+                    bool tile_ok;
+                    tile_ref<S>(wave, i, n, y, xx, tile_ok, ok[i]);
+                    tb[i] = y * S::PITCH + xx;
+                    if (!tile_ok) break;
+                    pool_window<S>(buf1, y, xx, g, wv[i]);
+                }
+#pragma unroll
+                for (int i = 0; i < S::NT; ++i) {
+                    if (wave + S::NWA * i >= S::NTILES) break;
+#pragma unroll
+                    for (int j = 0; j < S::FT; ++j) {
+                        floatx4 m = to_floatx4(wv[i][j][0]);
+#pragma unroll
+                        for (int d = 1; d < 9; ++d) m = max4(m, to_floatx4(wv[i][j][d]));
+                        x[i][j] = m;
+                        if (ok[i]) *(bf16x4*)(buf0 + tb[i] * 16 + loff + j * (2 * S::PLANE * 16)) = relu_bf16x4(to_bf16x4(m));
+                    }
+                }
+            }
+        } else if (wave < S::NWA) {
             const int loff = (S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
             bf16x4 pv[S::NT][S::FT], ev[S::NT][S::FT];
             bool ok[S::NT];
@@ -998,14 +1084,19 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
 
     // ---------------- residual blocks ----------------
     stage(I1{});
+    if constexpr (S::CONVMAP) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf1, tid);   // held the conv map until now
     conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB));
     stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 4);
     stage(I2{});
+    DETAIL_T0;
     conv(BT{}, I0{}, buf1, buf0, lds + wslot<M, S>(QB + 1));
+    DETAIL_MARK(0);
     stage_wait();
+    DETAIL_MARK(1);
     lds_barrier();
+    DETAIL_MARK(2);
     PHASE_MARK(SI * 8 + 5);
     stage(I3{});
     conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB + 2));
