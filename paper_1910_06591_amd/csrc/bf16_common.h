@@ -24,9 +24,18 @@ __device__ __forceinline__ floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-// fp32 -> bf16, round to nearest even.  Converting the whole vector at once lets the compiler use the
-// packed two-at-a-time hardware conversion; element-wise casts cost a conversion and a byte permute each.
-__device__ __forceinline__ bf16x4 to_bf16x4(floatx4 v) { return __builtin_convertvector(v, bf16x4); }
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+// fp32 -> bf16, round to nearest even.  Written as two 2-wide vector conversions so that each becomes one packed
+// hardware conversion (v_cvt_pk_bf16_f32); element-wise casts, and a 4-wide conversion whose result is then
+// reinterpreted as integers, cost a conversion and a byte permute per element.
+__device__ __forceinline__ bf16x4 to_bf16x4(floatx4 v)
+{
+    const bf16x2 lo = __builtin_convertvector((floatx2){v[0], v[1]}, bf16x2);
+    const bf16x2 hi = __builtin_convertvector((floatx2){v[2], v[3]}, bf16x2);
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+}
 
 __device__ __forceinline__ floatx4 relu4(floatx4 v)
 {
@@ -36,12 +45,16 @@ __device__ __forceinline__ floatx4 relu4(floatx4 v)
 }
 
 // ReLU on four packed bf16 values: as signed 16-bit integers every negative float is negative
-// and every non-negative float is non-negative, so max(x, 0) per 16-bit lane is exact.
-typedef short shortx4 __attribute__((ext_vector_type(4)));
+// and every non-negative float is non-negative, so max(x, 0) per 16-bit lane is exact (one v_pk_max_i16
+// per pair).
+typedef short shortx2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ bf16x4 relu_bf16x4(bf16x4 v)
 {
-    const shortx4 z = {0, 0, 0, 0};
-    return __builtin_bit_cast(bf16x4, __builtin_elementwise_max(__builtin_bit_cast(shortx4, v), z));
+    const shortx2 z = {0, 0};
+    const bf16x2 lo = __builtin_shufflevector(v, v, 0, 1), hi = __builtin_shufflevector(v, v, 2, 3);
+    const shortx2 l = __builtin_elementwise_max(__builtin_bit_cast(shortx2, lo), z);
+    const shortx2 h = __builtin_elementwise_max(__builtin_bit_cast(shortx2, hi), z);
+    return __builtin_shufflevector(__builtin_bit_cast(bf16x2, l), __builtin_bit_cast(bf16x2, h), 0, 1, 2, 3);
 }
 
 __device__ __forceinline__ floatx4 to_floatx4(bf16x4 v) { return __builtin_convertvector(v, floatx4); }

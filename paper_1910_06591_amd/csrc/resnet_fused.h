@@ -71,6 +71,16 @@ constexpr int WSLOT_BYTES = 19 * 1024;          // largest layer: 18 fragments o
 
 enum { IN_LDS = 0, IN_U8_C3 = 1, IN_U8_PLANAR = 2 };
 
+// Keeps the instruction scheduler from moving anything across this point: the hand-written order (loads of
+// the next tiles first, then the MFMA chains back to back, then the epilogue) is the software pipeline.
+// A wavefront's own vector-ALU instructions were measured not to overlap its MFMAs on this chip, so
+// interleaving the epilogue with the chain gains nothing; the overlap comes from the SIMD's other wavefront.
+#ifndef SEEDINF_NO_FENCE
+#define SCHED_FENCE __builtin_amdgcn_sched_barrier(0)
+#else
+#define SCHED_FENCE do { } while (0)
+#endif
+
 // Workgroup barrier for LDS-only communication: waits for this wavefront's LDS
 // traffic, not for its outstanding global loads (the prefetches stay in flight).
 __device__ __forceinline__ void lds_barrier()
@@ -748,11 +758,13 @@ __device__ __forceinline__ void block_conv_slide16(const char* src, char* dst, c
             }
             floatx4 a0 = ADD_X ? x[I0 + 2 * pp][0] + bv : bv;
             floatx4 a1 = ADD_X ? x[I0 + 2 * pp + 1][0] + bv : bv;
+            SCHED_FENCE;
             a0 = mfma16(w[0], R[2 * pp], a0);      a1 = mfma16(w[0], R[2 * pp + 1], a1);
             a0 = mfma16(w[1], R[2 * pp + 1], a0);  a1 = mfma16(w[1], R[2 * pp + 2], a1);
             a0 = mfma16(w[2], R[2 * pp + 2], a0);  a1 = mfma16(w[2], R[2 * pp + 3], a1);
             a0 = mfma16(w[3], E[pp], a0);          a1 = mfma16(w[5], E[pp], a1);
             a0 = mfma16(w[4], E[pp + 1], a0);      a1 = mfma16(w[6], E[pp + 1], a1);
+            SCHED_FENCE;
             const bool ok = 2 * pp < nt;                                   // uniform; chains have even lengths
             char* d = ok ? pD + (2 * pp) * ROWB : trash;
             if (ADD_X) { x[I0 + 2 * pp][0] = a0; x[I0 + 2 * pp + 1][0] = a1; }
