@@ -140,6 +140,8 @@ struct SecCfg {
     static constexpr int PRE_DW = INKIND == IN_U8_C3 ? 3 : (INKIND == IN_U8_PLANAR ? CIN / 4 : 1);
     static constexpr int PRE_ITEMS = INKIND == IN_U8_C3 ? (IROWS - 2) * (W / 4) : (INKIND == IN_U8_PLANAR ? (IROWS - 2 + 2) * W : 0);
     static constexpr int PRE_N = INKIND == IN_LDS ? 1 : (PRE_ITEMS + RN_THREADS - 1) / RN_THREADS;
+    // 3-channel frame: first byte of buf0 that the items j >= 1 of a sliced conversion write (see prefetch_commit)
+    static constexpr int PRE_SPLIT_BYTES = INKIND == IN_U8_C3 ? (RN_THREADS / (W / 4) + 1) * IPITCH * 8 : 0;
     static_assert(C % 16 == 0, "section channels must be a multiple of 16");
     static_assert(W % 2 == 0, "even width (pool padding only after the last column)");
     static_assert(INKIND == IN_U8_C3 ? CIN == 3 : (CIN == 16 || CIN == 32), "input channels: 3 (uint8), 16 or 32");
@@ -316,8 +318,10 @@ __device__ __forceinline__ void prefetch_issue(Prefetch<S>& p, const uint8_t* __
     }
 }
 
-// convert the prefetched bytes to bf16 and lay them out in buf0 (with zero halo)
-template <class S>
+// convert the prefetched bytes to bf16 and lay them out in buf0 (with zero halo).
+// PART < 0: everything.  The whole 3-channel frame can also be converted in slices: PART = j > 0 converts
+// only every thread's j-th item (frame rows from PRE_SPLIT_ROW on), PART = 0 the first items and the halo.
+template <class S, int PART = -1>
 __device__ __forceinline__ void prefetch_commit(const Prefetch<S>& p, char* buf0, int strip, int tid)
 {
     if constexpr (S::INKIND != IN_LDS) {
@@ -329,6 +333,7 @@ __device__ __forceinline__ void prefetch_commit(const Prefetch<S>& p, char* buf0
             const int nitems = (r1 - r0 + 1) * GPR;
 #pragma unroll
             for (int j = 0; j < S::PRE_N; ++j) {
+                if (PART >= 0 && j != PART) continue;
                 const int i = tid + j * RN_THREADS;
                 if (i < nitems) {
                     const uint32_t d0 = p.d[j][0], d1 = p.d[j][1], d2 = p.d[j][2];
@@ -344,6 +349,7 @@ __device__ __forceinline__ void prefetch_commit(const Prefetch<S>& p, char* buf0
                     }
                 }
             }
+            if (PART > 0) return;
             const bf16x4 z = {};
             // halo: first and last buffer rows, first and last columns, and the cell past the end that
             // the (zero-weight) kw = 3 half of the last fragment may touch
@@ -781,11 +787,20 @@ __device__ __forceinline__ void block_conv_slide16(const char* src, char* dst, c
 // src/dst: planar maps with halo.  OUT: 0 = store ReLU(v) to dst, 1 = store v
 // to dst, 2 = store ReLU(v) to the global feature row.  The B fragments of tile
 // i+1 are read from LDS while tile i's MFMAs run.
-template <class S, bool ADD_X, int OUT>
+struct NoFiller {
+    __device__ __forceinline__ void operator()() const {}
+};
+// `filler`: independent vector-ALU work that every wavefront runs once, placed behind the requests for the
+// weight and first activation fragments so that it executes while those travel from LDS.
+template <class S, bool ADD_X, int OUT, class Filler = NoFiller>
 __device__ __forceinline__ void block_conv(const char* src, char* dst, const char* wslot, const int (&tb)[S::NT],
-                                           floatx4 (&x)[S::NT][S::FT], __bf16* __restrict__ feat_row, int lane, int wave)
+                                           floatx4 (&x)[S::NT][S::FT], __bf16* __restrict__ feat_row, int lane, int wave,
+                                           Filler filler = Filler{})
 {
-    if (wave >= S::NWA) return;                            // uniform per wavefront
+    if (wave >= S::NWA) {                                  // uniform per wavefront
+        filler();
+        return;
+    }
     const int g = lane >> 4, n = lane & 15;
     constexpr bool WHOLE = S::NPIX % 16 == 0;              // no partial last tile
     bf16x8 w[S::WB_FRAGS];
@@ -810,6 +825,11 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
     constexpr bool DBUF = S::KCB <= 5;
     bf16x8 bcur[S::KCB], bnxt[DBUF ? S::KCB : 1];
     load_b(bcur, tb[0]);
+    if constexpr (!std::is_same<Filler, NoFiller>::value) {
+        SCHED_FENCE;
+        filler();
+        SCHED_FENCE;
+    }
 #pragma unroll
     for (int i = 0; i < S::NT; ++i) {
         const int t = wave + S::NWA * i;
@@ -1086,24 +1106,39 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
         lds_barrier();
         PHASE_MARK(SI * 8 + 3);
     }
-    auto conv = [&](auto add_x, auto out, const char* src, char* dst, const char* ws) {
+    auto conv = [&](auto add_x, auto out, const char* src, char* dst, const char* ws, auto filler) {
         constexpr bool ADD_X = decltype(add_x)::value;
         constexpr int OUT = decltype(out)::value;
-        if constexpr (S::SLIDE) block_conv_slide16<S, ADD_X, OUT>(src, dst, lds + M::TRASH + lane * 8, ws, x, lane, wave);
-        else block_conv<S, ADD_X, OUT>(src, dst, ws, tb, x, feat_row, lane, wave);
+        if constexpr (S::SLIDE) {
+            filler();
+            block_conv_slide16<S, ADD_X, OUT>(src, dst, lds + M::TRASH + lane * 8, ws, x, lane, wave);
+        } else {
+            block_conv<S, ADD_X, OUT>(src, dst, ws, tb, x, feat_row, lane, wave, filler);
+        }
     };
     using BF = std::false_type; using BT = std::true_type;
 
     // ---------------- residual blocks ----------------
+    // The last section's maps are small and the next frame sits in registers: its rows that land behind
+    // those maps in buf0 are converted a slice per block phase (the wavefronts mostly wait for LDS here), the
+    // rest in the last phase, when buf0 is free.
+    using PS = typename PreT::Sec;
+    constexpr bool SLICED = LAST && PS::INKIND == IN_U8_C3 && PS::NSTRIPS == 1 && PS::PRE_N == 4 &&
+                            S::ACT_BYTES <= PS::PRE_SPLIT_BYTES;
+    auto slice = [&](auto part) {
+        return [&pre, buf0, tid]() {
+            if constexpr (SLICED) prefetch_commit<PS, decltype(part)::value>(pre, buf0, 0, tid);
+        };
+    };
     stage(I1{});
     if constexpr (S::CONVMAP) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf1, tid);   // held the conv map until now
-    conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB));
+    conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB), slice(I1{}));
     stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 4);
     stage(I2{});
     DETAIL_T0;
-    conv(BT{}, I0{}, buf1, buf0, lds + wslot<M, S>(QB + 1));
+    conv(BT{}, I0{}, buf1, buf0, lds + wslot<M, S>(QB + 1), slice(I2{}));
     DETAIL_MARK(0);
     stage_wait();
     DETAIL_MARK(1);
@@ -1111,15 +1146,15 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     DETAIL_MARK(2);
     PHASE_MARK(SI * 8 + 5);
     stage(I3{});
-    conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB + 2));
+    conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB + 2), slice(I3{}));
     stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 6);
     if constexpr (!LAST) stage(I4{});
-    conv(BT{}, std::integral_constant<int, LAST ? 2 : 1>{}, buf1, buf0, lds + wslot<M, S>(QB + 3));
+    conv(BT{}, std::integral_constant<int, LAST ? 2 : 1>{}, buf1, buf0, lds + wslot<M, S>(QB + 3), NoFiller{});
     // The last layer writes to global memory, so buf0 is free: the next frame's first strip (prefetched into
     // registers before this section) is converted into it here, under this phase's barrier.
-    if constexpr (LAST) prefetch_commit<typename PreT::Sec>(pre, buf0, 0, tid);
+    if constexpr (LAST) prefetch_commit<PS, SLICED ? 0 : -1>(pre, buf0, 0, tid);
     stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 7);
