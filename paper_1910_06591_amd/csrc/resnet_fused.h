@@ -114,6 +114,11 @@ struct SecCfg {
     // The 3-channel first layer pools without lane shifts (conv0_pool3): it needs no edge buffer and its
     // pooled map is complete when the conv0 phase ends.
     static constexpr bool POOL3 = INKIND == IN_U8_C3;
+    // With lane-wise pooling AND the sliding block scheme, a conv0 unit (16 pooled columns of one pooled row) is
+    // exactly a block tile in the accumulator layout: conv0 then walks the wavefront's own tile chains, keeps
+    // the pooled values as the residual stream x in registers and stores ReLU(x) directly, and the section
+    // needs no x-read phase.  Its maps swap roles (R in buf1, U in buf0), so its output lands in buf1.
+    static constexpr bool XFUSED = POOL3 && SLIDE;
     // Small 32 -> 32 channel sections write conv0's full-resolution output to LDS as a planar map (conv_map)
     // and pool it while the residual stream is read: on a map this narrow the strip scheme wastes half of its
     // second column strip and its per-row pooling costs more than the extra LDS round trip.
@@ -686,6 +691,88 @@ __device__ __forceinline__ void conv0_pool3(const char* in, char* xout, const bf
     }
 }
 
+// conv0_pool3 for an XFUSED section: the same arithmetic, walked along the wavefront's tile chains (see
+// SlideMap16).  x[i] receives tile i's pooled values (fp32, bias added), rout the planar map of ReLU(x).
+template <class S>
+__device__ __forceinline__ void conv0_pool3_x(const char* in, char* rout, const bf16x8 (&w0)[S::W0_FRAGS], const char* wslot,
+                                              floatx4 (&x)[S::NT][S::FT], int lane, int wave)
+{
+    static_assert(S::XFUSED && S::FT == 1 && S::W0_FRAGS == 4 && S::NSTRIPS == 1 && S::PADH == 0 && S::H % 2 == 0,
+                  "conv0_pool3_x: whole 3-channel frame, even height, sliding block scheme");
+    using SM = SlideMap16;
+    const int g = lane >> 4, n = lane & 15;
+    constexpr float SCALE = 1.0f / 255.0f;
+    constexpr int ROWB = S::IPITCH * 8;
+    const floatx4 bv = *(const floatx4*)(wslot + S::W0_FRAGS * 1024 + g * 16);
+    const int koffp = (g >> 1) * S::IPITCH + (g & 1) * 2;
+    typedef bf16x8 Pair[3];
+    const floatx4 ZERO = {0.f, 0.f, 0.f, 0.f};
+    using EVEN = std::integral_constant<int, 0>;
+    using ODD = std::integral_constant<int, 1>;
+    auto conv_row = [&](auto par, const Pair& lo, const Pair& hi) {
+        constexpr int P = decltype(par)::value;
+        floatx4 acc[3];
+#pragma unroll
+        for (int d = 0; d < 3; ++d) {
+            acc[d] = mfma16(w0[2 * P], lo[d], ZERO);
+            acc[d] = mfma16(w0[2 * P + 1], hi[d], acc[d]);
+        }
+        return max4(max4(acc[0], acc[1]), acc[2]);
+    };
+    auto run_chain = [&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        constexpr int LEN = c == 0 ? SM::LEN0 : SM::LEN1, I0 = c == 0 ? 0 : SM::LEN0;
+        int strip, row0, nt;
+        SM::chain(wave, c, strip, row0, nt);
+        const int px = strip * 16 + n;
+        const char* pa = in + (2 * row0 * S::IPITCH + 2 * px + koffp) * 8;
+        const char* pa2 = pa + (px == S::PW - 1 ? 8 : 16);
+        int kp = row0;                                       // pair the pointers sit on; the map's last pair is PH
+        auto load_pair = [&](Pair& f) {
+#pragma unroll
+            for (int d = 0; d < 3; ++d) {
+                const char* cp = d < 2 ? pa + d * 8 : pa2;
+                const bf16x4 lo = *(const bf16x4*)cp, hi = *(const bf16x4*)(cp + 8);
+                f[d] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+            const bool more = kp < S::PH;                    // past the last pair: stay (those fragments are never used)
+            pa += more ? 2 * ROWB : 0;
+            pa2 += more ? 2 * ROWB : 0;
+            kp += more ? 1 : 0;
+        };
+        Pair F[3];                                           // pair k lives in F[(k - row0) % 3]
+        load_pair(F[0]);
+        load_pair(F[1]);
+        floatx4 top = conv_row(EVEN{}, F[0], F[1]);
+        load_pair(F[2]);
+        char* rptr = rout + ((row0 + 1) * S::PITCH + px + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
+#pragma unroll
+        for (int pos = 0; pos < LEN; ++pos) {
+            constexpr int dummy = 0; (void)dummy;
+            if (pos < nt) {                                  // uniform
+                floatx4 v;
+                if (row0 + pos < S::PH - 1) {                // uniform: the map's bottom row has no third conv row
+                    const floatx4 hm = conv_row(ODD{}, F[pos % 3], F[(pos + 1) % 3]);
+                    const floatx4 hb = conv_row(EVEN{}, F[(pos + 1) % 3], F[(pos + 2) % 3]);
+                    load_pair(F[pos % 3]);                   // pair py + 3 replaces pair py
+                    v = max4(max4(top, hm), hb);
+                    top = hb;
+                } else {
+                    v = max4(top, conv_row(ODD{}, F[pos % 3], F[(pos + 1) % 3]));
+                }
+                v = v * SCALE + bv;
+                x[I0 + pos][0] = v;
+                *(bf16x4*)rptr = relu_bf16x4(to_bf16x4(v));
+                rptr += S::PITCH * 16;
+            } else {
+                x[I0 + pos][0] = ZERO;
+            }
+        }
+    };
+    run_chain(std::integral_constant<int, 0>{});
+    run_chain(std::integral_constant<int, 1>{});
+}
+
 // Per-lane cell index (row * PITCH + column, plane 0, tap (0,0)) of the pixel this lane holds in each of
 // the wavefront's tiles; pixels past the end of the map are clamped to the last one.  NWA = wavefronts
 // that own tiles in this section.
@@ -946,17 +1033,20 @@ struct LdsMap {
     static constexpr int PERM = LDS_TOTAL - r256(PERM_);           // first layer's weights, resident for the whole kernel
     static constexpr int WSB_HI_CAP = PERM - WSB_HI;
     static constexpr int WSB_LO = BUF1 + 36 * 1024;                // inside buf1's tail: only while buf1 holds <= 36 KiB
+    static constexpr int WSB_LO0 = BUF0 + 36 * 1024;               // inside buf0's tail, for sections whose input sits in buf1
+    static_assert(WSB_LO0 + WSLOT_BYTES <= BUF1, "low weight slot must fit in buf0's tail");
     static_assert(WSB_HI_CAP >= 0, "LDS layout does not fit");
     static_assert(WSB_LO + WSLOT_BYTES <= EDGE, "low weight slot must fit in buf1's tail");
 };
 
 // Weight sets are numbered along one image: S1.block1.a = 0 ... (the first layer's set is resident).  Set q
-// lives in slot A when q is even, else in slot B; B is the high slot while the consuming section keeps buf1
-// full (section 1) and the low slot inside buf1's unused tail otherwise.
-template <class M, class S>
+// lives in slot A when q is even, else in slot B; B is the high slot while the consuming section keeps its maps
+// full size (section 1) and otherwise the low slot inside the unused tail of buf1, or of buf0 when the
+// consuming section's input sits in buf1 (INB: it follows an XFUSED section).
+template <class M, class S, bool INB>
 constexpr int wslot(int q)
 {
-    return (q & 1) == 0 ? M::WSA : (S::ACT_BYTES > 36 * 1024 ? M::WSB_HI : M::WSB_LO);
+    return (q & 1) == 0 ? M::WSA : (S::ACT_BYTES > 36 * 1024 ? M::WSB_HI : (INB ? M::WSB_LO0 : M::WSB_LO));
 }
 
 // One section for one image.
@@ -966,7 +1056,7 @@ constexpr int wslot(int q)
 //   waits for it just before its closing barrier (the x-read phase uses no set and stages nothing).
 // On entry (INKIND == IN_LDS) buf0 holds the previous section's un-rectified output as a planar map with
 // halo; on exit (not LAST) buf0 holds this section's.  LAST writes ReLU(x) to feat_row.
-template <class S, class SN, class M, bool LAST, int SI, int J0, int NSETS, class PreT>
+template <class S, class SN, class M, bool LAST, int SI, int J0, int NSETS, bool INB, class PreT>
 __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, const SecWeights& nsw,
                                             const uint8_t* __restrict__ obs_img, PreT& pre,
                                             __bf16* __restrict__ feat_row, int tid)
@@ -979,8 +1069,17 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     char* buf0 = lds + M::BUF0;
     char* buf1 = lds + M::BUF1;
     char* edge = lds + M::EDGE;
+    // Buffer roles.  Normally conv0 reads buf0 and pools into buf1, the x-read phase moves ReLU(x) to buf0, and
+    // the blocks alternate R (buf0) -> U (buf1) -> R.  INB: the input sits in buf1 (the previous section was
+    // XFUSED), conv0 pools into buf0 and the x-read phase rectifies in place.  XFUSED: conv0 leaves R in buf1
+    // and the blocks run buf1 -> buf0 -> buf1, so this section's output lands in buf1.
+    static_assert(!INB || (S::INKIND == IN_LDS && !S::CONVMAP && !S::XFUSED && (J0 < 0 || J0 % 2 == 0)), "input in buf1: strip-pooled LDS sections only");
+    char* cin = INB ? buf1 : buf0;
+    char* pool = INB ? buf0 : buf1;
+    char* bufR = S::XFUSED ? buf1 : buf0;
+    char* bufU = S::XFUSED ? buf0 : buf1;
     constexpr int QB = J0 + 1;                                   // set number of block1.a
-    constexpr int SLOT_C0 = J0 < 0 ? M::PERM : wslot<M, S>(J0);
+    constexpr int SLOT_C0 = J0 < 0 ? M::PERM : wslot<M, S, INB>(J0);
     static_assert(S::ACT_BYTES <= 36 * 1024 || S::WB_SET * 1024 <= M::WSB_HI_CAP, "block weights do not fit the high slot");
     static_assert(S::WB_SET * 1024 <= WSLOT_BYTES && S::W0_SET * 1024 <= WSLOT_BYTES, "weight set larger than a slot");
     static_assert(LAST || (QB + 4) % 2 == 0 || SN::ACT_BYTES <= 36 * 1024 || SN::W0_SET * 1024 <= M::WSB_HI_CAP, "next conv0 set does not fit");
@@ -989,8 +1088,8 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
         constexpr int r = decltype(rel)::value;
         constexpr int q = QB + r;
         if constexpr (q < NSETS) {
-            if constexpr (r < 4) stage_set<S::WB_SET>(sw.wb[r], lds + wslot<M, S>(q), lane, wave);
-            else stage_set<SN::W0_SET>(nsw.w0, lds + wslot<M, SN>(q), lane, wave);
+            if constexpr (r < 4) stage_set<S::WB_SET>(sw.wb[r], lds + wslot<M, S, INB>(q), lane, wave);
+            else stage_set<SN::W0_SET>(nsw.w0, lds + wslot<M, SN, S::XFUSED>(q), lane, wave);
         }
     };
     using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
@@ -1002,13 +1101,13 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     // ---------------- conv0 + max-pool ----------------
     {
         stage(I0{});                                             // this phase uses set J0: stage J0 + 1
-        if constexpr (!S::CONVMAP) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf1, tid);
+        if constexpr (!S::CONVMAP) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(pool, tid);
         bf16x8 w0[S::CONVMAP ? 1 : S::W0_FRAGS];
         if constexpr (S::CONVMAP) {
             conv_map<S>(buf0, buf1, lds + SLOT_C0, lane, wave);     // buf1 <- the full-resolution conv map
         } else if constexpr (S::INKIND == IN_LDS) {
             load_a_frags(w0, lds + SLOT_C0, lane);
-            conv0_pool<S>(buf0, buf1, edge, lds + M::TRASH, w0, lds + SLOT_C0, 0, S::PH, -1, lane, wave);
+            conv0_pool<S>(cin, pool, edge, lds + M::TRASH, w0, lds + SLOT_C0, 0, S::PH, -1, lane, wave);
         } else {
 #pragma unroll 1
             for (int strip = 0; strip < S::NSTRIPS; ++strip) {
@@ -1020,7 +1119,8 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                 if (strip == 0) load_a_frags(w0, lds + SLOT_C0, lane);
                 int pr0, pr1, r0, r1;
                 strip_rows<S>(strip, pr0, pr1, r0, r1);
-                if constexpr (S::POOL3) conv0_pool3<S>(buf0, buf1, w0, lds + SLOT_C0, lane, wave);
+                if constexpr (S::XFUSED) conv0_pool3_x<S>(buf0, buf1, w0, lds + SLOT_C0, x, lane, wave);
+                else if constexpr (S::POOL3) conv0_pool3<S>(buf0, buf1, w0, lds + SLOT_C0, lane, wave);
                 else conv0_pool<S>(buf0, buf1, edge, lds + M::TRASH, w0, lds + SLOT_C0, pr0, pr1, r0 - 1, lane, wave);
                 if (strip + 1 < S::NSTRIPS) lds_barrier();
             }
@@ -1032,8 +1132,10 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
 
     // ---------------- x <- pooled map (+ edge columns); R = ReLU(x) ----------------
     int tb[S::NT];                                     // per tile: cell index of the lane's pixel (tap (0,0), plane 0)
-    {
-        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf0, tid);
+    if constexpr (!S::XFUSED) {
+        // INB: R replaces the pooled values in buf0 cell by cell (a lane reads and writes only its own cells and
+        // the halo is already zero); buf1 gets the zero halo the first block's output needs
+        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(INB ? buf1 : buf0, tid);
         if constexpr (S::CONVMAP) {
             if (wave < S::NWA) {                       // x = 3x3/2 maximum of the conv map in buf1
                 const int loff = (S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
@@ -1080,7 +1182,7 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                 const int off = tb[i] * 16 + loff;
 #pragma unroll
                 for (int j = 0; j < S::FT; ++j) {
-                    pv[i][j] = *(const bf16x4*)(buf1 + off + j * (2 * S::PLANE * 16));
+                    pv[i][j] = *(const bf16x4*)(pool + off + j * (2 * S::PLANE * 16));
                     if constexpr (!S::POOL3) ev[i][j] = *(const bf16x4*)(lds + eoff + j * ejmp);
                 }
             }
@@ -1131,14 +1233,16 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
         };
     };
     stage(I1{});
-    if constexpr (S::CONVMAP) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf1, tid);   // held the conv map until now
-    conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB), slice(I1{}));
+    // U's buffer held the conv map (CONVMAP) or the frame (XFUSED) until now: its halo ring is zeroed while
+    // this phase fills its interior
+    if constexpr (S::CONVMAP || S::XFUSED) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(bufU, tid);
+    conv(BF{}, I0{}, bufR, bufU, lds + wslot<M, S, INB>(QB), slice(I1{}));
     stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 4);
     stage(I2{});
     DETAIL_T0;
-    conv(BT{}, I0{}, buf1, buf0, lds + wslot<M, S>(QB + 1), slice(I2{}));
+    conv(BT{}, I0{}, bufU, bufR, lds + wslot<M, S, INB>(QB + 1), slice(I2{}));
     DETAIL_MARK(0);
     stage_wait();
     DETAIL_MARK(1);
@@ -1146,12 +1250,12 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     DETAIL_MARK(2);
     PHASE_MARK(SI * 8 + 5);
     stage(I3{});
-    conv(BF{}, I0{}, buf0, buf1, lds + wslot<M, S>(QB + 2), slice(I3{}));
+    conv(BF{}, I0{}, bufR, bufU, lds + wslot<M, S, INB>(QB + 2), slice(I3{}));
     stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 6);
     if constexpr (!LAST) stage(I4{});
-    conv(BT{}, std::integral_constant<int, LAST ? 2 : 1>{}, buf1, buf0, lds + wslot<M, S>(QB + 3), NoFiller{});
+    conv(BT{}, std::integral_constant<int, LAST ? 2 : 1>{}, bufU, bufR, lds + wslot<M, S, INB>(QB + 3), NoFiller{});
     // The last layer writes to global memory, so buf0 is free: the next frame's first strip (prefetched into
     // registers before this section) is converted into it here, under this phase's barrier.
     if constexpr (LAST) prefetch_commit<PS, SLICED ? 0 : -1>(pre, buf0, 0, tid);
@@ -1195,12 +1299,12 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
     for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
-        run_section<S1, S2, M, false, 0, -1, N::NSETS>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
-        run_section<S2, S3, M, false, 1, 4, N::NSETS>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
+        run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
+        run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
         // the next frame's bytes travel while section 3 computes
         const int nimg = img + (int)gridDim.x < a.B ? img + (int)gridDim.x : img;   // unconditional load address
         prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
-        run_section<S3, S3, M, true, 2, 9, N::NSETS>(lds, a.sec[2], a.sec[2], obs_img, pre, feat_row, tid);
+        run_section<S3, S3, M, true, 2, 9, N::NSETS, S2::XFUSED>(lds, a.sec[2], a.sec[2], obs_img, pre, feat_row, tid);
     }
 }
 
@@ -1239,12 +1343,12 @@ __global__ __launch_bounds__(RN_THREADS) void resnet4_bf16_kernel(TorsoArgs a)
     for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
-        run_section<S1, S2, M, false, 0, -1, N::NSETS>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
-        run_section<S2, S3, M, false, 1, 4, N::NSETS>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
-        run_section<S3, S4, M, false, 2, 9, N::NSETS>(lds, a.sec[2], a.sec[3], obs_img, pre, feat_row, tid);
+        run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
+        run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
+        run_section<S3, S4, M, false, 2, 9, N::NSETS, S2::XFUSED>(lds, a.sec[2], a.sec[3], obs_img, pre, feat_row, tid);
         const int nimg = img + (int)gridDim.x < a.B ? img + (int)gridDim.x : img;
         prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
-        run_section<S4, S4, M, true, 3, 14, N::NSETS>(lds, a.sec[3], a.sec[3], obs_img, pre, feat_row, tid);
+        run_section<S4, S4, M, true, 3, 14, N::NSETS, S3::XFUSED>(lds, a.sec[3], a.sec[3], obs_img, pre, feat_row, tid);
     }
 }
 
