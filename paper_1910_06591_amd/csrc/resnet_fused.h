@@ -891,27 +891,36 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
     const int g = lane >> 4, n = lane & 15;
     constexpr bool WHOLE = S::NPIX % 16 == 0;              // no partial last tile
     bf16x8 w[S::WB_FRAGS];
-    load_a_frags(w, wslot, lane);
     floatx4 bv[S::FT];
-#pragma unroll
-    for (int j = 0; j < S::FT; ++j) bv[j] = *(const floatx4*)(wslot + S::WB_FRAGS * 1024 + (j * 4 + g) * 16);
     using K = KMap<S::C>;
     int lb[K::NBASE];
     K::lane_bases(lb, g, S::PLANE, S::PITCH);
-    auto load_b = [&](bf16x8 (&b)[S::KCB], int tbase) {
-        const char* pa[K::NBASE];
-#pragma unroll
-        for (int q = 0; q < K::NBASE; ++q) pa[q] = src + (tbase + lb[q]) * 16;
-#pragma unroll
-        for (int kc = 0; kc < S::KCB; ++kc) b[kc] = *(const bf16x8*)(pa[K::kbase(kc)] + K::kimm(kc, S::PITCH) * 16);
-    };
     // destination of this lane's four channels, tile base excluded
     char* dstl = dst + ((S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8);
 
-    // double-buffer the B fragments only where the registers allow it (the 16-channel section)
-    constexpr bool DBUF = S::KCB <= 5;
-    bf16x8 bcur[S::KCB], bnxt[DBUF ? S::KCB : 1];
-    load_b(bcur, tb[0]);
+    // Software pipeline over (tile, chunk), pinned with scheduling fences: the activation fragment of chunk
+    // kc + AHEAD (of this tile or, past its end, of the next one) is requested right after the MFMAs of chunk
+    // kc, into the register slot that chunk kc + AHEAD - KCB of this tile has already left.  During the first
+    // tile the weight fragments travel the same way: every wavefront of the workgroup asks for its whole weight
+    // operand at the same moment, and requesting it in consumption order lets the chain start after the first
+    // few fragments instead of after all of them.  (The counter of outstanding LDS reads is 4 bits wide: with
+    // every read issued up front, the first wait could not be told apart from waiting for half of them.)
+    constexpr int AHEAD = S::KCB < 4 ? S::KCB - 1 : 4;
+    static_assert(AHEAD >= 1 && AHEAD < S::KCB, "prefetch distance");
+    bf16x8 bfr[S::KCB];
+    auto request = [&](int i, int kc, bool with_w) {          // i, kc: compile-time after unrolling
+        const int ii = i < S::NT ? i : S::NT - 1;             // past the last tile: a valid address, value unused
+        const char* pa = src + (tb[ii] + lb[K::kbase(kc)]) * 16;
+        if (with_w) {
+#pragma unroll
+            for (int j = 0; j < S::FT; ++j) w[j * S::KCB + kc] = *(const bf16x8*)(wslot + ((j * S::KCB + kc) * 64 + lane) * 16);
+        }
+        bfr[kc] = *(const bf16x8*)(pa + K::kimm(kc, S::PITCH) * 16);
+    };
+#pragma unroll
+    for (int j = 0; j < S::FT; ++j) bv[j] = *(const floatx4*)(wslot + S::WB_FRAGS * 1024 + (j * 4 + g) * 16);
+#pragma unroll
+    for (int kc = 0; kc < AHEAD; ++kc) request(0, kc, true);
     if constexpr (!std::is_same<Filler, NoFiller>::value) {
         SCHED_FENCE;
         filler();
@@ -921,17 +930,18 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
     for (int i = 0; i < S::NT; ++i) {
         const int t = wave + S::NWA * i;
         if (t >= S::NTILES) break;
-        const bool more = i + 1 < S::NT && t + S::NWA < S::NTILES;     // uniform
-        if constexpr (DBUF) {
-            if (more) load_b(bnxt, tb[i + 1 < S::NT ? i + 1 : i]);
-        }
         floatx4 acc[S::FT];
 #pragma unroll
         for (int j = 0; j < S::FT; ++j) acc[j] = ADD_X ? x[i][j] + bv[j] : bv[j];
 #pragma unroll
-        for (int kc = 0; kc < S::KCB; ++kc)
+        for (int kc = 0; kc < S::KCB; ++kc) {
+            SCHED_FENCE;
 #pragma unroll
-            for (int j = 0; j < S::FT; ++j) acc[j] = mfma16(w[j * S::KCB + kc], bcur[kc], acc[j]);
+            for (int j = 0; j < S::FT; ++j) acc[j] = mfma16(w[j * S::KCB + kc], bfr[kc], acc[j]);
+            if (kc + AHEAD < S::KCB) request(i, kc + AHEAD, i == 0);
+            else if (i + 1 < S::NT) request(i + 1, kc + AHEAD - S::KCB, false);
+        }
+        SCHED_FENCE;
         const int p = t * 16 + n;
 #pragma unroll
         for (int j = 0; j < S::FT; ++j) {
@@ -941,14 +951,6 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
                 const bf16x4 out = OUT == 1 ? vb : relu_bf16x4(vb);
                 if (OUT == 2) *(bf16x4*)(feat_row + (size_t)p * S::C + j * 16 + g * 4) = out;
                 else *(bf16x4*)(dstl + tb[i] * 16 + j * (2 * S::PLANE * 16)) = out;
-            }
-        }
-        if (more) {
-            if constexpr (DBUF) {
-#pragma unroll
-                for (int kc = 0; kc < S::KCB; ++kc) bcur[kc] = bnxt[kc];
-            } else {
-                load_b(bcur, tb[i + 1 < S::NT ? i + 1 : i]);
             }
         }
     }
