@@ -262,3 +262,30 @@ class Oracle:
         if rc != 0:
             raise ValueError("oracle_forward: unsupported arch")
         return out
+
+    def unroll(self, arch: Arch, weights, obs, prev_action=None, prev_reward=None,
+               h0=None, c0=None, uniforms=None, done=None):
+        """Forward pass over stored trajectories, time-major (Section 3: a trajectory is
+        unrolled step by step; Appendix A: unroll length): step t runs forward() on
+        obs[t] with the recurrent state that step t-1 left, done[t] zeroing the state a
+        row starts from.  obs [T, B, H, W, C]; prev_action, prev_reward, done [T, B];
+        uniforms [T, B, A]; h0, c0 [B, Hn].  Returns action [T, B], logits [T, B, A],
+        value [T, B], probs [T, B, A], margin [T, B] and the final h, c [B, Hn]."""
+        obs = np.ascontiguousarray(obs, dtype=np.uint8)
+        T = obs.shape[0]
+        Hn = arch.lstm_units
+        h, c = (self._r(h0), self._r(c0)) if Hn > 0 else (None, None)
+        steps = []
+        for t in range(T):
+            o = self.forward(arch, weights, obs[t],
+                             prev_action[t] if Hn > 0 else None, prev_reward[t] if Hn > 0 else None,
+                             h, c, uniforms[t] if arch.select else None,
+                             done=done[t] if done is not None else None)
+            if Hn > 0:
+                h, c = o["h"], o["c"]
+            steps.append(o)
+        out = {k: np.stack([o[k] for o in steps]) for k in ("action", "logits", "value", "probs", "margin")}
+        if Hn > 0:
+            out["h"], out["c"] = h, c
+        return out
+

@@ -227,6 +227,21 @@ def make_batch(cfg, batch=None, seed_shift=0):
                 h_in=h, c_in=c, uniforms=make_uniforms(cfg, B, 3000 + k + seed_shift))
 
 
+def make_trajectory(cfg, T, batch, done_rate=0.1):
+    """Inputs of a T-step unroll over `batch` trajectories, time-major: obs [T, B, H, W, C], prev_action,
+    prev_reward, done [T, B], uniforms [T, B, A] and the initial state h0, c0 [B, Hn].  Step t draws from the
+    same recipes as a single step, with seeds shifted by 10 t (done: seed 3600 + 10 t + config index)."""
+    steps = [make_batch(cfg, batch, seed_shift=10 * t) for t in range(T)]
+    out = {k: (np.stack([s[k] for s in steps]) if steps[0][k] is not None else None)
+           for k in ("obs", "prev_action", "prev_reward", "uniforms")}
+    out["h0"], out["c0"] = steps[0]["h_in"], steps[0]["c_in"]
+    out["done"] = None
+    if cfg["lstm_units"]:
+        out["done"] = np.stack([make_episode_inputs(cfg, batch, seed=3600 + 10 * t + cfg["index"], done_rate=done_rate)[0]
+                                for t in range(T)])
+    return out
+
+
 def macs_per_frame(cfg) -> int:
     """Useful multiply-accumulates per frame (no tile padding counted)."""
     h, w, c = cfg["obs_h"], cfg["obs_w"], cfg["obs_c"]
