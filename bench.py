@@ -119,6 +119,18 @@ def time_extensions(cfg, B, weights):
     res["set_weights_host_ms"] = float(np.median(t))
     res["step_after_set_weights_p50_ms"] = p50(lambda: (net.set_weights(weights), net.step(out=out, **dev)), n=5)
     res["weights_mb"] = weights.size * 4 / 1e6
+    # T-step unroll over stored trajectories: T = 32 (the unroll length of the paper's V-trace agents), B / 32 rows
+    if B % 32 == 0 and B >= 32:
+        T, Bt = 32, B // 32
+        r = lambda k, *tail: None if dev[k] is None else dev[k].reshape(T, Bt, *tail).contiguous()
+        tdone = ext["done"].reshape(T, Bt).contiguous() if cfg["lstm_units"] else None
+        h0 = None if dev["h_in"] is None else dev["h_in"][:Bt].contiguous()
+        c0 = None if dev["c_in"] is None else dev["c_in"][:Bt].contiguous()
+        args = (r("obs", cfg["obs_h"], cfg["obs_w"], cfg["obs_c"]), r("prev_action"), r("prev_reward"), h0, c0,
+                r("uniforms", cfg["num_actions"]), tdone)
+        ms = p50(lambda: net.unroll(*args), n=20)
+        res["unroll_T32_p50_ms"] = ms
+        res["unroll_T32_frames_per_s"] = B / ms * 1e3
     # host batching front-end: frames start in host memory; two batches in flight (PCIe-inclusive rate)
     bat = seedinf.Batcher(net, 2 * B)
     actors = [np.arange(B, dtype=np.int32), np.arange(B, 2 * B, dtype=np.int32)]

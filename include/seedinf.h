@@ -204,6 +204,39 @@ seed_status_t seed_infer_step_ext(seed_infer_t* handle, int32_t B,
                                   void* hip_stream);
 
 /*
+ * T-step unroll: the forward pass over stored trajectories, time-major
+ * (Section 3: the learner unrolls trajectories step by step with the stored
+ * recurrent state; Appendix A lists the unroll length, 32 for the V-trace
+ * agents).  Step t is seed_infer_step on the t-th slice of every input with
+ * the state step t-1 left; done[t] zeroes the state a row starts step t from.
+ * The torso and the linear layer do not depend on time and run once over all
+ * T * B frames; the recurrent core, the heads and the selection step through
+ * time on the same kernels as seed_infer_step.
+ *
+ *   obs          [T, B, H, W, C] uint8      prev_action, prev_reward  [T, B]
+ *   done         [T, B] uint8 or NULL       uniforms  [T, B, A] (iff Gumbel-max)
+ *   h0, c0       [B, lstm_units] fp32: the state before step 0
+ *   action_out   [T, B]   logits_out [T, B, A]   value_out [T, B]
+ *   probs_out    [T, B, A] or NULL
+ *   h_out, c_out [B, lstm_units]: the state after step T-1
+ * All device pointers; recurrent arguments NULL iff the arch has no core (then
+ * the call is one step over T * B rows).  T * B must not exceed max_batch
+ * (SEED_ERR_BATCH_TOO_LARGE).  The states between steps live in the handle;
+ * h_out / c_out must not overlap h0 / c0 or each other (SEED_ERR_ALIASING).
+ * Allocates nothing, enqueues on `hip_stream`, returns without synchronising;
+ * on an error status nothing has been enqueued.
+ */
+seed_status_t seed_infer_unroll(seed_infer_t* handle, int32_t T, int32_t B,
+                                const uint8_t* obs,
+                                const int32_t* prev_action, const float* prev_reward,
+                                const uint8_t* done,
+                                const float* h0, const float* c0,
+                                const float* uniforms,
+                                int32_t* action_out, float* logits_out, float* value_out,
+                                float* h_out, float* c_out, float* probs_out,
+                                void* hip_stream);
+
+/*
  * Replace the weights of a live handle (Section 3: the learner holds the only
  * copy of the model and the inference threads always use the latest one, so
  * every training step is followed by a weight refresh of the inference path).

@@ -484,15 +484,12 @@ inline void launch_lw_conv(hipStream_t st, const LwConvArgs& c, int ft, bool u8)
     else by_ft(std::false_type{});
 }
 
-// Runs torso, linear layer, recurrent core and dueling hidden layers.  On
-// return *core / *ld_core name the fp32 rows the output heads read.
-inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hipStream_t st, int B, const uint8_t* obs,
-                               const int32_t* prev_action, const float* prev_reward, const float* h_in,
-                               const float* c_in, const uint8_t* done, float* h_out, float* c_out, float* d_hid,
-                               const float** core, int* ld_core, hipEvent_t ev0, hipEvent_t ev1, std::string& err)
+// Torso and linear layer over B rows: leaves the rectified linear-layer output of row r in row r of
+// fc_bf16 / fc_f32.
+inline seed_status_t bf16_torso_fc(Bf16State* s, const Plan& p, const float* d_w, hipStream_t st, int B, const uint8_t* obs,
+                                   hipEvent_t ev0, hipEvent_t ev1, std::string& err)
 {
     const seed_arch_t& a = p.arch;
-    (void)err;
     const Bf16WeightSet& W = s->ws[s->active];
     if (ev0) (void)hipEventRecord(ev0, st);
     if (a.torso == SEED_TORSO_RESNET && s->torso_kind == TORSO_NONE) {
@@ -570,10 +567,26 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
         g.y_bf16 = s->fc_bf16; g.ldy_bf16 = s->ldfc; g.y_f32 = s->fc_f32; g.ldy_f32 = a.fc_units; g.n_out = a.fc_units;
         launch_gemm<EPI_RELU>(st, g, (s->ft_fc + 3) / 4, s->n_cu);
     }
-    *core = s->fc_f32; *ld_core = a.fc_units;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { err = std::string("kernel launch: ") + hipGetErrorString(e); return SEED_ERR_DEVICE; }
+    return SEED_OK;
+}
+
+// Recurrent core and dueling hidden layers for the B rows that start at row `row0` of the linear layer's
+// output (the caller's pointers already name those rows' own inputs and outputs).  On return *core /
+// *ld_core name the fp32 rows the output heads read.
+inline seed_status_t bf16_core(Bf16State* s, const Plan& p, const float* d_w, hipStream_t st, int row0, int B,
+                               const int32_t* prev_action, const float* prev_reward, const float* h_in,
+                               const float* c_in, const uint8_t* done, float* h_out, float* c_out, float* d_hid,
+                               const float** core, int* ld_core, std::string& err)
+{
+    const seed_arch_t& a = p.arch;
+    const Bf16WeightSet& W = s->ws[s->active];
+    const __bf16* fc_bf16 = s->fc_bf16 + (size_t)row0 * s->ldfc;
+    *core = s->fc_f32 + (size_t)row0 * a.fc_units; *ld_core = a.fc_units;
     if (a.lstm_units > 0) {
         GemmArgs g{};
-        g.x1 = s->fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->kc1_lstm;
+        g.x1 = fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->kc1_lstm;
         g.x2 = h_in; g.ld2 = a.lstm_units; g.k2 = a.lstm_units;
         g.wp = W.wp_lstm; g.n_ftiles = (a.lstm_units / 16) * 4; g.rows = B;
         g.lstm_w = d_w + p.lstm_w; g.lstm_b = d_w + p.lstm_b; g.prev_action = prev_action; g.prev_reward = prev_reward;
@@ -584,8 +597,8 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
     }
     if (a.head == SEED_HEAD_DUELING_Q) {
         GemmArgs g{};
-        if (a.lstm_units > 0) { g.kc1 = 0; g.x1 = s->fc_bf16; g.ld1 = s->ldfc; g.x2 = h_out; g.ld2 = a.lstm_units; g.k2 = a.lstm_units; }
-        else { g.x1 = s->fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->ldfc / 32; g.k2 = 0; }
+        if (a.lstm_units > 0) { g.kc1 = 0; g.x1 = fc_bf16; g.ld1 = s->ldfc; g.x2 = h_out; g.ld2 = a.lstm_units; g.k2 = a.lstm_units; }
+        else { g.x1 = fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->ldfc / 32; g.k2 = 0; }
         g.wp = W.wp_hid; g.n_ftiles = s->ft_hid; g.rows = B; g.bias_pad = W.bias_hid;
         g.y_bf16 = nullptr; g.y_f32 = d_hid; g.ldy_f32 = 2 * a.head_hidden; g.n_out = 2 * a.head_hidden;
         launch_gemm<EPI_RELU>(st, g, (s->ft_hid + 3) / 4, s->n_cu);
@@ -593,6 +606,17 @@ inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hi
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { err = std::string("kernel launch: ") + hipGetErrorString(e); return SEED_ERR_DEVICE; }
     return SEED_OK;
+}
+
+// One step: torso, linear layer, recurrent core and dueling hidden layers.
+inline seed_status_t bf16_step(Bf16State* s, const Plan& p, const float* d_w, hipStream_t st, int B, const uint8_t* obs,
+                               const int32_t* prev_action, const float* prev_reward, const float* h_in,
+                               const float* c_in, const uint8_t* done, float* h_out, float* c_out, float* d_hid,
+                               const float** core, int* ld_core, hipEvent_t ev0, hipEvent_t ev1, std::string& err)
+{
+    const seed_status_t st0 = bf16_torso_fc(s, p, d_w, st, B, obs, ev0, ev1, err);
+    if (st0 != SEED_OK) return st0;
+    return bf16_core(s, p, d_w, st, 0, B, prev_action, prev_reward, h_in, c_in, done, h_out, c_out, d_hid, core, ld_core, err);
 }
 
 inline seed_status_t bf16_read_intermediate(Bf16State* s, const Plan& p, int which, int B, float* dst, hipStream_t st,

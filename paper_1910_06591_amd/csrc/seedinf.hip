@@ -30,6 +30,7 @@ struct seed_infer {
     float* d_act[2] = {nullptr, nullptr};   // fp32 ping-pong activations (fp32 mode)
     float* d_fc = nullptr;         // [max_batch, fc_units] fp32 (fp32 mode)
     float* d_hid = nullptr;        // [max_batch, 2*head_hidden] dueling hidden, fp32
+    float* d_roll = nullptr;       // recurrent archs: 2 x (h, c) [max_batch, lstm_units], the states between the steps of an unroll
     const float* feat_f32 = nullptr;   // where the last fp32-mode step left the torso features
     Bf16State* bf = nullptr;       // everything the bf16 path owns
     std::vector<hipEvent_t> ev;    // profiling: 2 events per slot (empty = profiling off)
@@ -97,6 +98,7 @@ static void free_all(seed_infer* h)
     if (h->d_act[1]) (void)hipFree(h->d_act[1]);
     if (h->d_fc) (void)hipFree(h->d_fc);
     if (h->d_hid) (void)hipFree(h->d_hid);
+    if (h->d_roll) (void)hipFree(h->d_roll);
     delete h;
 }
 
@@ -113,6 +115,7 @@ static seed_status_t create_impl(seed_infer* h, const float* weights_host)
     HIP_TRY(h, hipMemcpy(h->d_w, weights_host, p.n_weights * sizeof(float), hipMemcpyHostToDevice));
     const size_t mb = (size_t)a.max_batch;
     if (a.head == SEED_HEAD_DUELING_Q) HIP_TRY(h, hipMalloc(&h->d_hid, mb * 2 * a.head_hidden * sizeof(float)));
+    if (a.lstm_units > 0) HIP_TRY(h, hipMalloc(&h->d_roll, 4 * mb * a.lstm_units * sizeof(float)));
     if (a.precision == SEED_PRECISION_FP32) {
         HIP_TRY(h, hipMalloc(&h->d_act[0], mb * p.max_act * sizeof(float)));
         HIP_TRY(h, hipMalloc(&h->d_act[1], mb * p.max_act * sizeof(float)));
@@ -229,6 +232,78 @@ static void launch_heads(hipStream_t s, const HeadsArgs& ha)
     else launch_heads_p<64>(s, ha);
 }
 
+// Torso and linear layer over B rows (rows of the handle's linear-layer buffers).
+static seed_status_t run_torso_fc(seed_infer* h, hipStream_t s, int B, const uint8_t* obs)
+{
+    const Plan& p = h->plan;
+    const bool prof = !h->ev.empty() && h->ev_used < SEED_PROFILE_SLOTS;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (prof) { ev0 = h->ev[2 * h->ev_used]; ev1 = h->ev[2 * h->ev_used + 1]; ++h->ev_used; }
+    if (p.arch.precision == SEED_PRECISION_FP32) {
+        if (prof) HIP_TRY(h, hipEventRecord(ev0, s));
+        torso_fc_f32(h, s, B, obs);
+        if (prof) HIP_TRY(h, hipEventRecord(ev1, s));
+        HIP_TRY(h, hipGetLastError());
+        return SEED_OK;
+    }
+    return bf16_torso_fc(h->bf, p, h->d_w, s, B, obs, ev0, ev1, h->err);
+}
+
+// Recurrent core, heads and action selection for the B rows that start at row `row0` of the linear layer's
+// output; every pointer argument already names those rows' own data.
+static seed_status_t run_core_heads(seed_infer* h, hipStream_t s, int row0, int B, const int32_t* prev_action,
+                                    const float* prev_reward, const float* h_in, const float* c_in, const uint8_t* done,
+                                    float* h_out, float* c_out, const float* uniforms, const float* epsilon,
+                                    const float* explore_u, int32_t* action_out, float* logits_out, float* value_out,
+                                    float* probs_out)
+{
+    const Plan& p = h->plan;
+    const seed_arch_t& a = p.arch;
+    const float* w = h->d_w;
+    const bool rec = a.lstm_units > 0;
+    const float* core = nullptr;       // fp32 [B, p.core]
+    int ld_core = p.core;
+    if (a.precision == SEED_PRECISION_FP32) {
+        const float* fc = h->d_fc + (size_t)row0 * a.fc_units;
+        core = fc;
+        if (rec) {
+            hipLaunchKernelGGL(lstm_f32_kernel, dim3(B, (a.lstm_units + 255) / 256), dim3(256), 0, s, fc, prev_action,
+                               prev_reward, h_in, c_in, w + p.lstm_w, w + p.lstm_b, h_out, c_out, B, a.fc_units,
+                               a.num_actions, a.lstm_units, done);
+            core = h_out;
+        }
+        if (a.head == SEED_HEAD_DUELING_Q) {
+            int hid = a.head_hidden;
+            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(256), 0, s, core, w + p.v1_w, w + p.v1_b,
+                               h->d_hid, p.core, hid, ld_core, 2 * hid, 1);
+            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(256), 0, s, core, w + p.a1_w, w + p.a1_b,
+                               h->d_hid + hid, p.core, hid, ld_core, 2 * hid, 1);
+        }
+    } else {
+        seed_status_t st = bf16_core(h->bf, p, w, s, row0, B, prev_action, prev_reward, h_in, c_in, done, h_out, c_out,
+                                     h->d_hid, &core, &ld_core, h->err);
+        if (st != SEED_OK) return st;
+    }
+
+    HeadsArgs ha{};
+    ha.n = p.core; ha.A = a.num_actions; ha.B = B;
+    ha.uniforms = uniforms; ha.epsilon = epsilon; ha.explore_u = explore_u; ha.action = action_out; ha.logits = logits_out; ha.value = value_out; ha.probs = probs_out;
+    if (a.head == SEED_HEAD_POLICY_VALUE) {
+        ha.vec_a = core; ha.ld_a = ld_core; ha.vec_v = core; ha.ld_v = ld_core;
+        ha.w_a = w + p.pol_w; ha.b_a = w + p.pol_b; ha.w_v = w + p.val_w; ha.b_v = w + p.val_b;
+        ha.dueling = 0;
+    } else {
+        int hid = a.head_hidden;
+        ha.n = hid;
+        ha.vec_v = h->d_hid; ha.ld_v = 2 * hid; ha.vec_a = h->d_hid + hid; ha.ld_a = 2 * hid;
+        ha.w_a = w + p.a2_w; ha.b_a = w + p.a2_b; ha.w_v = w + p.v2_w; ha.b_v = w + p.v2_b;
+        ha.dueling = 1;
+    }
+    launch_heads(s, ha);
+    HIP_TRY(h, hipGetLastError());
+    return SEED_OK;
+}
+
 extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8_t* obs,
                                          const int32_t* prev_action, const float* prev_reward,
                                          const float* h_in, const float* c_in, const float* uniforms,
@@ -281,53 +356,61 @@ extern "C" seed_status_t seed_infer_step_ext(seed_infer_t* h, int32_t B, const u
     if (dev != h->device) return fail(SEED_ERR_INVALID_ARG, "current HIP device differs from the handle's device");
 
     hipStream_t s = (hipStream_t)hip_stream;
-    const float* w = h->d_w;
-    const float* core = nullptr;       // fp32 [B, p.core]
-    int ld_core = p.core;
+    seed_status_t st = run_torso_fc(h, s, B, obs);
+    if (st != SEED_OK) return st;
+    return run_core_heads(h, s, 0, B, prev_action, prev_reward, h_in, c_in, done, h_out, c_out, uniforms, epsilon, explore_u,
+                          action_out, logits_out, value_out, probs_out);
+}
 
-    const bool prof = !h->ev.empty() && h->ev_used < SEED_PROFILE_SLOTS;
-    hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    if (prof) { ev0 = h->ev[2 * h->ev_used]; ev1 = h->ev[2 * h->ev_used + 1]; ++h->ev_used; }
-    if (a.precision == SEED_PRECISION_FP32) {
-        if (prof) HIP_TRY(h, hipEventRecord(ev0, s));
-        torso_fc_f32(h, s, B, obs);
-        if (prof) HIP_TRY(h, hipEventRecord(ev1, s));
-        core = h->d_fc;
-        if (rec) {
-            hipLaunchKernelGGL(lstm_f32_kernel, dim3(B, (a.lstm_units + 255) / 256), dim3(256), 0, s, h->d_fc, prev_action,
-                               prev_reward, h_in, c_in, w + p.lstm_w, w + p.lstm_b, h_out, c_out, B, a.fc_units,
-                               a.num_actions, a.lstm_units, done);
-            core = h_out;
-        }
-        if (a.head == SEED_HEAD_DUELING_Q) {
-            int hid = a.head_hidden;
-            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(256), 0, s, core, w + p.v1_w, w + p.v1_b,
-                               h->d_hid, p.core, hid, ld_core, 2 * hid, 1);
-            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(256), 0, s, core, w + p.a1_w, w + p.a1_b,
-                               h->d_hid + hid, p.core, hid, ld_core, 2 * hid, 1);
-        }
-    } else {
-        seed_status_t st = bf16_step(h->bf, p, w, s, B, obs, prev_action, prev_reward, h_in, c_in, done, h_out, c_out,
-                                     h->d_hid, &core, &ld_core, ev0, ev1, h->err);
+extern "C" seed_status_t seed_infer_unroll(seed_infer_t* h, int32_t T, int32_t B, const uint8_t* obs,
+                                           const int32_t* prev_action, const float* prev_reward, const uint8_t* done,
+                                           const float* h0, const float* c0, const float* uniforms,
+                                           int32_t* action_out, float* logits_out, float* value_out,
+                                           float* h_out, float* c_out, float* probs_out, void* hip_stream)
+{
+    if (!h) return SEED_ERR_INVALID_ARG;
+    const Plan& p = h->plan;
+    const seed_arch_t& a = p.arch;
+    auto fail = [&](seed_status_t st, const char* m) { h->err = m; return st; };
+    if (T < 0 || B < 0) return fail(SEED_ERR_INVALID_ARG, "T or B is negative");
+    if ((long long)T * B > a.max_batch) return fail(SEED_ERR_BATCH_TOO_LARGE, "T * B exceeds max_batch");
+    if (T == 0 || B == 0) return SEED_OK;
+    if (!obs || !action_out || !logits_out || !value_out) return fail(SEED_ERR_INVALID_ARG, "obs, action_out, logits_out and value_out are required");
+    const bool rec = a.lstm_units > 0;
+    if (rec && (!prev_action || !prev_reward || !h0 || !c0 || !h_out || !c_out))
+        return fail(SEED_ERR_INVALID_ARG, "a recurrent arch needs prev_action, prev_reward, h0, c0, h_out and c_out");
+    if (!rec && (prev_action || prev_reward || done || h0 || c0 || h_out || c_out))
+        return fail(SEED_ERR_INVALID_ARG, "a feed-forward arch takes no recurrent arguments (pass NULL)");
+    if (a.select == SEED_SELECT_GUMBEL && !uniforms) return fail(SEED_ERR_INVALID_ARG, "Gumbel-max selection needs uniforms");
+    if (a.select == SEED_SELECT_GREEDY && uniforms) return fail(SEED_ERR_INVALID_ARG, "greedy selection takes no uniforms (pass NULL)");
+    if (rec) {
+        size_t nb = (size_t)B * a.lstm_units * sizeof(float);
+        if (overlaps(h_out, nb, h0, nb) || overlaps(h_out, nb, c0, nb) || overlaps(c_out, nb, h0, nb) ||
+            overlaps(c_out, nb, c0, nb) || overlaps(h_out, nb, c_out, nb))
+            return fail(SEED_ERR_ALIASING, "h_out / c_out must not overlap h0 / c0 or each other");
+    }
+    int dev = -1;
+    HIP_TRY(h, hipGetDevice(&dev));
+    if (dev != h->device) return fail(SEED_ERR_INVALID_ARG, "current HIP device differs from the handle's device");
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    // the torso and the linear layer do not depend on time: one pass over all T * B frames
+    seed_status_t st = run_torso_fc(h, s, T * B, obs);
+    if (st != SEED_OK) return st;
+    const size_t A = (size_t)a.num_actions, Hn = (size_t)a.lstm_units, mb = (size_t)a.max_batch;
+    for (int t = 0; t < T; ++t) {
+        const size_t r = (size_t)t * B;
+        // states between steps alternate between the handle's two buffers; the last step writes the caller's
+        float* hb[2] = {h->d_roll, h->d_roll ? h->d_roll + 2 * mb * Hn : nullptr};
+        const float* hi = !rec ? nullptr : (t == 0 ? h0 : hb[(t - 1) & 1]);
+        const float* ci = !rec ? nullptr : (t == 0 ? c0 : hb[(t - 1) & 1] + mb * Hn);
+        float* ho = !rec ? nullptr : (t == T - 1 ? h_out : hb[t & 1]);
+        float* co = !rec ? nullptr : (t == T - 1 ? c_out : hb[t & 1] + mb * Hn);
+        st = run_core_heads(h, s, (int)r, B, rec ? prev_action + r : nullptr, rec ? prev_reward + r : nullptr, hi, ci,
+                            done ? done + r : nullptr, ho, co, uniforms ? uniforms + r * A : nullptr, nullptr, nullptr,
+                            action_out + r, logits_out + r * A, value_out + r, probs_out ? probs_out + r * A : nullptr);
         if (st != SEED_OK) return st;
     }
-
-    HeadsArgs ha{};
-    ha.n = p.core; ha.A = a.num_actions; ha.B = B;
-    ha.uniforms = uniforms; ha.epsilon = epsilon; ha.explore_u = explore_u; ha.action = action_out; ha.logits = logits_out; ha.value = value_out; ha.probs = probs_out;
-    if (a.head == SEED_HEAD_POLICY_VALUE) {
-        ha.vec_a = core; ha.ld_a = ld_core; ha.vec_v = core; ha.ld_v = ld_core;
-        ha.w_a = w + p.pol_w; ha.b_a = w + p.pol_b; ha.w_v = w + p.val_w; ha.b_v = w + p.val_b;
-        ha.dueling = 0;
-    } else {
-        int hid = a.head_hidden;
-        ha.n = hid;
-        ha.vec_v = h->d_hid; ha.ld_v = 2 * hid; ha.vec_a = h->d_hid + hid; ha.ld_a = 2 * hid;
-        ha.w_a = w + p.a2_w; ha.b_a = w + p.a2_b; ha.w_v = w + p.v2_w; ha.b_v = w + p.v2_b;
-        ha.dueling = 1;
-    }
-    launch_heads(s, ha);
-    HIP_TRY(h, hipGetLastError());
     return SEED_OK;
 }
 

@@ -22,8 +22,9 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 
 STATUS = {0: "SEED_OK", 1: "SEED_ERR_INVALID_ARG", 2: "SEED_ERR_UNSUPPORTED_ARCH", 3: "SEED_ERR_BATCH_TOO_LARGE",
           4: "SEED_ERR_ALIASING", 5: "SEED_ERR_DEVICE", 6: "SEED_ERR_OOM"}
+STATUS_BY_NAME = {v: k for k, v in STATUS.items()}
 EXPORTS = ["seed_infer_weight_count", "seed_infer_validate", "seed_infer_create", "seed_infer_step",
-           "seed_infer_step_ext", "seed_infer_set_weights",
+           "seed_infer_step_ext", "seed_infer_unroll", "seed_infer_set_weights",
            "seed_batcher_create", "seed_batcher_add", "seed_batcher_reserve", "seed_batcher_add_many", "seed_batcher_submit", "seed_batcher_wait",
            "seed_batcher_read_state", "seed_batcher_stream", "seed_batcher_last_error", "seed_batcher_destroy",
            "seed_infer_read_intermediate", "seed_infer_torso_features", "seed_infer_last_error",
@@ -96,6 +97,8 @@ def load_library():
     lib.seed_infer_step_ext.restype = C.c_int
     lib.seed_infer_step_ext.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 6 + [C.POINTER(SeedStepExt)] + [C.c_void_p] * 7
     lib.seed_infer_set_weights.restype = C.c_int
+    lib.seed_infer_unroll.restype = C.c_int
+    lib.seed_infer_unroll.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 14
     lib.seed_infer_set_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.seed_batcher_create.restype = C.c_int
     lib.seed_batcher_create.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)]
@@ -277,6 +280,51 @@ class SeedInfer:
         if st != 0:
             raise SeedError(st, self.lib.seed_infer_last_error(self._h).decode())
         return out
+
+    def unroll(self, obs, prev_action=None, prev_reward=None, h0=None, c0=None, uniforms=None, done=None,
+               want_probs=True, stream=None):
+        """seed_infer_unroll on time-major device tensors: obs [T, B, H, W, C]; prev_action, prev_reward,
+        done [T, B]; uniforms [T, B, A]; h0, c0 [B, Hn].  Returns action [T, B], logits [T, B, A],
+        value [T, B], probs [T, B, A] and, with a core, the final h, c [B, Hn]."""
+        import torch
+        a = self.arch
+        T, B = obs.shape[0], obs.shape[1]
+        dev = obs.device
+        out = {"action": torch.empty(T, B, dtype=torch.int32, device=dev),
+               "logits": torch.empty(T, B, self.A, dtype=torch.float32, device=dev),
+               "value": torch.empty(T, B, dtype=torch.float32, device=dev)}
+        if self.Hn:
+            out["h"] = torch.empty(B, self.Hn, dtype=torch.float32, device=dev)
+            out["c"] = torch.empty(B, self.Hn, dtype=torch.float32, device=dev)
+        if want_probs:
+            out["probs"] = torch.empty(T, B, self.A, dtype=torch.float32, device=dev)
+        s = torch.cuda.current_stream(dev).cuda_stream if stream is None else stream
+        st = self.lib.seed_infer_unroll(
+            self._h, T, B,
+            _ptr(obs, torch.uint8, (T, B, a.obs_h, a.obs_w, a.obs_c), "obs"),
+            _ptr(prev_action, torch.int32, (T, B), "prev_action"),
+            _ptr(prev_reward, torch.float32, (T, B), "prev_reward"),
+            _ptr(done, torch.uint8, (T, B), "done"),
+            _ptr(h0, torch.float32, (B, self.Hn), "h0"),
+            _ptr(c0, torch.float32, (B, self.Hn), "c0"),
+            _ptr(uniforms, torch.float32, (T, B, self.A), "uniforms"),
+            _ptr(out["action"], torch.int32, (T, B), "action"),
+            _ptr(out["logits"], torch.float32, (T, B, self.A), "logits"),
+            _ptr(out["value"], torch.float32, (T, B), "value"),
+            _ptr(out.get("h"), torch.float32, (B, self.Hn), "h_out"),
+            _ptr(out.get("c"), torch.float32, (B, self.Hn), "c_out"),
+            _ptr(out.get("probs"), torch.float32, (T, B, self.A), "probs"),
+            C.c_void_p(s))
+        if st != 0:
+            raise SeedError(st, self.lib.seed_infer_last_error(self._h).decode())
+        return out
+
+    def unroll_raw(self, T, B, obs, prev_action, prev_reward, done, h0, c0, uniforms, action, logits, value,
+                   h_out, c_out, probs, stream=0):
+        """Direct call of seed_infer_unroll with raw pointers/ints (error-path tests)."""
+        st = self.lib.seed_infer_unroll(self._h, T, B, obs, prev_action, prev_reward, done, h0, c0, uniforms,
+                                        action, logits, value, h_out, c_out, probs, stream)
+        return st, self.lib.seed_infer_last_error(self._h).decode()
 
     def set_profiling(self, enable: bool):
         st = self.lib.seed_infer_set_profiling(self._h, int(enable))
