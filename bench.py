@@ -157,6 +157,44 @@ def time_extensions(cfg, B, weights):
     return res
 
 
+def measure_peaks():
+    """What this GPU sustains on the two rooflines: an MFMA-only bf16 loop and a plain streaming copy
+    (libseedprobe.so), timed with events on the current stream."""
+    import torch
+    from paper_1910_06591_amd import seedinf
+    lib = seedinf.load_probe_library()
+    st = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    blocks, iters = 2048, 400                       # 8 blocks per compute unit, ~1 ms per launch
+
+    def timed(fn, n):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n * 1e-3
+
+    def mfma():
+        rc = lib.seed_probe_mfma_bf16(blocks, iters, sink.data_ptr(), st)
+        assert rc == 0, rc
+    t = timed(mfma, 10)
+    tflops = lib.seed_probe_mfma_flops(blocks, iters) / t / 1e12
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+
+    def copy():
+        rc = lib.seed_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, st)
+        assert rc == 0, rc
+    t = timed(copy, 10)
+    return {"mfma_bf16_tflops": tflops, "hbm_copy_gbs": 2.0 * nbytes / t / 1e9,
+            "how": "MFMA-only loop (2048 blocks x 8 wavefronts x 25600 v_mfma_f32_16x16x32_bf16); copy of 1 GiB, read + write bytes"}
+
+
 def cpu_baseline(cfg, rows):
     """The CPU oracle as it stands, on `rows` rows of the same workload."""
     import oracle
@@ -244,6 +282,9 @@ def main():
                      "kernel_ms": r["torso_ms"], "traffic": read_traffic()},
     }
     if not args.no_extras:
+        peaks = measure_peaks()
+        line["measured_peaks"] = peaks
+        line["roofline"]["frac_of_measured_peak"] = achieved / peaks["mfma_bf16_tflops"]
         sweep = []
         for b in cfg["sweep"]:
             k = max(20, min(args.steps, 200))

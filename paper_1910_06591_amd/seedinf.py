@@ -16,7 +16,10 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 LIB_PATH = os.environ.get("SEEDINF_LIB", os.path.join(_PKG, "libseedinf.so"))
 SOURCES = [os.path.join(_PKG, "csrc", f) for f in
-           ("seedinf.hip", "plan.h", "kernels_fp32.h", "kernels_heads.h", "bf16_path.h", "bf16_common.h", "gemm_bf16.h", "conv_stack_bf16.h", "resnet_fused.h")]
+           ("seedinf.hip", "plan.h", "kernels_fp32.h", "kernels_heads.h", "bf16_path.h", "bf16_common.h", "gemm_bf16.h", "conv_stack_bf16.h",
+            "resnet_fused.h", "resnet_layerwise.h", "batcher.h")]
+PROBE_SOURCE = os.path.join(_PKG, "csrc", "probe.hip")
+PROBE_LIB_PATH = os.path.join(_PKG, "libseedprobe.so")
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fno-honor-nans"]
 
@@ -60,15 +63,31 @@ class SeedArch(C.Structure):
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile csrc/ into libseedinf.so for gfx950 with hipcc (cross-compiles
-    without a GPU)."""
-    cmd = ["hipcc", *HIPCC_FLAGS, SOURCES[0], "-o", LIB_PATH]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + r.stderr)
-    if verbose:
-        print(" ".join(cmd))
+    """Compile csrc/ into libseedinf.so (and the measurement probes into
+    libseedprobe.so) for gfx950 with hipcc (cross-compiles without a GPU)."""
+    for src, out in ((SOURCES[0], LIB_PATH), (PROBE_SOURCE, PROBE_LIB_PATH)):
+        cmd = ["hipcc", *HIPCC_FLAGS, src, "-o", out]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + r.stderr)
+        if verbose:
+            print(" ".join(cmd))
     return LIB_PATH
+
+
+def load_probe_library():
+    """libseedprobe.so: the MFMA-only loop and the streaming copy bench.py measures the chip's own peaks with."""
+    import torch  # noqa: F401
+    if not os.path.exists(PROBE_LIB_PATH):
+        raise RuntimeError(f"{PROBE_LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(PROBE_LIB_PATH)
+    lib.seed_probe_mfma_bf16.restype = C.c_int
+    lib.seed_probe_mfma_bf16.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    lib.seed_probe_mfma_flops.restype = C.c_double
+    lib.seed_probe_mfma_flops.argtypes = [C.c_int, C.c_int]
+    lib.seed_probe_copy.restype = C.c_int
+    lib.seed_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    return lib
 
 
 _lib = None

@@ -85,3 +85,14 @@ def test_create_rejects_null_and_wrong_count(lib):
     # NULL handles are tolerated
     lib.seed_infer_destroy(None)
     assert lib.seed_infer_step(None, 1, *([None] * 13)) == 1
+
+
+def test_probe_library_loads_and_exports():
+    """bench.py's measurement probes (the MFMA-only loop and the streaming copy) live in their own library."""
+    if not os.path.exists(seedinf.PROBE_LIB_PATH):
+        seedinf.build_library()
+    probe = seedinf.load_probe_library()
+    for name in ("seed_probe_mfma_bf16", "seed_probe_mfma_flops", "seed_probe_copy"):
+        assert hasattr(probe, name)
+    # 1 block x 8 wavefronts x 1 iteration x 64 MFMAs of 16 x 16 x 32 multiply-adds
+    assert probe.seed_probe_mfma_flops(1, 1) == 8 * 64 * 2 * 16 * 16 * 32
