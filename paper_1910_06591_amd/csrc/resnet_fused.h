@@ -6,32 +6,28 @@
 // out, so the torso runs against the matrix-core roofline, not the HBM one.
 //
 // Per section (conv 3x3 SAME -> max-pool 3x3/2 SAME -> 2 residual blocks):
-//   * conv0 + pool: a unit of work is a 16-column strip x a band of pooled
-//     rows.  The wavefront walks its unit top to bottom, keeps the last conv
-//     row in registers, takes the vertical 3-maximum lane-wise and the
-//     horizontal 3-maximum (stride 2) with DPP row shifts, and writes the
-//     pooled bf16 value.  The one neighbour column a strip lacks comes from the
-//     next strip through a small edge buffer.  The full-resolution conv output
-//     never exists in memory.
-//   * The residual stream x stays in fp32 registers: pooled pixel tile t (16
-//     pixels) belongs to wavefront t % 8 for the whole section, in the MFMA
-//     accumulator layout, so "x + conv_b(...)" is the MFMA's C operand.  LDS
-//     holds the two rectified bf16 conv inputs R = ReLU(x) and
-//     U = ReLU(conv_a(R)), each with a zero halo ring (SAME padding without
-//     bounds tests).
-//   * LDS maps are channel-group planar, [C/8][rows+2][cols+2][8 bf16]: a B
-//     fragment (8 consecutive input channels of one tap of one pixel) is one
-//     16-byte ds_read, and the 16 lanes of a lane group read 256 contiguous
-//     bytes.
-//   * Weights: every wavefront needs the whole A operand of a layer, so the
-//     workgroup copies each layer's packed fragments global -> LDS once, one
-//     phase ahead (the loads are issued before the current layer's math and
-//     committed after it), and the wavefronts fill their registers from LDS.
-//   * The uint8 frame (or the next strip of it) is prefetched into registers
-//     one phase ahead as well.
-// The 3-channel first layer keeps its frame as [row][col][4] (one zero lane):
-// K = 3 rows x (2 fragments of 2 pixels x 4 channels) = 48, two MFMAs per tile.
-// uint8 inputs enter as exact bf16 integers; 1/255 scales the accumulator.
+//   * conv0 + pool, three schemes.  The 3-channel first layer (conv0_pool3_x): a lane owns a POOLED column and
+//     takes its three conv columns from three MFMA tiles one frame cell apart, so the 3x3/2 maximum is lane-wise
+//     and the pooled values stay in registers as the section's residual stream.  16 -> 32 channels on the
+//     36 x 48 map (conv0_pool): 16-column strips x runs of pooled rows, vertical maximum lane-wise, horizontal
+//     with DPP row shifts, the neighbour column a strip lacks through a small edge buffer; the conv output
+//     never exists in memory.  Small 32 -> 32 channel maps (conv_map): the conv output goes to LDS at full
+//     resolution and is pooled while the residual stream is read.
+//   * The residual stream x stays in fp32 registers: a pooled tile of 16 pixels belongs to one wavefront for
+//     the whole section, in the MFMA accumulator layout, so "x + conv_b(...)" is the MFMA's C operand.  LDS
+//     holds the two rectified bf16 conv inputs R = ReLU(x) and U = ReLU(conv_a(R)), each with a zero halo
+//     ring (SAME padding without bounds tests).
+//   * LDS maps are channel-group planar, [C/8][rows+2][cols+2][8 bf16]: a B fragment (8 consecutive input
+//     channels of one tap of one pixel) is one 16-byte ds_read, and the 16 lanes of a lane group read 256
+//     contiguous bytes.
+//   * Weights: every wavefront needs the whole A operand of a layer, so the workgroup copies each layer's
+//     packed fragments global -> LDS once with asynchronous direct loads, one phase ahead, and the wavefronts
+//     fill their registers from LDS.
+//   * The uint8 frame of the next image is prefetched into registers before the last section and converted
+//     into LDS during that section's phases.
+// The 3-channel first layer keeps its frame as [row][col][4] (one zero lane): a B fragment covers two frame
+// rows x 4 pixels x 4 channels, two MFMAs per conv-row tile.  uint8 inputs enter as exact bf16 integers; 1/255
+// scales the accumulator.
 #pragma once
 #include <type_traits>
 
