@@ -163,6 +163,8 @@ def run_full(orc, cfg, B, sample=None):
     torch.cuda.synchronize()
     got = {k: v.cpu().numpy() for k, v in out.items()}
     idx = np.arange(B) if sample is None else np.sort(np.random.default_rng(B).choice(B, sample, replace=False))
+    if sample is not None:
+        idx = np.unique(np.concatenate([idx, [0, B - 1]]))          # always the first and the last row
     sub = _rows(batch, idx)
     ref = orc.forward(oracle.make_arch(cfg), weights, sub["obs"], **{k: sub[k] for k in CORE_KEYS})
     rep = check_against_oracle({k: v[idx] for k, v in got.items()}, ref, TOL[cfg["precision"]], sub["uniforms"])
@@ -190,8 +192,10 @@ def test_full_size_c4(orc):
     run_full(orc, wl.CONFIGS["C4"], 2048, sample=512)
 
 
-@pytest.mark.parametrize("B,sample", [(64, None), (256, None), (4096, 256), (8192, 256)])
+@pytest.mark.parametrize("B,sample", [(64, None), (256, None), (4096, 256), (8192, 256), (4099, 96)])
 def test_full_size_c5_sweep(orc, B, sample):
+    """The batch sweep of the headline workload; 4099 = a ragged last 64-row tile of the linear layer's
+    wide-batch launch shape (three rows in its last block)."""
     run_full(orc, wl.CONFIGS["C5"], B, sample)
 
 
