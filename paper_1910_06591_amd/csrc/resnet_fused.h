@@ -321,8 +321,9 @@ __device__ __forceinline__ void prefetch_issue(Prefetch<S>& p, const uint8_t* __
 
 // convert the prefetched bytes to bf16 and lay them out in buf0 (with zero halo).
 // PART < 0: everything.  The whole 3-channel frame can also be converted in slices: PART = j > 0 converts
-// only every thread's j-th item (frame rows from PRE_SPLIT_ROW on), PART = 0 the first items and the halo.
-template <class S, int PART = -1>
+// only every thread's j-th item, PART = 0 the first items and the halo.  With LIMIT > 0 the slices j > 0 leave
+// out the cells below byte LIMIT of the buffer (live maps sit there); slice 0 converts those too.
+template <class S, int PART = -1, int LIMIT = 0>
 __device__ __forceinline__ void prefetch_commit(const Prefetch<S>& p, char* buf0, int strip, int tid)
 {
     if constexpr (S::INKIND != IN_LDS) {
@@ -334,15 +335,18 @@ __device__ __forceinline__ void prefetch_commit(const Prefetch<S>& p, char* buf0
             const int nitems = (r1 - r0 + 1) * GPR;
 #pragma unroll
             for (int j = 0; j < S::PRE_N; ++j) {
-                if (PART >= 0 && j != PART) continue;
+                if (PART > 0 && j != PART) continue;
+                if (PART == 0 && LIMIT == 0 && j != 0) continue;
                 const int i = tid + j * RN_THREADS;
-                if (i < nitems) {
+                const int cell = (i / GPR + 1) * S::IPITCH + (i % GPR) * 4 + 1;
+                const bool low = LIMIT > 0 && j > 0 && cell * 8 < LIMIT;       // this item's cells start below LIMIT
+                if (i < nitems && (PART < 0 || j == 0 || (PART == 0) == low)) {
                     const uint32_t d0 = p.d[j][0], d1 = p.d[j][1], d2 = p.d[j][2];
                     const uint32_t by[12] = {d0 & 0xff, (d0 >> 8) & 0xff, (d0 >> 16) & 0xff, d0 >> 24,
                                              d1 & 0xff, (d1 >> 8) & 0xff, (d1 >> 16) & 0xff, d1 >> 24,
                                              d2 & 0xff, (d2 >> 8) & 0xff, (d2 >> 16) & 0xff, d2 >> 24};
                     // buffer row of image row iy is iy - (r0 - 1); whole frame: r0 = 0 -> iy + 1
-                    char* d = buf0 + ((i / GPR + 1) * S::IPITCH + (i % GPR) * 4 + 1) * 8;
+                    char* d = buf0 + cell * 8;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const floatx4 c = {(float)by[q * 3], (float)by[q * 3 + 1], (float)by[q * 3 + 2], 0.0f};
@@ -875,11 +879,16 @@ struct NoFiller {
 };
 // `filler`: independent vector-ALU work that every wavefront runs once, placed behind the requests for the
 // weight and first activation fragments so that it executes while those travel from LDS.
-template <class S, bool ADD_X, int OUT, class Filler = NoFiller>
+// NIMG = 2: the tiles of two images, whose maps sit S::ACT_BYTES apart in src and in dst, share the phase (and
+// the wavefront's weight fragments): tile i < NT belongs to the first image, tile NT + i to the second.
+template <class S, bool ADD_X, int OUT, class Filler = NoFiller, int NIMG = 1>
 __device__ __forceinline__ void block_conv(const char* src, char* dst, const char* wslot, const int (&tb)[S::NT],
-                                           floatx4 (&x)[S::NT][S::FT], __bf16* __restrict__ feat_row, int lane, int wave,
+                                           floatx4 (&x)[NIMG * S::NT][S::FT], __bf16* const (&feat_rows)[NIMG], int lane, int wave,
                                            Filler filler = Filler{})
 {
+    static_assert(NIMG == 1 || (NIMG == 2 && S::NT == 1), "two images share a phase only with one tile per wavefront each");
+    constexpr int NTT = NIMG * S::NT;
+    constexpr int IMG_CELLS = S::ACT_BYTES / 16;           // cells between the two images' maps
     if (wave >= S::NWA) {                                  // uniform per wavefront
         filler();
         return;
@@ -904,9 +913,10 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
     constexpr int AHEAD = S::KCB < 4 ? S::KCB - 1 : 4;
     static_assert(AHEAD >= 1 && AHEAD < S::KCB, "prefetch distance");
     bf16x8 bfr[S::KCB];
+    auto tbv = [&](int i) { return tb[i % S::NT] + (i / S::NT) * IMG_CELLS; };
     auto request = [&](int i, int kc, bool with_w) {          // i, kc: compile-time after unrolling
-        const int ii = i < S::NT ? i : S::NT - 1;             // past the last tile: a valid address, value unused
-        const char* pa = src + (tb[ii] + lb[K::kbase(kc)]) * 16;
+        const int ii = i < NTT ? i : NTT - 1;                 // past the last tile: a valid address, value unused
+        const char* pa = src + (tbv(ii) + lb[K::kbase(kc)]) * 16;
         if (with_w) {
 #pragma unroll
             for (int j = 0; j < S::FT; ++j) w[j * S::KCB + kc] = *(const bf16x8*)(wslot + ((j * S::KCB + kc) * 64 + lane) * 16);
@@ -923,9 +933,9 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
         SCHED_FENCE;
     }
 #pragma unroll
-    for (int i = 0; i < S::NT; ++i) {
-        const int t = wave + S::NWA * i;
-        if (t >= S::NTILES) break;
+    for (int i = 0; i < NTT; ++i) {
+        const int t = wave + S::NWA * (i % S::NT);
+        if (t >= S::NTILES) break;                         // (two images: one tile each, both exist or neither)
         floatx4 acc[S::FT];
 #pragma unroll
         for (int j = 0; j < S::FT; ++j) acc[j] = ADD_X ? x[i][j] + bv[j] : bv[j];
@@ -935,7 +945,7 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
 #pragma unroll
             for (int j = 0; j < S::FT; ++j) acc[j] = mfma16(w[j * S::KCB + kc], bfr[kc], acc[j]);
             if (kc + AHEAD < S::KCB) request(i, kc + AHEAD, i == 0);
-            else if (i + 1 < S::NT) request(i + 1, kc + AHEAD - S::KCB, false);
+            else if (i + 1 < NTT) request(i + 1, kc + AHEAD - S::KCB, false);
         }
         SCHED_FENCE;
         const int p = t * 16 + n;
@@ -945,8 +955,8 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
             if (WHOLE || p < S::NPIX) {
                 const bf16x4 vb = to_bf16x4(acc[j]);
                 const bf16x4 out = OUT == 1 ? vb : relu_bf16x4(vb);
-                if (OUT == 2) *(bf16x4*)(feat_row + (size_t)p * S::C + j * 16 + g * 4) = out;
-                else *(bf16x4*)(dstl + tb[i] * 16 + j * (2 * S::PLANE * 16)) = out;
+                if (OUT == 2) *(bf16x4*)(feat_rows[i / S::NT] + (size_t)p * S::C + j * 16 + g * 4) = out;
+                else *(bf16x4*)(dstl + tbv(i) * 16 + j * (2 * S::PLANE * 16)) = out;
             }
         }
     }
@@ -959,7 +969,7 @@ struct ConvMapCfg {
     static constexpr int C = S::C, FT = S::FT, KCB = S::KC0, WB_FRAGS = S::W0_FRAGS;
     static constexpr int PH = S::H, PW = S::W, NPIX = PH * PW, NTILES = (NPIX + 15) / 16;
     static constexpr int NWA = RN_WAVES, NT = (NTILES + NWA - 1) / NWA;
-    static constexpr int PITCH = S::IPITCH, PLANE = S::IPLANE;
+    static constexpr int PITCH = S::IPITCH, PLANE = S::IPLANE, ACT_BYTES = S::CM_BYTES;
     static_assert(S::CONVMAP && S::IROWS == S::H + 2 && PLANE * (C / 8) * 16 == S::CM_BYTES, "conv map geometry");
 };
 
@@ -976,7 +986,8 @@ __device__ __forceinline__ void conv_map(const char* in, char* out, const char* 
         tb[i] = y * CM::PITCH + xx;
     }
     floatx4 unused[CM::NT][CM::FT];                        // block_conv reads x only when it adds it
-    block_conv<CM, false, 1>(in, out, wslot, tb, unused, nullptr, lane, wave);
+    __bf16* const no_rows[1] = {nullptr};
+    block_conv<CM, false, 1>(in, out, wslot, tb, unused, no_rows, lane, wave);
 }
 
 // 3x3 / stride-2 maximum of a CONVMAP section's conv map at pooled pixel (y, xx) for the lane's four channels of
@@ -1036,6 +1047,54 @@ struct LdsMap {
     static_assert(WSB_HI_CAP >= 0, "LDS layout does not fit");
     static_assert(WSB_LO + WSLOT_BYTES <= EDGE, "low weight slot must fit in buf1's tail");
 };
+
+// x-read of a CONVMAP section, in two halves so that two images can share the block phases: pooled_x takes the
+// 3x3/2 maximum of the conv map for this wavefront's tiles (x, and the tiles' cell indices tb); store_relu
+// writes R = ReLU(x) into a planar map.
+template <class S>
+__device__ __forceinline__ void pooled_x(const char* cmap, int (&tb)[S::NT], floatx4 (&x)[S::NT][S::FT], bool (&ok)[S::NT],
+                                         int lane, int wave)
+{
+    const int g = lane >> 4, n = lane & 15;
+    if (wave >= S::NWA) return;
+    bf16x4 wv[S::NT][S::FT][9];
+#pragma unroll
+    for (int i = 0; i < S::NT; ++i) {                      // all loads first
+        int y, xx;
+        bool tile_ok;
+        tile_ref<S>(wave, i, n, y, xx, tile_ok, ok[i]);
+        tb[i] = y * S::PITCH + xx;
+        if (!tile_ok) break;
+        pool_window<S>(cmap, y, xx, g, wv[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < S::NT; ++i) {
+        if (wave + S::NWA * i >= S::NTILES) break;
+#pragma unroll
+        for (int j = 0; j < S::FT; ++j) {
+            floatx4 m = to_floatx4(wv[i][j][0]);
+#pragma unroll
+            for (int d = 1; d < 9; ++d) m = max4(m, to_floatx4(wv[i][j][d]));
+            x[i][j] = m;
+        }
+    }
+}
+
+template <class S>
+__device__ __forceinline__ void store_relu(char* rmap, const int (&tb)[S::NT], const floatx4 (&x)[S::NT][S::FT],
+                                           const bool (&ok)[S::NT], int lane, int wave)
+{
+    const int g = lane >> 4;
+    if (wave >= S::NWA) return;
+    const int loff = (S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
+#pragma unroll
+    for (int i = 0; i < S::NT; ++i) {
+        if (wave + S::NWA * i >= S::NTILES) break;
+#pragma unroll
+        for (int j = 0; j < S::FT; ++j)
+            if (ok[i]) *(bf16x4*)(rmap + tb[i] * 16 + loff + j * (2 * S::PLANE * 16)) = relu_bf16x4(to_bf16x4(x[i][j]));
+    }
+}
 
 // Weight sets are numbered along one image: S1.block1.a = 0 ... (the first layer's set is resident).  Set q
 // lives in slot A when q is even, else in slot B; B is the high slot while the consuming section keeps its maps
@@ -1135,32 +1194,9 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
         // the halo is already zero); buf1 gets the zero halo the first block's output needs
         zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(INB ? buf1 : buf0, tid);
         if constexpr (S::CONVMAP) {
-            if (wave < S::NWA) {                       // x = 3x3/2 maximum of the conv map in buf1
-                const int loff = (S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
-                bf16x4 wv[S::NT][S::FT][9];
-                bool ok[S::NT];
-#pragma unroll
-                for (int i = 0; i < S::NT; ++i) {      // all loads first
-                    int y, xx;
-                    bool tile_ok;
-                    tile_ref<S>(wave, i, n, y, xx, tile_ok, ok[i]);
-                    tb[i] = y * S::PITCH + xx;
-                    if (!tile_ok) break;
-                    pool_window<S>(buf1, y, xx, g, wv[i]);
-                }
-#pragma unroll
-                for (int i = 0; i < S::NT; ++i) {
-                    if (wave + S::NWA * i >= S::NTILES) break;
-#pragma unroll
-                    for (int j = 0; j < S::FT; ++j) {
-                        floatx4 m = to_floatx4(wv[i][j][0]);
-#pragma unroll
-                        for (int d = 1; d < 9; ++d) m = max4(m, to_floatx4(wv[i][j][d]));
-                        x[i][j] = m;
-                        if (ok[i]) *(bf16x4*)(buf0 + tb[i] * 16 + loff + j * (2 * S::PLANE * 16)) = relu_bf16x4(to_bf16x4(m));
-                    }
-                }
-            }
+            bool ok[S::NT];
+            pooled_x<S>(buf1, tb, x, ok, lane, wave);   // x = 3x3/2 maximum of the conv map in buf1
+            store_relu<S>(buf0, tb, x, ok, lane, wave);
         } else if (wave < S::NWA) {
             const int loff = (S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8;
             bf16x4 pv[S::NT][S::FT], ev[S::NT][S::FT];
@@ -1206,6 +1242,7 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
         lds_barrier();
         PHASE_MARK(SI * 8 + 3);
     }
+    __bf16* const feat_rows[1] = {feat_row};
     auto conv = [&](auto add_x, auto out, const char* src, char* dst, const char* ws, auto filler) {
         constexpr bool ADD_X = decltype(add_x)::value;
         constexpr int OUT = decltype(out)::value;
@@ -1213,7 +1250,7 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
             filler();
             block_conv_slide16<S, ADD_X, OUT>(src, dst, lds + M::TRASH + lane * 8, ws, x, lane, wave);
         } else {
-            block_conv<S, ADD_X, OUT>(src, dst, ws, tb, x, feat_row, lane, wave, filler);
+            block_conv<S, ADD_X, OUT>(src, dst, ws, tb, x, feat_rows, lane, wave, filler);
         }
     };
     using BF = std::false_type; using BT = std::true_type;
@@ -1262,6 +1299,102 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     PHASE_MARK(SI * 8 + 7);
 }
 
+// ---- two images through the last section's block phases together ----
+// The last section's maps are small (7 tiles of 16 pixels on the 9 x 12 map): a block phase there is mostly the
+// price of every wavefront fetching the layer's whole weight operand, the barrier and the operand latencies, for
+// one tile of work.  A workgroup therefore takes its images in pairs: first image through sections 1 and 2 and
+// the last section's conv0 and pooling (its residual stream then waits in 8 registers per lane), second image
+// the same way, and then the four block convolutions run once for both images, two tiles per wavefront on one
+// set of weight fragments.
+//   last_front_first: conv0 + pooling of the pair's first image; no R map is written yet.  The second image's
+//     frame (prefetched into `pre`) is converted into buf0, which is free once conv0 has read it.
+//   last_pair: conv0 + pooling of the second image, R maps of both (buf0 and buf0 + ACT_BYTES), the block phases
+//     on both, features of both to global memory; the next pair's first frame is converted into buf0 in slices
+//     behind the block phases' fragment requests, above the two R maps, and below them in the last phase.
+template <class S, class M, int J0, class PreT>
+__device__ __forceinline__ void last_front_first(char* lds, floatx4 (&xa)[S::NT][S::FT], PreT& pre, int tid)
+{
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    char* buf0 = lds + M::BUF0;
+    char* buf1 = lds + M::BUF1;
+    conv_map<S>(buf0, buf1, lds + wslot<M, S, false>(J0), lane, wave);
+    lds_barrier();
+    int tb[S::NT];
+    bool ok[S::NT];
+    pooled_x<S>(buf1, tb, xa, ok, lane, wave);
+    prefetch_commit<typename PreT::Sec>(pre, buf0, 0, tid);
+    lds_barrier();
+}
+
+template <class S, class M, int J0, int NSETS, class PreT>
+__device__ __forceinline__ void last_pair(char* lds, const SecWeights& sw, const floatx4 (&xa)[S::NT][S::FT], PreT& pre,
+                                          __bf16* __restrict__ feat_a, __bf16* __restrict__ feat_b, int tid)
+{
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    char* buf0 = lds + M::BUF0;
+    char* buf1 = lds + M::BUF1;
+    using PS = typename PreT::Sec;
+    constexpr int QB = J0 + 1;
+    constexpr int IMG = S::ACT_BYTES;                      // distance between the two images' maps
+    constexpr int LIMIT = 2 * IMG;                         // the frame's cells below this byte wait for the last phase
+    static_assert(S::CONVMAP && S::NT == 1 && 2 * IMG <= 36 * 1024, "pairs: small conv-map sections, one tile per wavefront");
+    static_assert(PS::INKIND == IN_U8_C3 && PS::NSTRIPS == 1 && PS::PRE_N == 4, "pairs: whole 3-channel frame in four items per thread");
+    auto stage = [&](auto rel) {
+        constexpr int r = decltype(rel)::value;
+        static_assert(QB + r < NSETS, "set number");
+        stage_set<S::WB_SET>(sw.wb[r], lds + wslot<M, S, false>(QB + r), lane, wave);
+    };
+    auto halos = [&](char* buf) {
+        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf, tid);
+        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf + IMG, tid);
+    };
+    using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
+
+    // conv0 of the second image
+    stage(I0{});
+    conv_map<S>(buf0, buf1, lds + wslot<M, S, false>(J0), lane, wave);
+    stage_wait();
+    lds_barrier();
+    // pooled x of the second image; R of both
+    floatx4 x[2 * S::NT][S::FT];
+    int tb[S::NT];
+    bool ok[S::NT];
+    {
+        floatx4 xb[S::NT][S::FT];
+        pooled_x<S>(buf1, tb, xb, ok, lane, wave);
+        halos(buf0);
+        store_relu<S>(buf0, tb, xa, ok, lane, wave);
+        store_relu<S>(buf0 + IMG, tb, xb, ok, lane, wave);
+#pragma unroll
+        for (int j = 0; j < S::FT; ++j) { x[0][j] = xa[0][j]; x[1][j] = xb[0][j]; }
+    }
+    lds_barrier();
+    // block phases on both images
+    __bf16* const feats[2] = {feat_a, feat_b};
+    auto slice = [&](auto part) {
+        return [&pre, buf0, tid]() { prefetch_commit<PS, decltype(part)::value, LIMIT>(pre, buf0, 0, tid); };
+    };
+    stage(I1{});
+    halos(buf1);                                           // held the conv map until now
+    block_conv<S, false, 0, decltype(slice(I1{})), 2>(buf0, buf1, lds + wslot<M, S, false>(QB), tb, x, feats, lane, wave, slice(I1{}));
+    stage_wait();
+    lds_barrier();
+    stage(I2{});
+    block_conv<S, true, 0, decltype(slice(I2{})), 2>(buf1, buf0, lds + wslot<M, S, false>(QB + 1), tb, x, feats, lane, wave, slice(I2{}));
+    stage_wait();
+    lds_barrier();
+    stage(I3{});
+    block_conv<S, false, 0, decltype(slice(I3{})), 2>(buf0, buf1, lds + wslot<M, S, false>(QB + 2), tb, x, feats, lane, wave, slice(I3{}));
+    stage_wait();
+    lds_barrier();
+    block_conv<S, true, 2, NoFiller, 2>(buf1, buf0, lds + wslot<M, S, false>(QB + 3), tb, x, feats, lane, wave);
+    prefetch_commit<PS, 0, LIMIT>(pre, buf0, 0, tid);      // buf0's maps are dead: the rest of the frame and its halo
+    lds_barrier();
+}
+
 template <class S1, class S2, class S3>
 struct Net3 {
     static constexpr int mx(int a, int b) { return a > b ? a : b; }
@@ -1294,15 +1427,36 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
     prefetch_commit<S1>(pre, lds + M::BUF0, 0, tid);
     stage_wait();
     lds_barrier();
-    for (int img = blockIdx.x; img < a.B; img += gridDim.x) {
+    // images in pairs where the last section allows it (see last_pair); a workgroup's odd last image goes alone
+    constexpr bool PAIRS = S3::CONVMAP && S3::NT == 1 && 2 * S3::ACT_BYTES <= 36 * 1024 && !S2::XFUSED &&
+                           S1::INKIND == IN_U8_C3 && S1::NSTRIPS == 1 && S1::PRE_N == 4;
+    const int step = (PAIRS ? 2 : 1) * (int)gridDim.x;
+    for (int img = blockIdx.x; img < a.B; img += step) {
         const uint8_t* obs_img = a.obs + FRAME * img;
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
+        const int imgb = img + (int)gridDim.x;
+        const bool pair = PAIRS && imgb < a.B;                         // uniform over the workgroup
         run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
         run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
-        // the next frame's bytes travel while section 3 computes
-        const int nimg = img + (int)gridDim.x < a.B ? img + (int)gridDim.x : img;   // unconditional load address
-        prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
-        run_section<S3, S3, M, true, 2, 9, N::NSETS, S2::XFUSED>(lds, a.sec[2], a.sec[2], obs_img, pre, feat_row, tid);
+        // the next frame's bytes travel while the last section computes (unconditional load address)
+        if (!pair) {
+            const int nimg = img + step < a.B ? img + step : img;
+            prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
+            run_section<S3, S3, M, true, 2, 9, N::NSETS, S2::XFUSED>(lds, a.sec[2], a.sec[2], obs_img, pre, feat_row, tid);
+            continue;
+        }
+        if constexpr (PAIRS) {
+            prefetch_issue<S1>(pre, a.obs + FRAME * imgb, 0, tid);
+            floatx4 xa[S3::NT][S3::FT];
+            last_front_first<S3, M, 9>(lds, xa, pre, tid);
+            const uint8_t* obs_b = a.obs + FRAME * imgb;
+            __bf16* feat_b = a.feat + (size_t)imgb * a.ldf;
+            run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_b, pre, feat_b, tid);
+            run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_b, pre, feat_b, tid);
+            const int nimg = img + step < a.B ? img + step : img;
+            prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
+            last_pair<S3, M, 9, N::NSETS>(lds, a.sec[2], xa, pre, feat_row, feat_b, tid);
+        }
     }
 }
 
