@@ -48,6 +48,15 @@ __device__ unsigned long long seed_phase_cycles[32];
         }                                                                               \
     } while (0)
 #define PHASE_DECL unsigned long long phase_last_ = clock64()
+// finer split of one block phase (section DETAIL_SEC, wavefront DETAIL_WAVE): convolution, wait for the staged
+// weights, barrier -> seed_phase_cycles[24..26]; the atomics are issued after the barrier so that the wait for
+// the staged weights does not also wait for them
+#ifndef DETAIL_SEC
+#define DETAIL_SEC 1
+#endif
+#ifndef DETAIL_WAVE
+#define DETAIL_WAVE 0
+#endif
 #define DETAIL_T0 unsigned long long dt_[4]; dt_[0] = clock64()
 #define DETAIL_MARK(k) do { dt_[k + 1] = clock64(); if (k == 2 && SI == DETAIL_SEC && (tid & 63) == 0 && (tid >> 6) == DETAIL_WAVE) { for (int q_ = 0; q_ < 3; ++q_) atomicAdd(&seed_phase_cycles[24 + q_], dt_[q_ + 1] - dt_[q_]); } } while (0)
 #else
