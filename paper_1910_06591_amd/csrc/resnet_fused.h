@@ -69,6 +69,10 @@ __device__ unsigned long long seed_phase_cycles[32];
 #ifndef SEEDINF_RN_WAVES
 #define SEEDINF_RN_WAVES 8
 #endif
+#ifndef SEEDINF_GROUP
+#define SEEDINF_GROUP 2                         // images a workgroup takes through the last section's block phases together
+                                                // (3 and, with a low weight slot at 40 KiB, 4 were measured within 1 % of 2)
+#endif
 constexpr int RN_WAVES = SEEDINF_RN_WAVES;
 constexpr int RN_THREADS = RN_WAVES * 64;
 constexpr int LDS_TOTAL = 160 * 1024;
@@ -888,14 +892,14 @@ struct NoFiller {
 };
 // `filler`: independent vector-ALU work that every wavefront runs once, placed behind the requests for the
 // weight and first activation fragments so that it executes while those travel from LDS.
-// NIMG = 2: the tiles of two images, whose maps sit S::ACT_BYTES apart in src and in dst, share the phase (and
-// the wavefront's weight fragments): tile i < NT belongs to the first image, tile NT + i to the second.
+// NIMG > 1: the tiles of NIMG images, whose maps sit S::ACT_BYTES apart in src and in dst, share the phase (and
+// the wavefront's weight fragments): tile i belongs to image i / NT.
 template <class S, bool ADD_X, int OUT, class Filler = NoFiller, int NIMG = 1>
 __device__ __forceinline__ void block_conv(const char* src, char* dst, const char* wslot, const int (&tb)[S::NT],
                                            floatx4 (&x)[NIMG * S::NT][S::FT], __bf16* const (&feat_rows)[NIMG], int lane, int wave,
                                            Filler filler = Filler{})
 {
-    static_assert(NIMG == 1 || (NIMG == 2 && S::NT == 1), "two images share a phase only with one tile per wavefront each");
+    static_assert(NIMG == 1 || S::NT == 1, "several images share a phase only with one tile per wavefront each");
     constexpr int NTT = NIMG * S::NT;
     constexpr int IMG_CELLS = S::ACT_BYTES / 16;           // cells between the two images' maps
     if (wave >= S::NWA) {                                  // uniform per wavefront
@@ -982,8 +986,8 @@ struct ConvMapCfg {
     static_assert(S::CONVMAP && S::IROWS == S::H + 2 && PLANE * (C / 8) * 16 == S::CM_BYTES, "conv map geometry");
 };
 
-template <class S>
-__device__ __forceinline__ void conv_map(const char* in, char* out, const char* wslot, int lane, int wave)
+template <class S, class Filler = NoFiller>
+__device__ __forceinline__ void conv_map(const char* in, char* out, const char* wslot, int lane, int wave, Filler filler = Filler{})
 {
     using CM = ConvMapCfg<S>;
     int tb[CM::NT];
@@ -996,7 +1000,7 @@ __device__ __forceinline__ void conv_map(const char* in, char* out, const char* 
     }
     floatx4 unused[CM::NT][CM::FT];                        // block_conv reads x only when it adds it
     __bf16* const no_rows[1] = {nullptr};
-    block_conv<CM, false, 1>(in, out, wslot, tb, unused, no_rows, lane, wave);
+    block_conv<CM, false, 1, Filler>(in, out, wslot, tb, unused, no_rows, lane, wave, filler);
 }
 
 // 3x3 / stride-2 maximum of a CONVMAP section's conv map at pooled pixel (y, xx) for the lane's four channels of
@@ -1050,8 +1054,9 @@ struct LdsMap {
     static constexpr int WSB_HI = WSA + WSLOT_BYTES;
     static constexpr int PERM = LDS_TOTAL - r256(PERM_);           // first layer's weights, resident for the whole kernel
     static constexpr int WSB_HI_CAP = PERM - WSB_HI;
-    static constexpr int WSB_LO = BUF1 + 36 * 1024;                // inside buf1's tail: only while buf1 holds <= 36 KiB
-    static constexpr int WSB_LO0 = BUF0 + 36 * 1024;               // inside buf0's tail, for sections whose input sits in buf1
+    static constexpr int LOW_SLOT_AT = 36 * 1024;                  // maps of at most this size leave room for a weight slot behind them
+    static constexpr int WSB_LO = BUF1 + LOW_SLOT_AT;              // inside buf1's tail: only while buf1 holds <= LOW_SLOT_AT bytes
+    static constexpr int WSB_LO0 = BUF0 + LOW_SLOT_AT;             // inside buf0's tail, for sections whose input sits in buf1
     static_assert(WSB_LO0 + WSLOT_BYTES <= BUF1, "low weight slot must fit in buf0's tail");
     static_assert(WSB_HI_CAP >= 0, "LDS layout does not fit");
     static_assert(WSB_LO + WSLOT_BYTES <= EDGE, "low weight slot must fit in buf1's tail");
@@ -1112,7 +1117,7 @@ __device__ __forceinline__ void store_relu(char* rmap, const int (&tb)[S::NT], c
 template <class M, class S, bool INB>
 constexpr int wslot(int q)
 {
-    return (q & 1) == 0 ? M::WSA : (S::ACT_BYTES > 36 * 1024 ? M::WSB_HI : (INB ? M::WSB_LO0 : M::WSB_LO));
+    return (q & 1) == 0 ? M::WSA : (S::ACT_BYTES > M::LOW_SLOT_AT ? M::WSB_HI : (INB ? M::WSB_LO0 : M::WSB_LO));
 }
 
 // One section for one image.
@@ -1146,9 +1151,9 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     char* bufU = S::XFUSED ? buf0 : buf1;
     constexpr int QB = J0 + 1;                                   // set number of block1.a
     constexpr int SLOT_C0 = J0 < 0 ? M::PERM : wslot<M, S, INB>(J0);
-    static_assert(S::ACT_BYTES <= 36 * 1024 || S::WB_SET * 1024 <= M::WSB_HI_CAP, "block weights do not fit the high slot");
+    static_assert(S::ACT_BYTES <= M::LOW_SLOT_AT || S::WB_SET * 1024 <= M::WSB_HI_CAP, "block weights do not fit the high slot");
     static_assert(S::WB_SET * 1024 <= WSLOT_BYTES && S::W0_SET * 1024 <= WSLOT_BYTES, "weight set larger than a slot");
-    static_assert(LAST || (QB + 4) % 2 == 0 || SN::ACT_BYTES <= 36 * 1024 || SN::W0_SET * 1024 <= M::WSB_HI_CAP, "next conv0 set does not fit");
+    static_assert(LAST || (QB + 4) % 2 == 0 || SN::ACT_BYTES <= M::LOW_SLOT_AT || SN::W0_SET * 1024 <= M::WSB_HI_CAP, "next conv0 set does not fit");
     // set q (relative to this section: 0 = block1.a ... 3 = block2.b, 4 = next conv0)
     auto stage = [&](auto rel) {
         constexpr int r = decltype(rel)::value;
@@ -1308,18 +1313,18 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     PHASE_MARK(SI * 8 + 7);
 }
 
-// ---- two images through the last section's block phases together ----
+// ---- several images through the last section's block phases together ----
 // The last section's maps are small (7 tiles of 16 pixels on the 9 x 12 map): a block phase there is mostly the
 // price of every wavefront fetching the layer's whole weight operand, the barrier and the operand latencies, for
-// one tile of work.  A workgroup therefore takes its images in pairs: first image through sections 1 and 2 and
-// the last section's conv0 and pooling (its residual stream then waits in 8 registers per lane), second image
-// the same way, and then the four block convolutions run once for both images, two tiles per wavefront on one
-// set of weight fragments.
-//   last_front_first: conv0 + pooling of the pair's first image; no R map is written yet.  The second image's
-//     frame (prefetched into `pre`) is converted into buf0, which is free once conv0 has read it.
-//   last_pair: conv0 + pooling of the second image, R maps of both (buf0 and buf0 + ACT_BYTES), the block phases
-//     on both, features of both to global memory; the next pair's first frame is converted into buf0 in slices
-//     behind the block phases' fragment requests, above the two R maps, and below them in the last phase.
+// one tile of work.  A workgroup therefore takes its images in groups: every member runs through sections 1 and
+// 2 and the last section's conv0 and pooling; the residual streams of all but the last member then wait in 8
+// registers per lane each, and the four block convolutions run once for the whole group, one tile per image and
+// wavefront on one set of weight fragments.
+//   last_front_first: conv0 + pooling of a waiting member; no R map is written yet.  The next member's frame
+//     (prefetched into `pre`) is converted into buf0, which is free once conv0 has read it.
+//   last_group: conv0 + pooling of the last member, R maps of all (buf0 + k * ACT_BYTES), the block phases on
+//     all, features of all to global memory; the next group's first frame is converted into buf0 in slices
+//     behind the block phases' fragment requests, above the R maps, and below them in the last phase.
 template <class S, class M, int J0, class PreT>
 __device__ __forceinline__ void last_front_first(char* lds, floatx4 (&xa)[S::NT][S::FT], PreT& pre, int tid)
 {
@@ -1327,81 +1332,101 @@ __device__ __forceinline__ void last_front_first(char* lds, floatx4 (&xa)[S::NT]
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     char* buf0 = lds + M::BUF0;
     char* buf1 = lds + M::BUF1;
+    PHASE_DECL;
     conv_map<S>(buf0, buf1, lds + wslot<M, S, false>(J0), lane, wave);
     lds_barrier();
+    PHASE_MARK(16 + 0);
     int tb[S::NT];
     bool ok[S::NT];
     pooled_x<S>(buf1, tb, xa, ok, lane, wave);
     prefetch_commit<typename PreT::Sec>(pre, buf0, 0, tid);
     lds_barrier();
+    PHASE_MARK(16 + 2);
 }
 
-template <class S, class M, int J0, int NSETS, class PreT>
-__device__ __forceinline__ void last_pair(char* lds, const SecWeights& sw, const floatx4 (&xa)[S::NT][S::FT], PreT& pre,
-                                          __bf16* __restrict__ feat_a, __bf16* __restrict__ feat_b, int tid)
+template <class S, class M, int J0, int NSETS, int N, int NQ, class PreT>
+__device__ __forceinline__ void last_group(char* lds, const SecWeights& sw, const floatx4 (&xq)[NQ][S::NT][S::FT], PreT& pre,
+                                           __bf16* __restrict__ feat0, size_t feat_step, int tid)
 {
+    // image k of the group (k = 0 .. N-2) waits in xq[N-2-k] (the most recent one in xq[0]); image N-1 is the
+    // one whose section-2 output sits in buf0 now; image k's features go to feat0 + k * feat_step
+    static_assert(N >= 2 && N - 1 <= NQ, "group size");
     asm volatile("" : "+v"(tid));
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     char* buf0 = lds + M::BUF0;
     char* buf1 = lds + M::BUF1;
     using PS = typename PreT::Sec;
     constexpr int QB = J0 + 1;
-    constexpr int IMG = S::ACT_BYTES;                      // distance between the two images' maps
-    constexpr int LIMIT = 2 * IMG;                         // the frame's cells below this byte wait for the last phase
-    static_assert(S::CONVMAP && S::NT == 1 && 2 * IMG <= 36 * 1024, "pairs: small conv-map sections, one tile per wavefront");
-    static_assert(PS::INKIND == IN_U8_C3 && PS::NSTRIPS == 1 && PS::PRE_N == 4, "pairs: whole 3-channel frame in four items per thread");
+    constexpr int IMG = S::ACT_BYTES;                      // distance between two images' maps
+    constexpr int LIMIT = N * IMG;                         // the frame's cells below this byte wait for the last phase
+    static_assert(S::CONVMAP && S::NT == 1 && N * IMG <= M::LOW_SLOT_AT, "groups: small conv-map sections, one tile per wavefront");
+    static_assert(PS::INKIND == IN_U8_C3 && PS::NSTRIPS == 1 && PS::PRE_N == 4, "groups: whole 3-channel frame in four items per thread");
     auto stage = [&](auto rel) {
         constexpr int r = decltype(rel)::value;
         static_assert(QB + r < NSETS, "set number");
         stage_set<S::WB_SET>(sw.wb[r], lds + wslot<M, S, false>(QB + r), lane, wave);
     };
     auto halos = [&](char* buf) {
-        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf, tid);
-        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf + IMG, tid);
+#pragma unroll
+        for (int k = 0; k < N; ++k) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf + k * IMG, tid);
     };
     using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
     using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
 
-    // conv0 of the second image
+    // conv0 of the last image
+    PHASE_DECL;
     stage(I0{});
     conv_map<S>(buf0, buf1, lds + wslot<M, S, false>(J0), lane, wave);
     stage_wait();
     lds_barrier();
-    // pooled x of the second image; R of both
-    floatx4 x[2 * S::NT][S::FT];
+    PHASE_MARK(16 + 1);
+    // pooled x of the last image; R of all
+    floatx4 x[N * S::NT][S::FT];
     int tb[S::NT];
     bool ok[S::NT];
     {
         floatx4 xb[S::NT][S::FT];
         pooled_x<S>(buf1, tb, xb, ok, lane, wave);
         halos(buf0);
-        store_relu<S>(buf0, tb, xa, ok, lane, wave);
-        store_relu<S>(buf0 + IMG, tb, xb, ok, lane, wave);
 #pragma unroll
-        for (int j = 0; j < S::FT; ++j) { x[0][j] = xa[0][j]; x[1][j] = xb[0][j]; }
+        for (int k = 0; k < N - 1; ++k) {
+            store_relu<S>(buf0 + k * IMG, tb, xq[N - 2 - k], ok, lane, wave);
+#pragma unroll
+            for (int j = 0; j < S::FT; ++j) x[k][j] = xq[N - 2 - k][0][j];
+        }
+        store_relu<S>(buf0 + (N - 1) * IMG, tb, xb, ok, lane, wave);
+#pragma unroll
+        for (int j = 0; j < S::FT; ++j) x[N - 1][j] = xb[0][j];
     }
     lds_barrier();
-    // block phases on both images
-    __bf16* const feats[2] = {feat_a, feat_b};
+    PHASE_MARK(16 + 3);
+    // block phases on all images
+    __bf16* feats[N];
+#pragma unroll
+    for (int k = 0; k < N; ++k) feats[k] = feat0 + k * feat_step;
     auto slice = [&](auto part) {
         return [&pre, buf0, tid]() { prefetch_commit<PS, decltype(part)::value, LIMIT>(pre, buf0, 0, tid); };
     };
     stage(I1{});
     halos(buf1);                                           // held the conv map until now
-    block_conv<S, false, 0, decltype(slice(I1{})), 2>(buf0, buf1, lds + wslot<M, S, false>(QB), tb, x, feats, lane, wave, slice(I1{}));
+    block_conv<S, false, 0, decltype(slice(I1{})), N>(buf0, buf1, lds + wslot<M, S, false>(QB), tb, x, feats, lane, wave, slice(I1{}));
     stage_wait();
     lds_barrier();
+    PHASE_MARK(16 + 4);
     stage(I2{});
-    block_conv<S, true, 0, decltype(slice(I2{})), 2>(buf1, buf0, lds + wslot<M, S, false>(QB + 1), tb, x, feats, lane, wave, slice(I2{}));
+    block_conv<S, true, 0, decltype(slice(I2{})), N>(buf1, buf0, lds + wslot<M, S, false>(QB + 1), tb, x, feats, lane, wave, slice(I2{}));
     stage_wait();
     lds_barrier();
+    PHASE_MARK(16 + 5);
     stage(I3{});
-    block_conv<S, false, 0, decltype(slice(I3{})), 2>(buf0, buf1, lds + wslot<M, S, false>(QB + 2), tb, x, feats, lane, wave, slice(I3{}));
+    block_conv<S, false, 0, decltype(slice(I3{})), N>(buf0, buf1, lds + wslot<M, S, false>(QB + 2), tb, x, feats, lane, wave, slice(I3{}));
     stage_wait();
     lds_barrier();
-    block_conv<S, true, 2, NoFiller, 2>(buf1, buf0, lds + wslot<M, S, false>(QB + 3), tb, x, feats, lane, wave);
+    PHASE_MARK(16 + 6);
+    block_conv<S, true, 2, NoFiller, N>(buf1, buf0, lds + wslot<M, S, false>(QB + 3), tb, x, feats, lane, wave);
     prefetch_commit<PS, 0, LIMIT>(pre, buf0, 0, tid);      // buf0's maps are dead: the rest of the frame and its halo
     lds_barrier();
+    PHASE_MARK(16 + 7);
 }
 
 template <class S1, class S2, class S3>
@@ -1436,35 +1461,44 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
     prefetch_commit<S1>(pre, lds + M::BUF0, 0, tid);
     stage_wait();
     lds_barrier();
-    // images in pairs where the last section allows it (see last_pair); a workgroup's odd last image goes alone
-    constexpr bool PAIRS = S3::CONVMAP && S3::NT == 1 && 2 * S3::ACT_BYTES <= 36 * 1024 && !S2::XFUSED &&
-                           S1::INKIND == IN_U8_C3 && S1::NSTRIPS == 1 && S1::PRE_N == 4;
-    const int step = (PAIRS ? 2 : 1) * (int)gridDim.x;
-    for (int img = blockIdx.x; img < a.B; img += step) {
-        const uint8_t* obs_img = a.obs + FRAME * img;
-        __bf16* feat_row = a.feat + (size_t)img * a.ldf;
-        const int imgb = img + (int)gridDim.x;
-        const bool pair = PAIRS && imgb < a.B;                         // uniform over the workgroup
-        run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
-        run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
-        // the next frame's bytes travel while the last section computes (unconditional load address)
-        if (!pair) {
-            const int nimg = img + step < a.B ? img + step : img;
-            prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
-            run_section<S3, S3, M, true, 2, 9, N::NSETS, S2::XFUSED>(lds, a.sec[2], a.sec[2], obs_img, pre, feat_row, tid);
-            continue;
-        }
-        if constexpr (PAIRS) {
-            prefetch_issue<S1>(pre, a.obs + FRAME * imgb, 0, tid);
-            floatx4 xa[S3::NT][S3::FT];
-            last_front_first<S3, M, 9>(lds, xa, pre, tid);
-            const uint8_t* obs_b = a.obs + FRAME * imgb;
-            __bf16* feat_b = a.feat + (size_t)imgb * a.ldf;
-            run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_b, pre, feat_b, tid);
-            run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_b, pre, feat_b, tid);
-            const int nimg = img + step < a.B ? img + step : img;
-            prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
-            last_pair<S3, M, 9, N::NSETS>(lds, a.sec[2], xa, pre, feat_row, feat_b, tid);
+    // Images in groups of up to NG where the last section allows it (see last_group): the members of a group run
+    // one after the other through ONE copy of the code of sections 1 and 2; all but the last then do the last
+    // section's conv0 and pooling and wait, the last one finishes the group.  A group of one takes the plain path.
+    constexpr int NG = (S3::CONVMAP && S3::NT == 1 && !S2::XFUSED && S1::INKIND == IN_U8_C3 && S1::NSTRIPS == 1 && S1::PRE_N == 4)
+                           ? SEEDINF_GROUP : 1;
+    static_assert(NG == 1 || NG * S3::ACT_BYTES <= M::LOW_SLOT_AT, "the group's maps must leave the low weight slot free");
+    const int grid = (int)gridDim.x;
+    floatx4 xq[NG > 1 ? NG - 1 : 1][S3::NT][S3::FT];                   // pooled x of the waiting members, most recent first
+    for (int img = blockIdx.x; img < a.B; img += NG * grid) {
+        int n = 1;                                                     // members of this group (uniform over the workgroup)
+        while (n < NG && img + n * grid < a.B) ++n;
+        for (int k = 0; k < n; ++k) {
+            const int cur = img + k * grid;
+            const uint8_t* obs_img = a.obs + FRAME * cur;
+            __bf16* feat_row = a.feat + (size_t)cur * a.ldf;
+            run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
+            run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
+            // the next frame's bytes travel while the last section computes (unconditional load address)
+            const int nxt = k + 1 < n ? cur + grid : (img + NG * grid < a.B ? img + NG * grid : cur);
+            prefetch_issue<S1>(pre, a.obs + FRAME * nxt, 0, tid);
+            if (n == 1) {
+                run_section<S3, S3, M, true, 2, 9, N::NSETS, S2::XFUSED>(lds, a.sec[2], a.sec[2], obs_img, pre, feat_row, tid);
+            } else if constexpr (NG > 1) {
+                __bf16* feat0 = a.feat + (size_t)img * a.ldf;
+                const size_t fstep = (size_t)grid * a.ldf;
+                if (k + 1 < n) {
+#pragma unroll
+                    for (int q = NG - 2; q > 0; --q)
+#pragma unroll
+                        for (int j = 0; j < S3::FT; ++j) xq[q][0][j] = xq[q - 1][0][j];
+                    last_front_first<S3, M, 9>(lds, xq[0], pre, tid);
+                } else if (n == 2) {
+                    last_group<S3, M, 9, N::NSETS, 2, NG - 1>(lds, a.sec[2], xq, pre, feat0, fstep, tid);
+                } else if constexpr (NG >= 3) {
+                    if (n == 3) last_group<S3, M, 9, N::NSETS, 3, NG - 1>(lds, a.sec[2], xq, pre, feat0, fstep, tid);
+                    else if constexpr (NG >= 4) last_group<S3, M, 9, N::NSETS, 4, NG - 1>(lds, a.sec[2], xq, pre, feat0, fstep, tid);
+                }
+            }
         }
     }
 }
