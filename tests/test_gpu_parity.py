@@ -199,9 +199,11 @@ def test_full_size_c5_sweep(orc, B, sample):
     run_full(orc, wl.CONFIGS["C5"], B, sample)
 
 
-@pytest.mark.parametrize("B", [1, 257, 300])
+@pytest.mark.parametrize("B", [1, 257, 300, 512, 513, 770])
 def test_bf16_persistent_grid_edges(orc, B):
-    """B = 1; one more image than there are compute units (one workgroup takes two); a ragged count."""
+    """B = 1; one more image than there are compute units (one workgroup takes two, as a group); a ragged count;
+    exactly two images per workgroup; a workgroup with a group and then a single image; groups and singles mixed
+    in the second round."""
     run_full(orc, wl.CONFIGS["C3"], B, sample=None if B == 1 else 64)
 
 
