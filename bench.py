@@ -108,6 +108,16 @@ def time_extensions(cfg, B, weights):
 
     res = {"step_plain_p50_ms": p50(lambda: net.step(out=out, **dev)),
            "step_ext_p50_ms": p50(lambda: net.step(out=out, **dev, **ext))}
+    # the same step captured once into a HIP graph (the step is kernel launches only) and replayed
+    def graphed_p50(nb):
+        sub = {k: (None if v is None else v[:nb].contiguous()) for k, v in dev.items()}
+        o = net.step(**sub)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            net.step(out=o, **sub)
+        return p50(g.replay), p50(lambda: net.step(out=o, **sub))
+    res["graph_replay_vs_eager_p50_ms"] = {str(nb): list(graphed_p50(nb)) for nb in (64, 256, B) if nb <= B}
     # weight refresh: host time of the call (repack + enqueue) and a step issued right behind it
     t = []
     for _ in range(5):
