@@ -414,7 +414,10 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     s->fc_bf16 = (__bf16*)(s->arena + o_fcb);
     s->fc_f32 = (float*)(s->arena + o_fcf);
 
-    // the fused torso kernels use more than 64 KiB of LDS
+    // the LDS-tiled layer-by-layer convolution and the fused torso kernels may use more than 64 KiB of LDS
+    BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
+    BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
+    BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
     if (s->torso_kind == TORSO_DMLAB) {
         BF_TRY(hipFuncSetAttribute((const void*)resnet3_bf16_kernel<DmS1, DmS2, DmS3>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, Net3<DmS1, DmS2, DmS3>::LDS_BYTES));
@@ -466,6 +469,17 @@ inline void launch_lw_conv(hipStream_t st, const LwConvArgs& c, int ft, bool u8)
 {
     const long npix = (long)c.B * c.H * c.W;
     const int gy = c.Cout / (16 * ft);
+    if (!u8 && c.Cin % 32 == 0 && lt_lds_bytes(c.W, c.Cin) <= LT_LDS_MAX) {
+        // bf16 input with whole 32-channel chunks: the LDS-tiled kernel
+        const int hw = c.H * c.W;
+        const dim3 grid((unsigned)(c.B * ((hw + LT_PIX - 1) / LT_PIX)), gy);
+        const size_t lds = lt_lds_bytes(c.W, c.Cin);
+        const int plane = lt_plane_cells(c.W);
+        if (ft == 4) hipLaunchKernelGGL(conv3x3_lds_kernel<4>, grid, dim3(LT_THREADS), lds, st, c, plane);
+        else if (ft == 2) hipLaunchKernelGGL(conv3x3_lds_kernel<2>, grid, dim3(LT_THREADS), lds, st, c, plane);
+        else hipLaunchKernelGGL(conv3x3_lds_kernel<1>, grid, dim3(LT_THREADS), lds, st, c, plane);
+        return;
+    }
     auto go = [&](auto ftc, auto rtc, auto u8c) {
         constexpr int FT = decltype(ftc)::value, RT = decltype(rtc)::value;
         constexpr bool U8 = decltype(u8c)::value;

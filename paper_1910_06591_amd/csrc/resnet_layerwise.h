@@ -125,6 +125,100 @@ __global__ __launch_bounds__(256) void conv3x3_lw_kernel(LwConvArgs p)
     }
 }
 
+// LDS-tiled variant for bf16 inputs whose channel count is a multiple of 32.  A block takes 128 consecutive
+// pixels of one image (row-major, so narrow maps lose nothing to ragged tiles) and NF feature tiles; the input
+// rows those pixels touch, one row above and below and a zero column left and right, are staged once in LDS as
+// channel-group planes [Cin/8][rows][W+2][8 bf16] (plane stride a multiple of 256 B), so every input value is
+// read from global memory once per block instead of nine times and a B fragment is one 16-byte LDS read.
+// Wavefront w of the 8 multiplies feature tile w % NF with the pixel tiles w / NF, w / NF + 8 / NF, ...; chunk kc
+// = (tap, 32 channels) matches the packed weight order k = tap * Cin + ci.
+constexpr int LT_THREADS = 512, LT_PIX = 128;
+constexpr size_t LT_LDS_MAX = 128 * 1024;                   // dynamic LDS the kernel may ask for
+
+// rows of the staged patch: the rows 128 consecutive pixels can touch, plus one above and one below
+inline int lt_patch_rows(int W) { return (LT_PIX + W - 2) / W + 1 + 2; }
+inline int lt_plane_cells(int W) { return (lt_patch_rows(W) * (W + 2) + 15) / 16 * 16; }
+inline size_t lt_lds_bytes(int W, int Cin) { return (size_t)(Cin / 8) * lt_plane_cells(W) * 16; }
+
+template <int NF>
+__global__ __launch_bounds__(LT_THREADS) void conv3x3_lds_kernel(LwConvArgs p, int plane_cells)
+{
+    static_assert(NF == 1 || NF == 2 || NF == 4, "feature tiles per block");
+    constexpr int NPG = 8 / NF;                            // pixel groups (wavefronts per feature tile)
+    constexpr int TPW = (LT_PIX / 16) / NPG;               // pixel tiles per wavefront
+    extern __shared__ __attribute__((aligned(16))) char lt_lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, n = lane & 15;
+    const int hw = p.H * p.W;
+    const int nblk = (hw + LT_PIX - 1) / LT_PIX;
+    const int b = blockIdx.x / nblk;
+    const int p0 = (blockIdx.x % nblk) * LT_PIX;
+    const int p1 = min(p0 + LT_PIX, hw);
+    const int y0 = p0 / p.W, y1 = (p1 - 1) / p.W;
+    const int prow = y1 - y0 + 3;                          // patch rows: image rows y0-1 .. y1+1
+    const int PW2 = p.W + 2;
+    const int ncg = p.Cin >> 3;
+
+    // stage the patch (zeros outside the image)
+    const __bf16* img = (const __bf16*)p.in + (size_t)b * hw * p.Cin;
+    const int cells = prow * PW2;
+    for (int idx = threadIdx.x; idx < cells * ncg; idx += LT_THREADS) {
+        const int cell = idx / ncg, cg = idx - cell * ncg;             // channel groups of one pixel are adjacent in memory
+        const int r = cell / PW2, c = cell - r * PW2;
+        const int y = y0 - 1 + r, x = c - 1;
+        bf16x8 v = {};
+        if (y >= 0 && y < p.H && x >= 0 && x < p.W) v = *(const bf16x8*)(img + ((size_t)y * p.W + x) * p.Cin + cg * 8);
+        *(bf16x8*)(lt_lds + ((size_t)cg * plane_cells + cell) * 16) = v;
+    }
+    __syncthreads();
+
+    const int ft = blockIdx.y * NF + wave % NF;
+    const int pg = wave / NF;
+    int base[TPW];                                         // patch cell of the lane's pixel, tap (0, 0)
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int pix = min(p0 + (pg + NPG * i) * 16 + n, p1 - 1);
+        const int y = pix / p.W, x = pix - y * p.W;
+        base[i] = (y - y0) * PW2 + x;
+    }
+    floatx4 acc[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int cq_n = p.Cin >> 5;
+    const bf16x8* wl = p.wp + (size_t)ft * p.kchunks * 64 + lane;
+    const char* lane_plane = lt_lds + (size_t)g * plane_cells * 16;
+    bf16x8 a = wl[0];
+    int kc = 0;
+    for (int tap = 0; tap < 9; ++tap) {
+        const int toff = (tap / 3) * PW2 + tap % 3;
+        for (int cq = 0; cq < cq_n; ++cq, ++kc) {
+            const bf16x8 a_next = wl[(size_t)min(kc + 1, p.kchunks - 1) * 64];
+            const char* src = lane_plane + ((size_t)cq * 4 * plane_cells + toff) * 16;
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) acc[i] = mfma16(a, *(const bf16x8*)(src + base[i] * 16), acc[i]);
+            a = a_next;
+        }
+    }
+
+    const int f = ft * 16 + g * 4;
+    const floatx4 bv = *(const floatx4*)(p.bias + f);
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int pl = p0 + (pg + NPG * i) * 16 + n;
+        if (pl >= p1) continue;
+        const long pix = (long)b * hw + pl;
+        floatx4 v = acc[i] + bv;
+        if (p.x_in) v += *(const floatx4*)(p.x_in + pix * p.Cout + f);
+        if (p.x_out) *(floatx4*)(p.x_out + pix * p.Cout + f) = v;
+        if (p.y) {
+            const bf16x4 o = to_bf16x4(v);
+            const long at = p.ldy > 0 ? (long)b * p.ldy + (long)pl * p.Cout + f : pix * p.Cout + f;
+            *(bf16x4*)(p.y + at) = p.y_relu ? relu_bf16x4(o) : o;
+        }
+    }
+}
+
 // 3x3 / stride-2 max-pool with TF-style SAME padding on a bf16 NHWC map: writes the pooled values as the fp32
 // residual stream x and their rectified bf16 copy R (the first block's input).  One thread per 4 channels.
 __global__ __launch_bounds__(256) void pool3x3s2_lw_kernel(const __bf16* __restrict__ in, float* __restrict__ x,

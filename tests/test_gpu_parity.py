@@ -239,6 +239,7 @@ def test_bf16_head_and_core_variants(orc):
     ("Football torso, large map 144x108", dict(obs_h=108, obs_w=144), 2),
     ("odd frame 50x70x3, two sections, 48 channels", dict(obs_h=50, obs_w=70, sections=[16, 48]), 7),
     ("4-plane minimap 72x96x4", dict(obs_c=4, sections=[16, 32, 32, 32]), 6),
+    ("odd frame 46x62x3, 32 then 96 channels", dict(obs_h=46, obs_w=62, sections=[32, 96]), 5),
 ])
 def test_bf16_model_size_variants_run_layer_by_layer(orc, label, over, B):
     """Model-size variants (Section 4.1: wider filters; Section 4.2: larger minimaps) have no fused kernel and
