@@ -81,4 +81,16 @@ __device__ __forceinline__ bf16x8 u8x8_to_bf16x8(uint32_t lo, uint32_t hi)
     return to_bf16x8(a, b);
 }
 
+// Asynchronous global -> LDS load (no registers): lane l's 16 bytes land at (wave-uniform LDS base in M0) +
+// 16 * l.  Written as inline assembly because the compiler would otherwise wait for it before the next LDS
+// access of any kind; stage_wait() collects every such load the wavefront has issued.
+__device__ __forceinline__ void g2lds16(const void* gptr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void stage_wait()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 }  // namespace seedinf

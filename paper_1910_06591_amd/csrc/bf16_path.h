@@ -11,6 +11,7 @@
 #include "plan.h"
 #include "kernels_fp32.h"
 #include "gemm_bf16.h"
+#include "gemm_bf16_lds.h"
 #include "conv_stack_bf16.h"
 #include "resnet_fused.h"
 #include "resnet_layerwise.h"
@@ -413,6 +414,8 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     s->feat = (__bf16*)(s->arena + o_feat);
     s->fc_bf16 = (__bf16*)(s->arena + o_fcb);
     s->fc_f32 = (float*)(s->arena + o_fcf);
+    BF_TRY(gemm_lds_set_attributes<EPI_RELU>());
+    BF_TRY(gemm_lds_set_attributes<EPI_LSTM>());
 
     // the LDS-tiled layer-by-layer convolution and the fused torso kernels may use more than 64 KiB of LDS
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
@@ -428,9 +431,33 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     return SEED_OK;
 }
 
+// Large batch: LDS-staged tiles.
+template <int EPI>
+inline bool launch_gemm_lds(hipStream_t st, const GemmArgs& g, int tile_groups, int n_cu)
+{
+    if (g.rows < GL_MIN_ROWS || (g.kc1 & 1)) return false;
+    const int kct = g.kc1 + (g.k2 + 31) / 32;
+    if constexpr (EPI == EPI_RELU) {
+        if (kct >= 64 && g.k2 == 0 && (long)((g.rows + 127) / 128) * ((tile_groups + 3) / 4) < n_cu) {
+            // long K, too few 128 x 256 tiles for the chip (the linear layer after the torso): 64 x 64 tiles
+            constexpr int LDS = GemmLdsCfg<1, 1, 8, false>::LDS_BYTES;
+            hipLaunchKernelGGL((gemm_bf16_lds_kernel<1, 1, 8, EPI, false>), dim3((g.rows + 63) / 64, tile_groups), dim3(GL_THREADS), LDS, st, g);
+            return true;
+        }
+    }
+    const int by = (tile_groups + 3) / 4;
+    constexpr int LDS42 = GemmLdsCfg<4, 2, 1, true>::LDS_BYTES, LDS41 = GemmLdsCfg<4, 1, 2, true>::LDS_BYTES;
+    if ((long)((g.rows + 127) / 128) * by >= n_cu)
+        hipLaunchKernelGGL((gemm_bf16_lds_kernel<4, 2, 1, EPI, true>), dim3((g.rows + 127) / 128, by), dim3(GL_THREADS), LDS42, st, g);
+    else
+        hipLaunchKernelGGL((gemm_bf16_lds_kernel<4, 1, 2, EPI, true>), dim3((g.rows + 63) / 64, by), dim3(GL_THREADS), LDS41, st, g);
+    return true;
+}
+
 template <int EPI>
 inline void launch_gemm(hipStream_t st, const GemmArgs& g, int tile_groups, int n_cu)
 {
+    if (launch_gemm_lds<EPI>(st, g, tile_groups, n_cu)) return;
     // RT (row tiles of 16 per wavefront / block): the largest that still gives every compute unit two blocks
     const long want = 2L * n_cu;
     const int kct = g.kc1 + (g.k2 + 31) / 32;

@@ -179,18 +179,8 @@ struct TorsoArgs {
 };
 
 // ---- weight staging: global -> LDS slot (asynchronous, no registers) -> A fragments ----
-// A set is NF chunks of 1 KiB; chunk c is moved by wavefront c % RN_WAVES with one global_load_lds_dwordx4:
-// lane l's 16 bytes land at (wave-uniform LDS base in M0) + 16 * l.  The load is written as inline assembly
-// because the compiler would otherwise wait for it before the next LDS access of any kind; here it stays in
-// flight for the whole phase and stage_wait() (before the phase's closing barrier) collects it.
-__device__ __forceinline__ void g2lds16(const void* gptr, uint32_t lds_base)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
-}
-__device__ __forceinline__ void stage_wait()
-{
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
+// A set is NF chunks of 1 KiB; chunk c is moved by wavefront c % RN_WAVES with one asynchronous load (g2lds16):
+// it stays in flight for the whole phase and stage_wait() (before the phase's closing barrier) collects it.
 template <int NF>
 __device__ __forceinline__ void stage_set(const bf16x8* __restrict__ src, char* slot, int lane, int wave)
 {

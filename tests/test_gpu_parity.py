@@ -199,6 +199,21 @@ def test_full_size_c5_sweep(orc, B, sample):
     run_full(orc, wl.CONFIGS["C5"], B, sample)
 
 
+@pytest.mark.parametrize("label,base,over,B,sample", [
+    ("R2D2 net at batch 4096", "C2", {}, 4096, 96),
+    ("R2D2 net at ragged batch 2050", "C2", {}, 2050, 64),
+    ("Football torso + LSTM-128 at batch 2100", "C4", dict(lstm_units=128), 2100, 64),
+    ("DMLab net, 96 linear units, batch 2048", "C3", dict(fc_units=96), 2048, 48),
+])
+def test_large_batch_dense_layers(orc, label, base, over, B, sample):
+    """From 2048 rows on the linear layer, the recurrent core and the dueling hidden layers run LDS-staged GEMM
+    kernels; these cases cover the tilings the C5 sweep does not reach (512 linear units, 128 x 256 tiles for
+    the 512-unit core, hidden layers fed by fp32 rows only, a ragged last tile, a 128-unit core) and a linear
+    width whose odd chunk count keeps the direct kernels."""
+    cfg = dict(wl.CONFIGS[base], label=label, index=41, **over)
+    run_full(orc, cfg, B, sample)
+
+
 @pytest.mark.parametrize("B", [1, 257, 300, 512, 513, 770])
 def test_bf16_persistent_grid_edges(orc, B):
     """B = 1; one more image than there are compute units (one workgroup takes two, as a group); a ragged count;
