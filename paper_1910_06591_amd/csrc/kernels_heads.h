@@ -33,49 +33,14 @@ struct HeadsArgs {
     int dueling;                     // 1: logits = V + Adv - mean(Adv)
 };
 
+// Everything after the dot products: `acc` = this lane's action output before the bias (already summed over
+// the lane groups), `val` = the value output.  Bias, dueling combination, softmax, (Gumbel-)argmax, exploration.
 template <int P>
-__global__ __launch_bounds__(256) void heads_select_kernel(HeadsArgs p)
+__device__ __forceinline__ void heads_finish(const HeadsArgs& p, int row, int lane, float acc, float val)
 {
-    constexpr int G = 64 / P;
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= p.B) return;                      // whole wavefront leaves together
     const int a = lane & (P - 1);
-    const int g = lane / P;
     const bool live = a < p.A;
-
-    // action outputs
-    float acc = 0.0f;
-    {
-        const float* v = p.vec_a + (size_t)row * p.ld_a;
-        if (live) {
-            // several independent partial sums keep many loads in flight (the loop is latency-bound otherwise);
-            // the summation order is fixed, so results stay reproducible
-            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-            int i = g;
-            for (; i + 3 * G < p.n; i += 4 * G) {
-                s0 = fmaf(v[i], p.w_a[(size_t)i * p.A + a], s0);
-                s1 = fmaf(v[i + G], p.w_a[(size_t)(i + G) * p.A + a], s1);
-                s2 = fmaf(v[i + 2 * G], p.w_a[(size_t)(i + 2 * G) * p.A + a], s2);
-                s3 = fmaf(v[i + 3 * G], p.w_a[(size_t)(i + 3 * G) * p.A + a], s3);
-            }
-            for (; i < p.n; i += G) s0 = fmaf(v[i], p.w_a[(size_t)i * p.A + a], s0);
-            acc = (s0 + s1) + (s2 + s3);
-        }
-    }
-#pragma unroll
-    for (int off = P; off < 64; off <<= 1) acc += __shfl_xor(acc, off, 64);
     float out = live ? acc + p.b_a[a] : 0.0f;
-
-    // value output: all 64 lanes share the dot product
-    float vacc = 0.0f;
-    {
-        const float* v = p.vec_v + (size_t)row * p.ld_v;
-        for (int i = lane; i < p.n; i += 64) vacc = fmaf(v[i], p.w_v[i], vacc);
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) vacc += __shfl_xor(vacc, off, 64);
-    const float val = vacc + p.b_v[0];
 
     if (p.dueling) {
         float s = out;                            // dead lanes hold 0
@@ -118,6 +83,95 @@ __global__ __launch_bounds__(256) void heads_select_kernel(HeadsArgs p)
             best = r < 0 ? 0 : (r > p.A - 1 ? p.A - 1 : r);
         }
         p.action[row] = best;
+    }
+}
+
+template <int P>
+__global__ __launch_bounds__(256) void heads_select_kernel(HeadsArgs p)
+{
+    constexpr int G = 64 / P;
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= p.B) return;                      // whole wavefront leaves together
+    const int a = lane & (P - 1);
+    const int g = lane / P;
+    const bool live = a < p.A;
+
+    // action outputs
+    float acc = 0.0f;
+    {
+        const float* v = p.vec_a + (size_t)row * p.ld_a;
+        if (live) {
+            // several independent partial sums keep many loads in flight (the loop is latency-bound otherwise);
+            // the summation order is fixed, so results stay reproducible
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            int i = g;
+            for (; i + 3 * G < p.n; i += 4 * G) {
+                s0 = fmaf(v[i], p.w_a[(size_t)i * p.A + a], s0);
+                s1 = fmaf(v[i + G], p.w_a[(size_t)(i + G) * p.A + a], s1);
+                s2 = fmaf(v[i + 2 * G], p.w_a[(size_t)(i + 2 * G) * p.A + a], s2);
+                s3 = fmaf(v[i + 3 * G], p.w_a[(size_t)(i + 3 * G) * p.A + a], s3);
+            }
+            for (; i < p.n; i += G) s0 = fmaf(v[i], p.w_a[(size_t)i * p.A + a], s0);
+            acc = (s0 + s1) + (s2 + s3);
+        }
+    }
+#pragma unroll
+    for (int off = P; off < 64; off <<= 1) acc += __shfl_xor(acc, off, 64);
+
+    // value output: all 64 lanes share the dot product
+    float vacc = 0.0f;
+    {
+        const float* v = p.vec_v + (size_t)row * p.ld_v;
+        for (int i = lane; i < p.n; i += 64) vacc = fmaf(v[i], p.w_v[i], vacc);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) vacc += __shfl_xor(vacc, off, 64);
+    heads_finish<P>(p, row, lane, acc, vacc + p.b_v[0]);
+}
+
+// The same heads for n = (64 / P) * NPL inputs with NPL <= 64: every lane keeps its NPL action weights (and its
+// n / 64 value weights) in registers and walks several rows, reading each row's inputs 16 bytes at a time: lane
+// (g, a) takes the contiguous inputs g * NPL .. (g + 1) * NPL - 1.  A quarter of the load instructions of the
+// kernel above per row, whose time is the load instructions it issues.  Needs 16-byte aligned rows.
+typedef float heads_f4 __attribute__((ext_vector_type(4)));
+template <int P, int NPL>
+__global__ __launch_bounds__(256) void heads_rows_kernel(HeadsArgs p)
+{
+    constexpr int G = 64 / P, NV = G * NPL / 64;
+    static_assert(NPL % 4 == 0 && (G * NPL) % 64 == 0, "inputs per lane");
+    const int lane = threadIdx.x & 63;
+    const int a = lane & (P - 1);
+    const int g = lane / P;
+    const bool live = a < p.A;
+    float w[NPL], wv[NV];
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) w[k] = live ? p.w_a[(size_t)(g * NPL + k) * p.A + a] : 0.0f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) wv[k] = p.w_v[lane + 64 * k];
+    const float bv = p.b_v[0];
+    const int nw = gridDim.x * 4;
+    for (int row = blockIdx.x * 4 + (threadIdx.x >> 6); row < p.B; row += nw) {     // uniform per wavefront
+        const float* v = p.vec_a + (size_t)row * p.ld_a + g * NPL;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+        for (int k = 0; k < NPL / 4; ++k) {
+            const heads_f4 x = *(const heads_f4*)(v + 4 * k);
+            s0 = fmaf(x[0], w[4 * k], s0);
+            s1 = fmaf(x[1], w[4 * k + 1], s1);
+            s2 = fmaf(x[2], w[4 * k + 2], s2);
+            s3 = fmaf(x[3], w[4 * k + 3], s3);
+        }
+        float acc = (s0 + s1) + (s2 + s3);
+#pragma unroll
+        for (int off = P; off < 64; off <<= 1) acc += __shfl_xor(acc, off, 64);
+        const float* vv = p.vec_v + (size_t)row * p.ld_v;
+        float vacc = 0.0f;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) vacc = fmaf(vv[lane + 64 * k], wv[k], vacc);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) vacc += __shfl_xor(vacc, off, 64);
+        heads_finish<P>(p, row, lane, acc, vacc + bv);
     }
 }
 

@@ -2,6 +2,8 @@
 // the per-step kernel sequence.  See include/seedinf.h for the contract.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -221,14 +223,30 @@ static void launch_heads_p(hipStream_t s, const HeadsArgs& ha)
     hipLaunchKernelGGL(heads_select_kernel<P>, dim3((ha.B + 3) / 4), dim3(256), 0, s, ha);
 }
 
+// The register-resident variant for n = (64 / P) * NPL inputs, NPL = 32 or 64, with 16-byte aligned input rows;
+// the choice depends on the network and the buffers' alignment only, never on B, so a row's result does not
+// depend on the batch it travels in.  At most 256 workgroups: at large B every wavefront walks several rows.
+template <int P>
+static bool launch_heads_rows(hipStream_t s, const HeadsArgs& ha)
+{
+    constexpr int G = 64 / P;
+    const bool aligned = ((uintptr_t)ha.vec_a % 16 == 0) && ha.ld_a % 4 == 0;
+    if (!aligned || ha.n % 64 != 0) return false;
+    const int grid = std::min((ha.B + 3) / 4, 256);
+    if (ha.n == G * 64) hipLaunchKernelGGL((heads_rows_kernel<P, 64>), dim3(grid), dim3(256), 0, s, ha);
+    else if (ha.n == G * 32) hipLaunchKernelGGL((heads_rows_kernel<P, 32>), dim3(grid), dim3(256), 0, s, ha);
+    else return false;
+    return true;
+}
+
 static void launch_heads(hipStream_t s, const HeadsArgs& ha)
 {
     int A = ha.A;
     if (A <= 2) launch_heads_p<2>(s, ha);
     else if (A <= 4) launch_heads_p<4>(s, ha);
-    else if (A <= 8) launch_heads_p<8>(s, ha);
-    else if (A <= 16) launch_heads_p<16>(s, ha);
-    else if (A <= 32) launch_heads_p<32>(s, ha);
+    else if (A <= 8) { if (!launch_heads_rows<8>(s, ha)) launch_heads_p<8>(s, ha); }
+    else if (A <= 16) { if (!launch_heads_rows<16>(s, ha)) launch_heads_p<16>(s, ha); }
+    else if (A <= 32) { if (!launch_heads_rows<32>(s, ha)) launch_heads_p<32>(s, ha); }
     else launch_heads_p<64>(s, ha);
 }
 
