@@ -13,6 +13,7 @@
 #include "gemm_bf16.h"
 #include "gemm_bf16_lds.h"
 #include "conv_stack_bf16.h"
+#include "conv_stack_fused.h"
 #include "resnet_fused.h"
 #include "resnet_layerwise.h"
 
@@ -28,6 +29,15 @@ using FbS1 = SecCfg<72, 96, 16, 16, IN_U8_PLANAR, 4, 8>;
 using FbS4 = SecCfg<9, 12, 32, 32, IN_LDS, 5, 0, 2>;
 
 enum { TORSO_NONE = 0, TORSO_DMLAB = 1, TORSO_FOOTBALL = 2 };
+
+// The conv stack this build has a fused kernel for: the recurrent Atari agent's (Appendix A.3.1).
+inline bool match_r2d2_stack(const seed_arch_t& a)
+{
+    return a.torso == SEED_TORSO_CONV_STACK && a.obs_h == 84 && a.obs_w == 84 && a.obs_c == 4 && a.n_conv == 3 &&
+           a.conv_ch[0] == 32 && a.conv_k[0] == 8 && a.conv_stride[0] == 4 &&
+           a.conv_ch[1] == 64 && a.conv_k[1] == 4 && a.conv_stride[1] == 2 &&
+           a.conv_ch[2] == 64 && a.conv_k[2] == 3 && a.conv_stride[2] == 1;
+}
 
 inline int match_resnet(const seed_arch_t& a)
 {
@@ -115,6 +125,7 @@ struct Bf16Packed {
 
 struct Bf16State {
     int torso_kind = TORSO_NONE;
+    bool stack_fused = false;                  // conv stack with the fused kernel
     int n_cu = 256;
     char* arena = nullptr;
     // two copies of the packed weights: steps read ws[active]; a weight update fills the other and flips
@@ -350,6 +361,7 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     BF_TRY(hipGetDeviceProperties(&prop, dev));
     s->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     s->torso_kind = match_resnet(a);
+    s->stack_fused = match_r2d2_stack(a);
     s->ldf = round_up((int)p.flat, 32);
     s->ldfc = round_up(a.fc_units, 32);
 
@@ -421,6 +433,8 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
+    if (s->stack_fused)
+        BF_TRY(hipFuncSetAttribute((const void*)r2d2_torso_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, r2d2::LDS_BYTES));
     if (s->torso_kind == TORSO_DMLAB) {
         BF_TRY(hipFuncSetAttribute((const void*)resnet3_bf16_kernel<DmS1, DmS2, DmS3>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, Net3<DmS1, DmS2, DmS3>::LDS_BYTES));
@@ -579,6 +593,12 @@ inline seed_status_t bf16_torso_fc(Bf16State* s, const Plan& p, const float* d_w
             hipLaunchKernelGGL((resnet3_bf16_kernel<DmS1, DmS2, DmS3>), dim3(grid), dim3(RN_THREADS), LDS_DM, st, t);
         else
             hipLaunchKernelGGL((resnet4_bf16_kernel<FbS1, DmS2, DmS3, FbS4>), dim3(grid), dim3(RN_THREADS), LDS_FB, st, t);
+    } else if (s->stack_fused) {
+        R2d2TorsoArgs t{};
+        t.obs = obs; t.feat = s->feat; t.ldf = s->ldf; t.B = B;
+        t.w1 = W.wp_conv + s->stack[0].wp_off / 8; t.w2 = W.wp_conv + s->stack[1].wp_off / 8; t.w3 = W.wp_conv + s->stack[2].wp_off / 8;
+        t.b1 = d_w + p.convs[0].b_off; t.b2 = d_w + p.convs[1].b_off; t.b3 = d_w + p.convs[2].b_off;
+        hipLaunchKernelGGL(r2d2_torso_bf16_kernel, dim3(B < s->n_cu ? B : s->n_cu), dim3(r2d2::THREADS), r2d2::LDS_BYTES, st, t);
     } else {
         const void* x = obs;
         for (size_t l = 0; l < p.convs.size(); ++l) {

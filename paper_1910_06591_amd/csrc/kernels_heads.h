@@ -102,18 +102,17 @@ __global__ __launch_bounds__(256) void heads_select_kernel(HeadsArgs p)
     {
         const float* v = p.vec_a + (size_t)row * p.ld_a;
         if (live) {
-            // several independent partial sums keep many loads in flight (the loop is latency-bound otherwise);
-            // the summation order is fixed, so results stay reproducible
-            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            // eight independent partial sums keep sixteen loads in flight per lane (the loop is bound by load
+            // latency: its weights do not fit the first-level cache); the summation order is fixed, so results
+            // stay reproducible
+            float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             int i = g;
-            for (; i + 3 * G < p.n; i += 4 * G) {
-                s0 = fmaf(v[i], p.w_a[(size_t)i * p.A + a], s0);
-                s1 = fmaf(v[i + G], p.w_a[(size_t)(i + G) * p.A + a], s1);
-                s2 = fmaf(v[i + 2 * G], p.w_a[(size_t)(i + 2 * G) * p.A + a], s2);
-                s3 = fmaf(v[i + 3 * G], p.w_a[(size_t)(i + 3 * G) * p.A + a], s3);
+            for (; i + 7 * G < p.n; i += 8 * G) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) s[u] = fmaf(v[i + u * G], p.w_a[(size_t)(i + u * G) * p.A + a], s[u]);
             }
-            for (; i < p.n; i += G) s0 = fmaf(v[i], p.w_a[(size_t)i * p.A + a], s0);
-            acc = (s0 + s1) + (s2 + s3);
+            for (; i < p.n; i += G) s[0] = fmaf(v[i], p.w_a[(size_t)i * p.A + a], s[0]);
+            acc = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
         }
     }
 #pragma unroll
@@ -123,7 +122,14 @@ __global__ __launch_bounds__(256) void heads_select_kernel(HeadsArgs p)
     float vacc = 0.0f;
     {
         const float* v = p.vec_v + (size_t)row * p.ld_v;
-        for (int i = lane; i < p.n; i += 64) vacc = fmaf(v[i], p.w_v[i], vacc);
+        float t[4] = {0.f, 0.f, 0.f, 0.f};
+        int i = lane;
+        for (; i + 3 * 64 < p.n; i += 4 * 64) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t[u] = fmaf(v[i + u * 64], p.w_v[i + u * 64], t[u]);
+        }
+        for (; i < p.n; i += 64) t[0] = fmaf(v[i], p.w_v[i], t[0]);
+        vacc = (t[0] + t[1]) + (t[2] + t[3]);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) vacc += __shfl_xor(vacc, off, 64);
