@@ -136,48 +136,68 @@ __global__ __launch_bounds__(256) void heads_select_kernel(HeadsArgs p)
     heads_finish<P>(p, row, lane, acc, vacc + p.b_v[0]);
 }
 
-// The same heads for n = (64 / P) * NPL inputs with NPL <= 64: every lane keeps its NPL action weights (and its
-// n / 64 value weights) in registers and walks several rows, reading each row's inputs 16 bytes at a time: lane
-// (g, a) takes the contiguous inputs g * NPL .. (g + 1) * NPL - 1.  A quarter of the load instructions of the
-// kernel above per row, whose time is the load instructions it issues.  Needs 16-byte aligned rows.
+// The same heads for n = KS * (64 / P) * NPL inputs with NPL <= 64: every lane keeps its NPL action weights (and
+// its share of the value weights) in registers and the workgroup walks several rows, reading each row's inputs
+// 16 bytes at a time.  KS wavefronts share a row, each taking a contiguous KS-th of the inputs (lane (g, a) of
+// slice ks: inputs (ks * G + g) * NPL .. + NPL - 1); their partial sums meet in LDS in slice order and the
+// slice-0 wavefront finishes the row.  A fraction of the load instructions of the kernel above per row, whose
+// time is the load instructions it issues.  Needs 16-byte aligned rows.
 typedef float heads_f4 __attribute__((ext_vector_type(4)));
-template <int P, int NPL>
+template <int P, int NPL, int KS>
 __global__ __launch_bounds__(256) void heads_rows_kernel(HeadsArgs p)
 {
-    constexpr int G = 64 / P, NV = G * NPL / 64;
-    static_assert(NPL % 4 == 0 && (G * NPL) % 64 == 0, "inputs per lane");
-    const int lane = threadIdx.x & 63;
+    constexpr int G = 64 / P, NS = G * NPL, NV = NS / 64, RPB = 4 / KS;      // NS: inputs per slice; RPB: rows per pass
+    static_assert(NPL % 4 == 0 && NS % 64 == 0 && (KS == 1 || KS == 2 || KS == 4), "inputs per lane");
+    __shared__ float part[2][4][64];                     // [acc | value][wavefront][lane]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ks = wave % KS, rs = wave / KS;
     const int a = lane & (P - 1);
     const int g = lane / P;
     const bool live = a < p.A;
+    const int i0 = ks * NS + g * NPL;                    // this lane's first action input
     float w[NPL], wv[NV];
 #pragma unroll
-    for (int k = 0; k < NPL; ++k) w[k] = live ? p.w_a[(size_t)(g * NPL + k) * p.A + a] : 0.0f;
+    for (int k = 0; k < NPL; ++k) w[k] = live ? p.w_a[(size_t)(i0 + k) * p.A + a] : 0.0f;
 #pragma unroll
-    for (int k = 0; k < NV; ++k) wv[k] = p.w_v[lane + 64 * k];
+    for (int k = 0; k < NV; ++k) wv[k] = p.w_v[ks * NS + lane + 64 * k];
     const float bv = p.b_v[0];
-    const int nw = gridDim.x * 4;
-    for (int row = blockIdx.x * 4 + (threadIdx.x >> 6); row < p.B; row += nw) {     // uniform per wavefront
-        const float* v = p.vec_a + (size_t)row * p.ld_a + g * NPL;
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    for (int base = blockIdx.x * RPB; base < p.B; base += gridDim.x * RPB) {        // uniform per workgroup
+        const int row = base + rs;
+        float acc = 0.0f, vacc = 0.0f;
+        if (row < p.B) {                                 // uniform per wavefront
+            const float* v = p.vec_a + (size_t)row * p.ld_a + i0;
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
-        for (int k = 0; k < NPL / 4; ++k) {
-            const heads_f4 x = *(const heads_f4*)(v + 4 * k);
-            s0 = fmaf(x[0], w[4 * k], s0);
-            s1 = fmaf(x[1], w[4 * k + 1], s1);
-            s2 = fmaf(x[2], w[4 * k + 2], s2);
-            s3 = fmaf(x[3], w[4 * k + 3], s3);
+            for (int k = 0; k < NPL / 4; ++k) {
+                const heads_f4 x = *(const heads_f4*)(v + 4 * k);
+                s0 = fmaf(x[0], w[4 * k], s0);
+                s1 = fmaf(x[1], w[4 * k + 1], s1);
+                s2 = fmaf(x[2], w[4 * k + 2], s2);
+                s3 = fmaf(x[3], w[4 * k + 3], s3);
+            }
+            acc = (s0 + s1) + (s2 + s3);
+#pragma unroll
+            for (int off = P; off < 64; off <<= 1) acc += __shfl_xor(acc, off, 64);
+            const float* vv = p.vec_v + (size_t)row * p.ld_v + ks * NS;
+#pragma unroll
+            for (int k = 0; k < NV; ++k) vacc = fmaf(vv[lane + 64 * k], wv[k], vacc);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) vacc += __shfl_xor(vacc, off, 64);
         }
-        float acc = (s0 + s1) + (s2 + s3);
+        if constexpr (KS > 1) {
+            part[0][wave][lane] = acc;
+            part[1][wave][lane] = vacc;
+            __syncthreads();
+            if (ks == 0) {
 #pragma unroll
-        for (int off = P; off < 64; off <<= 1) acc += __shfl_xor(acc, off, 64);
-        const float* vv = p.vec_v + (size_t)row * p.ld_v;
-        float vacc = 0.0f;
-#pragma unroll
-        for (int k = 0; k < NV; ++k) vacc = fmaf(vv[lane + 64 * k], wv[k], vacc);
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) vacc += __shfl_xor(vacc, off, 64);
-        heads_finish<P>(p, row, lane, acc, vacc + bv);
+                for (int q = 1; q < KS; ++q) {
+                    acc += part[0][wave + q][lane];
+                    vacc += part[1][wave + q][lane];
+                }
+            }
+            __syncthreads();                             // the partial sums are read before the next pass overwrites them
+        }
+        if (ks == 0 && row < p.B) heads_finish<P>(p, row, lane, acc, vacc + bv);
     }
 }
 

@@ -223,18 +223,27 @@ static void launch_heads_p(hipStream_t s, const HeadsArgs& ha)
     hipLaunchKernelGGL(heads_select_kernel<P>, dim3((ha.B + 3) / 4), dim3(256), 0, s, ha);
 }
 
-// The register-resident variant for n = (64 / P) * NPL inputs, NPL = 32 or 64, with 16-byte aligned input rows;
-// the choice depends on the network and the buffers' alignment only, never on B, so a row's result does not
-// depend on the batch it travels in.  At most 256 workgroups: at large B every wavefront walks several rows.
+// The register-resident variant for n = KS * (64 / P) * NPL inputs (NPL = 32 or 64; KS = 1, 2 or 4 wavefronts per
+// row) with 16-byte aligned input rows; the choice depends on the network and the buffers' alignment only,
+// never on B, so a row's result does not depend on the batch it travels in.  At most 1024 workgroups (four per
+// compute unit, which hides each row's load latency): at large B every workgroup walks several rows with its weights in registers.
 template <int P>
 static bool launch_heads_rows(hipStream_t s, const HeadsArgs& ha)
 {
     constexpr int G = 64 / P;
     const bool aligned = ((uintptr_t)ha.vec_a % 16 == 0) && ha.ld_a % 4 == 0;
     if (!aligned || ha.n % 64 != 0) return false;
-    const int grid = std::min((ha.B + 3) / 4, 256);
-    if (ha.n == G * 64) hipLaunchKernelGGL((heads_rows_kernel<P, 64>), dim3(grid), dim3(256), 0, s, ha);
-    else if (ha.n == G * 32) hipLaunchKernelGGL((heads_rows_kernel<P, 32>), dim3(grid), dim3(256), 0, s, ha);
+    auto go = [&](auto npl, auto ksc) {
+        constexpr int NPL = decltype(npl)::value, KS = decltype(ksc)::value, RPB = 4 / KS;
+        const int grid = std::min((ha.B + RPB - 1) / RPB, 1024);
+        hipLaunchKernelGGL((heads_rows_kernel<P, NPL, KS>), dim3(grid), dim3(256), 0, s, ha);
+    };
+    using N32 = std::integral_constant<int, 32>; using N64 = std::integral_constant<int, 64>;
+    using K1 = std::integral_constant<int, 1>; using K2 = std::integral_constant<int, 2>; using K4 = std::integral_constant<int, 4>;
+    if (ha.n == G * 32) go(N32{}, K1{});
+    else if (ha.n == G * 64) go(N64{}, K1{});
+    else if (ha.n == 2 * G * 64) go(N64{}, K2{});
+    else if (ha.n == 4 * G * 64) go(N64{}, K4{});
     else return false;
     return true;
 }
