@@ -1170,11 +1170,20 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
             load_a_frags(w0, lds + SLOT_C0, lane);
             conv0_pool<S>(cin, pool, edge, lds + M::TRASH, w0, lds + SLOT_C0, 0, S::PH, -1, lane, wave);
         } else {
-#pragma unroll 1
-            for (int strip = 0; strip < S::NSTRIPS; ++strip) {
-                // strip 0 is already in buf0: the previous image's last phase (or the kernel prologue) put it there
-                if (strip > 0) prefetch_commit<S>(pre, buf0, strip, tid);
-                if (strip + 1 < S::NSTRIPS) prefetch_issue<S>(pre, obs_img, strip + 1, tid);
+            // Strips: strip 0 is already in buf0 (the previous image's last phase or the kernel prologue put it
+            // there).  With several strips the loads run TWO strips ahead, alternating between the caller's
+            // register set (even strips) and a second one (odd strips): one strip's convolution is several
+            // times shorter than a trip to memory.
+            constexpr bool TWO_AHEAD = S::NSTRIPS > 1 && S::NSTRIPS % 2 == 0;
+            PreT pre_odd;
+            auto one_strip = [&](int strip, PreT& mine) {          // `mine`: the register set strips of this parity use
+                if (strip > 0) prefetch_commit<S>(mine, buf0, strip, tid);
+                if constexpr (TWO_AHEAD) {
+                    if (strip == 0) prefetch_issue<S>(pre_odd, obs_img, 1, tid);
+                    if (strip + 2 < S::NSTRIPS) prefetch_issue<S>(mine, obs_img, strip + 2, tid);
+                } else {
+                    if (strip + 1 < S::NSTRIPS) prefetch_issue<S>(mine, obs_img, strip + 1, tid);
+                }
                 if (strip > 0) lds_barrier();
                 PHASE_MARK(SI * 8 + 0);
                 if (strip == 0) load_a_frags(w0, lds + SLOT_C0, lane);
@@ -1184,6 +1193,16 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                 else if constexpr (S::POOL3) conv0_pool3<S>(buf0, buf1, w0, lds + SLOT_C0, lane, wave);
                 else conv0_pool<S>(buf0, buf1, edge, lds + M::TRASH, w0, lds + SLOT_C0, pr0, pr1, r0 - 1, lane, wave);
                 if (strip + 1 < S::NSTRIPS) lds_barrier();
+            };
+            if constexpr (TWO_AHEAD) {
+#pragma unroll 1
+                for (int strip = 0; strip < S::NSTRIPS; strip += 2) {
+                    one_strip(strip, pre);
+                    one_strip(strip + 1, pre_odd);
+                }
+            } else {
+#pragma unroll 1
+                for (int strip = 0; strip < S::NSTRIPS; ++strip) one_strip(strip, pre);
             }
         }
         stage_wait();
@@ -1530,8 +1549,8 @@ __global__ __launch_bounds__(RN_THREADS) void resnet4_bf16_kernel(TorsoArgs a)
         __bf16* feat_row = a.feat + (size_t)img * a.ldf;
         run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
         run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
-        run_section<S3, S4, M, false, 2, 9, N::NSETS, S2::XFUSED>(lds, a.sec[2], a.sec[3], obs_img, pre, feat_row, tid);
         const int nimg = img + (int)gridDim.x < a.B ? img + (int)gridDim.x : img;
+        run_section<S3, S4, M, false, 2, 9, N::NSETS, S2::XFUSED>(lds, a.sec[2], a.sec[3], obs_img, pre, feat_row, tid);
         prefetch_issue<S1>(pre, a.obs + FRAME * nimg, 0, tid);
         run_section<S4, S4, M, true, 3, 14, N::NSETS, S3::XFUSED>(lds, a.sec[3], a.sec[3], obs_img, pre, feat_row, tid);
     }
