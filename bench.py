@@ -320,14 +320,14 @@ def main():
         line["other_workloads"] = others
         line["extensions"] = time_extensions(cfg, B, weights)
         # model-size variants (Section 4.1: filters x2 / x4; Section 4.2: medium and large minimaps; Atari without
-        # frame stacking): no fused kernel, layer-by-layer bf16 path (fp32 where bf16 mode has no kernels)
+        # frame stacking): the layer-by-layer bf16 ResNet path; the Atari agent on single frames has the fused conv stack
         variants = []
         c3, c4, c2 = wl.CONFIGS["C3"], wl.CONFIGS["C4"], wl.CONFIGS["C2"]
         for label, c, b in (("DMLab filters x2", dict(c3, sections=[32, 64, 64]), 1024),
                             ("DMLab filters x4", dict(c3, sections=[64, 128, 128]), 1024),
                             ("Football map 120x90", dict(c4, obs_h=90, obs_w=120), 1024),
                             ("Football map 144x108", dict(c4, obs_h=108, obs_w=144), 1024),
-                            ("Atari without frame stacking (fp32 mode)", dict(c2, obs_c=1, precision="fp32"), 256)):
+                            ("Atari without frame stacking", dict(c2, obs_c=1), 256)):
             c = dict(c, label=label, index=40)
             s = time_config(c, b, 20, 3, profile=False)
             variants.append({"config": label, "batch": b, "dtype": c["precision"], "frames_per_s": b / (s["p50_ms"] * 1e-3),

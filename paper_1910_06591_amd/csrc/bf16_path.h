@@ -30,10 +30,11 @@ using FbS4 = SecCfg<9, 12, 32, 32, IN_LDS, 5, 0, 2>;
 
 enum { TORSO_NONE = 0, TORSO_DMLAB = 1, TORSO_FOOTBALL = 2 };
 
-// The conv stack this build has a fused kernel for: the recurrent Atari agent's (Appendix A.3.1).
+// The conv stack this build has a fused kernel for: the recurrent Atari agent's (Appendix A.3.1), with four
+// stacked frames or one.
 inline bool match_r2d2_stack(const seed_arch_t& a)
 {
-    return a.torso == SEED_TORSO_CONV_STACK && a.obs_h == 84 && a.obs_w == 84 && a.obs_c == 4 && a.n_conv == 3 &&
+    return a.torso == SEED_TORSO_CONV_STACK && a.obs_h == 84 && a.obs_w == 84 && (a.obs_c == 4 || a.obs_c == 1) && a.n_conv == 3 &&
            a.conv_ch[0] == 32 && a.conv_k[0] == 8 && a.conv_stride[0] == 4 &&
            a.conv_ch[1] == 64 && a.conv_k[1] == 4 && a.conv_stride[1] == 2 &&
            a.conv_ch[2] == 64 && a.conv_k[2] == 3 && a.conv_stride[2] == 1;
@@ -61,7 +62,7 @@ inline seed_status_t bf16_supported(const Plan& p, std::string& err)
         if (match_resnet(a) == TORSO_NONE)
             for (int i = 0; i < a.n_sections; ++i)
                 if (a.section_ch[i] % 16) return no("ResNet section channels must be multiples of 16");
-    } else {
+    } else if (!match_r2d2_stack(a)) {
         for (size_t l = 0; l < p.convs.size(); ++l) {
             const ConvLayer& c = p.convs[l];
             if (c.Cout % 16) return no("conv channels must be multiples of 16");
@@ -69,7 +70,7 @@ inline seed_status_t bf16_supported(const Plan& p, std::string& err)
             if ((c.W * c.Cin) % 8 || (c.stride * c.Cin) % 8 || ((size_t)c.H * c.W * c.Cin) % 8) return no("conv rows must be 8-element aligned");
         }
         if (p.flat % 32) return no("the conv stack's flattened output must be a multiple of 32 values");
-    }
+    }   // (the fused conv stack has none of these limits)
     if (a.lstm_units % 16) return no("lstm_units must be a multiple of 16");
     if (a.head == SEED_HEAD_DUELING_Q && a.head_hidden % 16) return no("head_hidden must be a multiple of 16");
     return SEED_OK;
@@ -384,7 +385,7 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     }
     const size_t o_ko = off; off += al(o.ko.size() * 4 + 16);
     size_t o_act[2] = {0, 0};
-    if (a.torso == SEED_TORSO_CONV_STACK && p.convs.size() > 1) {
+    if (a.torso == SEED_TORSO_CONV_STACK && p.convs.size() > 1 && !s->stack_fused) {   // (the fused stack keeps them in LDS)
         size_t m = 0;
         for (size_t l = 0; l + 1 < p.convs.size(); ++l) {
             size_t n = (size_t)p.convs[l].OH * p.convs[l].OW * p.convs[l].Cout;
@@ -433,8 +434,10 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
-    if (s->stack_fused)
-        BF_TRY(hipFuncSetAttribute((const void*)r2d2_torso_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, r2d2::LDS_BYTES));
+    if (s->stack_fused) {
+        BF_TRY(hipFuncSetAttribute((const void*)r2d2_torso_bf16_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, r2d2::LDS_BYTES));
+        BF_TRY(hipFuncSetAttribute((const void*)r2d2_torso_bf16_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, r2d2::LDS_BYTES));
+    }
     if (s->torso_kind == TORSO_DMLAB) {
         BF_TRY(hipFuncSetAttribute((const void*)resnet3_bf16_kernel<DmS1, DmS2, DmS3>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, Net3<DmS1, DmS2, DmS3>::LDS_BYTES));
@@ -598,7 +601,9 @@ inline seed_status_t bf16_torso_fc(Bf16State* s, const Plan& p, const float* d_w
         t.obs = obs; t.feat = s->feat; t.ldf = s->ldf; t.B = B;
         t.w1 = W.wp_conv + s->stack[0].wp_off / 8; t.w2 = W.wp_conv + s->stack[1].wp_off / 8; t.w3 = W.wp_conv + s->stack[2].wp_off / 8;
         t.b1 = d_w + p.convs[0].b_off; t.b2 = d_w + p.convs[1].b_off; t.b3 = d_w + p.convs[2].b_off;
-        hipLaunchKernelGGL(r2d2_torso_bf16_kernel, dim3(B < s->n_cu ? B : s->n_cu), dim3(r2d2::THREADS), r2d2::LDS_BYTES, st, t);
+        const dim3 grid(B < s->n_cu ? B : s->n_cu);
+        if (a.obs_c == 4) hipLaunchKernelGGL(r2d2_torso_bf16_kernel<4>, grid, dim3(r2d2::THREADS), r2d2::LDS_BYTES, st, t);
+        else hipLaunchKernelGGL(r2d2_torso_bf16_kernel<1>, grid, dim3(r2d2::THREADS), r2d2::LDS_BYTES, st, t);
     } else {
         const void* x = obs;
         for (size_t l = 0; l < p.convs.size(); ++l) {

@@ -1,11 +1,12 @@
-// Fused bf16 torso of the recurrent Atari agent (Appendix A.3.1): 84x84x4 uint8 frame -> conv 8x8/4 (32) ->
-// conv 4x4/2 (64) -> conv 3x3/1 (64), "valid" padding, ReLU after each, flattened (h, w, c).
+// Fused bf16 torso of the recurrent Atari agent (Appendix A.3.1): 84x84xCIN uint8 frame -> conv 8x8/4 (32) ->
+// conv 4x4/2 (64) -> conv 3x3/1 (64), "valid" padding, ReLU after each, flattened (h, w, c).  CIN = 4 (four
+// stacked frames) or 1 (no frame stacking, the configuration of Section 4.3's fastest Atari run).
 //
 // One persistent workgroup of 8 wavefronts per compute unit takes one image at a time through all three
 // layers with every activation in LDS, and keeps ALL convolution weights (152 KiB of bf16) in registers for its
 // whole life, spread over the wavefronts:
-//   conv1 (K = 256, 2 feature tiles): every wavefront holds all 16 weight fragments and takes every eighth
-//          pixel tile of the 20 x 20 map;
+//   conv1 (K = 64 CIN, 2 feature tiles): every wavefront holds all 16 (CIN = 4) or 4 (CIN = 1) weight fragments
+//          and takes every eighth pixel tile of the 20 x 20 map;
 //   conv2 (K = 512, 4 feature tiles) and conv3 (K = 576, 4 feature tiles): wavefront w holds feature tile
 //          w % 4 and half w / 4 of K (8 and 9 fragments), multiplies every pixel tile of the 9 x 9 / 7 x 7 map
 //          by them, and the two halves swap partial sums through LDS (each finishes half of the tiles).
@@ -16,7 +17,8 @@
 // cells, which is what keeps the reads free of bank conflicts; the strided and shifted windows of the
 // convolutions are absorbed by storing shifted copies, written by the producing layer's epilogue:
 //   frame  the raw uint8 frame, twice (the next image lands while this one is computed).  A conv1 fragment
-//          (kernel row kh, pixels 4 ow + 2 g, + 1) is 8 consecutive bytes, converted to bf16 in registers.
+//          (CIN = 4: kernel row kh, pixels 4 ow + 2 g, + 1; CIN = 1: kernel row 4 c + g, pixels 4 ow .. + 7) is 8
+//          consecutive bytes, converted to bf16 in registers.
 //   act1   bf16 [copy 2][plane 4 (8 channels)][x parity 2][y parity 2][yh 10][9 cells]: conv2 (stride 2) reads
 //          x = 2 ow + kw, y = 2 oh + kh -> parities kw & 1, kh & 1; copy kw >> 1 holds column xh = ow' + copy at
 //          ow', so tap (kh, kw) of output pixel p = 9 oh + ow is cell (kh >> 1) * 9 + p of its sub-plane
@@ -25,14 +27,14 @@
 //   Sub-planes are padded to multiples of 256 bytes (the two lane groups of a half-wavefront read different
 //   planes, and this LDS serves them at full rate only when they are a multiple of 256 bytes apart).
 // Weight fragments come from the conv stack's packed A operands ([ftile][chunk][lane], k = (kh, kw, ci)): a
-// chunk of 32 k is one kernel row of conv1, one tap of conv2 and half a tap of conv3.
+// chunk of 32 k is one kernel row of conv1 (four rows with CIN = 1), one tap of conv2 and half a tap of conv3.
 #pragma once
 #include "bf16_common.h"
 
 namespace seedinf {
 
 struct R2d2TorsoArgs {
-    const uint8_t* obs;          // [B, 84, 84, 4]
+    const uint8_t* obs;          // [B, 84, 84, CIN]
     const bf16x8* w1; const bf16x8* w2; const bf16x8* w3;     // packed A fragments of the three layers
     const float* b1; const float* b2; const float* b3;        // fp32 biases [32], [64], [64]
     __bf16* feat; int ldf;       // [B, ldf] rectified features
@@ -57,11 +59,11 @@ __device__ unsigned long long r2d2_phase_cycles[8];
 #endif
 
 namespace r2d2 {
-constexpr int H = 84, W = 84, FRAME_U8 = H * W * 4;             // 28224 bytes
+constexpr int H = 84, W = 84;
 constexpr int O1 = 20, O2 = 9, O3 = 7;
 constexpr int NP1 = O1 * O1, NP2 = O2 * O2, NP3 = O3 * O3;      // 400, 81, 49 output pixels
 constexpr int NT1 = NP1 / 16, NT2 = (NP2 + 15) / 16, NT3 = (NP3 + 15) / 16;   // 25, 6, 4 pixel tiles
-constexpr int RAW_BYTES = 28 * 1024;                          // one raw frame, 28 loads of 1 KiB
+constexpr int RAW_BYTES = 28 * 1024;                          // one raw frame (CIN = 4: 28224 bytes, 28 loads of 1 KiB)
 constexpr int RAW_OFF = 0;                                    // two of them
 constexpr int A1_SUB = 96 * 16;                               // act1 sub-plane: 90 cells, padded
 constexpr int ACT1_OFF = RAW_OFF + 2 * RAW_BYTES, ACT1_BYTES = 2 * 4 * 4 * A1_SUB;       // 49152
@@ -73,9 +75,13 @@ static_assert(NT1 * 16 == NP1 && LDS_BYTES <= 160 * 1024, "R2D2 torso LDS plan")
 constexpr int THREADS = 512;
 }  // namespace r2d2
 
+template <int CIN>
 __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2TorsoArgs p)
 {
     using namespace r2d2;
+    static_assert(CIN == 4 || CIN == 1, "stacked or single frames");
+    constexpr int FRAME_U8 = H * W * CIN, NLOAD = (FRAME_U8 + 1023) / 1024;
+    constexpr int NW1 = CIN == 4 ? 16 : 4;                     // conv1 weight fragments: [ftile 2][chunk 8 or 2]
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -84,9 +90,9 @@ __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2Tors
     const int f23 = wave & 3, half = wave >> 2;               // conv2 / conv3: feature tile and K half
 
     // ---- resident weights and biases ----
-    bf16x8 w1[16], w2[8], w3[9];
+    bf16x8 w1[NW1], w2[8], w3[9];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) w1[i] = p.w1[i * 64 + lane];                              // [ftile 2][chunk 8]
+    for (int i = 0; i < NW1; ++i) w1[i] = p.w1[i * 64 + lane];
 #pragma unroll
     for (int i = 0; i < 8; ++i) w2[i] = p.w2[((size_t)f23 * 16 + half * 8 + i) * 64 + lane];
 #pragma unroll
@@ -101,10 +107,12 @@ __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2Tors
         if (wave == 0) return;
         const uint8_t* src = p.obs + (size_t)b * FRAME_U8;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < (NLOAD + 6) / 7; ++j) {
             const int c = wave - 1 + 7 * j;                    // uniform
-            const int off = min(c * 1024 + lane * 16, FRAME_U8 - 16);
-            g2lds16(src + off, lds0 + RAW_OFF + buf * RAW_BYTES + c * 1024);
+            if (c < NLOAD) {
+                const int off = min(c * 1024 + lane * 16, FRAME_U8 - 16);
+                g2lds16(src + off, lds0 + RAW_OFF + buf * RAW_BYTES + c * 1024);
+            }
         }
     };
 
@@ -130,14 +138,26 @@ __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2Tors
             if (t >= NT1) break;
             const int pix = t * 16 + n;
             const int oh = pix / O1, ow = pix - oh * O1;
-            const char* fb = lds + RAW_OFF + buf * RAW_BYTES + ((4 * oh) * W + 4 * ow + 2 * g) * 4;
             floatx4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0;
+            if constexpr (CIN == 4) {
+                const char* fb = lds + RAW_OFF + buf * RAW_BYTES + ((4 * oh) * W + 4 * ow + 2 * g) * 4;
 #pragma unroll
-            for (int kh = 0; kh < 8; ++kh) {
-                const uint2 v = *(const uint2*)(fb + kh * (W * 4));
-                const bf16x8 bf = u8x8_to_bf16x8(v.x, v.y);
-                a0 = mfma16(w1[kh], bf, a0);
-                a1 = mfma16(w1[8 + kh], bf, a1);
+                for (int kh = 0; kh < 8; ++kh) {
+                    const uint2 v = *(const uint2*)(fb + kh * (W * 4));
+                    const bf16x8 bf = u8x8_to_bf16x8(v.x, v.y);
+                    a0 = mfma16(w1[kh], bf, a0);
+                    a1 = mfma16(w1[8 + kh], bf, a1);
+                }
+            } else {
+                // chunk c: kernel rows 4 c .. 4 c + 3, one per lane group; 8 bytes at a 4-byte aligned address
+                const char* fb = lds + RAW_OFF + buf * RAW_BYTES + (4 * oh + g) * W + 4 * ow;
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const uint32_t lo = *(const uint32_t*)(fb + c * (4 * W)), hi = *(const uint32_t*)(fb + c * (4 * W) + 4);
+                    const bf16x8 bf = u8x8_to_bf16x8(lo, hi);
+                    a0 = mfma16(w1[c], bf, a0);
+                    a1 = mfma16(w1[2 + c], bf, a1);
+                }
             }
             // channels f * 16 + 4 g .. + 3 of pixel (oh, ow): plane 2 f + (g >> 1), 8-byte half g & 1, sub-plane
             // (x parity, y parity), row oh >> 1; copy 0 takes column xh = ow >> 1 if it is < 9, copy 1 stores xh >= 1 at xh - 1

@@ -265,6 +265,14 @@ def test_bf16_model_size_variants_run_layer_by_layer(orc, label, over, B):
     assert rep["max_rel_err"] <= 2e-2
 
 
+@pytest.mark.parametrize("B", [3, 256, 700])
+def test_bf16_atari_agent_without_frame_stacking(orc, B):
+    """The recurrent Atari agent on single 84x84 frames (Section 4.3: the run without frame stacking): the fused
+    conv stack's one-channel first layer, at a ragged small batch, one image per compute unit and several."""
+    cfg = dict(wl.CONFIGS["C2"], label="Atari agent, no frame stacking", obs_c=1, index=42)
+    run_case(orc, cfg, B, "bf16")
+
+
 def test_bf16_unsupported_arch_is_reported():
     cfg = dict(wl.CONFIGS["C3"], sections=[16, 32, 40])
     with pytest.raises(seedinf.SeedError) as e:
