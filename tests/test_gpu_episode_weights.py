@@ -59,7 +59,7 @@ def test_ext_fp32(orc, name, B):
     ext_case(orc, wl.CONFIGS[name], B, "fp32")
 
 
-@pytest.mark.parametrize("name,B", [("C2", 70), ("C3", 300), ("C4", 33), ("C3", 2100)])
+@pytest.mark.parametrize("name,B", [("C2", 70), ("C3", 300), ("C4", 33), ("C3", 2100), ("C2", 4100)])
 def test_ext_bf16(orc, name, B):
     ext_case(orc, wl.CONFIGS[name], B, "bf16")
 

@@ -51,8 +51,10 @@ def test_unroll_fp32(orc, name, T, B):
     unroll_case(orc, recurrent_c1() if name == "C1r" else wl.CONFIGS[name], T, B, "fp32")
 
 
-@pytest.mark.parametrize("name,T,B", [("C3", 5, 40), ("C2", 3, 33), ("C4", 2, 20), ("C3", 1, 17)])
+@pytest.mark.parametrize("name,T,B", [("C3", 5, 40), ("C2", 3, 33), ("C4", 2, 20), ("C3", 1, 17), ("C2", 9, 250)])
 def test_unroll_bf16(orc, name, T, B):
+    """(C2 with T * B = 2250: the linear layer over all T * B rows takes the large-batch kernel, the per-step
+    core the small-batch one.)"""
     unroll_case(orc, wl.CONFIGS[name], T, B, "bf16")
 
 
