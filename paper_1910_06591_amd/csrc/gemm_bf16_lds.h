@@ -15,9 +15,9 @@
 // i + NSLOT - 1 are in flight; one barrier per stage.
 //
 // KG = 8 (long K, few output tiles: the linear layer after the torso): the eight wavefronts share one 64 x 64
-// tile and each takes every eighth chunk.  Nothing is shared between them, so each runs a private two-slot
-// ring in its own 16 KiB of LDS with no barrier inside the K loop; the staging buys the coalesced row fetch
-// and loads that need no registers.  The eight partial tiles meet in LDS and four wavefronts finish one row
+// tile and each takes every eighth chunk.  Nothing is shared between them, so each runs private rings in its
+// own 20 KiB of LDS (three slots of activation fragments, two of weight fragments) with no barrier inside the
+// K loop; the staging buys the coalesced row fetch and loads that need no registers.  The eight partial tiles meet in LDS and four wavefronts finish one row
 // tile each.  (Splitting K over workgroups instead costs more than it saves here: partial sums that cross the
 // chip's L2 slices need device-scope fences, each of which writes back and invalidates a whole slice.)
 #pragma once
