@@ -126,14 +126,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, floatx4 (&acc)[
 // whole 128-byte line while it is in L1.  F32: the activations of this segment are fp32 rows (converted when
 // multiplied; one chunk is a whole line), chunk numbering inside the segment starts at `seg0`, and only columns
 // < kvalid exist.
-template <int RT, int NST, int CPS, bool F32>
-__device__ __forceinline__ void gemm_k_loop(floatx4 (&acc)[RT][4], const bf16x8* const (&wl)[4], const void* xbase, int ld,
+template <int RT, int NST, int CPS, bool F32, int FT = 4>
+__device__ __forceinline__ void gemm_k_loop(floatx4 (&acc)[RT][FT], const bf16x8* const (&wl)[FT], const void* xbase, int ld,
                                             const int (&rowi)[RT], int kb, int ke, int seg0, int kvalid, int g,
                                             const bool (&zero_row)[RT])
 {
     if (kb >= ke) return;
     struct Stage {
-        bf16x8 a[CPS][4];
+        bf16x8 a[CPS][FT];
         bf16x8 b[CPS][F32 ? 1 : RT];
         floatx4 f[CPS][F32 ? RT : 1][2];
     };
@@ -143,7 +143,7 @@ __device__ __forceinline__ void gemm_k_loop(floatx4 (&acc)[RT][4], const bf16x8*
         for (int c = 0; c < CPS; ++c) {
             const int kc = k0 + c < ke ? k0 + c : ke - 1;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) s.a[c][j] = wl[j][(size_t)kc * 64];
+            for (int j = 0; j < FT; ++j) s.a[c][j] = wl[j][(size_t)kc * 64];
             if constexpr (!F32) {
                 const __bf16* x = (const __bf16*)xbase;
 #pragma unroll
@@ -174,7 +174,7 @@ __device__ __forceinline__ void gemm_k_loop(floatx4 (&acc)[RT][4], const bf16x8*
                 b = to_bf16x8(ok ? s.f[c][r][0] : z, ok ? s.f[c][r][1] : z);
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[r][j] = mfma16(s.a[c][j], b, acc[r][j]);
+            for (int j = 0; j < FT; ++j) acc[r][j] = mfma16(s.a[c][j], b, acc[r][j]);
         }
     };
 #pragma unroll
@@ -231,17 +231,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
 }
 
 // ---- long K: the block's 4 wavefronts share one output tile and split K ----
-template <int RT, int EPI, int NW>
+// FT = feature tiles of the output tile: 4 (a whole group, every epilogue) or 1 (EPI_RELU only: small batches,
+// where 16 x 16 tiles put four times as many compute units to work on the weight matrix).
+template <int RT, int EPI, int NW, int FT = 4>
 __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
 {
     static_assert(NW == 4 || NW == 8, "4 or 8 wavefronts share the output tile");
+    static_assert(FT == 4 || (FT == 1 && EPI == EPI_RELU), "whole gate groups for the LSTM epilogue");
     extern __shared__ __attribute__((aligned(16))) char gemm_lds[];     // partial sums [wave][row tile][feature tile][lane]
     floatx4* part = (floatx4*)gemm_lds;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, n = lane & 15;
-    const int wt = blockIdx.y;                         // the block's tile group along features
-    const int ft0 = wt * 4;
+    const int wt = blockIdx.y;                         // the block's tile group (FT = 4) or tile (FT = 1) along features
+    const int ft0 = wt * FT;
     const int r0 = blockIdx.x * (RT * 16);
     const int kc2 = (p.k2 + 31) >> 5;
     const int kct = p.kc1 + kc2;
@@ -249,23 +252,23 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
     const int kpairs = (kct + 1) / 2;
     const int k0 = 2 * (wave * kpairs / NW), k1 = min(2 * ((wave + 1) * kpairs / NW), kct);
 
-    floatx4 acc[RT][4];
+    floatx4 acc[RT][FT];
 #pragma unroll
     for (int r = 0; r < RT; ++r)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[r][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < FT; ++j) acc[r][j] = floatx4{0.f, 0.f, 0.f, 0.f};
     int rowi[RT];
 #pragma unroll
     for (int r = 0; r < RT; ++r) rowi[r] = min(r0 + r * 16 + n, p.rows - 1);
-    const bf16x8* wl[4];
+    const bf16x8* wl[FT];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) wl[j] = p.wp + ((size_t)min(ft0 + j, p.n_ftiles - 1) * kct) * 64 + lane;
+    for (int j = 0; j < FT; ++j) wl[j] = p.wp + ((size_t)min(ft0 + j, p.n_ftiles - 1) * kct) * 64 + lane;
 
     bool fresh[RT];
 #pragma unroll
     for (int r = 0; r < RT; ++r) fresh[r] = EPI == EPI_LSTM && p.done && p.done[rowi[r]];
-    gemm_k_loop<RT, 3, 2, false>(acc, wl, p.x1, p.ld1, rowi, k0, min(k1, p.kc1), 0, 0, g, fresh);
-    gemm_k_loop<RT, 3, 1, true>(acc, wl, p.x2, p.ld2, rowi, max(k0, p.kc1), k1, p.kc1, p.k2, g, fresh);
+    gemm_k_loop<RT, 3, 2, false, FT>(acc, wl, p.x1, p.ld1, rowi, k0, min(k1, p.kc1), 0, 0, g, fresh);
+    gemm_k_loop<RT, 3, 1, true, FT>(acc, wl, p.x2, p.ld2, rowi, max(k0, p.kc1), k1, p.kc1, p.k2, g, fresh);
 
     // K reduction through LDS.  With 8 wavefronts the upper four first hand everything to the lower four.
     if constexpr (NW == 8) {
@@ -273,14 +276,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
 #pragma unroll
             for (int r = 0; r < RT; ++r)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) part[(((wave - 4) * RT + r) * 4 + j) * 64 + lane] = acc[r][j];
+                for (int j = 0; j < FT; ++j) part[(((wave - 4) * RT + r) * 4 + j) * 64 + lane] = acc[r][j];
         }
         __syncthreads();
         if (wave >= 4) return;
 #pragma unroll
         for (int r = 0; r < RT; ++r)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[r][j] += part[((wave * RT + r) * 4 + j) * 64 + lane];
+            for (int j = 0; j < FT; ++j) acc[r][j] += part[((wave * RT + r) * 4 + j) * 64 + lane];
         // (wavefront w has read only region w of the buffer, the region it writes next; the barrier below
         // counts the four wavefronts that are still alive)
     }
@@ -289,7 +292,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
     for (int r = 0; r < RT; ++r) {
         if (r == wave) continue;                       // uniform
 #pragma unroll
-        for (int j = 0; j < 4; ++j) part[((wave * RT + r) * 4 + j) * 64 + lane] = acc[r][j];
+        for (int j = 0; j < FT; ++j) part[((wave * RT + r) * 4 + j) * 64 + lane] = acc[r][j];
     }
     __syncthreads();
     if (wave >= RT) return;
@@ -300,10 +303,30 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
         for (int w2 = 0; w2 < 4; ++w2) {
             if (w2 == r) continue;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[r][j] += part[((w2 * RT + r) * 4 + j) * 64 + lane];
+            for (int j = 0; j < FT; ++j) acc[r][j] += part[((w2 * RT + r) * 4 + j) * 64 + lane];
         }
     }
-    gemm_epilogue<RT, EPI>(p, acc, wave, wt, r0, lane);
+    if constexpr (FT == 4) {
+        gemm_epilogue<RT, EPI>(p, acc, wave, wt, r0, lane);
+    } else {
+        // one feature tile: bias, ReLU, store (row tile `wave` of this wavefront)
+        const int f = ft0 * 16 + g * 4;
+        const floatx4 bv = *(const floatx4*)(p.bias_pad + f);
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            const int row = r0 + r * 16 + n;
+            if (r != wave || row >= p.rows) continue;
+            const floatx4 v = relu4(acc[r][0] + bv);
+            if (p.y_bf16) *(bf16x4*)(p.y_bf16 + (size_t)row * p.ldy_bf16 + f) = to_bf16x4(v);
+            if (p.y_f32) {
+                float* d = p.y_f32 + (size_t)row * p.ldy_f32 + f;
+                if (f + 4 <= p.n_out) *(floatx4*)d = v;
+                else
+                    for (int i = 0; i < 4; ++i)
+                        if (f + i < p.n_out) d[i] = v[i];
+            }
+        }
+    }
 }
 
 // bf16 rows -> fp32 rows (diagnostic tap)
