@@ -265,6 +265,17 @@ def test_bf16_model_size_variants_run_layer_by_layer(orc, label, over, B):
     assert rep["max_rel_err"] <= 2e-2
 
 
+@pytest.mark.parametrize("B", [37, 300, 1100])
+def test_bf16_odd_widths_through_the_dense_layer_tilings(orc, B):
+    """Widths that are not whole tile groups (48 linear units = 3 feature tiles, 48 LSTM units = 3 gate groups,
+    7 actions) at batches on both sides of the small-batch tilings' limits; a one-layer conv stack (layer by
+    layer)."""
+    cfg = dict(label="odd widths", obs_h=23, obs_w=24, obs_c=8, torso=0, convs=[(16, 4, 2)], fc_units=48,
+               lstm_units=48, num_actions=7, head=0, head_hidden=0, select=1, precision="bf16", obs_kind="uniform",
+               index=43)
+    run_case(orc, cfg, B, "bf16")
+
+
 @pytest.mark.parametrize("B", [3, 256, 700])
 def test_bf16_atari_agent_without_frame_stacking(orc, B):
     """The recurrent Atari agent on single 84x84 frames (Section 4.3: the run without frame stacking): the fused
