@@ -265,7 +265,7 @@ def test_bf16_model_size_variants_run_layer_by_layer(orc, label, over, B):
     assert rep["max_rel_err"] <= 2e-2
 
 
-@pytest.mark.parametrize("B", [37, 300, 1100])
+@pytest.mark.parametrize("B", [37, 300, 1100, 2100])
 def test_bf16_odd_widths_through_the_dense_layer_tilings(orc, B):
     """Widths that are not whole tile groups (48 linear units = 3 feature tiles, 48 LSTM units = 3 gate groups,
     7 actions) at batches on both sides of the small-batch tilings' limits; a one-layer conv stack (layer by
