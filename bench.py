@@ -229,13 +229,13 @@ def cpu_baseline(cfg, rows):
             "one_core_value": 1.0 / d1}
 
 
-def read_traffic():
-    """HBM bytes per launch of the torso kernel from the committed rocprofv3
-    counter summary (profiles/), or None."""
+def read_traffic(key="traffic_bytes_per_launch"):
+    """HBM bytes per launch of the torso kernel (or, key = "step_traffic_bytes", of all the step's kernels) from
+    the committed rocprofv3 counter summary (profiles/), or None."""
     path = os.path.join(ROOT, "profiles", "resnet_torso_c5_b4096_pmc.txt")
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
+            if line.startswith(key):
                 return float(line.split("=")[1].split()[0])
     except OSError:
         pass
@@ -306,9 +306,16 @@ def main():
         for b in cfg["sweep"]:
             k = max(20, min(args.steps, 200))
             s = time_config(cfg, b, k, args.warmup, weights)
-            sweep.append({"batch": b, "frames_per_s": b / (s["p50_ms"] * 1e-3), "p50_ms": s["p50_ms"],
-                          "frac_of_bf16_peak": 2.0 * wl.macs_per_frame(cfg) * b / (s["p50_ms"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                          "torso_ms": s["torso_ms"]})
+            entry = {"batch": b, "frames_per_s": b / (s["p50_ms"] * 1e-3), "p50_ms": s["p50_ms"],
+                     "frac_of_bf16_peak": 2.0 * wl.macs_per_frame(cfg) * b / (s["p50_ms"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                     "torso_ms": s["torso_ms"],
+                     # HBM rate of the bytes every implementation must move (frame, state, outputs) ...
+                     "hbm_gbs_algorithmic": wl.hbm_bytes_per_frame(cfg) * b / (s["p50_ms"] * 1e-3) / 1e9}
+            # ... and, at the batch the counter profile was taken at, of the bytes this one does move
+            step_bytes = read_traffic("step_traffic_bytes")
+            if b == B and step_bytes:
+                entry["hbm_gbs_counters"] = step_bytes / (s["p50_ms"] * 1e-3) / 1e9
+            sweep.append(entry)
         line["sweep"] = sweep
         others = []
         for name in ("C1", "C2", "C3", "C4"):

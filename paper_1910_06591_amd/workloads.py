@@ -242,6 +242,18 @@ def make_trajectory(cfg, T, batch, done_rate=0.1):
     return out
 
 
+def hbm_bytes_per_frame(cfg) -> int:
+    """Bytes per frame that any implementation of the step must move to and from HBM: the frame, the row's
+    other inputs (previous action and reward, recurrent state, uniforms) and its outputs (action, logits, value,
+    probabilities, new state).  Weights (read once per step) are not per-frame traffic."""
+    a, hn = cfg["num_actions"], cfg["lstm_units"]
+    frame = cfg["obs_h"] * cfg["obs_w"] * cfg["obs_c"]
+    core_in = (8 + 2 * hn * 4) if hn else 0
+    core_out = 2 * hn * 4 if hn else 0
+    uniforms = a * 4 if cfg["select"] == 1 else 0
+    return frame + core_in + uniforms + core_out + 4 + a * 4 + 4 + a * 4
+
+
 def macs_per_frame(cfg) -> int:
     """Useful multiply-accumulates per frame (no tile padding counted)."""
     h, w, c = cfg["obs_h"], cfg["obs_w"], cfg["obs_c"]

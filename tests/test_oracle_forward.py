@@ -52,6 +52,13 @@ def test_weight_counts_agree(orc):
     assert wl.macs_per_frame(wl.CONFIGS["C2"]) == 12_013_056
     assert wl.macs_per_frame(wl.CONFIGS["C3"]) == 52_191_232
     assert wl.macs_per_frame(wl.CONFIGS["C4"]) == 66_053_120
+    # bytes per frame any implementation moves to and from HBM, written out by hand:
+    # C3/C5: frame 72*96*3, prev action + reward 8, state in and out 4 * 256 * 4, uniforms 60, action 4, logits 60,
+    # value 4, probabilities 60; C2: frame 84*84*4, 8, state 4 * 512 * 4, no uniforms, 4 + 72 + 4 + 72;
+    # C4: frame 72*96*16, no core, uniforms 76, 4 + 76 + 4 + 76
+    assert wl.hbm_bytes_per_frame(wl.CONFIGS["C5"]) == 20736 + 8 + 4096 + 60 + 4 + 60 + 4 + 60 == 25_028
+    assert wl.hbm_bytes_per_frame(wl.CONFIGS["C2"]) == 28224 + 8 + 8192 + 4 + 72 + 4 + 72 == 36_576
+    assert wl.hbm_bytes_per_frame(wl.CONFIGS["C4"]) == 110592 + 76 + 4 + 76 + 4 + 76 == 110_828
     for cfg in wl.CONFIGS.values():
         a = oracle.make_arch(cfg)
         assert orc.weight_count(a) == wl.weight_count(cfg)
