@@ -30,7 +30,13 @@ __global__ __launch_bounds__(256) void conv2d_f32_kernel(
     int oh = (int)(t % OH);
     int b = (int)(t / OH);
     const size_t img = (size_t)b * H * W * Cin;
-    float acc = bias[co];
+    // four independent partial sums over the input channels: a single chain would wait out a load per term
+    float a0 = bias[co], a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+    auto term = [&](size_t xi, const float* wq) {
+        float v = load_in(x, xi);
+        if (relu_in) v = fmaxf(v, 0.0f);
+        return v * wq[0];
+    };
     for (int kh = 0; kh < k; ++kh) {
         int ih = oh * stride + kh - pad;
         if (ih < 0 || ih >= H) continue;
@@ -39,13 +45,17 @@ __global__ __launch_bounds__(256) void conv2d_f32_kernel(
             if (iw < 0 || iw >= W) continue;
             size_t xo = img + ((size_t)ih * W + iw) * Cin;
             const float* wp = w + ((size_t)(kh * k + kw) * Cin) * Cout + co;
-            for (int ci = 0; ci < Cin; ++ci) {
-                float v = load_in(x, xo + ci);
-                if (relu_in) v = fmaxf(v, 0.0f);
-                acc = fmaf(v, wp[(size_t)ci * Cout], acc);
+            int ci = 0;
+            for (; ci + 3 < Cin; ci += 4) {
+                a0 += term(xo + ci, wp + (size_t)ci * Cout);
+                a1 += term(xo + ci + 1, wp + (size_t)(ci + 1) * Cout);
+                a2 += term(xo + ci + 2, wp + (size_t)(ci + 2) * Cout);
+                a3 += term(xo + ci + 3, wp + (size_t)(ci + 3) * Cout);
             }
+            for (; ci < Cin; ++ci) a0 += term(xo + ci, wp + (size_t)ci * Cout);
         }
     }
+    float acc = (a0 + a1) + (a2 + a3);
     if (resid) acc += resid[idx];
     if (relu_out) acc = fmaxf(acc, 0.0f);
     y[idx] = acc;
@@ -84,26 +94,40 @@ __global__ __launch_bounds__(256) void relu_f32_kernel(const float* __restrict__
     if (idx < n) y[idx] = fmaxf(x[idx], 0.0f);
 }
 
-// y[b, o] = act(bias[o] + sum_i x[b, i] * w[i, o]).  One wavefront per (row,
-// 64-output group) would idle at small B, so the reduction dimension is split
-// over the 4 wavefronts of a block and combined through LDS.
-__global__ __launch_bounds__(256) void dense_f32_kernel(
+// y[b, o] = act(bias[o] + sum_i x[b, i] * w[i, o]).  One wavefront per (row, 64-output group) would idle at
+// small B and wait out one load per term, so the reduction dimension is split over the 16 wavefronts of a block
+// (combined through LDS in a fixed order) and every lane keeps four independent partial sums.
+constexpr int DENSE_F32_WAVES = 16;
+__global__ __launch_bounds__(DENSE_F32_WAVES * 64) void dense_f32_kernel(
     const float* __restrict__ x, const float* __restrict__ w, const float* __restrict__ bias,
     float* __restrict__ y, int n_in, int n_out, int ldx, int ldy, int relu_out)
 {
-    __shared__ float part[4][64];
+    __shared__ float part[DENSE_F32_WAVES][64];
     int b = blockIdx.x;
-    int o = blockIdx.y * 64 + (threadIdx.x & 63);
+    int lane = threadIdx.x & 63;
+    int o = blockIdx.y * 64 + lane;
     int q = threadIdx.x >> 6;
     float acc = 0.0f;
     if (o < n_out) {
         const float* xr = x + (size_t)b * ldx;
-        for (int i = q; i < n_in; i += 4) acc = fmaf(xr[i], w[(size_t)i * n_out + o], acc);
+        constexpr int Q = DENSE_F32_WAVES;
+        float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+        int i = q;
+        for (; i + 3 * Q < n_in; i += 4 * Q) {
+            a0 = fmaf(xr[i], w[(size_t)i * n_out + o], a0);
+            a1 = fmaf(xr[i + Q], w[(size_t)(i + Q) * n_out + o], a1);
+            a2 = fmaf(xr[i + 2 * Q], w[(size_t)(i + 2 * Q) * n_out + o], a2);
+            a3 = fmaf(xr[i + 3 * Q], w[(size_t)(i + 3 * Q) * n_out + o], a3);
+        }
+        for (; i < n_in; i += Q) a0 = fmaf(xr[i], w[(size_t)i * n_out + o], a0);
+        acc = (a0 + a1) + (a2 + a3);
     }
-    part[q][threadIdx.x & 63] = acc;
+    part[q][lane] = acc;
     __syncthreads();
     if (q == 0 && o < n_out) {
-        float s = bias[o] + ((part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]));
+        float s = bias[o];
+#pragma unroll
+        for (int j = 0; j < DENSE_F32_WAVES; ++j) s += part[j][lane];
         if (relu_out) s = fmaxf(s, 0.0f);
         y[(size_t)b * ldy + o] = s;
     }

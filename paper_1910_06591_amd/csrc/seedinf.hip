@@ -213,7 +213,7 @@ static void torso_fc_f32(seed_infer* h, hipStream_t s, int B, const uint8_t* obs
     }
     h->feat_f32 = cur;
     const seed_arch_t& a = p.arch;
-    hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (a.fc_units + 63) / 64), dim3(256), 0, s, cur, w + p.fc_w, w + p.fc_b,
+    hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (a.fc_units + 63) / 64), dim3(DENSE_F32_WAVES * 64), 0, s, cur, w + p.fc_w, w + p.fc_b,
                        h->d_fc, (int)p.flat, a.fc_units, (int)p.flat, a.fc_units, 1);
 }
 
@@ -301,9 +301,9 @@ static seed_status_t run_core_heads(seed_infer* h, hipStream_t s, int row0, int 
         }
         if (a.head == SEED_HEAD_DUELING_Q) {
             int hid = a.head_hidden;
-            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(256), 0, s, core, w + p.v1_w, w + p.v1_b,
+            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(DENSE_F32_WAVES * 64), 0, s, core, w + p.v1_w, w + p.v1_b,
                                h->d_hid, p.core, hid, ld_core, 2 * hid, 1);
-            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(256), 0, s, core, w + p.a1_w, w + p.a1_b,
+            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(DENSE_F32_WAVES * 64), 0, s, core, w + p.a1_w, w + p.a1_b,
                                h->d_hid + hid, p.core, hid, ld_core, 2 * hid, 1);
         }
     } else {
