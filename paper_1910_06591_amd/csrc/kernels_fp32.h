@@ -37,12 +37,15 @@ __global__ __launch_bounds__(256) void conv2d_f32_kernel(
         if (relu_in) v = fmaxf(v, 0.0f);
         return v * wq[0];
     };
-    for (int kh = 0; kh < k; ++kh) {
+    // taps inside the image: [kh0, kh1) x [kw0, kw1) (loops without early exits can be unrolled, which is what
+    // lets the loads of several taps be in flight together)
+    const int kh0 = max(0, pad - oh * stride), kh1 = min(k, H + pad - oh * stride);
+    const int kw0 = max(0, pad - ow * stride), kw1 = min(k, W + pad - ow * stride);
+    for (int kh = kh0; kh < kh1; ++kh) {
         int ih = oh * stride + kh - pad;
-        if (ih < 0 || ih >= H) continue;
-        for (int kw = 0; kw < k; ++kw) {
+#pragma unroll 4
+        for (int kw = kw0; kw < kw1; ++kw) {
             int iw = ow * stride + kw - pad;
-            if (iw < 0 || iw >= W) continue;
             size_t xo = img + ((size_t)ih * W + iw) * Cin;
             const float* wp = w + ((size_t)(kh * k + kw) * Cin) * Cout + co;
             int ci = 0;
