@@ -150,8 +150,10 @@ seed_status_t seed_infer_create(const seed_arch_t* arch, const float* weights_ho
  *                overlap h_in / c_in (SEED_ERR_ALIASING): the caller ping-pongs
  *   probs_out    [B, num_actions] fp32 softmax(logits_out), or NULL to skip
  *
- * B == 0 is a no-op returning SEED_OK.  B < 0 is SEED_ERR_INVALID_ARG,
- * B > max_batch is SEED_ERR_BATCH_TOO_LARGE.
+ * obs, h_in, c_in, h_out and c_out must be 16-byte aligned (any hipMalloc'ed
+ * or framework-allocated buffer is; the kernels move frames and state 16 bytes
+ * per lane), else SEED_ERR_INVALID_ARG.  B == 0 is a no-op returning SEED_OK.
+ * B < 0 is SEED_ERR_INVALID_ARG, B > max_batch is SEED_ERR_BATCH_TOO_LARGE.
  */
 seed_status_t seed_infer_step(seed_infer_t* handle, int32_t B,
                               const uint8_t* obs,
@@ -222,7 +224,8 @@ seed_status_t seed_infer_step_ext(seed_infer_t* handle, int32_t B,
  * All device pointers; recurrent arguments NULL iff the arch has no core (then
  * the call is one step over T * B rows).  T * B must not exceed max_batch
  * (SEED_ERR_BATCH_TOO_LARGE).  The states between steps live in the handle;
- * h_out / c_out must not overlap h0 / c0 or each other (SEED_ERR_ALIASING).
+ * h_out / c_out must not overlap h0 / c0 or each other (SEED_ERR_ALIASING);
+ * obs, h0, c0, h_out and c_out must be 16-byte aligned (SEED_ERR_INVALID_ARG).
  * Allocates nothing, enqueues on `hip_stream`, returns without synchronising;
  * on an error status nothing has been enqueued.
  */

@@ -331,6 +331,13 @@ static seed_status_t run_core_heads(seed_infer* h, hipStream_t s, int row0, int 
     return SEED_OK;
 }
 
+// The kernels move frames and recurrent state 16 bytes per lane.
+template <class... P>
+static bool misaligned16(P... ptrs)
+{
+    return (((uintptr_t)ptrs | ...) & 15) != 0;
+}
+
 extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8_t* obs,
                                          const int32_t* prev_action, const float* prev_reward,
                                          const float* h_in, const float* c_in, const float* uniforms,
@@ -363,6 +370,8 @@ extern "C" seed_status_t seed_infer_step_ext(seed_infer_t* h, int32_t B, const u
         return fail(SEED_ERR_INVALID_ARG, "a feed-forward arch takes no recurrent arguments (pass NULL)");
     if (a.select == SEED_SELECT_GUMBEL && !uniforms) return fail(SEED_ERR_INVALID_ARG, "Gumbel-max selection needs uniforms");
     if (a.select == SEED_SELECT_GREEDY && uniforms) return fail(SEED_ERR_INVALID_ARG, "greedy selection takes no uniforms (pass NULL)");
+    if (misaligned16(obs, h_in, c_in, h_out, c_out))
+        return fail(SEED_ERR_INVALID_ARG, "obs, h_in, c_in, h_out and c_out must be 16-byte aligned");
     const uint8_t* done = nullptr;
     const float* epsilon = nullptr;
     const float* explore_u = nullptr;
@@ -410,6 +419,8 @@ extern "C" seed_status_t seed_infer_unroll(seed_infer_t* h, int32_t T, int32_t B
         return fail(SEED_ERR_INVALID_ARG, "a feed-forward arch takes no recurrent arguments (pass NULL)");
     if (a.select == SEED_SELECT_GUMBEL && !uniforms) return fail(SEED_ERR_INVALID_ARG, "Gumbel-max selection needs uniforms");
     if (a.select == SEED_SELECT_GREEDY && uniforms) return fail(SEED_ERR_INVALID_ARG, "greedy selection takes no uniforms (pass NULL)");
+    if (misaligned16(obs, h0, c0, h_out, c_out))
+        return fail(SEED_ERR_INVALID_ARG, "obs, h0, c0, h_out and c_out must be 16-byte aligned");
     if (rec) {
         size_t nb = (size_t)B * a.lstm_units * sizeof(float);
         if (overlaps(h_out, nb, h0, nb) || overlaps(h_out, nb, c0, nb) || overlaps(c_out, nb, h0, nb) ||

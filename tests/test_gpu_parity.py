@@ -113,6 +113,8 @@ def test_error_paths_on_device(orc):
     bad = list(args); bad[9] = p(batch["h_in"])          # h_out aliases h_in
     st, _ = net.step_raw(4, *bad)
     assert st == 4
+    bad = list(args); bad[0] = C.c_void_p(batch["obs"].data_ptr() + 4)   # obs not 16-byte aligned
+    assert net.step_raw(3, *bad)[0] == 1
     bad = list(args); bad[0] = None                      # obs missing
     assert net.step_raw(4, *bad)[0] == 1
     bad = list(args); bad[5] = None                      # uniforms missing for Gumbel selection
