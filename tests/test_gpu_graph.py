@@ -9,7 +9,7 @@ from tests.parity import to_device
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name,B", [("C3", 70), ("C2", 33), ("C1", 5)])
+@pytest.mark.parametrize("name,B", [("C3", 70), ("C2", 33), ("C1", 5), ("C3", 2300), ("C2", 2100)])
 def test_graph_replays_equal_eager(name, B):
     import torch
     cfg = wl.CONFIGS[name]
