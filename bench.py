@@ -246,7 +246,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--batch", type=int, default=4096)
     ap.add_argument("--no-extras", action="store_true", help="skip the batch sweep and the other configs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
