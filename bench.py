@@ -37,16 +37,16 @@ def torso_macs_per_frame(cfg):
     return full - rest
 
 
-def wake_device(ms=25.0):
+def wake_device(launches=25):
     """Bring the clocks up from idle before a measurement: the host-side preparation of a workload (random frames,
     weight packing) leaves the device idle for up to a second, and the first tens of milliseconds of work after
-    that run at reduced clocks whatever the number of warm-up steps.  ~25 ms of the MFMA probe loop."""
+    that run at reduced clocks whatever the number of warm-up steps.  25 launches of the MFMA probe loop, ~70 ms."""
     import torch
     from paper_1910_06591_amd import seedinf
     lib = seedinf.load_probe_library()
     sink = torch.zeros(4096, dtype=torch.float32, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
-    for _ in range(max(1, int(ms))):                # ~1 ms per launch
+    for _ in range(max(1, int(launches))):          # ~2.8 ms per launch
         rc = lib.seed_probe_mfma_bf16(2048, 400, sink.data_ptr(), st)
         assert rc == 0, rc
     torch.cuda.synchronize()
