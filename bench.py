@@ -263,7 +263,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--batch", type=int, default=4096)
+    ap.add_argument("--batch", type=int, default=None, help="rows per step (default: 4096 for C5, the workload's own batch otherwise)")
+    ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3", "C4", "C5"],
+                    help="C5 (default) is the headline line; any other name times that workload alone and prints a "
+                         "short line for it (used to profile the other workloads' kernels)")
     ap.add_argument("--no-extras", action="store_true", help="skip the batch sweep and the other configs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=512)
@@ -292,8 +295,20 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.workload != "C5":
+        c = wl.CONFIGS[args.workload]
+        b = args.batch or c["batch"]
+        s = time_config(c, b, args.steps, args.warmup)
+        print(json.dumps({"metric": "batched inference frames/sec at batch B (1 GPU)", "value": b / (s["ms_per_step"] * 1e-3),
+                          "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": s["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                          "dtype": c["precision"], "data": "synthetic",
+                          "config": {"workload": f"{args.workload}: {c.get('label', args.workload)}", "batch": b},
+                          "p50_ms": s["p50_ms"], "torso_ms": s.get("torso_ms"),
+                          "step_tflops": 2.0 * wl.macs_per_frame(c) * b / (s["ms_per_step"] * 1e-3) / 1e12}))
+        return
     cfg = wl.CONFIGS["C5"]
-    B = args.batch
+    B = args.batch or 4096
     weights = wl.make_weights(cfg)
     peaks = None if args.no_extras else measure_peaks()
     r = time_config(cfg, B, args.steps, args.warmup, weights)
