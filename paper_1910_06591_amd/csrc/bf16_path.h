@@ -457,17 +457,16 @@ inline bool launch_gemm_lds(hipStream_t st, const GemmArgs& g, int tile_groups, 
     if constexpr (EPI == EPI_RELU) {
         if (kct >= 64 && g.k2 == 0 && (long)((g.rows + 127) / 128) * ((tile_groups + 3) / 4) < n_cu) {
             // long K, too few 128 x 256 tiles for the chip (the linear layer after the torso): 64 x 64 tiles
-            constexpr int LDS = GemmLdsCfg<1, 1, 8, false>::LDS_BYTES;
-            hipLaunchKernelGGL((gemm_bf16_lds_kernel<1, 1, 8, EPI, false>), dim3((g.rows + 63) / 64, tile_groups), dim3(GL_THREADS), LDS, st, g);
+            hipLaunchKernelGGL((gemm_bf16_k8_kernel<EPI>), dim3((g.rows + 63) / 64, tile_groups), dim3(GL_THREADS), GL_K8_LDS_BYTES, st, g);
             return true;
         }
     }
     const int by = (tile_groups + 3) / 4;
-    constexpr int LDS42 = GemmLdsCfg<4, 2, 1, true>::LDS_BYTES, LDS41 = GemmLdsCfg<4, 1, 2, true>::LDS_BYTES;
+    constexpr int LDS42 = GemmXwCfg<4, 2, 1, true>::LDS_BYTES, LDS41 = GemmXwCfg<4, 1, 2, true>::LDS_BYTES;
     if ((long)((g.rows + 127) / 128) * by >= n_cu)
-        hipLaunchKernelGGL((gemm_bf16_lds_kernel<4, 2, 1, EPI, true>), dim3((g.rows + 127) / 128, by), dim3(GL_THREADS), LDS42, st, g);
+        hipLaunchKernelGGL((gemm_bf16_xw_kernel<4, 2, 1, EPI, true>), dim3((g.rows + 127) / 128, by), dim3(GL_THREADS), LDS42, st, g);
     else
-        hipLaunchKernelGGL((gemm_bf16_lds_kernel<4, 1, 2, EPI, true>), dim3((g.rows + 63) / 64, by), dim3(GL_THREADS), LDS41, st, g);
+        hipLaunchKernelGGL((gemm_bf16_xw_kernel<4, 1, 2, EPI, true>), dim3((g.rows + 63) / 64, by), dim3(GL_THREADS), LDS41, st, g);
     return true;
 }
 
