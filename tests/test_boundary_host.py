@@ -96,3 +96,14 @@ def test_probe_library_loads_and_exports():
         assert hasattr(probe, name)
     # 1 block x 8 wavefronts x 1 iteration x 64 MFMAs of 16 x 16 x 32 multiply-adds
     assert probe.seed_probe_mfma_flops(1, 1) == 8 * 64 * 2 * 16 * 16 * 32
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: any other --gpus value ends with a message and a non-zero status before anything
+    touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
