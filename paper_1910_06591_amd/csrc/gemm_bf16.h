@@ -188,8 +188,11 @@ __device__ __forceinline__ void gemm_k_loop(floatx4 (&acc)[RT][FT], const bf16x8
             for (int c = 0; c < CPS; ++c) mma1(st[i], c, kc + i * CPS + c);
         }
     }
+    // fewer than NST * CPS chunks are left; the first NST - 1 stages of them are already loaded, and a last
+    // partial stage (CPS > 1: e.g. five chunks left of six) is loaded now
+    if (CPS > 1 && kc + (NST - 1) * CPS < ke) load(st[NST - 1], kc + (NST - 1) * CPS);   // uniform
 #pragma unroll
-    for (int i = 0; i < NST - 1; ++i)                  // the last (fewer than NST) stages are already loaded
+    for (int i = 0; i < (CPS > 1 ? NST : NST - 1); ++i)
 #pragma unroll
         for (int c = 0; c < CPS; ++c)
             if (kc + i * CPS + c < ke) mma1(st[i], c, kc + i * CPS + c);

@@ -303,3 +303,66 @@ def test_bf16_unsupported_arch_is_reported():
     with pytest.raises(seedinf.SeedError) as e:
         seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=2, precision="bf16"), wl.make_weights(cfg))
     assert e.value.status == 2 and "fp32" in e.value.message
+
+
+def _random_arch(seed, precision):
+    """A seeded random valid architecture: fp32 mode takes any shape; bf16 mode keeps to the widths its kernels
+    cover (channels, LSTM units and head widths in multiples of 16, conv K in multiples of 32)."""
+    rng = np.random.default_rng(1000 + seed)
+    bf = precision == "bf16"
+    mult = 16 if bf else 1
+    width = lambda lo, hi: int(rng.integers(lo, hi + 1)) * mult
+    cfg = dict(label=f"random arch {seed} ({precision})", precision=precision, obs_kind="uniform", index=60 + seed,
+               num_actions=int(rng.integers(2, 25)), select=int(rng.integers(0, 2)), head=int(rng.integers(0, 2)))
+    cfg["head_hidden"] = (width(1, 3) if bf else int(rng.integers(3, 40))) if cfg["head"] == 1 else 0
+    cfg["lstm_units"] = 0 if rng.integers(0, 3) == 0 else (width(1, 4) if bf else int(rng.integers(3, 40)))
+    cfg["fc_units"] = width(1, 4) if bf else int(rng.integers(5, 60))
+    cfg["torso"] = int(rng.integers(0, 2))
+    if cfg["torso"] == 1:
+        cfg.update(obs_h=int(rng.integers(9, 31)), obs_w=int(rng.integers(9, 31)), obs_c=int(rng.integers(1, 7)),
+                   sections=[(width(1, 3) if bf else int(rng.integers(2, 12))) for _ in range(int(rng.integers(1, 4)))])
+    else:
+        # bf16 conv layers: Cout % 16 == 0, k * Cin % 8 == 0, k * k * Cin % 32 == 0, rows a multiple of 8 elements
+        h, w = int(rng.integers(18, 41)), int(rng.integers(18, 41))
+        c = 8 if bf else int(rng.integers(1, 6))
+        if bf:
+            w = (w + 7) // 8 * 8
+        cfg.update(obs_h=h, obs_w=w, obs_c=c)
+        convs = []
+        for _ in range(int(rng.integers(1, 4))):
+            k, s = (int(rng.choice([2, 4])) if bf else int(rng.integers(2, 6))), int(rng.integers(1, 3))
+            if (h - k) // s + 1 < 2 or (w - k) // s + 1 < 2:
+                break
+            convs.append((width(1, 2) if bf else int(rng.integers(2, 12)), k, s))
+            h, w = (h - k) // s + 1, (w - k) // s + 1
+        cfg["convs"] = convs or [(16 if bf else 5, 2, 1)]
+    return cfg
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_fp32_random_architectures(orc, seed):
+    """Seeded random architectures in fp32 mode (the reference mode covers every valid shape): both torso kinds,
+    with and without core, both heads, both selections, at a ragged batch."""
+    cfg = _random_arch(seed, "fp32")
+    st, msg = seedinf.validate(seedinf.make_arch(cfg, max_batch=5))
+    assert st == 0, (cfg, msg)
+    run_case(orc, cfg, 5, "fp32")
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_bf16_random_architectures(orc, seed):
+    """Seeded random architectures within the widths the bf16 kernels cover (layer-by-layer torsos, direct dense
+    kernels, every head / core / selection combination), at a batch that is not a multiple of a row tile."""
+    cfg = _random_arch(seed, "bf16")
+    run_case(orc, cfg, 21, "bf16")
+
+
+@pytest.mark.parametrize("fc_units,B", [(160, 21), (352, 40), (160, 300)])
+def test_bf16_direct_dense_kernels_with_chunk_counts_of_every_residue(orc, fc_units, B):
+    """The direct dense kernels walk K in stages of two 32-value chunks, three stages in flight: K segments of
+    5, 11, 21 ... chunks (one more than two whole stages left at the end) through both the whole-K and the
+    K-split kernels.  Linear layer K = 6 * 7 * 16 = 672 = 21 chunks; LSTM feature segment fc_units / 32 = 5 or 11."""
+    cfg = dict(label=f"chunk residues fc{fc_units}", obs_h=23, obs_w=26, obs_c=5, torso=1, sections=[48, 16],
+               fc_units=fc_units, lstm_units=32, num_actions=8, head=1, head_hidden=16, select=0, precision="bf16",
+               obs_kind="uniform", index=71)
+    run_case(orc, cfg, B, "bf16")
