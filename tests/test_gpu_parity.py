@@ -339,7 +339,7 @@ def _random_arch(seed, precision):
     return cfg
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(24))
 def test_fp32_random_architectures(orc, seed):
     """Seeded random architectures in fp32 mode (the reference mode covers every valid shape): both torso kinds,
     with and without core, both heads, both selections, at a ragged batch."""
@@ -349,11 +349,15 @@ def test_fp32_random_architectures(orc, seed):
     run_case(orc, cfg, 5, "fp32")
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", range(24))
 def test_bf16_random_architectures(orc, seed):
     """Seeded random architectures within the widths the bf16 kernels cover (layer-by-layer torsos, direct dense
     kernels, every head / core / selection combination), at a batch that is not a multiple of a row tile."""
     cfg = _random_arch(seed, "bf16")
+    st, msg = seedinf.validate(seedinf.make_arch(cfg, max_batch=21, precision="bf16"))
+    if st == seedinf.STATUS_BY_NAME["SEED_ERR_UNSUPPORTED_ARCH"]:
+        pytest.skip(msg)                                 # e.g. a flattened conv-stack output that is not whole chunks
+    assert st == 0, (cfg, msg)
     run_case(orc, cfg, 21, "bf16")
 
 
@@ -366,3 +370,23 @@ def test_bf16_direct_dense_kernels_with_chunk_counts_of_every_residue(orc, fc_un
                fc_units=fc_units, lstm_units=32, num_actions=8, head=1, head_hidden=16, select=0, precision="bf16",
                obs_kind="uniform", index=71)
     run_case(orc, cfg, B, "bf16")
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_bf16_random_dense_widths_at_large_batch(orc, seed):
+    """Seeded random widths of the linear layer, the core and the heads behind a small conv layer, at batches
+    from 2048 rows (LDS-staged dense kernels where their shape rules allow, direct kernels elsewhere), with
+    ragged last tiles; oracle on a sample of rows."""
+    rng = np.random.default_rng(500 + seed)
+    B = int(rng.choice([2048, 2049, 2200, 3000, 4100]))
+    head = int(rng.integers(0, 2))
+    cfg = dict(label=f"random dense widths {seed}", obs_h=int(rng.choice([10, 11, 14, 15, 18])), obs_w=int(rng.choice([16, 24])),
+               obs_c=8, torso=0, convs=[(int(rng.choice([16, 32, 48])), 4, 2)], fc_units=16 * int(rng.integers(1, 25)),
+               lstm_units=0 if rng.integers(0, 4) == 0 else 16 * int(rng.integers(1, 20)),
+               num_actions=int(rng.integers(2, 33)), head=head, head_hidden=16 * int(rng.integers(1, 20)) if head else 0,
+               select=int(rng.integers(0, 2)), precision="bf16", obs_kind="uniform", index=80 + seed)
+    st, msg = seedinf.validate(seedinf.make_arch(cfg, max_batch=B, precision="bf16"))
+    if st == seedinf.STATUS_BY_NAME["SEED_ERR_UNSUPPORTED_ARCH"]:
+        pytest.skip(msg)
+    assert st == 0, (cfg, msg)
+    run_full(orc, cfg, B, sample=48)
