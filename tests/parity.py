@@ -63,3 +63,37 @@ def check_against_oracle(got, ref, tol, uniforms=None):
         top2 = np.argsort(-keys, kind="stable")[:2]
         assert ga[b] in top2, f"row {b}: action {ga[b]} is not among the oracle's top two {top2}"
     return {"max_rel_err": worst, "actions_equal": int((~differ).sum()), "near_ties": int(near.sum())}
+
+
+def random_arch(seed, precision):
+    """A seeded random valid architecture: fp32 mode takes any shape; bf16 mode keeps to the widths its kernels
+    cover (channels, LSTM units and head widths in multiples of 16, conv K in multiples of 32)."""
+    rng = np.random.default_rng(1000 + seed)
+    bf = precision == "bf16"
+    mult = 16 if bf else 1
+    width = lambda lo, hi: int(rng.integers(lo, hi + 1)) * mult
+    cfg = dict(label=f"random arch {seed} ({precision})", precision=precision, obs_kind="uniform", index=60 + seed,
+               num_actions=int(rng.integers(2, 25)), select=int(rng.integers(0, 2)), head=int(rng.integers(0, 2)))
+    cfg["head_hidden"] = (width(1, 3) if bf else int(rng.integers(3, 40))) if cfg["head"] == 1 else 0
+    cfg["lstm_units"] = 0 if rng.integers(0, 3) == 0 else (width(1, 4) if bf else int(rng.integers(3, 40)))
+    cfg["fc_units"] = width(1, 4) if bf else int(rng.integers(5, 60))
+    cfg["torso"] = int(rng.integers(0, 2))
+    if cfg["torso"] == 1:
+        cfg.update(obs_h=int(rng.integers(9, 31)), obs_w=int(rng.integers(9, 31)), obs_c=int(rng.integers(1, 7)),
+                   sections=[(width(1, 3) if bf else int(rng.integers(2, 12))) for _ in range(int(rng.integers(1, 4)))])
+    else:
+        # bf16 conv layers: Cout % 16 == 0, k * Cin % 8 == 0, k * k * Cin % 32 == 0, rows a multiple of 8 elements
+        h, w = int(rng.integers(18, 41)), int(rng.integers(18, 41))
+        c = 8 if bf else int(rng.integers(1, 6))
+        if bf:
+            w = (w + 7) // 8 * 8
+        cfg.update(obs_h=h, obs_w=w, obs_c=c)
+        convs = []
+        for _ in range(int(rng.integers(1, 4))):
+            k, s = (int(rng.choice([2, 4])) if bf else int(rng.integers(2, 6))), int(rng.integers(1, 3))
+            if (h - k) // s + 1 < 2 or (w - k) // s + 1 < 2:
+                break
+            convs.append((width(1, 2) if bf else int(rng.integers(2, 12)), k, s))
+            h, w = (h - k) // s + 1, (w - k) // s + 1
+        cfg["convs"] = convs or [(16 if bf else 5, 2, 1)]
+    return cfg

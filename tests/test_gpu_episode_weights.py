@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 from paper_1910_06591_amd import seedinf, workloads as wl
-from tests.parity import check_against_oracle, to_device
+from tests.parity import check_against_oracle, random_arch, to_device
 
 pytestmark = pytest.mark.gpu
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
@@ -57,6 +57,16 @@ def ext_case(orc, cfg, B, precision, done_rate=0.3, use_done=True, use_eps=True)
 @pytest.mark.parametrize("name,B", [("C2", 37), ("C3", 41), ("C4", 19)])
 def test_ext_fp32(orc, name, B):
     ext_case(orc, wl.CONFIGS[name], B, "fp32")
+
+
+@pytest.mark.parametrize("seed,precision", [(s, p) for p in ("fp32", "bf16") for s in range(8)])
+def test_ext_random_architectures(orc, seed, precision):
+    """Episode flags and epsilon-greedy on seeded random architectures."""
+    cfg = random_arch(200 + seed, precision)
+    st, msg = seedinf.validate(seedinf.make_arch(cfg, max_batch=64, precision=precision))
+    if st == seedinf.STATUS_BY_NAME["SEED_ERR_UNSUPPORTED_ARCH"]:
+        pytest.skip(msg)
+    ext_case(orc, cfg, 19, precision)
 
 
 @pytest.mark.parametrize("name,B", [("C2", 70), ("C3", 300), ("C4", 33), ("C3", 2100), ("C2", 4100)])

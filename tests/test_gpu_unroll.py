@@ -6,7 +6,7 @@ import pytest
 
 import oracle
 from paper_1910_06591_amd import seedinf, workloads as wl
-from tests.parity import check_against_oracle
+from tests.parity import check_against_oracle, random_arch
 
 pytestmark = pytest.mark.gpu
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
@@ -56,6 +56,18 @@ def test_unroll_bf16(orc, name, T, B):
     """(C2 with T * B = 2250: the linear layer over all T * B rows takes the large-batch kernel, the per-step
     core the small-batch one.)"""
     unroll_case(orc, wl.CONFIGS[name], T, B, "bf16")
+
+
+@pytest.mark.parametrize("seed,precision", [(s, p) for p in ("fp32", "bf16") for s in range(8)])
+def test_unroll_random_architectures(orc, seed, precision):
+    """The unroll on seeded random architectures (recurrent and feed-forward, both heads and selections), random T
+    and B."""
+    cfg = random_arch(100 + seed, precision)
+    st, msg = seedinf.validate(seedinf.make_arch(cfg, max_batch=64, precision=precision))
+    if st == seedinf.STATUS_BY_NAME["SEED_ERR_UNSUPPORTED_ARCH"]:
+        pytest.skip(msg)
+    rng = np.random.default_rng(seed)
+    unroll_case(orc, cfg, int(rng.integers(1, 7)), int(rng.integers(1, 10)), precision)
 
 
 def test_unroll_without_flags_and_every_row_flagged(orc):
