@@ -356,3 +356,27 @@ def test_bf16_random_dense_widths_at_large_batch(orc, seed):
         pytest.skip(msg)
     assert st == 0, (cfg, msg)
     run_full(orc, cfg, B, sample=48)
+
+
+@pytest.mark.parametrize("name,B", [("C4", 257), ("C4", 600), ("C2", 257), ("C2", 515), ("C2", 1100)])
+def test_bf16_persistent_grid_edges_of_the_other_fused_torsos(orc, name, B):
+    """The Football torso and the fused conv stack with one more image than compute units, a ragged count and
+    several images per workgroup (the conv stack double-buffers its frames across images)."""
+    run_full(orc, wl.CONFIGS[name], B, sample=48)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_bf16_random_layerwise_resnets(orc, seed):
+    """Layer-by-layer ResNets with random odd image sizes and random channel counts in multiples of 16 and of 32
+    (the LDS-tiled 3x3 kernel takes layers whose input channels are a multiple of 32, the gather kernel the rest),
+    uint8 inputs of 1 .. 16 planes."""
+    rng = np.random.default_rng(900 + seed)
+    mult = 32 if seed % 2 == 0 else 16
+    cfg = dict(label=f"random layer-by-layer resnet {seed}", obs_h=int(rng.integers(17, 64)), obs_w=int(rng.integers(17, 64)),
+               obs_c=int(rng.choice([1, 3, 4, 8, 16])), torso=1,
+               sections=[mult * int(rng.integers(1, 4)) for _ in range(int(rng.integers(1, 4)))],
+               fc_units=64, lstm_units=32, num_actions=9, head=0, head_hidden=0, select=1, precision="bf16",
+               obs_kind="uniform", index=90 + seed)
+    st, msg = seedinf.validate(seedinf.make_arch(cfg, max_batch=8, precision="bf16"))
+    assert st == 0, (cfg, msg)
+    run_case(orc, cfg, int(rng.integers(1, 8)), "bf16")
