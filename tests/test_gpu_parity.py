@@ -380,3 +380,36 @@ def test_bf16_random_layerwise_resnets(orc, seed):
     st, msg = seedinf.validate(seedinf.make_arch(cfg, max_batch=8, precision="bf16"))
     assert st == 0, (cfg, msg)
     run_case(orc, cfg, int(rng.integers(1, 8)), "bf16")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_bf16_random_conv_stacks_and_wide_action_sets(orc, seed):
+    """Layer-by-layer bf16 conv stacks over the (channels, kernel) pairs their implicit-GEMM kernel covers
+    (k * Cin and stride * Cin multiples of 8, k * k * Cin of 32), up to three layers; heads with up to 64
+    actions (every lane-group width of the heads kernels), inputs of the widths both heads kernels take."""
+    rng = np.random.default_rng(700 + seed)
+    menu = {2: [4], 4: [4, 8], 8: [2, 4, 6], 16: [2, 4], 32: [1, 2, 3, 4], 48: [2, 4]}
+    c = int(rng.choice([2, 4, 8]))
+    h, w = int(rng.integers(20, 48)), 8 * int(rng.integers(3, 7))
+    cfg = dict(label=f"random conv stack {seed}", obs_h=h, obs_w=w, obs_c=c, torso=0, precision="bf16", obs_kind="uniform",
+               index=110 + seed, num_actions=int(rng.choice([2, 3, 5, 9, 17, 31, 33, 50, 64])), select=int(rng.integers(0, 2)),
+               head=int(rng.integers(0, 2)), fc_units=16 * int(rng.choice([2, 4, 8, 16, 5])),
+               lstm_units=int(rng.choice([0, 32, 64, 128, 256, 48])))
+    cfg["head_hidden"] = int(rng.choice([32, 64, 128, 512, 80])) if cfg["head"] == 1 else 0
+    convs = []
+    for _ in range(int(rng.integers(1, 4))):
+        k = int(rng.choice(menu[c]))
+        s = int(rng.choice([t for t in range(1, min(k, 4) + 1) if (t * c) % 8 == 0]))   # pixel step of 8 elements
+        if (h - k) // s + 1 < 2 or (w - k) // s + 1 < 2:
+            break
+        ch = int(rng.choice([16, 32, 48]))
+        convs.append((ch, k, s))
+        h, w, c = (h - k) // s + 1, (w - k) // s + 1, ch
+    if not convs:
+        pytest.skip("no layer fits")
+    cfg["convs"] = convs
+    st, msg = seedinf.validate(seedinf.make_arch(cfg, max_batch=64, precision="bf16"))
+    if st == seedinf.STATUS_BY_NAME["SEED_ERR_UNSUPPORTED_ARCH"]:
+        pytest.skip(msg)
+    assert st == 0, (cfg, msg)
+    run_case(orc, cfg, int(rng.choice([3, 16, 40, 64])), "bf16")
