@@ -413,3 +413,29 @@ def test_bf16_random_conv_stacks_and_wide_action_sets(orc, seed):
         pytest.skip(msg)
     assert st == 0, (cfg, msg)
     run_case(orc, cfg, int(rng.choice([3, 16, 40, 64])), "bf16")
+
+
+def test_two_instances_on_two_streams_do_not_interfere():
+    """Two networks alive at once, stepped alternately on two streams: each gives bit for bit what it gives alone
+    (the library keeps no state outside its handles)."""
+    import torch
+    res = {}
+    for name, B in (("C3", 300), ("C2", 130)):
+        cfg = wl.CONFIGS[name]
+        net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=B), wl.make_weights(cfg))
+        dev = to_device(wl.make_batch(cfg, B))
+        res[name] = ({k: v.clone() for k, v in net.step(**dev).items()}, dev, cfg, B)
+        torch.cuda.synchronize()
+        net.close()
+    nets = {n: seedinf.SeedInfer(seedinf.make_arch(c, max_batch=B), wl.make_weights(c)) for n, (_, _, c, B) in res.items()}
+    streams = {n: torch.cuda.Stream() for n in res}
+    outs = {}
+    for rep in range(3):
+        for n in res:
+            with torch.cuda.stream(streams[n]):
+                outs[n] = nets[n].step(**res[n][1])
+    torch.cuda.synchronize()
+    for n in res:
+        for k, v in res[n][0].items():
+            assert torch.equal(v, outs[n][k]), (n, k)
+        nets[n].close()
