@@ -439,3 +439,25 @@ def test_two_instances_on_two_streams_do_not_interfere():
         for k, v in res[n][0].items():
             assert torch.equal(v, outs[n][k]), (n, k)
         nets[n].close()
+
+
+def test_create_destroy_returns_device_memory():
+    """Handles free what they allocate: device memory in use is back where it was after 25 create / step /
+    destroy rounds of the headline network at batch 1024 (each holds > 100 MB of buffers and weights)."""
+    import torch
+    cfg = wl.CONFIGS["C3"]
+    w = wl.make_weights(cfg)
+    dev = to_device(wl.make_batch(cfg, 64))
+    def round_():
+        net = seedinf.SeedInfer(seedinf.make_arch(cfg, max_batch=1024), w)
+        net.step(**dev)
+        torch.cuda.synchronize()
+        net.close()
+    round_()
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(25):
+        round_()
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < 32 * 1024 * 1024, (free0, free1)
