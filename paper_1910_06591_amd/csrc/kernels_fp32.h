@@ -21,9 +21,9 @@ __global__ __launch_bounds__(256) void conv2d_f32_kernel(
     const float* resid, float* y, int B, int H, int W, int Cin, int OH, int OW, int Cout, int k,
     int stride, int pad, int relu_in, int relu_out)
 {
-    size_t total = (size_t)B * OH * OW * Cout;
-    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
+    const size_t total = (size_t)B * OH * OW * Cout;
+    // grid-stride: the launch caps its grid, so any batch the workspace can hold stays within the launch limits
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
     int co = (int)(idx % Cout);
     size_t t = idx / Cout;
     int ow = (int)(t % OW); t /= OW;
@@ -62,6 +62,7 @@ __global__ __launch_bounds__(256) void conv2d_f32_kernel(
     if (resid) acc += resid[idx];
     if (relu_out) acc = fmaxf(acc, 0.0f);
     y[idx] = acc;
+    }
 }
 
 // 3x3 / stride 2 max-pool with SAME geometry; cells outside the image are skipped.
@@ -69,9 +70,8 @@ __global__ __launch_bounds__(256) void maxpool3x3s2_f32_kernel(
     const float* __restrict__ x, float* __restrict__ y, int B, int H, int W, int C, int OH, int OW,
     int pad_h, int pad_w, int relu_out)
 {
-    size_t total = (size_t)B * OH * OW * C;
-    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
+    const size_t total = (size_t)B * OH * OW * C;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
     int c = (int)(idx % C);
     size_t t = idx / C;
     int ow = (int)(t % OW); t /= OW;
@@ -89,12 +89,13 @@ __global__ __launch_bounds__(256) void maxpool3x3s2_f32_kernel(
     }
     if (relu_out) m = fmaxf(m, 0.0f);
     y[idx] = m;
+    }
 }
 
 __global__ __launch_bounds__(256) void relu_f32_kernel(const float* __restrict__ x, float* __restrict__ y, size_t n)
 {
-    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx < n) y[idx] = fmaxf(x[idx], 0.0f);
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x)
+        y[idx] = fmaxf(x[idx], 0.0f);
 }
 
 // y[b, o] = act(bias[o] + sum_i x[b, i] * w[i, o]).  One wavefront per (row, 64-output group) would idle at
@@ -186,8 +187,8 @@ __global__ __launch_bounds__(256) void lstm_f32_kernel(
 // Conversions used by the diagnostic tap.
 __global__ __launch_bounds__(256) void copy_f32_kernel(const float* __restrict__ x, float* __restrict__ y, size_t n)
 {
-    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx < n) y[idx] = x[idx];
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x)
+        y[idx] = x[idx];
 }
 
 }  // namespace seedinf

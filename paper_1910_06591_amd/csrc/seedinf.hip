@@ -160,7 +160,13 @@ extern "C" seed_status_t seed_infer_create(const seed_arch_t* arch, const float*
     return SEED_OK;
 }
 
-static inline unsigned blocks_for(size_t n, unsigned per = 256) { return (unsigned)((n + per - 1) / per); }
+// Blocks of `per` threads for n elements, capped at 2^22 (the elementwise kernels stride over what is left): a
+// launch's thread count stays far below 2^32 whatever the batch.
+static inline unsigned blocks_for(size_t n, unsigned per = 256)
+{
+    const size_t b = (n + per - 1) / per;
+    return (unsigned)(b < ((size_t)1 << 22) ? b : ((size_t)1 << 22));
+}
 
 static bool overlaps(const void* a, size_t na, const void* b, size_t nb)
 {

@@ -461,3 +461,20 @@ def test_create_destroy_returns_device_memory():
     torch.cuda.synchronize()
     free1, _ = torch.cuda.mem_get_info()
     assert free0 - free1 < 32 * 1024 * 1024, (free0, free1)
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_largest_batch_the_interface_allows(orc, precision):
+    """B = max_batch = 2^20 rows, the limit of the interface, on small networks: 8.6e9 activation values per
+    layer in fp32 mode (more than 2^32 elements: the elementwise kernels' capped grids) and an 11 GB feature
+    matrix in bf16 mode (element and byte offsets beyond 2^32); oracle on a sample of rows that includes the last one."""
+    B = 1 << 20
+    if precision == "fp32":
+        cfg = dict(label="largest batch, fp32", obs_h=18, obs_w=18, obs_c=1, torso=0, convs=[(32, 3, 1)], fc_units=16,
+                   lstm_units=8, num_actions=4, head=0, head_hidden=0, select=1, precision="fp32", obs_kind="uniform",
+                   index=120)
+    else:
+        cfg = dict(label="largest batch, bf16", obs_h=12, obs_w=16, obs_c=8, torso=0, convs=[(32, 2, 1)], fc_units=32,
+                   lstm_units=16, num_actions=5, head=1, head_hidden=16, select=0, precision="bf16", obs_kind="uniform",
+                   index=121)
+    run_full(orc, cfg, B, sample=64)
