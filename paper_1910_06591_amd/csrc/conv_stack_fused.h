@@ -180,17 +180,25 @@ __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2Tors
         {
             const floatx4 bias2 = *(const floatx4*)(p.b2 + f23 * 16 + g * 4);
             floatx4 acc[NT2];
-#pragma unroll
-            for (int t = 0; t < NT2; ++t) {
+            // the fragments of tile t + 1 are requested before tile t is multiplied
+            bf16x8 bq[2][8];
+            auto fetch2 = [&](int t, bf16x8 (&b)[8]) {
                 const int pix = min(t * 16 + n, NP2 - 1);
-                acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int kh = half * 2 + (i >> 2), kw = i & 3;                              // uniform
                     const int sub = ((kw >> 1) * 4 + g) * 4 + (kw & 1) * 2 + (kh & 1);
-                    const bf16x8 bf = *(const bf16x8*)(lds + ACT1_OFF + sub * A1_SUB + ((kh >> 1) * 9 + pix) * 16);
-                    acc[t] = mfma16(w2[i], bf, acc[t]);
+                    b[i] = *(const bf16x8*)(lds + ACT1_OFF + sub * A1_SUB + ((kh >> 1) * 9 + pix) * 16);
                 }
+            };
+            fetch2(0, bq[0]);
+#pragma unroll
+            for (int t = 0; t < NT2; ++t) {
+                if (t + 1 < NT2) fetch2(t + 1, bq[(t + 1) & 1]);
+                R2D2_TILE_FENCE;
+                acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[t] = mfma16(w2[i], bq[t & 1][i], acc[t]);
                 R2D2_TILE_FENCE;
             }
             // swap halves: K half 0 finishes tiles 0..2, K half 1 tiles 3..5
@@ -225,16 +233,23 @@ __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2Tors
         {
             const floatx4 bias3 = *(const floatx4*)(p.b3 + f23 * 16 + g * 4);
             floatx4 acc[NT3];
-#pragma unroll
-            for (int t = 0; t < NT3; ++t) {
+            bf16x8 bq[2][9];
+            auto fetch3 = [&](int t, bf16x8 (&b)[9]) {
                 const int pix = min(t * 16 + n, NP3 - 1);
-                acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int i = 0; i < 9; ++i) {
                     const int kc = half * 9 + i, tap = kc >> 1, kh = tap / 3, kw = tap - 3 * kh;     // uniform
-                    const bf16x8 bf = *(const bf16x8*)(lds + ACT2_OFF + ((kw * 8 + (kc & 1) * 4 + g) * A2_SUB) + (kh * 7 + pix) * 16);
-                    acc[t] = mfma16(w3[i], bf, acc[t]);
+                    b[i] = *(const bf16x8*)(lds + ACT2_OFF + ((kw * 8 + (kc & 1) * 4 + g) * A2_SUB) + (kh * 7 + pix) * 16);
                 }
+            };
+            fetch3(0, bq[0]);
+#pragma unroll
+            for (int t = 0; t < NT3; ++t) {
+                if (t + 1 < NT3) fetch3(t + 1, bq[(t + 1) & 1]);
+                R2D2_TILE_FENCE;
+                acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int i = 0; i < 9; ++i) acc[t] = mfma16(w3[i], bq[t & 1][i], acc[t]);
                 R2D2_TILE_FENCE;
             }
             floatx4* ex = (floatx4*)(lds + EX_OFF);
