@@ -237,7 +237,7 @@ template <int P>
 static bool launch_heads_rows(hipStream_t s, const HeadsArgs& ha)
 {
     constexpr int G = 64 / P;
-    const bool aligned = ((uintptr_t)ha.vec_a % 16 == 0) && ha.ld_a % 4 == 0;
+    const bool aligned = ((uintptr_t)ha.vec_a % 16 == 0) && ha.ld_a % 4 == 0 && ((uintptr_t)ha.vec_v % 16 == 0) && ha.ld_v % 4 == 0;
     if (!aligned || ha.n % 64 != 0) return false;
     auto go = [&](auto npl, auto ksc) {
         constexpr int NPL = decltype(npl)::value, KS = decltype(ksc)::value, RPB = 4 / KS;
