@@ -489,10 +489,18 @@ inline void launch_gemm(hipStream_t st, const GemmArgs& g, int tile_groups, int 
         };
         using W4 = std::integral_constant<int, 4>; using W8 = std::integral_constant<int, 8>;
         if constexpr (EPI == EPI_RELU) {
-            // small batches: 16 x 16 output tiles while those still number no more than the compute units; every
-            // unit then pulls a quarter of the weight bytes (measured: 5.8 vs 8.8 us up to 256 rows, slower from 512)
-            if ((long)((g.rows + 15) / 16) * g.n_ftiles <= n_cu) {
-                hipLaunchKernelGGL((gemm_bf16_splitk_kernel<1, EPI, 4, 1>), dim3((g.rows + 15) / 16, g.n_ftiles), dim3(256),
+            // small batches: the finest output tiles (16 x 16, else 16 x 32) that still number no more than the
+            // compute units: the kernel's time is the weight bytes one unit pulls (measured, K = 3456: 5.8 / 6.9 /
+            // 8.9 us for 16 / 32 / 64 features per tile, whatever the rows, until the tiles outnumber the units -
+            // then it doubles)
+            const long rt16 = (g.rows + 15) / 16;
+            if (rt16 * g.n_ftiles <= n_cu) {
+                hipLaunchKernelGGL((gemm_bf16_splitk_kernel<1, EPI, 4, 1>), dim3(rt16, g.n_ftiles), dim3(256),
+                                   4 * 1 * 4 * 64 * sizeof(floatx4), st, g);
+                return;
+            }
+            if (rt16 * ((g.n_ftiles + 1) / 2) <= n_cu) {
+                hipLaunchKernelGGL((gemm_bf16_splitk_kernel<1, EPI, 4, 2>), dim3(rt16, (g.n_ftiles + 1) / 2), dim3(256),
                                    4 * 1 * 4 * 64 * sizeof(floatx4), st, g);
                 return;
             }

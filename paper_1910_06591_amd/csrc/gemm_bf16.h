@@ -234,13 +234,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p)
 }
 
 // ---- long K: the block's 4 wavefronts share one output tile and split K ----
-// FT = feature tiles of the output tile: 4 (a whole group, every epilogue) or 1 (EPI_RELU only: small batches,
-// where 16 x 16 tiles put four times as many compute units to work on the weight matrix).
+// FT = feature tiles of the output tile: 4 (a whole group, every epilogue), or 2 or 1 (EPI_RELU only: small
+// batches, where 16 x 32 or 16 x 16 tiles put two or four times as many compute units to work on the weight matrix).
 template <int RT, int EPI, int NW, int FT = 4>
 __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
 {
     static_assert(NW == 4 || NW == 8, "4 or 8 wavefronts share the output tile");
-    static_assert(FT == 4 || (FT == 1 && EPI == EPI_RELU), "whole gate groups for the LSTM epilogue");
+    static_assert(FT == 4 || ((FT == 1 || FT == 2) && EPI == EPI_RELU), "whole gate groups for the LSTM epilogue");
     extern __shared__ __attribute__((aligned(16))) char gemm_lds[];     // partial sums [wave][row tile][feature tile][lane]
     floatx4* part = (floatx4*)gemm_lds;
     const int lane = threadIdx.x & 63;
@@ -312,21 +312,25 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
     if constexpr (FT == 4) {
         gemm_epilogue<RT, EPI>(p, acc, wave, wt, r0, lane);
     } else {
-        // one feature tile: bias, ReLU, store (row tile `wave` of this wavefront)
-        const int f = ft0 * 16 + g * 4;
-        const floatx4 bv = *(const floatx4*)(p.bias_pad + f);
+        // one or two feature tiles: bias, ReLU, store (row tile `wave` of this wavefront)
 #pragma unroll
-        for (int r = 0; r < RT; ++r) {
-            const int row = r0 + r * 16 + n;
-            if (r != wave || row >= p.rows) continue;
-            const floatx4 v = relu4(acc[r][0] + bv);
-            if (p.y_bf16) *(bf16x4*)(p.y_bf16 + (size_t)row * p.ldy_bf16 + f) = to_bf16x4(v);
-            if (p.y_f32) {
-                float* d = p.y_f32 + (size_t)row * p.ldy_f32 + f;
-                if (f + 4 <= p.n_out) *(floatx4*)d = v;
-                else
-                    for (int i = 0; i < 4; ++i)
-                        if (f + i < p.n_out) d[i] = v[i];
+        for (int j = 0; j < FT; ++j) {
+            if (ft0 + j >= p.n_ftiles) break;              // uniform
+            const int f = (ft0 + j) * 16 + g * 4;
+            const floatx4 bv = *(const floatx4*)(p.bias_pad + f);
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+                const int row = r0 + r * 16 + n;
+                if (r != wave || row >= p.rows) continue;
+                const floatx4 v = relu4(acc[r][j] + bv);
+                if (p.y_bf16) *(bf16x4*)(p.y_bf16 + (size_t)row * p.ldy_bf16 + f) = to_bf16x4(v);
+                if (p.y_f32) {
+                    float* d = p.y_f32 + (size_t)row * p.ldy_f32 + f;
+                    if (f + 4 <= p.n_out) *(floatx4*)d = v;
+                    else
+                        for (int i = 0; i < 4; ++i)
+                            if (f + i < p.n_out) d[i] = v[i];
+                }
             }
         }
     }
