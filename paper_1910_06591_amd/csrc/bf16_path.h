@@ -477,7 +477,9 @@ inline void launch_gemm(hipStream_t st, const GemmArgs& g, int tile_groups, int 
     // RT (row tiles of 16 per wavefront / block): the largest that still gives every compute unit two blocks
     const long want = 2L * n_cu;
     const int kct = g.kc1 + (g.k2 + 31) / 32;
-    if (kct >= 32) {
+    // (the LSTM of a 512-unit core has 32 chunks: for it the kernels below were measured faster from 512 rows on -
+    // 13.9 vs 16.2 us at 512 rows, 35 vs 60 us at 1984 - and equal below, so its gates take the long-K path from 64 chunks)
+    if (kct >= (EPI == EPI_LSTM ? 64 : 32)) {
         // long K: one block per (RT*16 rows, 4 feature tiles), K split over its wavefronts.  The loop is bound by
         // the load instructions each compute unit issues, so the largest tile that still gives every compute
         // unit a block wins, with 8 wavefronts to keep enough loads in flight.
@@ -517,9 +519,12 @@ inline void launch_gemm(hipStream_t st, const GemmArgs& g, int tile_groups, int 
                                4 * 1 * 4 * 64 * sizeof(floatx4), st, g);
             return;
         }
+        // otherwise a tile group per wavefront, whole K: the largest row tile that still gives (nearly) every compute
+        // unit a block (measured, 512-unit LSTM at 1984 rows: 35 / 36 / 43 us with 248 / 496 / 992 blocks)
         const int gy = (tile_groups + 3) / 4;
-        if ((long)((g.rows + 63) / 64) * gy >= want) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI>), dim3((g.rows + 63) / 64, gy), dim3(256), 0, st, g);
-        else if ((long)((g.rows + 31) / 32) * gy >= want) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI>), dim3((g.rows + 31) / 32, gy), dim3(256), 0, st, g);
+        const long enough = (long)n_cu * 7 / 8;
+        if ((long)((g.rows + 63) / 64) * gy >= enough) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI>), dim3((g.rows + 63) / 64, gy), dim3(256), 0, st, g);
+        else if ((long)((g.rows + 31) / 32) * gy >= enough) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI>), dim3((g.rows + 31) / 32, gy), dim3(256), 0, st, g);
         else hipLaunchKernelGGL((gemm_bf16_kernel<1, EPI>), dim3((g.rows + 15) / 16, gy), dim3(256), 0, st, g);
     }
 }
