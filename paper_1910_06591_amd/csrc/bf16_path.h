@@ -455,8 +455,13 @@ inline bool launch_gemm_lds(hipStream_t st, const GemmArgs& g, int tile_groups, 
     if (g.rows < GL_MIN_ROWS || (g.kc1 & 1)) return false;
     const int kct = g.kc1 + (g.k2 + 31) / 32;
     if constexpr (EPI == EPI_RELU) {
-        if (kct >= 64 && g.k2 == 0 && (long)((g.rows + 127) / 128) * ((tile_groups + 3) / 4) < n_cu) {
-            // long K, too few 128 x 256 tiles for the chip (the linear layer after the torso): 64 x 64 tiles
+        // 64 x 64 tiles with K over the eight wavefronts where wider tiles would be too few for the chip: long K
+        // (the linear layer after the torso) with fewer 128 x 256 tiles than compute units, and shorter K with
+        // fewer 64 x 256 tiles than half the units (the Football agent's 960 -> 256 layer at 2048 rows: 6.9 us
+        // against 16.2 with 32 tiles of 64 x 256)
+        const long wide = (long)((g.rows + 127) / 128) * ((tile_groups + 3) / 4);
+        const long mid = (long)((g.rows + 63) / 64) * ((tile_groups + 3) / 4);
+        if (g.k2 == 0 && ((kct >= 64 && wide < n_cu) || (kct >= 16 && kct < 64 && mid < n_cu / 2))) {
             hipLaunchKernelGGL((gemm_bf16_k8_kernel<EPI>), dim3((g.rows + 63) / 64, tile_groups), dim3(GL_THREADS), GL_K8_LDS_BYTES, st, g);
             return true;
         }

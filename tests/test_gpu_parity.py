@@ -206,9 +206,12 @@ def test_full_size_c5_sweep(orc, B, sample):
     ("R2D2 net at ragged batch 2050", "C2", {}, 2050, 64),
     ("Football torso + LSTM-128 at batch 2100", "C4", dict(lstm_units=128), 2100, 64),
     ("DMLab net, 96 linear units, batch 2048", "C3", dict(fc_units=96), 2048, 48),
+    ("R2D2 net at batch 1600", "C2", {}, 1600, 48),
+    ("Football net at batch 1537", "C4", {}, 1537, 48),
+    ("DMLab net at batch 1536", "C3", {}, 1536, 48),
 ])
 def test_large_batch_dense_layers(orc, label, base, over, B, sample):
-    """From 2048 rows on the linear layer, the recurrent core and the dueling hidden layers run LDS-staged GEMM
+    """From 1536 rows on the linear layer, the recurrent core and the dueling hidden layers run LDS-staged GEMM
     kernels; these cases cover the tilings the C5 sweep does not reach (512 linear units, 128 x 256 tiles for
     the 512-unit core, hidden layers fed by fp32 rows only, a ragged last tile, a 128-unit core) and a linear
     width whose odd chunk count keeps the direct kernels."""
@@ -341,10 +344,10 @@ def test_bf16_direct_dense_kernels_with_chunk_counts_of_every_residue(orc, fc_un
 @pytest.mark.parametrize("seed", range(16))
 def test_bf16_random_dense_widths_at_large_batch(orc, seed):
     """Seeded random widths of the linear layer, the core and the heads behind a small conv layer, at batches
-    from 2048 rows (LDS-staged dense kernels where their shape rules allow, direct kernels elsewhere), with
+    from 1536 rows (LDS-staged dense kernels where their shape rules allow, direct kernels elsewhere), with
     ragged last tiles; oracle on a sample of rows."""
     rng = np.random.default_rng(500 + seed)
-    B = int(rng.choice([2048, 2049, 2200, 3000, 4100]))
+    B = int(rng.choice([1536, 1700, 2048, 2049, 2200, 3000, 4100]))
     head = int(rng.integers(0, 2))
     cfg = dict(label=f"random dense widths {seed}", obs_h=int(rng.choice([10, 11, 14, 15, 18])), obs_w=int(rng.choice([16, 24])),
                obs_c=8, torso=0, convs=[(int(rng.choice([16, 32, 48])), 4, 2)], fc_units=16 * int(rng.integers(1, 25)),
