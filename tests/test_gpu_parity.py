@@ -368,7 +368,7 @@ def test_bf16_persistent_grid_edges_of_the_other_fused_torsos(orc, name, B):
     run_full(orc, wl.CONFIGS[name], B, sample=48)
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(16))
 def test_bf16_random_layerwise_resnets(orc, seed):
     """Layer-by-layer ResNets with random odd image sizes and random channel counts in multiples of 16 and of 32
     (the LDS-tiled 3x3 kernel takes layers whose input channels are a multiple of 32, the gather kernel the rest),
@@ -385,7 +385,7 @@ def test_bf16_random_layerwise_resnets(orc, seed):
     run_case(orc, cfg, int(rng.integers(1, 8)), "bf16")
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(32))
 def test_bf16_random_conv_stacks_and_wide_action_sets(orc, seed):
     """Layer-by-layer bf16 conv stacks over the (channels, kernel) pairs their implicit-GEMM kernel covers
     (k * Cin and stride * Cin multiples of 8, k * k * Cin of 32), up to three layers; heads with up to 64
