@@ -206,6 +206,39 @@ seed_status_t seed_infer_step_ext(seed_infer_t* handle, int32_t B,
                                   void* hip_stream);
 
 /*
+ * seed_infer_step_ext for callers that cannot allocate device memory or want
+ * none allocated on their behalf at run time: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and same results as seed_infer_step_ext, but the activations between
+ * the kernels (torso features, linear-layer rows, dueling hidden rows, the
+ * layer-by-layer paths' maps) live in a static device array of
+ * SEED_STATIC_SCRATCH_BYTES that is part of the library's code object (each
+ * GPU the library runs on holds its own copy until the process ends), not in
+ * the handle's workspace.  The call itself makes no hipMalloc / hipFree and no
+ * allocating library call, records no memset, and does not synchronise.
+ *
+ *   - The rows must fit: a B whose workspace exceeds SEED_STATIC_SCRATCH_BYTES
+ *     is rejected with SEED_ERR_BATCH_TOO_LARGE and a message that states the
+ *     bytes needed (e.g. the DeepMind Lab agent in bf16 mode takes 8448 bytes
+ *     per row: up to 1985 rows).  B > max_batch is rejected as usual.
+ *   - All calls on one GPU, from any handle, share that GPU's array, and it
+ *     keeps the previous call's contents (what has to start at zero is cleared
+ *     by a fill kernel on the stream).  Calls that overlap in time on one GPU
+ *     race: order them on one stream or with events.
+ *   - seed_infer_read_intermediate reads the handle's own workspace, not this
+ *     one.
+ */
+#define SEED_STATIC_SCRATCH_BYTES (16u << 20)
+seed_status_t seed_infer_step_static(seed_infer_t* handle, int32_t B,
+                                     const uint8_t* obs,
+                                     const int32_t* prev_action, const float* prev_reward,
+                                     const float* h_in, const float* c_in,
+                                     const float* uniforms, const seed_step_ext_t* ext,
+                                     int32_t* action_out, float* logits_out, float* value_out,
+                                     float* h_out, float* c_out, float* probs_out,
+                                     void* hip_stream);
+
+/*
  * T-step unroll: the forward pass over stored trajectories, time-major
  * (Section 3: the learner unrolls trajectories step by step with the stored
  * recurrent state; Appendix A lists the unroll length, 32 for the V-trace

@@ -42,6 +42,29 @@ struct seed_infer {
 
 static thread_local std::string g_create_err;
 
+// ---- workspace in the library's static device array (seed_infer_step_static) ----
+// Device memory beyond a step's inputs and outputs: the activations between the kernels.  The handle's own copy is
+// allocated at creation; this one is part of the loaded code object, one instance per GPU.
+static __device__ __align__(256) unsigned char seed_static_scratch[SEED_STATIC_SCRATCH_BYTES];
+
+constexpr int SEED_MAX_DEVICES = 64;
+static void* g_scratch_ptr[SEED_MAX_DEVICES] = {};    // device address of seed_static_scratch on each GPU
+
+// Address of the current device's instance of the array; looked up once per device (no allocation).
+static hipError_t scratch_address(int dev, void** out)
+{
+    if (dev < 0 || dev >= SEED_MAX_DEVICES) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(seed_static_scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+
 #define HIP_TRY(h, expr)                                                              \
     do {                                                                              \
         hipError_t e_ = (expr);                                                       \
@@ -130,6 +153,8 @@ static seed_status_t create_impl(seed_infer* h, const float* weights_host)
     h->staging_bytes = p.n_weights * sizeof(float) + (h->bf ? h->bf->pk_bytes + h->bf->fb_bytes : 0);
     HIP_TRY(h, hipHostMalloc((void**)&h->staging, h->staging_bytes, hipHostMallocDefault));
     HIP_TRY(h, hipEventCreateWithFlags(&h->staged, hipEventDisableTiming));
+    void* scratch = nullptr;                   // seed_infer_step_static's workspace on this device
+    HIP_TRY(h, scratch_address(h->device, &scratch));
     HIP_TRY(h, hipDeviceSynchronize());
     return SEED_OK;
 }
@@ -354,12 +379,86 @@ extern "C" seed_status_t seed_infer_step(seed_infer_t* h, int32_t B, const uint8
                                value_out, h_out, c_out, probs_out, hip_stream);
 }
 
-extern "C" seed_status_t seed_infer_step_ext(seed_infer_t* h, int32_t B, const uint8_t* obs,
-                                             const int32_t* prev_action, const float* prev_reward,
-                                             const float* h_in, const float* c_in, const float* uniforms,
-                                             const seed_step_ext_t* ext,
-                                             int32_t* action_out, float* logits_out, float* value_out,
-                                             float* h_out, float* c_out, float* probs_out, void* hip_stream)
+// The per-step workspace pointers of a handle.
+struct WorkspacePtrs {
+    float* d_act[2]; float* d_fc; float* d_hid;
+    __bf16* bact[2]; __bf16* lw_c0; __bf16* lw_r; __bf16* lw_u; float* lw_x;
+    __bf16* feat; __bf16* fc_bf16; float* fc_f32;
+};
+
+static WorkspacePtrs workspace_get(const seed_infer* h)
+{
+    WorkspacePtrs w{};
+    w.d_act[0] = h->d_act[0]; w.d_act[1] = h->d_act[1]; w.d_fc = h->d_fc; w.d_hid = h->d_hid;
+    if (const Bf16State* b = h->bf) {
+        w.bact[0] = b->act[0]; w.bact[1] = b->act[1]; w.lw_c0 = b->lw_c0; w.lw_r = b->lw_r; w.lw_u = b->lw_u; w.lw_x = b->lw_x;
+        w.feat = b->feat; w.fc_bf16 = b->fc_bf16; w.fc_f32 = b->fc_f32;
+    }
+    return w;
+}
+
+static void workspace_set(seed_infer* h, const WorkspacePtrs& w)
+{
+    h->d_act[0] = w.d_act[0]; h->d_act[1] = w.d_act[1]; h->d_fc = w.d_fc; h->d_hid = w.d_hid;
+    if (Bf16State* b = h->bf) {
+        b->act[0] = w.bact[0]; b->act[1] = w.bact[1]; b->lw_c0 = w.lw_c0; b->lw_r = w.lw_r; b->lw_u = w.lw_u; b->lw_x = w.lw_x;
+        b->feat = w.feat; b->fc_bf16 = w.fc_bf16; b->fc_f32 = w.fc_f32;
+    }
+}
+
+// Lay a step's workspace for B rows out from `base` (the same pieces seed_infer_create allocates for max_batch
+// rows); returns the bytes it takes.  With base == nullptr only the size is computed.
+static size_t workspace_carve(const seed_infer* h, int B, char* base, WorkspacePtrs& w)
+{
+    const Plan& p = h->plan;
+    const seed_arch_t& a = p.arch;
+    const size_t rows = (size_t)B;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* at = base ? base + off : nullptr; off += (bytes + 255) / 256 * 256; return at; };
+    w = WorkspacePtrs{};
+    if (a.head == SEED_HEAD_DUELING_Q) w.d_hid = (float*)take(rows * 2 * a.head_hidden * sizeof(float));
+    if (a.precision == SEED_PRECISION_FP32) {
+        w.d_act[0] = (float*)take(rows * p.max_act * sizeof(float));
+        w.d_act[1] = (float*)take(rows * p.max_act * sizeof(float));
+        w.d_fc = (float*)take(rows * a.fc_units * sizeof(float));
+        return off;
+    }
+    const Bf16State* b = h->bf;
+    if (a.torso == SEED_TORSO_CONV_STACK && p.convs.size() > 1 && !b->stack_fused) {
+        size_t m = 0;
+        for (size_t l = 0; l + 1 < p.convs.size(); ++l) m = std::max(m, (size_t)p.convs[l].OH * p.convs[l].OW * p.convs[l].Cout);
+        w.bact[0] = (__bf16*)take(rows * m * 2);
+        w.bact[1] = (__bf16*)take(rows * m * 2);
+    }
+    if (a.torso == SEED_TORSO_RESNET && b->torso_kind == TORSO_NONE) {
+        size_t m0 = 0, m1 = 0;
+        for (const Section& sec : p.sections) {
+            m0 = std::max(m0, (size_t)sec.conv0.OH * sec.conv0.OW * sec.conv0.Cout);
+            m1 = std::max(m1, (size_t)sec.PH * sec.PW * sec.conv0.Cout);
+        }
+        w.lw_c0 = (__bf16*)take(rows * m0 * 2);
+        w.lw_r = (__bf16*)take(rows * m1 * 2);
+        w.lw_u = (__bf16*)take(rows * m1 * 2);
+        w.lw_x = (float*)take(rows * m1 * 4);
+    }
+    w.feat = (__bf16*)take(rows * b->ldf * 2);
+    w.fc_bf16 = (__bf16*)take(rows * b->ldfc * 2);
+    w.fc_f32 = (float*)take(rows * a.fc_units * 4);
+    return off;
+}
+
+__global__ __launch_bounds__(256) void zero_fill16_kernel(uint4* __restrict__ p, size_t n16)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = uint4{0u, 0u, 0u, 0u};
+}
+
+static seed_status_t step_impl(seed_infer_t* h, int32_t B, const uint8_t* obs,
+                               const int32_t* prev_action, const float* prev_reward,
+                               const float* h_in, const float* c_in, const float* uniforms,
+                               const seed_step_ext_t* ext,
+                               int32_t* action_out, float* logits_out, float* value_out,
+                               float* h_out, float* c_out, float* probs_out, void* hip_stream, bool static_ws)
 {
     if (!h) return SEED_ERR_INVALID_ARG;
     const Plan& p = h->plan;
@@ -398,10 +497,69 @@ extern "C" seed_status_t seed_infer_step_ext(seed_infer_t* h, int32_t B, const u
     if (dev != h->device) return fail(SEED_ERR_INVALID_ARG, "current HIP device differs from the handle's device");
 
     hipStream_t s = (hipStream_t)hip_stream;
+    if (!static_ws) {
+        seed_status_t st = run_torso_fc(h, s, B, obs);
+        if (st != SEED_OK) return st;
+        return run_core_heads(h, s, 0, B, prev_action, prev_reward, h_in, c_in, done, h_out, c_out, uniforms, epsilon, explore_u,
+                              action_out, logits_out, value_out, probs_out);
+    }
+    // The same kernels on a workspace laid out in the static array.  Only host-side pointers change hands: the
+    // kernels receive theirs by value at launch, and a handle is used from one thread at a time.
+    WorkspacePtrs ws;
+    const size_t need = workspace_carve(h, B, nullptr, ws);
+    if (need > (size_t)SEED_STATIC_SCRATCH_BYTES) {
+        char msg[200];
+        snprintf(msg, sizeof msg, "B = %d needs %zu bytes of workspace; the static workspace holds %u (use seed_infer_step)",
+                 B, need, (unsigned)SEED_STATIC_SCRATCH_BYTES);
+        h->err = msg;
+        return SEED_ERR_BATCH_TOO_LARGE;
+    }
+    void* base = nullptr;
+    HIP_TRY(h, scratch_address(dev, &base));
+    workspace_carve(h, B, (char*)base, ws);
+    if (h->bf) {
+        // rows of the feature and linear-layer matrices are padded to whole K chunks; the dense kernels read the
+        // padding (against zero weights), and the array keeps whatever the previous call left there
+        const Bf16State* b = h->bf;
+        if ((size_t)b->ldf != p.flat) {
+            const size_t n16 = ((size_t)B * b->ldf * 2 + 15) / 16;
+            hipLaunchKernelGGL(zero_fill16_kernel, dim3(blocks_for(n16)), dim3(256), 0, s, (uint4*)ws.feat, n16);
+        }
+        if (b->ldfc != a.fc_units) {
+            const size_t n16 = ((size_t)B * b->ldfc * 2 + 15) / 16;
+            hipLaunchKernelGGL(zero_fill16_kernel, dim3(blocks_for(n16)), dim3(256), 0, s, (uint4*)ws.fc_bf16, n16);
+        }
+    }
+    const WorkspacePtrs own = workspace_get(h);
+    workspace_set(h, ws);
     seed_status_t st = run_torso_fc(h, s, B, obs);
-    if (st != SEED_OK) return st;
-    return run_core_heads(h, s, 0, B, prev_action, prev_reward, h_in, c_in, done, h_out, c_out, uniforms, epsilon, explore_u,
-                          action_out, logits_out, value_out, probs_out);
+    if (st == SEED_OK)
+        st = run_core_heads(h, s, 0, B, prev_action, prev_reward, h_in, c_in, done, h_out, c_out, uniforms, epsilon, explore_u,
+                            action_out, logits_out, value_out, probs_out);
+    workspace_set(h, own);
+    return st;
+}
+
+extern "C" seed_status_t seed_infer_step_ext(seed_infer_t* h, int32_t B, const uint8_t* obs,
+                                             const int32_t* prev_action, const float* prev_reward,
+                                             const float* h_in, const float* c_in, const float* uniforms,
+                                             const seed_step_ext_t* ext,
+                                             int32_t* action_out, float* logits_out, float* value_out,
+                                             float* h_out, float* c_out, float* probs_out, void* hip_stream)
+{
+    return step_impl(h, B, obs, prev_action, prev_reward, h_in, c_in, uniforms, ext, action_out, logits_out, value_out,
+                     h_out, c_out, probs_out, hip_stream, false);
+}
+
+extern "C" seed_status_t seed_infer_step_static(seed_infer_t* h, int32_t B, const uint8_t* obs,
+                                                const int32_t* prev_action, const float* prev_reward,
+                                                const float* h_in, const float* c_in, const float* uniforms,
+                                                const seed_step_ext_t* ext,
+                                                int32_t* action_out, float* logits_out, float* value_out,
+                                                float* h_out, float* c_out, float* probs_out, void* hip_stream)
+{
+    return step_impl(h, B, obs, prev_action, prev_reward, h_in, c_in, uniforms, ext, action_out, logits_out, value_out,
+                     h_out, c_out, probs_out, hip_stream, true);
 }
 
 extern "C" seed_status_t seed_infer_unroll(seed_infer_t* h, int32_t T, int32_t B, const uint8_t* obs,

@@ -27,7 +27,7 @@ STATUS = {0: "SEED_OK", 1: "SEED_ERR_INVALID_ARG", 2: "SEED_ERR_UNSUPPORTED_ARCH
           4: "SEED_ERR_ALIASING", 5: "SEED_ERR_DEVICE", 6: "SEED_ERR_OOM"}
 STATUS_BY_NAME = {v: k for k, v in STATUS.items()}
 EXPORTS = ["seed_infer_weight_count", "seed_infer_validate", "seed_infer_create", "seed_infer_step",
-           "seed_infer_step_ext", "seed_infer_unroll", "seed_infer_set_weights",
+           "seed_infer_step_ext", "seed_infer_step_static", "seed_infer_unroll", "seed_infer_set_weights",
            "seed_batcher_create", "seed_batcher_add", "seed_batcher_reserve", "seed_batcher_add_many", "seed_batcher_submit", "seed_batcher_wait",
            "seed_batcher_read_state", "seed_batcher_stream", "seed_batcher_last_error", "seed_batcher_destroy",
            "seed_infer_read_intermediate", "seed_infer_torso_features", "seed_infer_last_error",
@@ -115,6 +115,8 @@ def load_library():
     lib.seed_infer_read_intermediate.restype = C.c_int
     lib.seed_infer_step_ext.restype = C.c_int
     lib.seed_infer_step_ext.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 6 + [C.POINTER(SeedStepExt)] + [C.c_void_p] * 7
+    lib.seed_infer_step_static.restype = C.c_int
+    lib.seed_infer_step_static.argtypes = lib.seed_infer_step_ext.argtypes
     lib.seed_infer_set_weights.restype = C.c_int
     lib.seed_infer_unroll.restype = C.c_int
     lib.seed_infer_unroll.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 14
@@ -254,11 +256,13 @@ class SeedInfer:
             raise SeedError(st, self.lib.seed_infer_last_error(self._h).decode())
 
     def step(self, obs, prev_action=None, prev_reward=None, h_in=None, c_in=None, uniforms=None,
-             want_probs=True, out=None, stream=None, done=None, epsilon=None, explore_uniforms=None):
+             want_probs=True, out=None, stream=None, done=None, epsilon=None, explore_uniforms=None,
+             static_workspace=False):
         """Run one inference step on device tensors; returns a dict of device
         tensors (allocated here with torch unless `out` supplies them).  done [B] uint8,
         epsilon [B] and explore_uniforms [B, 2] are the optional episode flags and
-        epsilon-greedy inputs (seed_infer_step_ext)."""
+        epsilon-greedy inputs (seed_infer_step_ext).  static_workspace=True calls
+        seed_infer_step_static (the library's static device workspace) instead."""
         import torch
         a = self.arch
         B = obs.shape[0]
@@ -280,7 +284,8 @@ class SeedInfer:
                               addr(_ptr(done, torch.uint8, (B,), "done")),
                               addr(_ptr(epsilon, torch.float32, (B,), "epsilon")),
                               addr(_ptr(explore_uniforms, torch.float32, (B, 2), "explore_uniforms")))
-        st = self.lib.seed_infer_step_ext(
+        entry = self.lib.seed_infer_step_static if static_workspace else self.lib.seed_infer_step_ext
+        st = entry(
             self._h, B,
             _ptr(obs, torch.uint8, (B, a.obs_h, a.obs_w, a.obs_c), "obs"),
             _ptr(prev_action, torch.int32, (B,), "prev_action"),
