@@ -21,7 +21,7 @@ SOURCES = [os.path.join(_PKG, "csrc", f) for f in
 PROBE_SOURCE = os.path.join(_PKG, "csrc", "probe.hip")
 PROBE_LIB_PATH = os.path.join(_PKG, "libseedprobe.so")
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-fno-honor-nans"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 STATUS = {0: "SEED_OK", 1: "SEED_ERR_INVALID_ARG", 2: "SEED_ERR_UNSUPPORTED_ARCH", 3: "SEED_ERR_BATCH_TOO_LARGE",
           4: "SEED_ERR_ALIASING", 5: "SEED_ERR_DEVICE", 6: "SEED_ERR_OOM"}

@@ -97,3 +97,18 @@ def random_arch(seed, precision):
             h, w = (h - k) // s + 1, (w - k) // s + 1
         cfg["convs"] = convs or [(16 if bf else 5, 2, 1)]
     return cfg
+
+
+def supported_random_arch(seed, precision):
+    """random_arch(seed), or the first of random_arch(seed + 1000), random_arch(seed + 2000), ... that the library's
+    host-side validation accepts in this precision (a bf16 draw can land on a shape no bf16 kernel covers, such as
+    a flattened conv-stack output that is not whole 32-value chunks).  Validation touches no device."""
+    from paper_1910_06591_amd import seedinf
+    for attempt in range(50):
+        cfg = random_arch(seed + 1000 * attempt, precision)
+        cfg["label"] = f"random arch {seed} ({precision})"
+        cfg["index"] = 60 + seed
+        st, _ = seedinf.validate(seedinf.make_arch(cfg, max_batch=8, precision=precision))
+        if st == 0:
+            return cfg
+    raise AssertionError(f"no supported architecture near seed {seed}")

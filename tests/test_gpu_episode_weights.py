@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 from paper_1910_06591_amd import seedinf, workloads as wl
-from tests.parity import check_against_oracle, random_arch, to_device
+from tests.parity import check_against_oracle, supported_random_arch, to_device
 
 pytestmark = pytest.mark.gpu
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
@@ -62,10 +62,9 @@ def test_ext_fp32(orc, name, B):
 @pytest.mark.parametrize("seed,precision", [(s, p) for p in ("fp32", "bf16") for s in range(8)])
 def test_ext_random_architectures(orc, seed, precision):
     """Episode flags and epsilon-greedy on seeded random architectures."""
-    cfg = random_arch(200 + seed, precision)
+    cfg = supported_random_arch(200 + seed, precision)
     st, msg = seedinf.validate(seedinf.make_arch(cfg, max_batch=64, precision=precision))
-    if st == seedinf.STATUS_BY_NAME["SEED_ERR_UNSUPPORTED_ARCH"]:
-        pytest.skip(msg)
+    assert st == 0, (cfg, msg)
     ext_case(orc, cfg, 19, precision)
 
 

@@ -6,7 +6,7 @@ import pytest
 
 import oracle
 from paper_1910_06591_amd import seedinf, workloads as wl
-from tests.parity import check_against_oracle, random_arch
+from tests.parity import check_against_oracle, supported_random_arch
 
 pytestmark = pytest.mark.gpu
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
@@ -62,10 +62,9 @@ def test_unroll_bf16(orc, name, T, B):
 def test_unroll_random_architectures(orc, seed, precision):
     """The unroll on seeded random architectures (recurrent and feed-forward, both heads and selections), random T
     and B."""
-    cfg = random_arch(100 + seed, precision)
+    cfg = supported_random_arch(100 + seed, precision)
     st, msg = seedinf.validate(seedinf.make_arch(cfg, max_batch=64, precision=precision))
-    if st == seedinf.STATUS_BY_NAME["SEED_ERR_UNSUPPORTED_ARCH"]:
-        pytest.skip(msg)
+    assert st == 0, (cfg, msg)
     rng = np.random.default_rng(seed)
     unroll_case(orc, cfg, int(rng.integers(1, 7)), int(rng.integers(1, 10)), precision)
 
