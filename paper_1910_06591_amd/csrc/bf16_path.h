@@ -22,8 +22,8 @@ namespace seedinf {
 // ---- the deep-ResNet torsos this build has fused kernels for ----------------
 // DMLab-shaped: 72x96x3 frames, sections 16/32/32.
 using DmS1 = SecCfg<72, 96, 3, 16, IN_U8_C3, 4, 36>;
-using DmS2 = SecCfg<36, 48, 16, 32, IN_LDS, 8, 0>;
-using DmS3 = SecCfg<18, 24, 32, 32, IN_LDS, 4, 0, 8>;
+using DmS2 = SecCfg<36, 48, 16, 32, IN_LDS, 8, 0, 8, 2, 0>;     // pooled map 18 x 24 with a 28-cell pitch (TileMap1824)
+using DmS3 = SecCfg<18, 24, 32, 32, IN_LDS, 4, 0, 8, 0, 2>;
 // Football-shaped: 72x96x16 minimap planes, sections 16/32/32/32.
 using FbS1 = SecCfg<72, 96, 16, 16, IN_U8_PLANAR, 4, 8>;
 using FbS4 = SecCfg<9, 12, 32, 32, IN_LDS, 5, 0, 2>;

@@ -66,6 +66,13 @@ __device__ unsigned long long seed_phase_cycles[32];
 #define PHASE_DECL do { } while (0)
 #endif
 
+#ifdef SEEDINF_TRACE
+__device__ unsigned long long seed_trace[8][64];
+#define TR(k) do { if (tr && lane == 0) seed_trace[wave][k] = clock64(); } while (0)
+#else
+#define TR(k) do { } while (0)
+#endif
+
 #ifndef SEEDINF_RN_WAVES
 #define SEEDINF_RN_WAVES 8
 #endif
@@ -101,9 +108,12 @@ __device__ __forceinline__ void lds_barrier()
 //   NB = bands of pooled rows per conv0 pass, SR = pooled rows per input strip
 //   (uint8 sections only; IN_LDS sections have their whole input resident), NWA = wavefronts that
 //   own pooled tiles: small maps use fewer, so fewer wavefronts re-read the layer's whole A operand.
-template <int H_, int W_, int CIN_, int C_, int INKIND_, int NB_, int SR_, int NWA_ = RN_WAVES>
+//   PADX / IPADX = unused cells at the end of every row of the section's pooled maps / of its LDS input map
+//   (which is the previous section's pooled map, so IPADX must be that section's PADX): a row pitch chosen so
+//   that the tiles' fragment reads are free of LDS bank conflicts (see TileMap1824).
+template <int H_, int W_, int CIN_, int C_, int INKIND_, int NB_, int SR_, int NWA_ = RN_WAVES, int PADX_ = 0, int IPADX_ = 0>
 struct SecCfg {
-    static constexpr int H = H_, W = W_, CIN = CIN_, C = C_, INKIND = INKIND_, NB = NB_;
+    static constexpr int H = H_, W = W_, CIN = CIN_, C = C_, INKIND = INKIND_, NB = NB_, PADX = PADX_, IPADX = IPADX_;
     static constexpr int PH = (H + 1) / 2, PW = (W + 1) / 2;
     static constexpr int PADH = (((PH - 1) * 2 + 3 - H) > 0 ? ((PH - 1) * 2 + 3 - H) : 0) / 2;
     static constexpr int SR = INKIND == IN_LDS ? PH : SR_;
@@ -131,23 +141,25 @@ struct SecCfg {
     // Small 32 -> 32 channel sections write conv0's full-resolution output to LDS as a planar map (conv_map)
     // and pool it while the residual stream is read: on a map this narrow the strip scheme wastes half of its
     // second column strip and its per-row pooling costs more than the extra LDS round trip.
-    static constexpr int CM_BYTES = (C / 8) * (((H + 2) * (W + 2) + 15) / 16 * 16) * 16;
+    static constexpr int CM_BYTES = (C / 8) * (((H + 2) * (W + 2 + IPADX_) + 15) / 16 * 16) * 16;
     static constexpr bool CONVMAP = INKIND == IN_LDS && CIN == 32 && C == 32 && CM_BYTES <= 36 * 1024;
     static constexpr int NPIX = PH * PW;
     static constexpr int NTILES = (NPIX + 15) / 16;
-    static constexpr int NT = SLIDE ? 14 : (NTILES + NWA - 1) / NWA;
+    // 32 channels on the 18 x 24 pooled map with a 28-cell pitch: conflict-free tiles in sliding chains (TileMap1824)
+    static constexpr bool V2 = C == 32 && PH == 18 && PW == 24 && PADX == 2 && NWA == 8 && RN_WAVES == 8;
+    static constexpr int NT = SLIDE ? 14 : (V2 ? 4 : (NTILES + NWA - 1) / NWA);
     static constexpr int NCS = (W + 15) / 16;               // 16-column strips of the conv0 output
     static constexpr int NUNITS = NCS * NB;
     static constexpr int NU = (NUNITS + RN_WAVES - 1) / RN_WAVES;
     // input map of conv0 as it sits in buf0
     static constexpr int IROWS = INKIND == IN_LDS ? H + 2 : (2 * SR + 1 < H ? 2 * SR + 1 : H) + 2;
-    static constexpr int IPITCH = W + 2;
+    static constexpr int IPITCH = W + 2 + IPADX;
     static constexpr int ICELL = INKIND == IN_U8_C3 ? 8 : 16;
     // plane strides are multiples of 16 cells (256 B): a ds_read_b128 whose two lane groups of a half-wave sit
     // a non-multiple of 256 B (and more than 64 B) apart runs at about 60 % rate on this LDS
     static constexpr int IPLANE = (IROWS * IPITCH + 15) / 16 * 16;
     static constexpr int IN_BYTES = (INKIND == IN_U8_C3 ? 1 : CIN / 8) * IPLANE * ICELL + 16;
-    static constexpr int PITCH = PW + 2, PLANE = ((PH + 2) * PITCH + 15) / 16 * 16;
+    static constexpr int PITCH = PW + 2 + PADX, PLANE = ((PH + 2) * PITCH + 15) / 16 * 16;
     static constexpr int ACT_BYTES = (C / 8) * PLANE * 16;
     static constexpr int EDGE_BYTES = POOL3 || CONVMAP ? 0 : NCS * PH * C * 2;
     // prefetch registers for the uint8 input: items of PRE_DW dwords, PRE_N per thread
@@ -163,6 +175,7 @@ struct SecCfg {
     static_assert(INKIND != IN_U8_C3 || ((W * 3) % 4 == 0 && W % 4 == 0), "3-channel rows must be whole dwords");
     static_assert(INKIND != IN_U8_PLANAR || CIN == 16, "planar uint8 input: 16 channels");
     static_assert(INKIND != IN_U8_C3 || NSTRIPS == 1, "the 3-channel frame is kept whole");
+    static_assert(INKIND == IN_LDS || IPADX == 0, "only LDS input maps carry a pitch pad");
 };
 
 struct SecWeights {
@@ -271,6 +284,42 @@ struct SlideMap16 {
         else if (wave < 2) { strip = wave; row0 = 32; nt = 4; }
         else { strip = 2; row0 = (wave - 2) * 6; nt = 6; }
     }
+};
+
+// ---- tiles of the 18 x 24 maps (32 channels) ----------------------------------------------
+// LDS serves a 16-byte read of 16 lanes at full rate only when their 256 bytes fall on 256 distinct bank bytes
+// (measured: a tile of 16 row-major pixels that wraps from one 24-pixel row to the next, two halo cells further,
+// reads at 57 % of that).  The 27 tiles of this map are therefore
+//   strip A: columns 0..15 of one row (18 tiles, 256 contiguous bytes), and
+//   strip B: columns 16..23 of the two rows (r, r + 10), r = 0..7: with a pitch of 28 cells the rows sit
+//            10 * 28 * 16 = 17.5 * 256 bytes apart, i.e. on the other half of the banks; rows 8 and 9 form the
+//            one tile left over (adjacent rows: its reads do conflict, one tile in 27),
+// and consecutive tiles of a strip (r -> r + 1) form a chain: the window rows r, r+1 of tile r are the rows
+// r-1+1, r+1 ... of tile r + 1, so a wavefront that walks down a chain reads three new fragments per tile
+// instead of nine.  Wavefront w owns at most four consecutive tiles:
+//   w0..w2: A rows 4w .. 4w+3;  w3: A 12..14;  w4: A 15..17;  w5: B r = 0..2;  w6: B r = 3..5;
+//   w7: B r = 6, 7 and the left-over tile (a new chain).
+// On a SIMD (wavefronts w and w + 4) that makes 7, 7, 7 and 6 tiles.
+struct TileMap1824 {
+    static constexpr int NT = 4;
+    __device__ static __forceinline__ int ntiles(int wave) { return wave < 3 ? 4 : 3; }
+    // pixel (y, xx) that lane n holds in slot i of `wave` (a missing slot repeats the last one)
+    __device__ static __forceinline__ void pixel(int wave, int i, int n, int& y, int& xx, bool& ok)
+    {
+        const int nt = ntiles(wave);
+        ok = i < nt;
+        const int ii = ok ? i : nt - 1;
+        if (wave < 5) {
+            y = (wave < 3 ? wave * 4 : 12 + (wave - 3) * 3) + ii;
+            xx = n;
+        } else {
+            const int r = (wave - 5) * 3 + ii;               // 0..7: the pair (r, r + 10); 8: rows 8 and 9
+            y = r < 8 ? (n < 8 ? r : r + 10) : (n < 8 ? 8 : 9);
+            xx = 16 + (n & 7);
+        }
+    }
+    // slot i starts a new chain (its window shares nothing with slot i - 1)
+    __device__ static __forceinline__ bool fresh(int wave, int i) { return i == 0 || (wave == 7 && i == 2); }
 };
 
 // ---- uint8 frame prefetch --------------------------------------------------------
@@ -798,7 +847,10 @@ __device__ __forceinline__ void tile_pixel(int t, int n, int& y, int& xx)
 template <class S>
 __device__ __forceinline__ void tile_ref(int wave, int i, int n, int& y, int& xx, bool& tile_ok, bool& lane_ok)
 {
-    if constexpr (S::SLIDE) {
+    if constexpr (S::V2) {
+        TileMap1824::pixel(wave, i, n, y, xx, tile_ok);
+        lane_ok = tile_ok;
+    } else if constexpr (S::SLIDE) {
         const int c = i < SlideMap16::LEN0 ? 0 : 1, pos = i - (c ? SlideMap16::LEN0 : 0);
         int strip, row0, nt;
         SlideMap16::chain(wave, c, strip, row0, nt);
@@ -819,8 +871,9 @@ __device__ __forceinline__ void tile_ref(int wave, int i, int n, int& y, int& xx
 // computed on whatever the map holds there and stored to `trash`.
 template <class S, bool ADD_X, int OUT>
 __device__ __forceinline__ void block_conv_slide16(const char* src, char* dst, char* trash, const char* wslot,
-                                                   floatx4 (&x)[S::NT][S::FT], int lane, int wave)
+                                                   floatx4 (&x)[S::NT][S::FT], int lane, int wave, bool tr = false)
 {
+    TR(0);
     static_assert(S::FT == 1 && OUT != 2, "sliding block convolution: 16 channels, LDS output");
     using SM = SlideMap16;
     const int g = lane >> 4, n = lane & 15;
@@ -845,6 +898,7 @@ __device__ __forceinline__ void block_conv_slide16(const char* src, char* dst, c
         for (int r = 0; r < 4; ++r) R[r] = *(const bf16x8*)(pR + r * ROWB);
         E[0] = *(const bf16x8*)pE;
         E[1] = *(const bf16x8*)(pE + 2 * ROWB);
+        TR(1 + 16 * c);
 #pragma unroll
         for (int pp = 0; pp < LEN / 2; ++pp) {
             if (pp + 1 < LEN / 2) {
@@ -867,6 +921,7 @@ __device__ __forceinline__ void block_conv_slide16(const char* src, char* dst, c
             const bf16x4 v0 = to_bf16x4(a0), v1 = to_bf16x4(a1);
             *(bf16x4*)d = OUT == 1 ? v0 : relu_bf16x4(v0);
             *(bf16x4*)(d + (ok ? ROWB : 0)) = OUT == 1 ? v1 : relu_bf16x4(v1);
+            TR(2 + 16 * c + pp);
         }
     };
     run_chain(std::integral_constant<int, 0>{});
@@ -887,8 +942,9 @@ struct NoFiller {
 template <class S, bool ADD_X, int OUT, class Filler = NoFiller, int NIMG = 1>
 __device__ __forceinline__ void block_conv(const char* src, char* dst, const char* wslot, const int (&tb)[S::NT],
                                            floatx4 (&x)[NIMG * S::NT][S::FT], __bf16* const (&feat_rows)[NIMG], int lane, int wave,
-                                           Filler filler = Filler{})
+                                           Filler filler = Filler{}, bool tr = false)
 {
+    TR(0);
     static_assert(NIMG == 1 || S::NT == 1, "several images share a phase only with one tile per wavefront each");
     constexpr int NTT = NIMG * S::NT;
     constexpr int IMG_CELLS = S::ACT_BYTES / 16;           // cells between the two images' maps
@@ -930,6 +986,7 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
     for (int j = 0; j < S::FT; ++j) bv[j] = *(const floatx4*)(wslot + S::WB_FRAGS * 1024 + (j * 4 + g) * 16);
 #pragma unroll
     for (int kc = 0; kc < AHEAD; ++kc) request(0, kc, true);
+    TR(1);
     if constexpr (!std::is_same<Filler, NoFiller>::value) {
         SCHED_FENCE;
         filler();
@@ -951,6 +1008,7 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
             else if (i + 1 < NTT) request(i + 1, kc + AHEAD - S::KCB, false);
         }
         SCHED_FENCE;
+        TR(2 + 2 * i);
         const int p = t * 16 + n;
 #pragma unroll
         for (int j = 0; j < S::FT; ++j) {
@@ -962,7 +1020,105 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
                 else *(bf16x4*)(dstl + tbv(i) * 16 + j * (2 * S::PLANE * 16)) = out;
             }
         }
+        TR(3 + 2 * i);
     }
+}
+
+// 3x3 SAME conv 32 -> 32 on an 18 x 24 map laid out for TileMap1824, this wavefront's chain of up to four tiles.
+// One instruction stream per wavefront, software-pipelined by hand (the order below is pinned with scheduling
+// fences): the MFMAs of tile i run back to back, kernel rows 0, 1, 2, and between them issue
+//   * the three fragment reads of tile i + 1's new window row, into the registers tile i's kernel row 0 has
+//     just left (they then have six chunks' time to arrive),
+//   * the epilogue of tile i - 1 (conversion, ReLU, store), a few instructions per chunk, and
+//   * the start values of tile i + 1's accumulators.
+// A wavefront's own vector instructions do issue under its running MFMAs (an MFMA occupies the issue port for
+// 8 of its 16 cycles; measured: up to two vector instructions per MFMA are free), so the epilogue costs no time
+// of its own and a wavefront running alone at the end of a phase still keeps the matrix pipe fed.
+template <class S, bool ADD_X, int OUT, class Filler = NoFiller>
+__device__ __forceinline__ void block_conv_v2(const char* src, char* dst, const char* wslot, const int (&tb)[4],
+                                              floatx4 (&x)[4][2], int lane, int wave, Filler filler = Filler{}, bool tr = false)
+{
+    static_assert(S::FT == 2 && S::C == 32 && OUT != 2, "18 x 24 maps of 32 channels, LDS output");
+    TR(0);
+    using TM = TileMap1824;
+    const int g = lane >> 4;
+    const int nt = TM::ntiles(wave);                                  // uniform
+    const bool restart2 = TM::fresh(wave, 2);                         // uniform
+    const int lb = g * S::PLANE;
+    char* dstl = dst + ((S::PITCH + 1) * 16 + (g >> 1) * (S::PLANE * 16) + (g & 1) * 8);
+    bf16x8 w[18];
+    bf16x8 F[3][3];                                                   // window row (i + kh) % 3, kernel column kw
+    floatx4 bv[2];
+    auto wfrag = [&](int kc) {
+        w[kc] = *(const bf16x8*)(wslot + (kc * 64 + lane) * 16);
+        w[9 + kc] = *(const bf16x8*)(wslot + ((9 + kc) * 64 + lane) * 16);
+    };
+    auto frag = [&](int i, int kh, int kw) { return *(const bf16x8*)(src + (tb[i] + lb + kh * S::PITCH + kw) * 16); };
+#pragma unroll
+    for (int j = 0; j < 2; ++j) bv[j] = *(const floatx4*)(wslot + 18 * 1024 + (j * 4 + g) * 16);
+    // tile 0: weights and fragments chunk by chunk in the order the chain consumes them, four chunks ahead
+    constexpr int AHEAD = 4;
+#pragma unroll
+    for (int kc = 0; kc < AHEAD; ++kc) { wfrag(kc); F[kc / 3][kc % 3] = frag(0, kc / 3, kc % 3); }
+    TR(1);
+    if constexpr (!std::is_same<Filler, NoFiller>::value) {
+        SCHED_FENCE;
+        filler();
+        SCHED_FENCE;
+    }
+    floatx4 acc[2], nxt[2], fin[2];
+    bf16x4 ob[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[j] = ADD_X ? x[0][j] + bv[j] : bv[j];
+    auto store = [&](int i, int j, bf16x4 v) { *(bf16x4*)(dstl + tb[i] * 16 + j * (2 * S::PLANE * 16)) = v; };
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (i >= nt) break;                                            // uniform
+        if (i == 2 && restart2) {                                      // uniform: a new chain, its first two window rows
+#pragma unroll
+            for (int q = 0; q < 6; ++q) F[(i + q / 3) % 3][q % 3] = frag(i, q / 3, q % 3);
+        }
+#pragma unroll
+        for (int kc = 0; kc < 9; ++kc) {
+            const int kh = kc / 3, kw = kc % 3;
+            SCHED_FENCE;
+            acc[0] = mfma16(w[kc], F[(i + kh) % 3][kw], acc[0]);
+            acc[1] = mfma16(w[9 + kc], F[(i + kh) % 3][kw], acc[1]);
+            if (i == 0 && kc + AHEAD < 9) { wfrag(kc + AHEAD); F[(kc + AHEAD) / 3][(kc + AHEAD) % 3] = frag(0, (kc + AHEAD) / 3, (kc + AHEAD) % 3); }
+            if (kc == 2 && i + 1 < 4) {                                // tile i + 1's new row (a missing tile repeats the last one)
+#pragma unroll
+                for (int q = 0; q < 3; ++q) F[i % 3][q] = frag(i + 1, 2, q);
+            }
+            if (i > 0) {                                               // epilogue of tile i - 1
+                if (kc == 3) ob[0] = to_bf16x4(fin[0]);
+                if (kc == 4) store(i - 1, 0, OUT == 1 ? ob[0] : relu_bf16x4(ob[0]));
+                if (kc == 5) ob[1] = to_bf16x4(fin[1]);
+                if (kc == 6) store(i - 1, 1, OUT == 1 ? ob[1] : relu_bf16x4(ob[1]));
+            }
+            if (kc == 7 && i + 1 < 4) nxt[0] = ADD_X ? x[i + 1][0] + bv[0] : bv[0];
+            if (kc == 8 && i + 1 < 4) nxt[1] = ADD_X ? x[i + 1][1] + bv[1] : bv[1];
+        }
+        SCHED_FENCE;
+        TR(2 + 2 * i);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            fin[j] = acc[j];
+            if (ADD_X) x[i][j] = acc[j];
+            acc[j] = nxt[j];
+        }
+    }
+    // the last tile's epilogue
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (i + 1 == nt) {                                             // uniform
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const bf16x4 vb = to_bf16x4(fin[j]);
+                store(i, j, OUT == 1 ? vb : relu_bf16x4(vb));
+            }
+        }
+    }
+    TR(12);
 }
 
 // conv0 of a CONVMAP section in block_conv's terms: a 3x3 SAME conv C -> C over the section's H x W input map,
@@ -971,7 +1127,8 @@ template <class S>
 struct ConvMapCfg {
     static constexpr int C = S::C, FT = S::FT, KCB = S::KC0, WB_FRAGS = S::W0_FRAGS;
     static constexpr int PH = S::H, PW = S::W, NPIX = PH * PW, NTILES = (NPIX + 15) / 16;
-    static constexpr int NWA = RN_WAVES, NT = (NTILES + NWA - 1) / NWA;
+    static constexpr bool V2 = C == 32 && PH == 18 && PW == 24 && S::IPADX == 2 && RN_WAVES == 8;
+    static constexpr int NWA = RN_WAVES, NT = V2 ? 4 : (NTILES + NWA - 1) / NWA;
     static constexpr int PITCH = S::IPITCH, PLANE = S::IPLANE, ACT_BYTES = S::CM_BYTES;
     static_assert(S::CONVMAP && S::IROWS == S::H + 2 && PLANE * (C / 8) * 16 == S::CM_BYTES, "conv map geometry");
 };
@@ -981,16 +1138,27 @@ __device__ __forceinline__ void conv_map(const char* in, char* out, const char* 
 {
     using CM = ConvMapCfg<S>;
     int tb[CM::NT];
-#pragma unroll
-    for (int i = 0; i < CM::NT; ++i) {
-        const int t = wave + CM::NWA * i;
-        int y, xx;
-        tile_pixel<CM>(t < CM::NTILES ? t : CM::NTILES - 1, lane & 15, y, xx);
-        tb[i] = y * CM::PITCH + xx;
-    }
     floatx4 unused[CM::NT][CM::FT];                        // block_conv reads x only when it adds it
-    __bf16* const no_rows[1] = {nullptr};
-    block_conv<CM, false, 1, Filler>(in, out, wslot, tb, unused, no_rows, lane, wave, filler);
+    if constexpr (CM::V2) {
+#pragma unroll
+        for (int i = 0; i < CM::NT; ++i) {
+            int y, xx;
+            bool ok;
+            TileMap1824::pixel(wave, i, lane & 15, y, xx, ok);
+            tb[i] = y * CM::PITCH + xx;
+        }
+        block_conv_v2<CM, false, 1, Filler>(in, out, wslot, tb, unused, lane, wave, filler);
+    } else {
+#pragma unroll
+        for (int i = 0; i < CM::NT; ++i) {
+            const int t = wave + CM::NWA * i;
+            int y, xx;
+            tile_pixel<CM>(t < CM::NTILES ? t : CM::NTILES - 1, lane & 15, y, xx);
+            tb[i] = y * CM::PITCH + xx;
+        }
+        __bf16* const no_rows[1] = {nullptr};
+        block_conv<CM, false, 1, Filler>(in, out, wslot, tb, unused, no_rows, lane, wave, filler);
+    }
 }
 
 // 3x3 / stride-2 maximum of a CONVMAP section's conv map at pooled pixel (y, xx) for the lane's four channels of
@@ -1015,18 +1183,18 @@ __device__ __forceinline__ void pool_window(const char* cmap, int y, int xx, int
 }
 
 // zero the halo ring of a planar map of CG planes (PLANE cells apart), interior IH x IW
-template <int CG, int IH, int IW, int PLANE>
+template <int CG, int IH, int IW, int PLANE, int PITCH = IW + 2>
 __device__ __forceinline__ void zero_halo(char* buf, int tid)
 {
-    constexpr int PITCH = IW + 2, ROWS = IH + 2;
-    constexpr int RING = 2 * PITCH + 2 * IH;          // cells in one plane's ring
+    constexpr int ROWS = IH + 2;
+    constexpr int RING = 2 * PITCH + 2 * IH;          // cells in one plane's ring (whole first and last rows)
     const bf16x8 z = {};
     for (int i = tid; i < CG * RING; i += RN_THREADS) {
         const int cg = i / RING, r = i % RING;
         int y, xx;
         if (r < PITCH) { y = 0; xx = r; }
         else if (r < 2 * PITCH) { y = ROWS - 1; xx = r - PITCH; }
-        else { const int q = r - 2 * PITCH; y = 1 + (q >> 1); xx = (q & 1) ? PITCH - 1 : 0; }
+        else { const int q = r - 2 * PITCH; y = 1 + (q >> 1); xx = (q & 1) ? IW + 1 : 0; }
         *(bf16x8*)(buf + (cg * PLANE + y * PITCH + xx) * 16) = z;
     }
 }
@@ -1120,7 +1288,7 @@ constexpr int wslot(int q)
 template <class S, class SN, class M, bool LAST, int SI, int J0, int NSETS, bool INB, class PreT>
 __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, const SecWeights& nsw,
                                             const uint8_t* __restrict__ obs_img, PreT& pre,
-                                            __bf16* __restrict__ feat_row, int tid)
+                                            __bf16* __restrict__ feat_row, int tid, bool trimg = false)
 {
     // keep per-tile index arithmetic inside the image loop: hoisted out of it, it would occupy
     // (and spill) hundreds of registers for the whole kernel
@@ -1162,7 +1330,7 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     // ---------------- conv0 + max-pool ----------------
     {
         stage(I0{});                                             // this phase uses set J0: stage J0 + 1
-        if constexpr (!S::CONVMAP) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(pool, tid);
+        if constexpr (!S::CONVMAP) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE, S::PITCH>(pool, tid);
         bf16x8 w0[S::CONVMAP ? 1 : S::W0_FRAGS];
         if constexpr (S::CONVMAP) {
             conv_map<S>(buf0, buf1, lds + SLOT_C0, lane, wave);     // buf1 <- the full-resolution conv map
@@ -1215,7 +1383,7 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     if constexpr (!S::XFUSED) {
         // INB: R replaces the pooled values in buf0 cell by cell (a lane reads and writes only its own cells and
         // the halo is already zero); buf1 gets the zero halo the first block's output needs
-        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(INB ? buf1 : buf0, tid);
+        zero_halo<S::C / 8, S::PH, S::PW, S::PLANE, S::PITCH>(INB ? buf1 : buf0, tid);
         if constexpr (S::CONVMAP) {
             bool ok[S::NT];
             pooled_x<S>(buf1, tb, x, ok, lane, wave);   // x = 3x3/2 maximum of the conv map in buf1
@@ -1266,14 +1434,16 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
         PHASE_MARK(SI * 8 + 3);
     }
     __bf16* const feat_rows[1] = {feat_row};
-    auto conv = [&](auto add_x, auto out, const char* src, char* dst, const char* ws, auto filler) {
+    auto conv = [&](auto add_x, auto out, const char* src, char* dst, const char* ws, auto filler, bool tr = false) {
         constexpr bool ADD_X = decltype(add_x)::value;
         constexpr int OUT = decltype(out)::value;
         if constexpr (S::SLIDE) {
             filler();
-            block_conv_slide16<S, ADD_X, OUT>(src, dst, lds + M::TRASH + lane * 8, ws, x, lane, wave);
+            block_conv_slide16<S, ADD_X, OUT>(src, dst, lds + M::TRASH + lane * 8, ws, x, lane, wave, tr);
+        } else if constexpr (S::V2) {
+            block_conv_v2<S, ADD_X, OUT>(src, dst, ws, tb, x, lane, wave, filler, tr);
         } else {
-            block_conv<S, ADD_X, OUT>(src, dst, ws, tb, x, feat_rows, lane, wave, filler);
+            block_conv<S, ADD_X, OUT>(src, dst, ws, tb, x, feat_rows, lane, wave, filler, tr);
         }
     };
     using BF = std::false_type; using BT = std::true_type;
@@ -1293,18 +1463,28 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     stage(I1{});
     // U's buffer held the conv map (CONVMAP) or the frame (XFUSED) until now: its halo ring is zeroed while
     // this phase fills its interior
-    if constexpr (S::CONVMAP || S::XFUSED) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(bufU, tid);
+    if constexpr (S::CONVMAP || S::XFUSED) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE, S::PITCH>(bufU, tid);
     conv(BF{}, I0{}, bufR, bufU, lds + wslot<M, S, INB>(QB), slice(I1{}));
     stage_wait();
     lds_barrier();
     PHASE_MARK(SI * 8 + 4);
+#ifdef SEEDINF_TRACE
+    const bool tr = trimg && SI == SEEDINF_TRACE;
+#else
+    const bool tr = false;
+#endif
+    TR(40);
     stage(I2{});
     DETAIL_T0;
-    conv(BT{}, I0{}, bufU, bufR, lds + wslot<M, S, INB>(QB + 1), slice(I2{}));
+    TR(41);
+    conv(BT{}, I0{}, bufU, bufR, lds + wslot<M, S, INB>(QB + 1), slice(I2{}), tr);
+    TR(42);
     DETAIL_MARK(0);
     stage_wait();
+    TR(43);
     DETAIL_MARK(1);
     lds_barrier();
+    TR(44);
     DETAIL_MARK(2);
     PHASE_MARK(SI * 8 + 5);
     stage(I3{});
@@ -1377,7 +1557,7 @@ __device__ __forceinline__ void last_group(char* lds, const SecWeights& sw, cons
     };
     auto halos = [&](char* buf) {
 #pragma unroll
-        for (int k = 0; k < N; ++k) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE>(buf + k * IMG, tid);
+        for (int k = 0; k < N; ++k) zero_halo<S::C / 8, S::PH, S::PW, S::PLANE, S::PITCH>(buf + k * IMG, tid);
     };
     using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
     using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
@@ -1485,8 +1665,13 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
             const int cur = img + k * grid;
             const uint8_t* obs_img = a.obs + FRAME * cur;
             __bf16* feat_row = a.feat + (size_t)cur * a.ldf;
-            run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
-            run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
+#ifdef SEEDINF_TRACE
+            const bool trimg = blockIdx.x == 7 && img == (int)blockIdx.x + 2 * NG * grid && k == 0;
+#else
+            const bool trimg = false;
+#endif
+            run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid, trimg);
+            run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid, trimg);
             // the next frame's bytes travel while the last section computes (unconditional load address)
             const int nxt = k + 1 < n ? cur + grid : (img + NG * grid < a.B ? img + NG * grid : cur);
             prefetch_issue<S1>(pre, a.obs + FRAME * nxt, 0, tid);
