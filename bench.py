@@ -21,6 +21,23 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16, published
 HBM_PEAK_GBS = 8000.0
 
 
+# model-size variants of Sections 4.1 (filters x2 / x4), 4.2 (medium and large minimaps) and 4.3 (Atari without
+# frame stacking): name -> (label, base workload, overrides, batch)
+VARIANTS = {
+    "x2": ("DMLab filters x2", "C3", dict(sections=[32, 64, 64]), 1024),
+    "x4": ("DMLab filters x4", "C3", dict(sections=[64, 128, 128]), 1024),
+    "map120": ("Football map 120x90", "C4", dict(obs_h=90, obs_w=120), 1024),
+    "map144": ("Football map 144x108", "C4", dict(obs_h=108, obs_w=144), 1024),
+    "atari1": ("Atari without frame stacking", "C2", dict(obs_c=1), 256),
+}
+
+
+def variant_cfg(name):
+    from paper_1910_06591_amd import workloads as wl
+    label, base, over, b = VARIANTS[name]
+    return dict(wl.CONFIGS[base], label=label, index=40, **over), b
+
+
 def torso_macs_per_frame(cfg):
     from paper_1910_06591_amd import workloads as wl
     h, w, c = wl.torso_out_shape(cfg)
@@ -134,9 +151,11 @@ def time_extensions(cfg, B, weights):
             net.step(out=o, **sub)
         return p50(g.replay), p50(lambda: net.step(out=o, **sub))
     res["graph_replay_vs_eager_p50_ms"] = {str(nb): list(graphed_p50(nb)) for nb in (64, 256, B) if nb <= B}
-    # weight refresh: host time of the call (repack + enqueue) and a step issued right behind it
+    # weight refresh: host time of the call (copy into pinned staging + enqueue; measured from an idle stream, as
+    # between two training steps) and a step issued right behind it
     t = []
-    for _ in range(5):
+    for _ in range(7):
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
         net.set_weights(weights)
         t.append((time.perf_counter() - t0) * 1e3)
@@ -145,6 +164,21 @@ def time_extensions(cfg, B, weights):
     res["set_weights_host_ms"] = float(np.median(t))
     res["step_after_set_weights_p50_ms"] = p50(lambda: (net.set_weights(weights), net.step(out=out, **dev)), n=5)
     res["weights_mb"] = weights.size * 4 / 1e6
+    # sustained rate: about a second of back-to-back steps from whatever state the device is in (no wake-up loop in
+    # front, one synchronisation at the end), with the torso kernel's own mean duration over the same steps
+    n_sus = min(4000, max(2000, int(1.0 / max(res["step_plain_p50_ms"] * 1e-3, 1e-5))))
+    net.set_profiling(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_sus):
+        net.step(out=out, **dev)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tms, tn = net.profile_read()
+    net.set_profiling(False)
+    res["sustained_1s"] = {"steps": n_sus, "seconds": dt, "ms_per_step": dt * 1e3 / n_sus, "frames_per_s": n_sus * B / dt,
+                           "torso_ms": tms / max(tn, 1),
+                           "step_frac_of_bf16_peak": 2.0 * wl.macs_per_frame(cfg) * B * n_sus / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS}
     # T-step unroll over stored trajectories: T = 32 (the unroll length of the paper's V-trace agents), B / 32 rows
     if B % 32 == 0 and B >= 32:
         T, Bt = 32, B // 32
@@ -217,8 +251,11 @@ def measure_peaks():
         rc = lib.seed_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, st)
         assert rc == 0, rc
     t = timed(copy, 10)
-    return {"mfma_bf16_tflops": tflops, "hbm_copy_gbs": 2.0 * nbytes / t / 1e9,
-            "how": "MFMA-only loop (2048 blocks x 8 wavefronts x 25600 v_mfma_f32_16x16x32_bf16); copy of 1 GiB, read + write bytes"}
+    gbs = 2.0 * nbytes / t / 1e9
+    return {"mfma_bf16_tflops": tflops, "mfma_frac_of_nominal": tflops / MFMA_BF16_PEAK_TFLOPS,
+            "hbm_copy_gbs": gbs, "hbm_copy_frac_of_nominal": gbs / HBM_PEAK_GBS,
+            "how": "MFMA-only loop (2048 blocks x 8 wavefronts x 25600 v_mfma_f32_16x16x32_bf16); streaming copy of 1 GiB "
+                   "(four 16-byte non-temporal loads in flight per lane), read + write bytes"}
 
 
 def cpu_baseline(cfg, rows):
@@ -267,6 +304,8 @@ def main():
     ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3", "C4", "C5"],
                     help="C5 (default) is the headline line; any other name times that workload alone and prints a "
                          "short line for it (used to profile the other workloads' kernels)")
+    ap.add_argument("--variant", default=None, choices=sorted(VARIANTS),
+                    help="time one model-size variant (Sections 4.1 / 4.2 / 4.3) alone and print a short line for it")
     ap.add_argument("--no-extras", action="store_true", help="skip the batch sweep and the other configs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=512)
@@ -295,9 +334,13 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if args.workload != "C5":
-        c = wl.CONFIGS[args.workload]
-        b = args.batch or c["batch"]
+    if args.workload != "C5" or args.variant:
+        if args.variant:
+            c, b0 = variant_cfg(args.variant)
+            args.workload = "variant " + args.variant
+        else:
+            c, b0 = wl.CONFIGS[args.workload], wl.CONFIGS[args.workload]["batch"]
+        b = args.batch or b0
         s = time_config(c, b, args.steps, args.warmup)
         print(json.dumps({"metric": "batched inference frames/sec at batch B (1 GPU)", "value": b / (s["ms_per_step"] * 1e-3),
                           "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -360,13 +403,9 @@ def main():
         # model-size variants (Section 4.1: filters x2 / x4; Section 4.2: medium and large minimaps; Atari without
         # frame stacking): the layer-by-layer bf16 ResNet path; the Atari agent on single frames has the fused conv stack
         variants = []
-        c3, c4, c2 = wl.CONFIGS["C3"], wl.CONFIGS["C4"], wl.CONFIGS["C2"]
-        for label, c, b in (("DMLab filters x2", dict(c3, sections=[32, 64, 64]), 1024),
-                            ("DMLab filters x4", dict(c3, sections=[64, 128, 128]), 1024),
-                            ("Football map 120x90", dict(c4, obs_h=90, obs_w=120), 1024),
-                            ("Football map 144x108", dict(c4, obs_h=108, obs_w=144), 1024),
-                            ("Atari without frame stacking", dict(c2, obs_c=1), 256)):
-            c = dict(c, label=label, index=40)
+        for name in ("x2", "x4", "map120", "map144", "atari1"):
+            c, b = variant_cfg(name)
+            label = c["label"]
             s = time_config(c, b, 20, 3, profile=False)
             variants.append({"config": label, "batch": b, "dtype": c["precision"], "frames_per_s": b / (s["p50_ms"] * 1e-3),
                              "p50_ms": s["p50_ms"], "tflops": 2.0 * wl.macs_per_frame(c) * b / (s["p50_ms"] * 1e-3) / 1e12})

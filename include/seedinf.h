@@ -278,44 +278,27 @@ seed_status_t seed_infer_unroll(seed_infer_t* handle, int32_t T, int32_t B,
  * every training step is followed by a weight refresh of the inference path).
  *
  *   weights_host  host pointer, the same flat layout and count as at creation;
- *                 copied (and repacked for the matrix-core kernels) before the
- *                 call returns: the caller may reuse the buffer at once.
+ *                 copied into the handle's pinned staging buffer before the call
+ *                 returns: the caller may reuse the buffer at once.
  *
- * The handle keeps two device copies of its weights.  The call fills the idle
- * copy with asynchronous copies enqueued on `hip_stream` and then makes it the
- * active one: steps enqueued afterwards use the new weights, steps enqueued
- * before keep the old ones, and no step waits for the upload.  Steps and
- * updates must be enqueued on the same stream (or be ordered by the caller):
- * the update after next overwrites the copy that steps enqueued before this
- * call are still reading.  Allocates nothing.  SEED_ERR_INVALID_ARG on a null
- * pointer or a wrong count; the active weights are then unchanged.
+ * The handle keeps two device copies of its weights.  The call enqueues, on
+ * `hip_stream`, the upload of the flat vector into the idle copy and (bf16 mode)
+ * one kernel that packs it into the matrix-core kernels' operand layouts, then
+ * makes that copy the active one: steps enqueued afterwards use the new
+ * weights, steps enqueued before keep the old ones.  The host's share is one
+ * copy of the flat vector (spread over a few threads); a step enqueued right
+ * behind the call is ordered behind the upload on its stream.  If an enqueue
+ * fails the active weights are unchanged.  Steps and updates must be enqueued
+ * on the same stream (or be ordered by the caller): the update after next
+ * overwrites the copy that steps enqueued before this call are still reading.
+ * The call waits only for the upload of the update BEFORE the previous one
+ * (two staging buffers are used alternately).  Allocates no device or pinned
+ * memory.
+ * SEED_ERR_INVALID_ARG on a null pointer or a wrong count; the active weights
+ * are then unchanged.
  */
 seed_status_t seed_infer_set_weights(seed_infer_t* handle, const float* weights_host,
                                      size_t n_weights, void* hip_stream);
-
-/*
- * Test/diagnostic tap: copy an intermediate of the most recent step into a
- * device buffer as fp32 (converted from the internal storage type), enqueued
- * on `hip_stream` after the step's work.  which = 0: the rectified, flattened
- * torso output [B, torso_features]; which = 1: the linear layer's rectified
- * output [B, fc_units].  `capacity` is the number of floats `dst` can hold.
- */
-seed_status_t seed_infer_read_intermediate(seed_infer_t* handle, int32_t which, int32_t B,
-                                           float* dst, size_t capacity, void* hip_stream);
-
-/*
- * Kernel timing for callers that measure (benchmarks, profilers).  With
- * profiling enabled, every seed_infer_step brackets its dominant kernel (the
- * torso: the fused ResNet kernel, or the conv-stack layers) with HIP events on
- * the step's stream, up to `SEED_PROFILE_SLOTS` steps between reads.
- * seed_infer_profile_read waits for the recorded events, returns the summed
- * torso time in milliseconds and the number of steps it covers, and starts a
- * new measurement.  Enabling allocates events (not allowed under graph
- * capture); disabled (the default) the step records nothing.
- */
-#define SEED_PROFILE_SLOTS 4096
-seed_status_t seed_infer_set_profiling(seed_infer_t* handle, int32_t enable);
-seed_status_t seed_infer_profile_read(seed_infer_t* handle, float* torso_ms_sum, int32_t* n_steps);
 
 /* Number of features the torso feeds the linear layer (H*W*C), 0 if invalid. */
 size_t seed_infer_torso_features(const seed_arch_t* arch);
@@ -397,6 +380,36 @@ void* seed_batcher_stream(seed_batcher_t* b);
 const char* seed_batcher_last_error(const seed_batcher_t* b);
 /* Waits for work in flight and frees the batcher.  NULL is allowed. */
 void seed_batcher_destroy(seed_batcher_t* b);
+
+/* ------------------------------------------------------------------------
+ * Diagnostics.  Not part of the inference path: a tap for tests that compare
+ * intermediates, and kernel timing for benchmarks.  A serving caller needs
+ * neither.
+ * ------------------------------------------------------------------------ */
+
+/*
+ * Test/diagnostic tap: copy an intermediate of the most recent step into a
+ * device buffer as fp32 (converted from the internal storage type), enqueued
+ * on `hip_stream` after the step's work.  which = 0: the rectified, flattened
+ * torso output [B, torso_features]; which = 1: the linear layer's rectified
+ * output [B, fc_units].  `capacity` is the number of floats `dst` can hold.
+ */
+seed_status_t seed_infer_read_intermediate(seed_infer_t* handle, int32_t which, int32_t B,
+                                           float* dst, size_t capacity, void* hip_stream);
+
+/*
+ * Kernel timing for callers that measure (benchmarks, profilers).  With
+ * profiling enabled, every seed_infer_step brackets its dominant kernel (the
+ * torso: the fused ResNet kernel, or the conv-stack layers) with HIP events on
+ * the step's stream, up to `SEED_PROFILE_SLOTS` steps between reads.
+ * seed_infer_profile_read waits for the recorded events, returns the summed
+ * torso time in milliseconds and the number of steps it covers, and starts a
+ * new measurement.  Enabling allocates events (not allowed under graph
+ * capture); disabled (the default) the step records nothing.
+ */
+#define SEED_PROFILE_SLOTS 4096
+seed_status_t seed_infer_set_profiling(seed_infer_t* handle, int32_t enable);
+seed_status_t seed_infer_profile_read(seed_infer_t* handle, float* torso_ms_sum, int32_t* n_steps);
 
 #ifdef __cplusplus
 }

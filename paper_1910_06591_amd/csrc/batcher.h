@@ -215,19 +215,17 @@ extern "C" seed_status_t seed_batcher_add_many(seed_batcher_t* b, int32_t n, con
         st = seed_batcher_reserve(b, actors[ok], prev_rewards[ok], dones[ok], &slot[ok]);
         if (st != SEED_OK) break;
     }
-    // the frame copies are the expensive part: spread large batches over a few host threads
-    const int nthr = ok >= 256 ? 8 : 1;
+    // the frame copies are the expensive part: large batches go over the handle's persistent host threads, in
+    // pieces of about a megabyte
+    const int32_t per = (int32_t)std::max<size_t>(1, ((size_t)1 << 20) / b->frame);
+    const int pieces = (ok + per - 1) / per;
     auto copy = [&](int t) {
-        for (int32_t i = t; i < ok; i += nthr) memcpy(slot[i], obs_host + (size_t)i * b->frame, b->frame);
+        const int32_t i1 = std::min(ok, (t + 1) * per);
+        for (int32_t i = t * per; i < i1; ++i) memcpy(slot[i], obs_host + (size_t)i * b->frame, b->frame);
     };
-    if (nthr == 1) {
-        copy(0);
-    } else {
-        std::vector<std::thread> th;
-        for (int t = 1; t < nthr; ++t) th.emplace_back(copy, t);
-        copy(0);
-        for (auto& x : th) x.join();
-    }
+    HostPool* pool = pieces > 1 ? host_pool(b->h) : nullptr;
+    if (pool) pool->run(pieces, copy);
+    else for (int t = 0; t < pieces; ++t) copy(t);
     return st;
 }
 

@@ -16,6 +16,7 @@
 #include "conv_stack_fused.h"
 #include "resnet_fused.h"
 #include "resnet_layerwise.h"
+#include "resnet_blockfused.h"
 
 namespace seedinf {
 
@@ -76,28 +77,32 @@ inline seed_status_t bf16_supported(const Plan& p, std::string& err)
     return SEED_OK;
 }
 
-// ---- host-side packing --------------------------------------------------------
-inline uint16_t f32_to_bf16_bits(float f)
+// ---- packing plan --------------------------------------------------------------
+// The packed operand stream of a network depends on the weights only through a gather: every 16-bit element of it
+// is zero padding, the bf16 rounding of one canonical weight, or one half of a canonical fp32 bias.  The host
+// works that gather out ONCE per handle (the layouts below, run over a vector that holds each weight's own index)
+// and uploads it as a table; the device then packs any weight vector with one kernel (bf16_repack_kernel), at
+// creation and at every weight update, so an update costs the host one copy of the flat vector.
+//   table entry = 4 * (index + 1) + kind;  kind 1: bf16(w[index]), 2 / 3: low / high half of the fp32 w[index];
+//   0 = zero.  The fp32 bias table holds index + 1, or 0 for padding.
+enum { PK_ZERO = 0, PK_BF16 = 1, PK_F32_LO = 2, PK_F32_HI = 3 };
+inline uint32_t pk_entry(float index_plus_1, int kind)
 {
-    uint32_t u;
-    memcpy(&u, &f, 4);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return index_plus_1 == 0.f ? 0u : (((uint32_t)index_plus_1) << 2) | (uint32_t)kind;
 }
 
-// A-operand fragments [ftile][kchunk][lane][8] from value(f, k)
+// A-operand fragments [ftile][kchunk][lane][8] from value(f, k) (value = the weight's index + 1, or 0)
 template <class F>
-inline void pack_a(std::vector<uint16_t>& out, int n_ftiles, int kchunks, F value)
+inline void pack_a(std::vector<uint32_t>& out, int n_ftiles, int kchunks, F value)
 {
     size_t base = out.size();
     out.resize(base + (size_t)n_ftiles * kchunks * 64 * 8);
-    uint16_t* d = out.data() + base;
+    uint32_t* d = out.data() + base;
     for (int ft = 0; ft < n_ftiles; ++ft)
         for (int kc = 0; kc < kchunks; ++kc)
             for (int lane = 0; lane < 64; ++lane)
                 for (int e = 0; e < 8; ++e)
-                    *d++ = f32_to_bf16_bits(value(ft * 16 + (lane & 15), kc * 32 + 8 * (lane >> 4) + e));
+                    *d++ = pk_entry(value(ft * 16 + (lane & 15), kc * 32 + 8 * (lane >> 4) + e), PK_BF16);
 }
 
 struct ConvStackLayerDev { size_t wp_off; size_t koff_off; int kchunks; };
@@ -114,8 +119,8 @@ struct Bf16WeightSet {
 
 // Host-side result of packing one set of weights; the offsets depend on the arch only.
 struct Bf16Packed {
-    std::vector<uint16_t> pk;                  // all packed bf16 weights
-    std::vector<float> fb;                     // padded fp32 biases
+    std::vector<uint32_t> pk;                  // gather table of the packed 16-bit operand stream (see pk_entry)
+    std::vector<uint32_t> fb;                  // gather table of the padded fp32 biases: index + 1, 0 = zero
     std::vector<int> ko;                       // conv-stack offset tables (weight-independent)
     size_t sec_off[4][5] = {};
     size_t off_fc = 0, off_bfc = 0, off_lstm = 0, off_hid = 0, off_bhid = 0;
@@ -134,6 +139,7 @@ struct Bf16State {
     int active = 0;
     size_t o_pk[2] = {0, 0}, o_fb[2] = {0, 0};
     size_t pk_bytes = 0, fb_bytes = 0;
+    const uint32_t* tab_pk = nullptr; const uint32_t* tab_fb = nullptr;   // device: the packing plan's gather tables
     int kc_fc = 0, ft_fc = 0, kc1_lstm = 0, ft_hid = 0;
     std::vector<ConvStackLayerDev> stack;
     std::vector<LwLayerDev> lw;
@@ -176,15 +182,18 @@ inline float planar_weight(const float* w, int cout, int f, int k)
 }
 
 // one 1 KiB chunk after a layer's fragments: its first C floats are the layer's biases
-inline void pack_bias_chunk(std::vector<uint16_t>& pk, const float* bias, int C)
+inline void pack_bias_chunk(std::vector<uint32_t>& pk, const float* bias, int C)
 {
     size_t base = pk.size();
     pk.resize(base + 512, 0);
-    memcpy(pk.data() + base, bias, (size_t)C * sizeof(float));
+    for (int c = 0; c < C; ++c) {
+        pk[base + 2 * c] = pk_entry(bias[c], PK_F32_LO);
+        pk[base + 2 * c + 1] = pk_entry(bias[c], PK_F32_HI);
+    }
 }
 
 template <class S>
-inline void pack_section(std::vector<uint16_t>& pk, const float* w, const Section& sec, size_t (&off)[5])
+inline void pack_section(std::vector<uint32_t>& pk, const float* w, const Section& sec, size_t (&off)[5])
 {
     const ConvLayer& c0 = sec.conv0;
     const float* w0 = w + c0.w_off;
@@ -222,12 +231,17 @@ inline void pack_section(std::vector<uint16_t>& pk, const float* w, const Sectio
     }
 }
 
-// Packs every layer's weights for the bf16 kernels (host side; `w` = canonical flat fp32 weights).
-inline void bf16_pack(const Plan& p, int torso_kind, int ldf_, int ldfc_, const float* w, Bf16Packed& o)
+// Lays out every layer's operands for the bf16 kernels as gather tables over the canonical flat weight vector
+// (host side, once per handle).
+inline void bf16_pack(const Plan& p, int torso_kind, int ldf_, int ldfc_, Bf16Packed& o)
 {
     const seed_arch_t& a = p.arch;
-    std::vector<uint16_t>& pk = o.pk;
-    std::vector<float>& fb = o.fb;
+    // the layouts below read "weights"; here every weight is its own index + 1 (exact in fp32 up to 2^24)
+    std::vector<float> iota(p.n_weights);
+    for (size_t i = 0; i < iota.size(); ++i) iota[i] = (float)(i + 1);
+    const float* w = iota.data();
+    std::vector<uint32_t>& pk = o.pk;
+    std::vector<float> fb;
     std::vector<int>& ko = o.ko;
     size_t (&sec_off)[4][5] = o.sec_off;
     if (a.torso == SEED_TORSO_RESNET && torso_kind == TORSO_NONE) {
@@ -327,7 +341,38 @@ inline void bf16_pack(const Plan& p, int torso_kind, int ldf_, int ldfc_, const 
         for (int f = 0; f < hid; ++f) fb.push_back(w[p.v1_b + f]);
         for (int f = 0; f < hid; ++f) fb.push_back(w[p.a1_b + f]);
     }
+    o.fb.resize(fb.size());
+    for (size_t i = 0; i < fb.size(); ++i) o.fb[i] = (uint32_t)fb[i];
+}
 
+// The device side of the packing plan: one thread per 16-bit element of the operand stream (and per bias).
+// fp32 -> bf16 rounds to nearest even; a NaN stays a NaN.
+__global__ __launch_bounds__(256) void bf16_repack_kernel(const float* __restrict__ w, const uint32_t* __restrict__ tab_pk,
+                                                          size_t n_pk, uint16_t* __restrict__ pk,
+                                                          const uint32_t* __restrict__ tab_fb, size_t n_fb, float* __restrict__ fb)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_pk + n_fb; i += stride) {
+        if (i < n_pk) {
+            const uint32_t e = tab_pk[i];
+            uint16_t v = 0;
+            if (e) {
+                uint32_t u = __float_as_uint(w[(e >> 2) - 1]);
+                const uint32_t kind = e & 3u;
+                if (kind == PK_BF16) {
+                    if ((u & 0x7fffffffu) > 0x7f800000u) u = (u >> 16) | 0x40u;
+                    else u = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+                } else if (kind == PK_F32_HI) {
+                    u >>= 16;
+                }
+                v = (uint16_t)(u & 0xffffu);
+            }
+            pk[i] = v;
+        } else {
+            const uint32_t e = tab_fb[i - n_pk];
+            fb[i - n_pk] = e ? w[e - 1] : 0.f;
+        }
+    }
 }
 
 // Resolves the pointers of weight set `set` from the packing offsets.
@@ -351,7 +396,19 @@ inline void bf16_bind(Bf16State* s, const Plan& p, const Bf16Packed& o, int set)
     }
 }
 
-inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out, std::string& err)
+// Packs the canonical weights at d_w (device) into weight set `set` of the arena, on stream st.
+inline void bf16_repack(Bf16State* s, const float* d_w, int set, hipStream_t st)
+{
+    const size_t n_pk = s->pk_bytes / 2, n_fb = s->fb_bytes / 4;
+    const size_t n = n_pk + n_fb;
+    if (n == 0) return;
+    const size_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(bf16_repack_kernel, dim3((unsigned)(blocks < 16384 ? blocks : 16384)), dim3(256), 0, st, d_w, s->tab_pk, n_pk,
+                       (uint16_t*)(s->arena + s->o_pk[set]), s->tab_fb, n_fb, (float*)(s->arena + s->o_fb[set]));
+}
+
+// d_w: the canonical weights, already on the device (set 0 is packed from them here).
+inline seed_status_t bf16_create(const Plan& p, const float* d_w, Bf16State** out, std::string& err)
 {
     const seed_arch_t& a = p.arch;
     Bf16State* s = new Bf16State;
@@ -366,12 +423,13 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     s->ldf = round_up((int)p.flat, 32);
     s->ldfc = round_up(a.fc_units, 32);
 
+    if (p.n_weights >= ((size_t)1 << 24) - 1) { err = "bf16 mode: more than 2^24 weights"; return SEED_ERR_UNSUPPORTED_ARCH; }
     Bf16Packed o;
-    bf16_pack(p, s->torso_kind, s->ldf, s->ldfc, w, o);
+    bf16_pack(p, s->torso_kind, s->ldf, s->ldfc, o);
     s->kc_fc = o.kc_fc; s->ft_fc = o.ft_fc; s->kc1_lstm = o.kc1_lstm; s->ft_hid = o.ft_hid;
     s->stack = o.stack;
     s->lw = o.lw;
-    s->pk_bytes = o.pk.size() * 2;
+    s->pk_bytes = o.pk.size() * 2;                // (one 16-bit element per table entry)
     s->fb_bytes = o.fb.size() * 4;
     const int F = a.fc_units;
 
@@ -384,6 +442,8 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
         s->o_fb[set] = off; off += al(s->fb_bytes + 16);
     }
     const size_t o_ko = off; off += al(o.ko.size() * 4 + 16);
+    const size_t o_tpk = off; off += al(o.pk.size() * 4 + 16);
+    const size_t o_tfb = off; off += al(o.fb.size() * 4 + 16);
     size_t o_act[2] = {0, 0};
     if (a.torso == SEED_TORSO_CONV_STACK && p.convs.size() > 1 && !s->stack_fused) {   // (the fused stack keeps them in LDS)
         size_t m = 0;
@@ -411,9 +471,13 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     const size_t o_fcf = off; off += al(mb * F * 4);
     BF_TRY(hipMalloc((void**)&s->arena, off));
     BF_TRY(hipMemset(s->arena, 0, off));      // padding columns of feat / fc stay zero for ever
-    BF_TRY(hipMemcpy(s->arena + s->o_pk[0], o.pk.data(), s->pk_bytes, hipMemcpyHostToDevice));
-    if (!o.fb.empty()) BF_TRY(hipMemcpy(s->arena + s->o_fb[0], o.fb.data(), s->fb_bytes, hipMemcpyHostToDevice));
+    if (!o.pk.empty()) BF_TRY(hipMemcpy(s->arena + o_tpk, o.pk.data(), o.pk.size() * 4, hipMemcpyHostToDevice));
+    if (!o.fb.empty()) BF_TRY(hipMemcpy(s->arena + o_tfb, o.fb.data(), o.fb.size() * 4, hipMemcpyHostToDevice));
     if (!o.ko.empty()) BF_TRY(hipMemcpy(s->arena + o_ko, o.ko.data(), o.ko.size() * 4, hipMemcpyHostToDevice));
+    s->tab_pk = (const uint32_t*)(s->arena + o_tpk);
+    s->tab_fb = (const uint32_t*)(s->arena + o_tfb);
+    bf16_repack(s, d_w, 0, nullptr);
+    BF_TRY(hipGetLastError());
     bf16_bind(s, p, o, 0);
     bf16_bind(s, p, o, 1);
     s->active = 0;
@@ -434,6 +498,10 @@ inline seed_status_t bf16_create(const Plan& p, const float* w, Bf16State** out,
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
+    BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
+    BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
+    BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
+    BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
     if (s->stack_fused) {
         BF_TRY(hipFuncSetAttribute((const void*)r2d2_torso_bf16_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, r2d2::LDS_BYTES));
         BF_TRY(hipFuncSetAttribute((const void*)r2d2_torso_bf16_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, r2d2::LDS_BYTES));
@@ -576,6 +644,37 @@ inline void launch_lw_conv(hipStream_t st, const LwConvArgs& c, int ft, bool u8)
     else by_ft(std::false_type{});
 }
 
+// One residual block (two 3x3 convolutions C -> C over an H x W map) as a single launch; false when the width has
+// no fused kernel or no tile fits, and nothing was launched.
+inline bool launch_resblock(hipStream_t st, const LwLayerDev& da, const LwLayerDev& db, const bf16x8* wp_conv, const float* d_w,
+                            const ConvLayer& ca, const ConvLayer& cb, int B, const float* x_in, float* x_out, __bf16* y, int y_relu,
+                            int ldy)
+{
+    const int C = ca.Cin;
+    if (ca.Cout != C || cb.Cin != C || cb.Cout != C || ca.H != cb.H || ca.W != cb.W) return false;
+    auto go = [&](auto cc) -> bool {
+        constexpr int CC = decltype(cc)::value;
+        using K = ResBlockCfg<CC>;
+        ResBlockArgs r{};
+        if (!K::choose(ca.H, ca.W, r.TH, r.TW)) return false;
+        r.x_in = x_in; r.wpa = wp_conv + da.wp_off / 8; r.wpb = wp_conv + db.wp_off / 8;
+        r.bias_a = d_w + ca.b_off; r.bias_b = d_w + cb.b_off;
+        r.x_out = x_out; r.y = y; r.y_relu = y_relu; r.ldy = ldy;
+        r.B = B; r.H = ca.H; r.W = ca.W; r.kchunks = da.kchunks;
+        r.tiles_y = (ca.H + r.TH - 1) / r.TH; r.tiles_x = (ca.W + r.TW - 1) / r.TW;
+        hipLaunchKernelGGL(resblock_fused_kernel<CC>, dim3((unsigned)((long)B * r.tiles_y * r.tiles_x)), dim3(RB_THREADS),
+                           K::lds_bytes(r.TH, r.TW), st, r);
+        return true;
+    };
+    switch (C) {
+    case 16: return go(std::integral_constant<int, 16>{});
+    case 32: return go(std::integral_constant<int, 32>{});
+    case 64: return go(std::integral_constant<int, 64>{});
+    case 128: return go(std::integral_constant<int, 128>{});
+    default: return false;
+    }
+}
+
 // Torso and linear layer over B rows: leaves the rectified linear-layer output of row r in row r of
 // fc_bf16 / fc_f32.
 inline seed_status_t bf16_torso_fc(Bf16State* s, const Plan& p, const float* d_w, hipStream_t st, int B, const uint8_t* obs,
@@ -609,12 +708,27 @@ inline seed_status_t bf16_torso_fc(Bf16State* s, const Plan& p, const float* d_w
             const long total = (long)B * sec.PH * sec.PW * (C / 4);
             hipLaunchKernelGGL(pool3x3s2_lw_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s->lw_c0, s->lw_x,
                                s->lw_r, B, sec.conv0.OH, sec.conv0.OW, C, sec.PH, sec.PW, sec.pool_pad_h, sec.pool_pad_w);
+            // a residual block in one launch where the width has a fused kernel and a tile fits; x ping-pongs between
+            // lw_x and the (by now dead) conv0 map, since tiles read their neighbours' halos of the block's input
+            float* x_cur = s->lw_x;
+            float* x_alt = (float*)s->lw_c0;
             for (int blk = 0; blk < 2; ++blk) {
-                conv(sec.block[2 * blk], s->lw_r, false, nullptr, nullptr, s->lw_u, 1, 0);
                 const bool closing = last_sec && blk == 1;          // the torso's last layer writes the rectified features
                 const bool to_next = !last_sec && blk == 1;         // the next section's conv0 takes x un-rectified
-                conv(sec.block[2 * blk + 1], s->lw_u, false, s->lw_x, s->lw_x, closing ? s->feat : s->lw_r,
-                     to_next ? 0 : 1, closing ? s->ldf : 0);
+                __bf16* y = closing ? s->feat : s->lw_r;
+                const int y_relu = to_next ? 0 : 1, ldy = closing ? s->ldf : 0;
+                if (launch_resblock(st, s->lw[li], s->lw[li + 1], W.wp_conv, d_w, sec.block[2 * blk], sec.block[2 * blk + 1], B, x_cur,
+                                    blk == 0 ? x_alt : nullptr, blk == 0 ? nullptr : y, y_relu, ldy)) {
+                    li += 2;
+                    if (blk == 0) std::swap(x_cur, x_alt);
+                    continue;
+                }
+                if (x_cur != s->lw_x) {                             // unreachable: both blocks of a section have one shape
+                    err = "residual blocks of one section differ in shape";
+                    return SEED_ERR_DEVICE;
+                }
+                conv(sec.block[2 * blk], s->lw_r, false, nullptr, nullptr, s->lw_u, 1, 0);
+                conv(sec.block[2 * blk + 1], s->lw_u, false, s->lw_x, s->lw_x, y, y_relu, ldy);
             }
             in = s->lw_r;
         }

@@ -1,0 +1,200 @@
+// One residual block per launch for the layer-by-layer ResNet path (model-size variants of Sections 4.1 / 4.2):
+//   x' = x + conv_b(ReLU(conv_a(ReLU(x))))        3x3 SAME, C -> C, bf16 MFMA operands, fp32 x and accumulators.
+// Run as two separate convolutions a block moves the fp32 residual stream through HBM twice and the bf16 maps R
+// and U four times; here a workgroup takes a TH x TW tile of one image, stages ReLU(x) of the tile plus a two-pixel
+// halo in LDS, computes U = ReLU(conv_a) on the tile plus a one-pixel halo into LDS (zero where that lies
+// outside the image: conv_b's SAME padding), then conv_b on the tile, adds x and writes x' (and / or its bf16
+// copy): HBM sees x once in and once out.  The halo of U is recomputed by neighbouring tiles ((TH + 2)(TW + 2) /
+// (TH TW) of conv_a's work); the path is HBM-bound, the matrix cores have that to spare.
+//
+// Both convolutions are implicit GEMMs over planar LDS maps [C/8][rows][pitch][8 bf16] with the weight packing
+// of conv3x3_lds_kernel (A fragments [feature tile][chunk][lane][8], k = tap * C + ci, fetched from global
+// memory one chunk ahead).  A region's pixels are cut row-major into tiles of 16; wavefront w takes feature tiles
+// FTW * (w % NFG) ... and every NPG-th pixel tile from w / NFG, at most TPW of them.
+#pragma once
+#include "bf16_common.h"
+
+namespace seedinf {
+
+struct ResBlockArgs {
+    const float* x_in;                 // [B, H, W, C] fp32 residual stream
+    const bf16x8* wpa; const bf16x8* wpb;
+    const float* bias_a; const float* bias_b;
+    float* x_out;                      // fp32 x' [B, H, W, C], or nullptr; must not alias x_in (tiles read each other's halos)
+    __bf16* y;                         // bf16 copy of x', or nullptr
+    int y_relu;                        // rectify y
+    int ldy;                           // 0: y is NHWC; > 0: y is the feature matrix [B, ldy], (h, w, c) order
+    int B, H, W, TH, TW, tiles_y, tiles_x, kchunks;
+};
+
+constexpr int RB_THREADS = 512, RB_TPW = 6;
+constexpr size_t RB_LDS_MAX = 128 * 1024;
+
+template <int C>
+struct ResBlockCfg {
+    static_assert(C % 16 == 0 && C <= 128, "channels: a multiple of 16 up to 128");
+    static constexpr int NCG = C / 8, NFT = C / 16;
+    static constexpr int FTW = NFT % 2 == 0 ? 2 : 1;        // feature tiles a wavefront multiplies with one fragment
+    static constexpr int NFG = NFT / FTW;                   // feature groups
+    static_assert(8 % NFG == 0, "feature groups must divide the eight wavefronts");
+    static constexpr int NPG = 8 / NFG;                     // wavefronts (pixel groups) per feature group
+    static constexpr int MAX_PIX = 16 * RB_TPW * NPG;       // pixels of conv_a's region a workgroup can take
+    __host__ __device__ static constexpr int plane(int rows, int pitch) { return (rows * pitch + 15) / 16 * 16; }
+    static size_t lds_bytes(int TH, int TW) { return (size_t)NCG * (plane(TH + 4, TW + 4) + plane(TH + 2, TW + 2)) * 16; }
+    // tile extents for an H x W map: the fewest tiles whose conv_a region fits a workgroup and whose maps fit LDS
+    static bool choose(int H, int W, int& TH, int& TW)
+    {
+        long best = -1;
+        for (int ny = 1; ny <= H; ++ny) {
+            const int th = (H + ny - 1) / ny;
+            for (int nx = 1; nx <= W; ++nx) {
+                const int tw = (W + nx - 1) / nx;
+                if ((th + 2) * (tw + 2) > MAX_PIX || lds_bytes(th, tw) > RB_LDS_MAX) continue;
+                // cost: conv_a work of all tiles (halo recomputation), then the tile count
+                const long cost = (long)ny * nx * ((th + 2) * (tw + 2) + th * tw);
+                if (best < 0 || cost < best) { best = cost; TH = th; TW = tw; }
+                break;                                      // larger nx only shrinks tw further: more tiles, more halo
+            }
+        }
+        return best >= 0;
+    }
+};
+
+// One implicit-GEMM pass: region of RW-wide pixels (npix of them) over the planar map `src` (plane cells PL, pitch
+// PITCH; a region pixel (r, c) has its tap (0, 0) at cell r * PITCH + c).  acc[i][j]: pixel tile pg + NPG * i,
+// feature tile ft0 + j.
+template <int C>
+__device__ __forceinline__ void rb_conv(const char* src, int PL, int PITCH, int RW, int npix, const bf16x8* __restrict__ wp,
+                                        int kchunks, int ft0, int pg, int lane, floatx4 (&acc)[RB_TPW][ResBlockCfg<C>::FTW])
+{
+    using K = ResBlockCfg<C>;
+    const int g = lane >> 4, n = lane & 15;
+    const int ntiles = (npix + 15) / 16;
+    int base[RB_TPW];
+#pragma unroll
+    for (int i = 0; i < RB_TPW; ++i) {
+        const int q = min((pg + K::NPG * i) * 16 + n, npix - 1);
+        base[i] = (q / RW) * PITCH + q % RW;
+#pragma unroll
+        for (int j = 0; j < K::FTW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    const bf16x8* wl = wp + (size_t)ft0 * kchunks * 64 + lane;
+    bf16x8 a[K::FTW], a_next[K::FTW];
+#pragma unroll
+    for (int j = 0; j < K::FTW; ++j) a[j] = wl[(size_t)j * kchunks * 64];
+    for (int kc = 0; kc < kchunks; ++kc) {
+        const int kn = min(kc + 1, kchunks - 1);
+#pragma unroll
+        for (int j = 0; j < K::FTW; ++j) a_next[j] = wl[((size_t)j * kchunks + kn) * 64];
+        // the lane's 8 consecutive k of this chunk: one tap, one channel group (k past 9 C has zero weights: any cell)
+        const int k0 = kc * 32 + g * 8;
+        const int tap = min(k0 / C, 8), cg = (k0 % C) >> 3;
+        const char* s = src + ((size_t)cg * PL + (tap / 3) * PITCH + tap % 3) * 16;
+#pragma unroll
+        for (int i = 0; i < RB_TPW; ++i) {
+            if (pg + K::NPG * i < ntiles) {                 // uniform
+                const bf16x8 b = *(const bf16x8*)(s + base[i] * 16);
+#pragma unroll
+                for (int j = 0; j < K::FTW; ++j) acc[i][j] = mfma16(a[j], b, acc[i][j]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < K::FTW; ++j) a[j] = a_next[j];
+    }
+}
+
+template <int C>
+__global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockArgs p)
+{
+    using K = ResBlockCfg<C>;
+    extern __shared__ __attribute__((aligned(16))) char rb_lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, n = lane & 15;
+    const int tiles = p.tiles_y * p.tiles_x;
+    const int b = blockIdx.x / tiles, t = blockIdx.x % tiles;
+    const int y0 = (t / p.tiles_x) * p.TH, x0 = (t % p.tiles_x) * p.TW;
+    const int RP = p.TW + 4, RPL = K::plane(p.TH + 4, RP);          // ReLU(x): tile + 2
+    const int UP = p.TW + 2, UPL = K::plane(p.TH + 2, UP);          // U: tile + 1
+    char* Rm = rb_lds;
+    char* Um = rb_lds + (size_t)K::NCG * RPL * 16;
+    const float* ximg = p.x_in + (size_t)b * p.H * p.W * C;
+
+    // ---- R = ReLU(x) as bf16, zeros outside the image ----
+    const int rcells = (p.TH + 4) * RP;
+    for (int idx = tid; idx < rcells * K::NCG; idx += RB_THREADS) {
+        const int cell = idx / K::NCG, cg = idx - cell * K::NCG;           // a pixel's channel groups are adjacent in memory
+        const int r = cell / RP, c = cell - r * RP;
+        const int gy = y0 - 2 + r, gx = x0 - 2 + c;
+        bf16x8 v = {};
+        if (gy >= 0 && gy < p.H && gx >= 0 && gx < p.W) {
+            const float* s = ximg + ((size_t)gy * p.W + gx) * C + cg * 8;
+            const bf16x8 raw = to_bf16x8(*(const floatx4*)s, *(const floatx4*)(s + 4));
+            const bf16x4 lo = relu_bf16x4(__builtin_shufflevector(raw, raw, 0, 1, 2, 3));
+            const bf16x4 hi = relu_bf16x4(__builtin_shufflevector(raw, raw, 4, 5, 6, 7));
+            v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+        *(bf16x8*)(Rm + ((size_t)cg * RPL + cell) * 16) = v;
+    }
+    __syncthreads();
+
+    const int fg = wave % K::NFG, pg = wave / K::NFG;
+    const int ft0 = fg * K::FTW;
+    floatx4 acc[RB_TPW][K::FTW];
+
+    // ---- U = ReLU(conv_a(R) + bias) on the tile + 1, zero outside the image ----
+    {
+        const int UW = p.TW + 2, npix = (p.TH + 2) * UW;
+        rb_conv<C>(Rm, RPL, RP, UW, npix, p.wpa, p.kchunks, ft0, pg, lane, acc);
+        const int ntiles = (npix + 15) / 16;
+#pragma unroll
+        for (int j = 0; j < K::FTW; ++j) {
+            const int f = (ft0 + j) * 16 + g * 4;
+            const floatx4 bv = *(const floatx4*)(p.bias_a + f);
+#pragma unroll
+            for (int i = 0; i < RB_TPW; ++i) {
+                const int q = (pg + K::NPG * i) * 16 + n;
+                if (pg + K::NPG * i >= ntiles || q >= npix) continue;
+                const int r = q / UW, c = q - r * UW;
+                const int gy = y0 - 1 + r, gx = x0 - 1 + c;
+                bf16x4 o = {};
+                if (gy >= 0 && gy < p.H && gx >= 0 && gx < p.W) o = relu_bf16x4(to_bf16x4(acc[i][j] + bv));
+                *(bf16x4*)(Um + ((size_t)(f >> 3) * UPL + r * UP + c) * 16 + (g & 1) * 8) = o;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- x' = x + conv_b(U) + bias on the tile ----
+    {
+        const int npix = p.TH * p.TW;
+        rb_conv<C>(Um, UPL, UP, p.TW, npix, p.wpb, p.kchunks, ft0, pg, lane, acc);
+        const int ntiles = (npix + 15) / 16;
+        const int hw = p.H * p.W;
+#pragma unroll
+        for (int j = 0; j < K::FTW; ++j) {
+            const int f = (ft0 + j) * 16 + g * 4;
+            const floatx4 bv = *(const floatx4*)(p.bias_b + f);
+#pragma unroll
+            for (int i = 0; i < RB_TPW; ++i) {
+                const int q = (pg + K::NPG * i) * 16 + n;
+                if (pg + K::NPG * i >= ntiles || q >= npix) continue;
+                const int r = q / p.TW, c = q - r * p.TW;
+                const int gy = y0 + r, gx = x0 + c;
+                if (gy >= p.H || gx >= p.W) continue;
+                const int pl = gy * p.W + gx;
+                const size_t pix = (size_t)b * hw + pl;
+                floatx4 v = acc[i][j] + bv;
+                v += *(const floatx4*)(p.x_in + pix * C + f);
+                if (p.x_out) *(floatx4*)(p.x_out + pix * C + f) = v;
+                if (p.y) {
+                    const bf16x4 o = to_bf16x4(v);
+                    const size_t at = p.ldy > 0 ? (size_t)b * p.ldy + (size_t)pl * C + f : pix * C + f;
+                    *(bf16x4*)(p.y + at) = p.y_relu ? relu_bf16x4(o) : o;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace seedinf

@@ -14,6 +14,7 @@
 
 #include "../../include/seedinf.h"
 #include "plan.h"
+#include "host_pool.h"
 #include "kernels_fp32.h"
 #include "kernels_heads.h"
 #include "bf16_path.h"
@@ -26,21 +27,27 @@ struct seed_infer {
     float* d_w = nullptr;          // canonical flat fp32 weights the steps read: d_w_set[active]
     float* d_w_set[2] = {nullptr, nullptr};   // two copies: a weight update fills the idle one and flips
     int active = 0;
-    char* staging = nullptr;       // pinned host buffer a weight update is staged in
+    char* staging[2] = {nullptr, nullptr};     // pinned host buffers weight updates are staged in, used alternately
     size_t staging_bytes = 0;
-    hipEvent_t staged = nullptr;   // recorded after the copies that read `staging`
+    hipEvent_t staged[2] = {nullptr, nullptr}; // recorded after the copy that reads staging[i]
+    int stage_next = 0;
     float* d_act[2] = {nullptr, nullptr};   // fp32 ping-pong activations (fp32 mode)
     float* d_fc = nullptr;         // [max_batch, fc_units] fp32 (fp32 mode)
     float* d_hid = nullptr;        // [max_batch, 2*head_hidden] dueling hidden, fp32
     float* d_roll = nullptr;       // recurrent archs: 2 x (h, c) [max_batch, lstm_units], the states between the steps of an unroll
     const float* feat_f32 = nullptr;   // where the last fp32-mode step left the torso features
     Bf16State* bf = nullptr;       // everything the bf16 path owns
+    HostPool* pool = nullptr;      // host threads for the large copies (weight updates, the batcher's frames); made on first use
     std::vector<hipEvent_t> ev;    // profiling: 2 events per slot (empty = profiling off)
     int ev_used = 0;
     std::string err;
 };
 
 static thread_local std::string g_create_err;
+
+// The handle's host threads (seven workers + the caller), started by the first large copy; nullptr if they cannot
+// be started (the copies then run on the calling thread).
+static HostPool* host_pool(seed_infer* h);
 
 // ---- workspace in the library's static device array (seed_infer_step_static) ----
 // Device memory beyond a step's inputs and outputs: the activations between the kernels.  The handle's own copy is
@@ -73,6 +80,18 @@ static hipError_t scratch_address(int dev, void** out)
             return e_ == hipErrorOutOfMemory ? SEED_ERR_OOM : SEED_ERR_DEVICE;        \
         }                                                                             \
     } while (0)
+
+static HostPool* host_pool(seed_infer* h)
+{
+    if (!h->pool) {
+        try {
+            h->pool = new HostPool(7);
+        } catch (...) {
+            h->pool = nullptr;
+        }
+    }
+    return h->pool;
+}
 
 extern "C" size_t seed_infer_weight_count(const seed_arch_t* arch)
 {
@@ -115,8 +134,11 @@ static void free_all(seed_infer* h)
     if (!h) return;
     if (h->bf) { bf16_destroy(h->bf); h->bf = nullptr; }
     for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
-    if (h->staged) (void)hipEventDestroy(h->staged);
-    if (h->staging) (void)hipHostFree(h->staging);
+    delete h->pool;
+    for (int i = 0; i < 2; ++i) {
+        if (h->staged[i]) (void)hipEventDestroy(h->staged[i]);
+        if (h->staging[i]) (void)hipHostFree(h->staging[i]);
+    }
     if (h->d_w_set[0]) (void)hipFree(h->d_w_set[0]);
     if (h->d_w_set[1]) (void)hipFree(h->d_w_set[1]);
     if (h->d_act[0]) (void)hipFree(h->d_act[0]);
@@ -146,13 +168,15 @@ static seed_status_t create_impl(seed_infer* h, const float* weights_host)
         HIP_TRY(h, hipMalloc(&h->d_act[1], mb * p.max_act * sizeof(float)));
         HIP_TRY(h, hipMalloc(&h->d_fc, mb * a.fc_units * sizeof(float)));
     } else {
-        seed_status_t st = bf16_create(p, weights_host, &h->bf, h->err);
+        seed_status_t st = bf16_create(p, h->d_w, &h->bf, h->err);
         if (st != SEED_OK) return st;
     }
     // staging for weight updates, allocated here so that seed_infer_set_weights allocates nothing
-    h->staging_bytes = p.n_weights * sizeof(float) + (h->bf ? h->bf->pk_bytes + h->bf->fb_bytes : 0);
-    HIP_TRY(h, hipHostMalloc((void**)&h->staging, h->staging_bytes, hipHostMallocDefault));
-    HIP_TRY(h, hipEventCreateWithFlags(&h->staged, hipEventDisableTiming));
+    h->staging_bytes = p.n_weights * sizeof(float);
+    for (int i = 0; i < 2; ++i) {
+        HIP_TRY(h, hipHostMalloc((void**)&h->staging[i], h->staging_bytes, hipHostMallocDefault));
+        HIP_TRY(h, hipEventCreateWithFlags(&h->staged[i], hipEventDisableTiming));
+    }
     void* scratch = nullptr;                   // seed_infer_step_static's workspace on this device
     HIP_TRY(h, scratch_address(h->device, &scratch));
     HIP_TRY(h, hipDeviceSynchronize());
@@ -628,26 +652,23 @@ extern "C" seed_status_t seed_infer_set_weights(seed_infer_t* h, const float* we
     HIP_TRY(h, hipGetDevice(&dev));
     if (dev != h->device) return fail(SEED_ERR_INVALID_ARG, "current HIP device differs from the handle's device");
     hipStream_t s = (hipStream_t)hip_stream;
-    // the previous update's copies may still be reading the staging buffer
-    HIP_TRY(h, hipEventSynchronize(h->staged));
+    // two staging buffers, used alternately: the upload of the update before the previous one may still be
+    // reading this one
+    const int sb = h->stage_next;
+    HIP_TRY(h, hipEventSynchronize(h->staged[sb]));
     const int idle = 1 - h->active;
     const size_t wb = p.n_weights * sizeof(float);
-    memcpy(h->staging, weights_host, wb);
-    HIP_TRY(h, hipMemcpyAsync(h->d_w_set[idle], h->staging, wb, hipMemcpyHostToDevice, s));
+    pool_memcpy(host_pool(h), h->staging[sb], weights_host, wb);
+    HIP_TRY(h, hipMemcpyAsync(h->d_w_set[idle], h->staging[sb], wb, hipMemcpyHostToDevice, s));
+    HIP_TRY(h, hipEventRecord(h->staged[sb], s));
+    h->stage_next = 1 - sb;
     if (h->bf) {
-        Bf16State* b = h->bf;
-        Bf16Packed o;
-        bf16_pack(p, b->torso_kind, b->ldf, b->ldfc, weights_host, o);
-        if (o.pk.size() * 2 != b->pk_bytes || o.fb.size() * 4 != b->fb_bytes) return fail(SEED_ERR_DEVICE, "packed weight size changed");
-        char* st_pk = h->staging + wb;
-        char* st_fb = st_pk + b->pk_bytes;
-        memcpy(st_pk, o.pk.data(), b->pk_bytes);
-        if (b->fb_bytes) memcpy(st_fb, o.fb.data(), b->fb_bytes);
-        HIP_TRY(h, hipMemcpyAsync(b->arena + b->o_pk[idle], st_pk, b->pk_bytes, hipMemcpyHostToDevice, s));
-        if (b->fb_bytes) HIP_TRY(h, hipMemcpyAsync(b->arena + b->o_fb[idle], st_fb, b->fb_bytes, hipMemcpyHostToDevice, s));
-        b->active = idle;
+        // the matrix-core kernels' operand layouts are a fixed gather of the flat vector: packed on the device
+        bf16_repack(h->bf, h->d_w_set[idle], idle, s);
+        HIP_TRY(h, hipGetLastError());
     }
-    HIP_TRY(h, hipEventRecord(h->staged, s));
+    // every piece of the update is enqueued: steps enqueued from here on read the new set
+    if (h->bf) h->bf->active = idle;
     h->active = idle;
     h->d_w = h->d_w_set[idle];
     return SEED_OK;
