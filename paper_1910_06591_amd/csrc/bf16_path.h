@@ -17,6 +17,7 @@
 #include "resnet_fused.h"
 #include "resnet_layerwise.h"
 #include "resnet_blockfused.h"
+#include "resnet_firstpool.h"
 
 namespace seedinf {
 
@@ -106,7 +107,14 @@ inline void pack_a(std::vector<uint32_t>& out, int n_ftiles, int kchunks, F valu
 }
 
 struct ConvStackLayerDev { size_t wp_off; size_t koff_off; int kchunks; };
-struct LwLayerDev { size_t wp_off; size_t ktab_off; int kchunks; };       // layer-by-layer ResNet: one 3x3 convolution
+// layer-by-layer ResNet, one 3x3 convolution; first_off: the network's first layer packed for the fused
+// convolution + pooling kernel as well (LW_NONE: not packed that way)
+constexpr size_t LW_NONE = (size_t)-1;
+struct LwLayerDev { size_t wp_off; size_t ktab_off; int kchunks; size_t first_off = LW_NONE; };
+inline bool first_pool_supported(const ConvLayer& c)
+{
+    return (c.Cin <= 4 || c.Cin == 8 || c.Cin == 16) && (c.Cout == 16 || c.Cout == 32 || c.Cout == 64);
+}
 
 // Device pointers into one uploaded copy of the packed weights.
 struct Bf16WeightSet {
@@ -245,7 +253,7 @@ inline void bf16_pack(const Plan& p, int torso_kind, int ldf_, int ldfc_, Bf16Pa
     std::vector<int>& ko = o.ko;
     size_t (&sec_off)[4][5] = o.sec_off;
     if (a.torso == SEED_TORSO_RESNET && torso_kind == TORSO_NONE) {
-        auto pack_conv = [&](const ConvLayer& c) {
+        auto pack_conv = [&](const ConvLayer& c, bool first) {
             LwLayerDev d;
             const int K = 9 * c.Cin;
             d.kchunks = (K + 31) / 32;
@@ -262,11 +270,21 @@ inline void bf16_pack(const Plan& p, int torso_kind, int ldf_, int ldfc_, Bf16Pa
                     ko.push_back((dy * c.W + dx) * c.Cin + k0 % c.Cin);
                     ko.push_back((dy + 1) | ((dx + 1) << 8));
                 }
+            if (first && first_pool_supported(c)) d.first_off = d.wp_off;       // 8 or 16 planes: the same packing
+            if (first && first_pool_supported(c) && c.Cin <= 4) {
+                d.first_off = pk.size();
+                pack_a(pk, c.Cout / 16, 2, [&](int f, int k) -> float {
+                    int dy, dx, ci;
+                    first_pool_k(k, dy, dx, ci);
+                    return dy < 3 && dx < 3 && ci < c.Cin ? wl[(size_t)((dy * 3 + dx) * c.Cin + ci) * c.Cout + f] : 0.f;
+                });
+            }
             o.lw.push_back(d);
         };
-        for (const Section& sec : p.sections) {
-            pack_conv(sec.conv0);
-            for (int j = 0; j < 4; ++j) pack_conv(sec.block[j]);
+        for (size_t si = 0; si < p.sections.size(); ++si) {
+            const Section& sec = p.sections[si];
+            pack_conv(sec.conv0, si == 0);
+            for (int j = 0; j < 4; ++j) pack_conv(sec.block[j], false);
         }
     } else if (a.torso == SEED_TORSO_RESNET) {
         if (torso_kind == TORSO_DMLAB) {
@@ -501,7 +519,6 @@ inline seed_status_t bf16_create(const Plan& p, const float* d_w, Bf16State** ou
     BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
-    BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
     if (s->stack_fused) {
         BF_TRY(hipFuncSetAttribute((const void*)r2d2_torso_bf16_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, r2d2::LDS_BYTES));
         BF_TRY(hipFuncSetAttribute((const void*)r2d2_torso_bf16_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, r2d2::LDS_BYTES));
@@ -644,15 +661,75 @@ inline void launch_lw_conv(hipStream_t st, const LwConvArgs& c, int ft, bool u8)
     else by_ft(std::false_type{});
 }
 
+// The first layer with its pooling as one launch (uint8 frame -> fp32 x and, if r is given, ReLU(x) as bf16);
+// false when the layer has no fused kernel, and nothing was launched.
+inline bool launch_first_pool(hipStream_t st, const LwLayerDev& d, const bf16x8* wp_conv, const float* d_w, const Section& sec, int B,
+                              const uint8_t* obs, float* x, __bf16* r)
+{
+    const ConvLayer& c = sec.conv0;
+    if (d.first_off == LW_NONE) return false;
+    auto go = [&](auto cc, auto cellc) -> bool {
+        constexpr int CC = decltype(cc)::value, CELL = decltype(cellc)::value;
+        using K = FirstPoolCfg<CC, CELL>;
+        FirstPoolArgs a{};
+        if (!K::choose(sec.PH, sec.PW, a.PTH, a.PTW)) return false;
+        if (CELL != 4 && d.kchunks != K::KCH) return false;
+        a.obs = obs; a.wp = wp_conv + d.first_off / 8; a.bias = d_w + c.b_off; a.scale = 1.0f / 255.0f;
+        a.x = x; a.r = r;
+        a.B = B; a.H = c.H; a.W = c.W; a.Cin = c.Cin; a.PH = sec.PH; a.PW = sec.PW; a.pad_h = sec.pool_pad_h; a.pad_w = sec.pool_pad_w;
+        a.tiles_y = (sec.PH + a.PTH - 1) / a.PTH; a.tiles_x = (sec.PW + a.PTW - 1) / a.PTW;
+        hipLaunchKernelGGL((first_pool_kernel<CC, CELL>), dim3((unsigned)((long)B * a.tiles_y * a.tiles_x)), dim3(FP_THREADS),
+                           K::lds_bytes(a.PTH, a.PTW), st, a);
+        return true;
+    };
+    auto by_cell = [&](auto cc) -> bool {
+        if (c.Cin <= 4) return go(cc, std::integral_constant<int, 4>{});
+        if (c.Cin == 8) return go(cc, std::integral_constant<int, 8>{});
+        if (c.Cin == 16) return go(cc, std::integral_constant<int, 16>{});
+        return false;
+    };
+    switch (c.Cout) {
+    case 16: return by_cell(std::integral_constant<int, 16>{});
+    case 32: return by_cell(std::integral_constant<int, 32>{});
+    case 64: return by_cell(std::integral_constant<int, 64>{});
+    default: return false;
+    }
+}
+
+template <class F>
+inline bool resblock_by_width(int C, F go)
+{
+    switch (C) {
+    case 16: return go(std::integral_constant<int, 16>{});
+    case 32: return go(std::integral_constant<int, 32>{});
+    case 64: return go(std::integral_constant<int, 64>{});
+    default: return false;
+    }
+}
+
+// Whether launch_resblock takes this block.  Measured at 1024 images against the two-launch form: 16 and 32
+// channels are faster fused at every map size (16 ch 54 x 72: 157 vs 308 us; 32 ch 27 x 36 and smaller: 60 vs 70;
+// 32 ch 36 x 48: 280 vs 284 and the pooling kernel need not write R), 64 channels up to 18 x 24 (95 vs 124); at
+// 64 channels on 36 x 48 and at 128 channels the small tiles LDS leaves room for lose (794 vs 526 us).
+inline bool resblock_fusable(const ConvLayer& ca, const ConvLayer& cb)
+{
+    const int C = ca.Cin;
+    if (ca.Cout != C || cb.Cin != C || cb.Cout != C || ca.H != cb.H || ca.W != cb.W) return false;
+    if (C > 64 || (C == 64 && ca.H * ca.W > 18 * 24)) return false;
+    return resblock_by_width(C, [&](auto cc) {
+        int th, tw;
+        return ResBlockCfg<decltype(cc)::value>::choose(ca.H, ca.W, th, tw);
+    });
+}
+
 // One residual block (two 3x3 convolutions C -> C over an H x W map) as a single launch; false when the width has
 // no fused kernel or no tile fits, and nothing was launched.
 inline bool launch_resblock(hipStream_t st, const LwLayerDev& da, const LwLayerDev& db, const bf16x8* wp_conv, const float* d_w,
                             const ConvLayer& ca, const ConvLayer& cb, int B, const float* x_in, float* x_out, __bf16* y, int y_relu,
                             int ldy)
 {
-    const int C = ca.Cin;
-    if (ca.Cout != C || cb.Cin != C || cb.Cout != C || ca.H != cb.H || ca.W != cb.W) return false;
-    auto go = [&](auto cc) -> bool {
+    if (!resblock_fusable(ca, cb)) return false;
+    return resblock_by_width(ca.Cin, [&](auto cc) -> bool {
         constexpr int CC = decltype(cc)::value;
         using K = ResBlockCfg<CC>;
         ResBlockArgs r{};
@@ -665,14 +742,7 @@ inline bool launch_resblock(hipStream_t st, const LwLayerDev& da, const LwLayerD
         hipLaunchKernelGGL(resblock_fused_kernel<CC>, dim3((unsigned)((long)B * r.tiles_y * r.tiles_x)), dim3(RB_THREADS),
                            K::lds_bytes(r.TH, r.TW), st, r);
         return true;
-    };
-    switch (C) {
-    case 16: return go(std::integral_constant<int, 16>{});
-    case 32: return go(std::integral_constant<int, 32>{});
-    case 64: return go(std::integral_constant<int, 64>{});
-    case 128: return go(std::integral_constant<int, 128>{});
-    default: return false;
-    }
+    });
 }
 
 // Torso and linear layer over B rows: leaves the rectified linear-layer output of row r in row r of
@@ -703,11 +773,17 @@ inline seed_status_t bf16_torso_fc(Bf16State* s, const Plan& p, const float* d_w
                 const int ft = nft % 4 == 0 ? 4 : (nft % 2 == 0 ? 2 : 1);
                 launch_lw_conv(st, ca, ft, u8);
             };
-            conv(sec.conv0, in, si == 0, nullptr, nullptr, s->lw_c0, 0, 0);
-            const int C = sec.conv0.Cout;
-            const long total = (long)B * sec.PH * sec.PW * (C / 4);
-            hipLaunchKernelGGL(pool3x3s2_lw_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s->lw_c0, s->lw_x,
-                               s->lw_r, B, sec.conv0.OH, sec.conv0.OW, C, sec.PH, sec.PW, sec.pool_pad_h, sec.pool_pad_w);
+            // only the layer-by-layer block convolutions read R; a fused block takes ReLU(x) itself
+            const bool need_r = !resblock_fusable(sec.block[0], sec.block[1]);
+            if (si == 0 && launch_first_pool(st, s->lw[li], W.wp_conv, d_w, sec, B, obs, s->lw_x, need_r ? s->lw_r : nullptr)) {
+                ++li;
+            } else {
+                conv(sec.conv0, in, si == 0, nullptr, nullptr, s->lw_c0, 0, 0);
+                const int C = sec.conv0.Cout;
+                const long total = (long)B * sec.PH * sec.PW * (C / 4);
+                hipLaunchKernelGGL(pool3x3s2_lw_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s->lw_c0, s->lw_x,
+                                   s->lw_r, B, sec.conv0.OH, sec.conv0.OW, C, sec.PH, sec.PW, sec.pool_pad_h, sec.pool_pad_w);
+            }
             // a residual block in one launch where the width has a fused kernel and a tile fits; x ping-pongs between
             // lw_x and the (by now dead) conv0 map, since tiles read their neighbours' halos of the block's input
             float* x_cur = s->lw_x;
