@@ -41,22 +41,7 @@ struct R2d2TorsoArgs {
     int B;
 };
 
-// Developer instrumentation: per-phase cycle counts of workgroup 0's first wavefront (compiled out by default).
-#ifdef SEEDINF_R2D2_TIMING
-__device__ unsigned long long r2d2_phase_cycles[8];
-#define R2D2_MARK(k)                                                                     \
-    do {                                                                                 \
-        const unsigned long long now_ = clock64();                                       \
-        tacc_[k] += now_ - tmark_;                                                       \
-        tmark_ = now_;                                                                   \
-    } while (0)
-#else
-#define R2D2_MARK(k) do { } while (0)
-#endif
-
-#ifndef R2D2_TILE_FENCE
 #define R2D2_TILE_FENCE __builtin_amdgcn_sched_barrier(0)
-#endif
 
 namespace r2d2 {
 constexpr int H = 84, W = 84;
@@ -116,9 +101,6 @@ __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2Tors
         }
     };
 
-#ifdef SEEDINF_R2D2_TIMING
-    unsigned long long tmark_ = clock64(), tacc_[6] = {0, 0, 0, 0, 0, 0};
-#endif
     int b = blockIdx.x, buf = 0;
     if (b < p.B) fetch_frame(b, 0);
     for (; b < p.B; b += gridDim.x, buf ^= 1) {
@@ -128,7 +110,6 @@ __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2Tors
         asm volatile("" : "+v"(g), "+v"(n));
         stage_wait();
         __syncthreads();                                       // the raw frame has landed; the previous image is finished
-        R2D2_MARK(0);
 
         // ---- conv1: 8x8 stride 4, 4 -> 32 channels, ReLU; acc holds 255 x the true sum ----
         const floatx4 bias1[2] = {*(const floatx4*)(p.b1 + g * 4), *(const floatx4*)(p.b1 + 16 + g * 4)};
@@ -169,12 +150,9 @@ __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2Tors
             if (xh >= 1) { *(bf16x4*)(d + 16 * A1_SUB - 16) = o0; *(bf16x4*)(d + (16 + 8) * A1_SUB - 16) = o1; }
             R2D2_TILE_FENCE;                                 // one tile's fragments in registers at a time
         }
-        R2D2_MARK(2);
         // the other raw buffer was last read by the previous image's conv1, two barriers ago
         if (b + (int)gridDim.x < p.B) fetch_frame(b + gridDim.x, buf ^ 1);
-        R2D2_MARK(1);
         __syncthreads();
-        R2D2_MARK(3);
 
         // ---- conv2: 4x4 stride 2, 32 -> 64 channels; this wavefront: feature tile f23, taps half*8 .. +7 ----
         {
@@ -227,7 +205,6 @@ __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2Tors
             else finish(std::integral_constant<int, 3>{});
         }
         __syncthreads();
-        R2D2_MARK(4);
 
         // ---- conv3: 3x3 stride 1, 64 -> 64 channels; this wavefront: feature tile f23, chunks half*9 .. +8 ----
         {
@@ -269,14 +246,9 @@ __global__ __launch_bounds__(r2d2::THREADS) void r2d2_torso_bf16_kernel(R2d2Tors
             if (half == 0) finish(std::integral_constant<int, 0>{});
             else finish(std::integral_constant<int, 2>{});
         }
-        R2D2_MARK(5);
         // (the next image's first barrier separates these reads of `ex` and `act2` from their next writes)
     }
     stage_wait();
-#ifdef SEEDINF_R2D2_TIMING
-    if (tid == 0 && blockIdx.x == 0)
-        for (int k = 0; k < 6; ++k) r2d2_phase_cycles[k] += tacc_[k];
-#endif
 }
 
 }  // namespace seedinf

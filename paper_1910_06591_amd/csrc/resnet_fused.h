@@ -35,67 +35,22 @@
 
 namespace seedinf {
 
-// Optional developer instrumentation: per-phase cycle totals (summed over workgroups) of the
-// torso kernel.  Compiled out unless SEEDINF_PHASE_TIMING is defined.
-#ifdef SEEDINF_PHASE_TIMING
-__device__ unsigned long long seed_phase_cycles[32];
-#define PHASE_MARK(id)                                                                  \
-    do {                                                                                \
-        if (tid == 0) {                                                                 \
-            const unsigned long long now_ = clock64();                                  \
-            atomicAdd(&seed_phase_cycles[id], now_ - phase_last_);                      \
-            phase_last_ = now_;                                                         \
-        }                                                                               \
-    } while (0)
-#define PHASE_DECL unsigned long long phase_last_ = clock64()
-// finer split of one block phase (section DETAIL_SEC, wavefront DETAIL_WAVE): convolution, wait for the staged
-// weights, barrier -> seed_phase_cycles[24..26]; the atomics are issued after the barrier so that the wait for
-// the staged weights does not also wait for them
-#ifndef DETAIL_SEC
-#define DETAIL_SEC 1
-#endif
-#ifndef DETAIL_WAVE
-#define DETAIL_WAVE 0
-#endif
-#define DETAIL_T0 unsigned long long dt_[4]; dt_[0] = clock64()
-#define DETAIL_MARK(k) do { dt_[k + 1] = clock64(); if (k == 2 && SI == DETAIL_SEC && (tid & 63) == 0 && (tid >> 6) == DETAIL_WAVE) { for (int q_ = 0; q_ < 3; ++q_) atomicAdd(&seed_phase_cycles[24 + q_], dt_[q_ + 1] - dt_[q_]); } } while (0)
-#else
-#define DETAIL_T0 do { } while (0)
-#define DETAIL_MARK(k) do { } while (0)
-#define PHASE_MARK(id) do { } while (0)
-#define PHASE_DECL do { } while (0)
-#endif
-
-#ifdef SEEDINF_TRACE
-__device__ unsigned long long seed_trace[8][64];
-#define TR(k) do { if (tr && lane == 0) seed_trace[wave][k] = clock64(); } while (0)
-#else
-#define TR(k) do { } while (0)
-#endif
-
-#ifndef SEEDINF_RN_WAVES
-#define SEEDINF_RN_WAVES 8
-#endif
-#ifndef SEEDINF_GROUP
-#define SEEDINF_GROUP 2                         // images a workgroup takes through the last section's block phases together
-                                                // (3 and, with a low weight slot at 40 KiB, 4 were measured within 1 % of 2)
-#endif
-constexpr int RN_WAVES = SEEDINF_RN_WAVES;
+constexpr int RN_WAVES = 8;
+// images a workgroup takes through the last section's block phases together (3 and, with a low weight slot at
+// 40 KiB, 4 were measured within 1 % of 2)
+constexpr int RN_GROUP = 2;
 constexpr int RN_THREADS = RN_WAVES * 64;
 constexpr int LDS_TOTAL = 160 * 1024;
 constexpr int WSLOT_BYTES = 19 * 1024;          // largest layer: 18 fragments of 1 KiB + the bias chunk
 
 enum { IN_LDS = 0, IN_U8_C3 = 1, IN_U8_PLANAR = 2 };
 
-// Keeps the instruction scheduler from moving anything across this point: the hand-written order (loads of
-// the next tiles first, then the MFMA chains back to back, then the epilogue) is the software pipeline.
-// A wavefront's own vector-ALU instructions were measured not to overlap its MFMAs on this chip, so
-// interleaving the epilogue with the chain gains nothing; the overlap comes from the SIMD's other wavefront.
-#ifndef SEEDINF_NO_FENCE
+// Keeps the instruction scheduler from moving anything across this point: the hand-written order (fragment
+// requests of the next tiles, the MFMA chains, the epilogue pieces placed between them) is the software
+// pipeline.  A wavefront's own vector-ALU work does issue under its running MFMAs (measured: about two vector
+// instructions per MFMA ride along free; an MFMA takes ~8 issue cycles of its wavefront, 16 of the pipe), so the
+// epilogue of a finished tile is spread over the chain of the next one.
 #define SCHED_FENCE __builtin_amdgcn_sched_barrier(0)
-#else
-#define SCHED_FENCE do { } while (0)
-#endif
 
 // Workgroup barrier for LDS-only communication: waits for this wavefront's LDS
 // traffic, not for its outstanding global loads (the prefetches stay in flight).
@@ -871,9 +826,8 @@ __device__ __forceinline__ void tile_ref(int wave, int i, int n, int& y, int& xx
 // computed on whatever the map holds there and stored to `trash`.
 template <class S, bool ADD_X, int OUT>
 __device__ __forceinline__ void block_conv_slide16(const char* src, char* dst, char* trash, const char* wslot,
-                                                   floatx4 (&x)[S::NT][S::FT], int lane, int wave, bool tr = false)
+                                                   floatx4 (&x)[S::NT][S::FT], int lane, int wave)
 {
-    TR(0);
     static_assert(S::FT == 1 && OUT != 2, "sliding block convolution: 16 channels, LDS output");
     using SM = SlideMap16;
     const int g = lane >> 4, n = lane & 15;
@@ -898,7 +852,6 @@ __device__ __forceinline__ void block_conv_slide16(const char* src, char* dst, c
         for (int r = 0; r < 4; ++r) R[r] = *(const bf16x8*)(pR + r * ROWB);
         E[0] = *(const bf16x8*)pE;
         E[1] = *(const bf16x8*)(pE + 2 * ROWB);
-        TR(1 + 16 * c);
 #pragma unroll
         for (int pp = 0; pp < LEN / 2; ++pp) {
             if (pp + 1 < LEN / 2) {
@@ -921,7 +874,6 @@ __device__ __forceinline__ void block_conv_slide16(const char* src, char* dst, c
             const bf16x4 v0 = to_bf16x4(a0), v1 = to_bf16x4(a1);
             *(bf16x4*)d = OUT == 1 ? v0 : relu_bf16x4(v0);
             *(bf16x4*)(d + (ok ? ROWB : 0)) = OUT == 1 ? v1 : relu_bf16x4(v1);
-            TR(2 + 16 * c + pp);
         }
     };
     run_chain(std::integral_constant<int, 0>{});
@@ -942,9 +894,8 @@ struct NoFiller {
 template <class S, bool ADD_X, int OUT, class Filler = NoFiller, int NIMG = 1>
 __device__ __forceinline__ void block_conv(const char* src, char* dst, const char* wslot, const int (&tb)[S::NT],
                                            floatx4 (&x)[NIMG * S::NT][S::FT], __bf16* const (&feat_rows)[NIMG], int lane, int wave,
-                                           Filler filler = Filler{}, bool tr = false)
+                                           Filler filler = Filler{})
 {
-    TR(0);
     static_assert(NIMG == 1 || S::NT == 1, "several images share a phase only with one tile per wavefront each");
     constexpr int NTT = NIMG * S::NT;
     constexpr int IMG_CELLS = S::ACT_BYTES / 16;           // cells between the two images' maps
@@ -986,7 +937,6 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
     for (int j = 0; j < S::FT; ++j) bv[j] = *(const floatx4*)(wslot + S::WB_FRAGS * 1024 + (j * 4 + g) * 16);
 #pragma unroll
     for (int kc = 0; kc < AHEAD; ++kc) request(0, kc, true);
-    TR(1);
     if constexpr (!std::is_same<Filler, NoFiller>::value) {
         SCHED_FENCE;
         filler();
@@ -1008,7 +958,6 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
             else if (i + 1 < NTT) request(i + 1, kc + AHEAD - S::KCB, false);
         }
         SCHED_FENCE;
-        TR(2 + 2 * i);
         const int p = t * 16 + n;
 #pragma unroll
         for (int j = 0; j < S::FT; ++j) {
@@ -1020,7 +969,6 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
                 else *(bf16x4*)(dstl + tbv(i) * 16 + j * (2 * S::PLANE * 16)) = out;
             }
         }
-        TR(3 + 2 * i);
     }
 }
 
@@ -1036,10 +984,9 @@ __device__ __forceinline__ void block_conv(const char* src, char* dst, const cha
 // of its own and a wavefront running alone at the end of a phase still keeps the matrix pipe fed.
 template <class S, bool ADD_X, int OUT, class Filler = NoFiller>
 __device__ __forceinline__ void block_conv_v2(const char* src, char* dst, const char* wslot, const int (&tb)[4],
-                                              floatx4 (&x)[4][2], int lane, int wave, Filler filler = Filler{}, bool tr = false)
+                                              floatx4 (&x)[4][2], int lane, int wave, Filler filler = Filler{})
 {
     static_assert(S::FT == 2 && S::C == 32 && OUT != 2, "18 x 24 maps of 32 channels, LDS output");
-    TR(0);
     using TM = TileMap1824;
     const int g = lane >> 4;
     const int nt = TM::ntiles(wave);                                  // uniform
@@ -1060,7 +1007,6 @@ __device__ __forceinline__ void block_conv_v2(const char* src, char* dst, const 
     constexpr int AHEAD = 4;
 #pragma unroll
     for (int kc = 0; kc < AHEAD; ++kc) { wfrag(kc); F[kc / 3][kc % 3] = frag(0, kc / 3, kc % 3); }
-    TR(1);
     if constexpr (!std::is_same<Filler, NoFiller>::value) {
         SCHED_FENCE;
         filler();
@@ -1099,7 +1045,6 @@ __device__ __forceinline__ void block_conv_v2(const char* src, char* dst, const 
             if (kc == 8 && i + 1 < 4) nxt[1] = ADD_X ? x[i + 1][1] + bv[1] : bv[1];
         }
         SCHED_FENCE;
-        TR(2 + 2 * i);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             fin[j] = acc[j];
@@ -1118,7 +1063,6 @@ __device__ __forceinline__ void block_conv_v2(const char* src, char* dst, const 
             }
         }
     }
-    TR(12);
 }
 
 // conv0 of a CONVMAP section in block_conv's terms: a 3x3 SAME conv C -> C over the section's H x W input map,
@@ -1288,7 +1232,7 @@ constexpr int wslot(int q)
 template <class S, class SN, class M, bool LAST, int SI, int J0, int NSETS, bool INB, class PreT>
 __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, const SecWeights& nsw,
                                             const uint8_t* __restrict__ obs_img, PreT& pre,
-                                            __bf16* __restrict__ feat_row, int tid, bool trimg = false)
+                                            __bf16* __restrict__ feat_row, int tid)
 {
     // keep per-tile index arithmetic inside the image loop: hoisted out of it, it would occupy
     // (and spill) hundreds of registers for the whole kernel
@@ -1325,7 +1269,6 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
     using I4 = std::integral_constant<int, 4>;
     floatx4 x[S::NT][S::FT];
-    PHASE_DECL;
 
     // ---------------- conv0 + max-pool ----------------
     {
@@ -1353,7 +1296,6 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                     if (strip + 1 < S::NSTRIPS) prefetch_issue<S>(mine, obs_img, strip + 1, tid);
                 }
                 if (strip > 0) lds_barrier();
-                PHASE_MARK(SI * 8 + 0);
                 if (strip == 0) load_a_frags(w0, lds + SLOT_C0, lane);
                 int pr0, pr1, r0, r1;
                 strip_rows<S>(strip, pr0, pr1, r0, r1);
@@ -1375,7 +1317,6 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
         }
         stage_wait();
         lds_barrier();
-        PHASE_MARK(SI * 8 + 1);
     }
 
     // ---------------- x <- pooled map (+ edge columns); R = ReLU(x) ----------------
@@ -1431,19 +1372,18 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
             }
         }
         lds_barrier();
-        PHASE_MARK(SI * 8 + 3);
     }
     __bf16* const feat_rows[1] = {feat_row};
-    auto conv = [&](auto add_x, auto out, const char* src, char* dst, const char* ws, auto filler, bool tr = false) {
+    auto conv = [&](auto add_x, auto out, const char* src, char* dst, const char* ws, auto filler) {
         constexpr bool ADD_X = decltype(add_x)::value;
         constexpr int OUT = decltype(out)::value;
         if constexpr (S::SLIDE) {
             filler();
-            block_conv_slide16<S, ADD_X, OUT>(src, dst, lds + M::TRASH + lane * 8, ws, x, lane, wave, tr);
+            block_conv_slide16<S, ADD_X, OUT>(src, dst, lds + M::TRASH + lane * 8, ws, x, lane, wave);
         } else if constexpr (S::V2) {
-            block_conv_v2<S, ADD_X, OUT>(src, dst, ws, tb, x, lane, wave, filler, tr);
+            block_conv_v2<S, ADD_X, OUT>(src, dst, ws, tb, x, lane, wave, filler);
         } else {
-            block_conv<S, ADD_X, OUT>(src, dst, ws, tb, x, feat_rows, lane, wave, filler, tr);
+            block_conv<S, ADD_X, OUT>(src, dst, ws, tb, x, feat_rows, lane, wave, filler);
         }
     };
     using BF = std::false_type; using BT = std::true_type;
@@ -1467,31 +1407,14 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     conv(BF{}, I0{}, bufR, bufU, lds + wslot<M, S, INB>(QB), slice(I1{}));
     stage_wait();
     lds_barrier();
-    PHASE_MARK(SI * 8 + 4);
-#ifdef SEEDINF_TRACE
-    const bool tr = trimg && SI == SEEDINF_TRACE;
-#else
-    const bool tr = false;
-#endif
-    TR(40);
     stage(I2{});
-    DETAIL_T0;
-    TR(41);
-    conv(BT{}, I0{}, bufU, bufR, lds + wslot<M, S, INB>(QB + 1), slice(I2{}), tr);
-    TR(42);
-    DETAIL_MARK(0);
+    conv(BT{}, I0{}, bufU, bufR, lds + wslot<M, S, INB>(QB + 1), slice(I2{}));
     stage_wait();
-    TR(43);
-    DETAIL_MARK(1);
     lds_barrier();
-    TR(44);
-    DETAIL_MARK(2);
-    PHASE_MARK(SI * 8 + 5);
     stage(I3{});
     conv(BF{}, I0{}, bufR, bufU, lds + wslot<M, S, INB>(QB + 2), slice(I3{}));
     stage_wait();
     lds_barrier();
-    PHASE_MARK(SI * 8 + 6);
     if constexpr (!LAST) stage(I4{});
     conv(BT{}, std::integral_constant<int, LAST ? 2 : 1>{}, bufU, bufR, lds + wslot<M, S, INB>(QB + 3), NoFiller{});
     // The last layer writes to global memory, so buf0 is free: the next frame's first strip (prefetched into
@@ -1499,7 +1422,6 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
     if constexpr (LAST) prefetch_commit<PS, SLICED ? 0 : -1>(pre, buf0, 0, tid);
     stage_wait();
     lds_barrier();
-    PHASE_MARK(SI * 8 + 7);
 }
 
 // ---- several images through the last section's block phases together ----
@@ -1521,16 +1443,13 @@ __device__ __forceinline__ void last_front_first(char* lds, floatx4 (&xa)[S::NT]
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     char* buf0 = lds + M::BUF0;
     char* buf1 = lds + M::BUF1;
-    PHASE_DECL;
     conv_map<S>(buf0, buf1, lds + wslot<M, S, false>(J0), lane, wave);
     lds_barrier();
-    PHASE_MARK(16 + 0);
     int tb[S::NT];
     bool ok[S::NT];
     pooled_x<S>(buf1, tb, xa, ok, lane, wave);
     prefetch_commit<typename PreT::Sec>(pre, buf0, 0, tid);
     lds_barrier();
-    PHASE_MARK(16 + 2);
 }
 
 template <class S, class M, int J0, int NSETS, int N, int NQ, class PreT>
@@ -1563,12 +1482,10 @@ __device__ __forceinline__ void last_group(char* lds, const SecWeights& sw, cons
     using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
 
     // conv0 of the last image
-    PHASE_DECL;
     stage(I0{});
     conv_map<S>(buf0, buf1, lds + wslot<M, S, false>(J0), lane, wave);
     stage_wait();
     lds_barrier();
-    PHASE_MARK(16 + 1);
     // pooled x of the last image; R of all
     floatx4 x[N * S::NT][S::FT];
     int tb[S::NT];
@@ -1588,7 +1505,6 @@ __device__ __forceinline__ void last_group(char* lds, const SecWeights& sw, cons
         for (int j = 0; j < S::FT; ++j) x[N - 1][j] = xb[0][j];
     }
     lds_barrier();
-    PHASE_MARK(16 + 3);
     // block phases on all images
     __bf16* feats[N];
 #pragma unroll
@@ -1601,21 +1517,17 @@ __device__ __forceinline__ void last_group(char* lds, const SecWeights& sw, cons
     block_conv<S, false, 0, decltype(slice(I1{})), N>(buf0, buf1, lds + wslot<M, S, false>(QB), tb, x, feats, lane, wave, slice(I1{}));
     stage_wait();
     lds_barrier();
-    PHASE_MARK(16 + 4);
     stage(I2{});
     block_conv<S, true, 0, decltype(slice(I2{})), N>(buf1, buf0, lds + wslot<M, S, false>(QB + 1), tb, x, feats, lane, wave, slice(I2{}));
     stage_wait();
     lds_barrier();
-    PHASE_MARK(16 + 5);
     stage(I3{});
     block_conv<S, false, 0, decltype(slice(I3{})), N>(buf0, buf1, lds + wslot<M, S, false>(QB + 2), tb, x, feats, lane, wave, slice(I3{}));
     stage_wait();
     lds_barrier();
-    PHASE_MARK(16 + 6);
     block_conv<S, true, 2, NoFiller, N>(buf1, buf0, lds + wslot<M, S, false>(QB + 3), tb, x, feats, lane, wave);
     prefetch_commit<PS, 0, LIMIT>(pre, buf0, 0, tid);      // buf0's maps are dead: the rest of the frame and its halo
     lds_barrier();
-    PHASE_MARK(16 + 7);
 }
 
 template <class S1, class S2, class S3>
@@ -1654,7 +1566,7 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
     // one after the other through ONE copy of the code of sections 1 and 2; all but the last then do the last
     // section's conv0 and pooling and wait, the last one finishes the group.  A group of one takes the plain path.
     constexpr int NG = (S3::CONVMAP && S3::NT == 1 && !S2::XFUSED && S1::INKIND == IN_U8_C3 && S1::NSTRIPS == 1 && S1::PRE_N == 4)
-                           ? SEEDINF_GROUP : 1;
+                           ? RN_GROUP : 1;
     static_assert(NG == 1 || NG * S3::ACT_BYTES <= M::LOW_SLOT_AT, "the group's maps must leave the low weight slot free");
     const int grid = (int)gridDim.x;
     floatx4 xq[NG > 1 ? NG - 1 : 1][S3::NT][S3::FT];                   // pooled x of the waiting members, most recent first
@@ -1665,13 +1577,8 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
             const int cur = img + k * grid;
             const uint8_t* obs_img = a.obs + FRAME * cur;
             __bf16* feat_row = a.feat + (size_t)cur * a.ldf;
-#ifdef SEEDINF_TRACE
-            const bool trimg = blockIdx.x == 7 && img == (int)blockIdx.x + 2 * NG * grid && k == 0;
-#else
-            const bool trimg = false;
-#endif
-            run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid, trimg);
-            run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid, trimg);
+            run_section<S1, S2, M, false, 0, -1, N::NSETS, false>(lds, a.sec[0], a.sec[1], obs_img, pre, feat_row, tid);
+            run_section<S2, S3, M, false, 1, 4, N::NSETS, S1::XFUSED>(lds, a.sec[1], a.sec[2], obs_img, pre, feat_row, tid);
             // the next frame's bytes travel while the last section computes (unconditional load address)
             const int nxt = k + 1 < n ? cur + grid : (img + NG * grid < a.B ? img + NG * grid : cur);
             prefetch_issue<S1>(pre, a.obs + FRAME * nxt, 0, tid);
