@@ -30,6 +30,7 @@
 // scales the accumulator.
 #pragma once
 #include <type_traits>
+#include <utility>
 
 #include "bf16_common.h"
 
@@ -51,6 +52,19 @@ enum { IN_LDS = 0, IN_U8_C3 = 1, IN_U8_PLANAR = 2 };
 // instructions per MFMA ride along free; an MFMA takes ~8 issue cycles of its wavefront, 16 of the pipe), so the
 // epilogue of a finished tile is spread over the chain of the next one.
 #define SCHED_FENCE __builtin_amdgcn_sched_barrier(0)
+
+// f(integral_constant<int, 0>{}) ... f(integral_constant<int, N - 1>{})
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+
+// A 16-byte LDS read that stays where it is written relative to the scheduling fences (a volatile access to
+// the LDS address space; through a generic pointer it would become a flat load).
+__device__ __forceinline__ bf16x8 lds_read_pinned(const char* p)
+{
+    return *(const volatile __attribute__((address_space(3))) bf16x8*)(const __attribute__((address_space(3))) char*)p;
+}
 
 // Workgroup barrier for LDS-only communication: waits for this wavefront's LDS
 // traffic, not for its outstanding global loads (the prefetches stay in flight).
@@ -440,6 +454,16 @@ __device__ __forceinline__ void conv0_load(bf16x8 (&b)[S::KC0], const char* in, 
     }
 }
 
+// The same for planar inputs from per-lane base pointers that already include the tile's cell: the chunk and
+// row offsets are ds_read immediates.
+template <class S, int ROWOFF>
+__device__ __forceinline__ void conv0_load_p(bf16x8 (&b)[S::KC0], const char* const (&pa)[KMap<S::CIN>::NBASE])
+{
+    using K = KMap<S::CIN>;
+#pragma unroll
+    for (int kc = 0; kc < S::KC0; ++kc) b[kc] = *(const bf16x8*)(pa[K::kbase(kc)] + (K::kimm(kc, S::IPITCH) + ROWOFF * S::IPITCH) * 16);
+}
+
 // acc = init + W * b: `init` carries the bias (divided by the input scale), so the epilogue has no bias add
 template <class S>
 __device__ __forceinline__ void conv0_mma(floatx4 (&acc)[S::FT], const bf16x8 (&b)[S::KC0], const bf16x8 (&w0)[S::W0_FRAGS],
@@ -521,21 +545,30 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
         const int xstep = wr_pool ? S::PITCH * 16 : 0, estep = wr_edge ? S::C * 2 : 0;
         const int xj = wr_pool ? 2 * S::PLANE * 16 : 0, ej = wr_edge ? 32 : 0;
 
-        // rows of pooled row py: mid = 2 py - PADH + 1 (always inside the image), bot = mid + 1 (may not exist);
-        // py past the unit's end re-reads its last row (the fragments are then never used)
-        auto load_pair = [&](bf16x8 (&a)[S::KC0], bf16x8 (&c)[S::KC0], int py) {
-            const int rm = 2 * (py < pb1 ? py : pb1 - 1) - S::PADH + 1;
-            conv0_load<S>(a, in, cbase + rm * S::IPITCH, koff);
-            conv0_load<S>(c, in, cbase + (rm + 1 < S::H ? rm + 1 : rm) * S::IPITCH, koff);
+        // rows of pooled row py: mid = 2 py - PADH + 1 (always inside the image), bot = mid + 1 (below the image for
+        // the map's last pooled row when the height is even: pool_row then leaves it out).  The lane bases walk
+        // down two rows per pooled row; requests past the unit's end read rows that are never used (past the
+        // map's end: whatever LDS holds behind it).
+        const char* pm[KMap<S::CIN>::NBASE];
+#pragma unroll
+        for (int q = 0; q < KMap<S::CIN>::NBASE; ++q) pm[q] = in + (cbase + (2 * pb0 - S::PADH + 1) * S::IPITCH + koff[q]) * 16;
+        auto load_pair = [&](bf16x8 (&a)[S::KC0], bf16x8 (&c)[S::KC0]) {
+            conv0_load_p<S, 0>(a, pm);
+            conv0_load_p<S, 1>(c, pm);
+#pragma unroll
+            for (int q = 0; q < KMap<S::CIN>::NBASE; ++q) pm[q] += 2 * S::IPITCH * 16;
         };
         auto mma_pair = [&](floatx4 (&mid)[S::FT], floatx4 (&bot)[S::FT], const bf16x8 (&a)[S::KC0], const bf16x8 (&c)[S::KC0]) {
             conv0_mma<S>(mid, a, w0, bv);
             conv0_mma<S>(bot, c, w0, bv);
         };
-        auto pool_row = [&](const floatx4 (&mid)[S::FT], const floatx4 (&bot)[S::FT]) {
+        // `last`: the unit's last pooled row, whose bottom conv row may lie below the image
+        const bool no_bot = 2 * (pb1 - 1) - S::PADH + 2 >= S::H;         // uniform
+        auto pool_row = [&](const floatx4 (&mid)[S::FT], const floatx4 (&bot)[S::FT], bool last = false) {
 #pragma unroll
             for (int j = 0; j < S::FT; ++j) {
-                floatx4 v = max4(max4(top[j], mid[j]), bot[j]);
+                floatx4 v = max4(top[j], mid[j]);
+                if (!(last && no_bot)) v = max4(v, bot[j]);
                 if (SCALE != 1.0f) v = v * SCALE;
                 if (!FULL && !live) v = NEG;
                 *(bf16x4*)(eptr + j * ej) = to_bf16x4(v);
@@ -545,6 +578,53 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
             }
             xptr += xstep;
             eptr += estep;
+        };
+        // One row's two conv rows multiplied while the previous row is pooled, interleaved by hand: after each
+        // chunk's MFMAs one piece of the pooling (5 pieces per feature tile: vertical maximum, edge store,
+        // horizontal maximum, store, top <- bot).  A wavefront's vector instructions issue under its own running
+        // MFMAs; left as a block of MFMAs and a block of vector work, the SIMD's two wavefronts fall into step
+        // after the phase's barrier and wait for the matrix pipe together, then for the vector unit together.
+        auto mma_pool = [&](floatx4 (&mid)[S::FT], floatx4 (&bot)[S::FT], bf16x8 (&a)[S::KC0], bf16x8 (&c)[S::KC0],
+                            const floatx4 (&pmid)[S::FT], const floatx4 (&pbot)[S::FT]) {
+            using K = KMap<S::CIN>;
+            constexpr int STEPS = 2 * S::KC0, NP = 5 * S::FT;
+            floatx4 v[S::FT], h[S::FT];
+            auto piece = [&](auto pc) {
+                constexpr int j = decltype(pc)::value / 5, part = decltype(pc)::value % 5;
+                if constexpr (part == 0) {
+                    v[j] = max4(max4(top[j], pmid[j]), pbot[j]);
+                    if (SCALE != 1.0f) v[j] = v[j] * SCALE;
+                    if (!FULL && !live) v[j] = NEG;
+                } else if constexpr (part == 1) {
+                    *(bf16x4*)(eptr + j * ej) = to_bf16x4(v[j]);
+                } else if constexpr (part == 2) {
+                    h[j] = hmax3_row16(v[j]);
+                } else if constexpr (part == 3) {
+                    *(bf16x4*)(xptr + j * xj) = to_bf16x4(h[j]);
+                } else {
+                    top[j] = pbot[j];
+                }
+            };
+            static_for<STEPS>([&](auto st) {
+                constexpr int s = decltype(st)::value, kc = s % S::KC0;
+#pragma unroll
+                for (int j = 0; j < S::FT; ++j) {
+                    if constexpr (s < S::KC0) mid[j] = mfma16(w0[j * S::KC0 + kc], a[kc], kc == 0 ? bv[j] : mid[j]);
+                    else bot[j] = mfma16(w0[j * S::KC0 + kc], c[kc], kc == 0 ? bv[j] : bot[j]);
+                }
+                // the fragment just multiplied is requested again for the next row of the sequence: a whole
+                // mma_pool ahead of its use
+                // (volatile: an ordinary load is free to move across the scheduling fences, and the compiler gathers
+                // all ten in front of the next row's first MFMA, which then waits for them)
+                if constexpr (s < S::KC0) a[kc] = lds_read_pinned(pm[K::kbase(kc)] + K::kimm(kc, S::IPITCH) * 16);
+                else c[kc] = lds_read_pinned(pm[K::kbase(kc)] + (K::kimm(kc, S::IPITCH) + S::IPITCH) * 16);
+                static_for<(s + 1) * NP / STEPS - s * NP / STEPS>([&](auto k) { piece(std::integral_constant<int, s * NP / STEPS + decltype(k)::value>{}); });
+                SCHED_FENCE;
+            });
+            xptr += xstep;
+            eptr += estep;
+#pragma unroll
+            for (int q = 0; q < K::NBASE; ++q) pm[q] += 2 * S::IPITCH * 16;
         };
         // Software pipeline over pooled rows: while row py is pooled (vector ALU), the matrix cores multiply row
         // py+1 and LDS delivers the fragments of row py+2 (py+3 with two fragment sets).  Accumulator sets
@@ -556,34 +636,30 @@ __device__ __forceinline__ void conv0_pool(const char* in, char* xout, char* edg
         if constexpr (!SWP) {
 #pragma unroll 1
             for (int py = pb0; py < pb1; ++py) {
-                load_pair(fa, fb, py);
+                load_pair(fa, fb);
                 mma_pair(m0, b0, fa, fb);
-                pool_row(m0, b0);
+                pool_row(m0, b0, py + 1 == pb1);
             }
         } else {
         auto& oa = pick_ref<TWO>(ga, fa);                                    // fragments of the odd rows
         auto& ob = pick_ref<TWO>(gb, fb);
         constexpr int LA = TWO ? 2 : 1;
         int py = pb0;
-        load_pair(fa, fb, py);
-        if constexpr (TWO) load_pair(ga, gb, py + 1);
+        load_pair(fa, fb);
+        if constexpr (TWO) load_pair(ga, gb);
         mma_pair(m0, b0, fa, fb);
-        load_pair(fa, fb, py + LA);
+        load_pair(fa, fb);
 #pragma unroll 1
         for (; py + 2 < pb1; py += 2) {
-            mma_pair(m1, b1, oa, ob);
-            load_pair(oa, ob, py + 1 + LA);
-            pool_row(m0, b0);
-            mma_pair(m0, b0, fa, fb);
-            load_pair(fa, fb, py + 2 + LA);
-            pool_row(m1, b1);
+            mma_pool(m1, b1, oa, ob, m0, b0);
+            mma_pool(m0, b0, fa, fb, m1, b1);
         }
         if (py + 1 < pb1) {
             mma_pair(m1, b1, oa, ob);
             pool_row(m0, b0);
-            pool_row(m1, b1);
+            pool_row(m1, b1, true);
         } else {
-            pool_row(m0, b0);
+            pool_row(m0, b0, true);
         }
         }
     }
