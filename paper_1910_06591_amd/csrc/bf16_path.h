@@ -868,13 +868,14 @@ inline seed_status_t bf16_torso_fc(Bf16State* s, const Plan& p, const float* d_w
 inline seed_status_t bf16_core(Bf16State* s, const Plan& p, const float* d_w, hipStream_t st, int row0, int B,
                                const int32_t* prev_action, const float* prev_reward, const float* h_in,
                                const float* c_in, const uint8_t* done, float* h_out, float* c_out, float* d_hid,
-                               const float** core, int* ld_core, std::string& err)
+                               const float** core, int* ld_core, std::string& err, bool do_core = true, bool do_hidden = true)
 {
     const seed_arch_t& a = p.arch;
     const Bf16WeightSet& W = s->ws[s->active];
     const __bf16* fc_bf16 = s->fc_bf16 + (size_t)row0 * s->ldfc;
     *core = s->fc_f32 + (size_t)row0 * a.fc_units; *ld_core = a.fc_units;
-    if (a.lstm_units > 0) {
+    if (a.lstm_units > 0 && !do_core) { *core = h_out; *ld_core = a.lstm_units; }
+    if (a.lstm_units > 0 && do_core) {
         GemmArgs g{};
         g.x1 = fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->kc1_lstm;
         g.x2 = h_in; g.ld2 = a.lstm_units; g.k2 = a.lstm_units;
@@ -885,7 +886,7 @@ inline seed_status_t bf16_core(Bf16State* s, const Plan& p, const float* d_w, hi
         launch_gemm<EPI_LSTM>(st, g, a.lstm_units / 16, s->n_cu);
         *core = h_out; *ld_core = a.lstm_units;
     }
-    if (a.head == SEED_HEAD_DUELING_Q) {
+    if (a.head == SEED_HEAD_DUELING_Q && do_hidden) {
         GemmArgs g{};
         if (a.lstm_units > 0) { g.kc1 = 0; g.x1 = fc_bf16; g.ld1 = s->ldfc; g.x2 = h_out; g.ld2 = a.lstm_units; g.k2 = a.lstm_units; }
         else { g.x1 = fc_bf16; g.ld1 = s->ldfc; g.kc1 = s->ldfc / 32; g.k2 = 0; }

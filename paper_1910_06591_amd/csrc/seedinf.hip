@@ -34,7 +34,7 @@ struct seed_infer {
     float* d_act[2] = {nullptr, nullptr};   // fp32 ping-pong activations (fp32 mode)
     float* d_fc = nullptr;         // [max_batch, fc_units] fp32 (fp32 mode)
     float* d_hid = nullptr;        // [max_batch, 2*head_hidden] dueling hidden, fp32
-    float* d_roll = nullptr;       // recurrent archs: 2 x (h, c) [max_batch, lstm_units], the states between the steps of an unroll
+    float* d_roll = nullptr;       // recurrent archs: 4 x [max_batch, lstm_units]: every step's h of an unroll, then two c buffers
     const float* feat_f32 = nullptr;   // where the last fp32-mode step left the torso features
     Bf16State* bf = nullptr;       // everything the bf16 path owns
     HostPool* pool = nullptr;      // host threads for the large copies (weight updates, the batcher's frames); made on first use
@@ -333,11 +333,15 @@ static seed_status_t run_torso_fc(seed_infer* h, hipStream_t s, int B, const uin
 
 // Recurrent core, heads and action selection for the B rows that start at row `row0` of the linear layer's
 // output; every pointer argument already names those rows' own data.
+// `phases`: CORE = the recurrent step (rows row0 .. row0 + B of the linear layer's output -> h_out, c_out), HEADS =
+// dueling hidden layers, output heads and action selection on the core's output.  A T-step unroll runs CORE per
+// step and HEADS once over all T * B rows (h_out then holds every step's output, row0 = 0).
+enum { PHASE_CORE = 1, PHASE_HEADS = 2, PHASE_BOTH = 3 };
 static seed_status_t run_core_heads(seed_infer* h, hipStream_t s, int row0, int B, const int32_t* prev_action,
                                     const float* prev_reward, const float* h_in, const float* c_in, const uint8_t* done,
                                     float* h_out, float* c_out, const float* uniforms, const float* epsilon,
                                     const float* explore_u, int32_t* action_out, float* logits_out, float* value_out,
-                                    float* probs_out)
+                                    float* probs_out, int phases = PHASE_BOTH)
 {
     const Plan& p = h->plan;
     const seed_arch_t& a = p.arch;
@@ -349,12 +353,13 @@ static seed_status_t run_core_heads(seed_infer* h, hipStream_t s, int row0, int 
         const float* fc = h->d_fc + (size_t)row0 * a.fc_units;
         core = fc;
         if (rec) {
-            hipLaunchKernelGGL(lstm_f32_kernel, dim3(B, (a.lstm_units + 255) / 256), dim3(256), 0, s, fc, prev_action,
-                               prev_reward, h_in, c_in, w + p.lstm_w, w + p.lstm_b, h_out, c_out, B, a.fc_units,
-                               a.num_actions, a.lstm_units, done);
+            if (phases & PHASE_CORE)
+                hipLaunchKernelGGL(lstm_f32_kernel, dim3(B, (a.lstm_units + 255) / 256), dim3(256), 0, s, fc, prev_action,
+                                   prev_reward, h_in, c_in, w + p.lstm_w, w + p.lstm_b, h_out, c_out, B, a.fc_units,
+                                   a.num_actions, a.lstm_units, done);
             core = h_out;
         }
-        if (a.head == SEED_HEAD_DUELING_Q) {
+        if (a.head == SEED_HEAD_DUELING_Q && (phases & PHASE_HEADS)) {
             int hid = a.head_hidden;
             hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(DENSE_F32_WAVES * 64), 0, s, core, w + p.v1_w, w + p.v1_b,
                                h->d_hid, p.core, hid, ld_core, 2 * hid, 1);
@@ -363,8 +368,12 @@ static seed_status_t run_core_heads(seed_infer* h, hipStream_t s, int row0, int 
         }
     } else {
         seed_status_t st = bf16_core(h->bf, p, w, s, row0, B, prev_action, prev_reward, h_in, c_in, done, h_out, c_out,
-                                     h->d_hid, &core, &ld_core, h->err);
+                                     h->d_hid, &core, &ld_core, h->err, (phases & PHASE_CORE) != 0, (phases & PHASE_HEADS) != 0);
         if (st != SEED_OK) return st;
+    }
+    if (!(phases & PHASE_HEADS)) {
+        HIP_TRY(h, hipGetLastError());
+        return SEED_OK;
     }
 
     HeadsArgs ha{};
@@ -624,20 +633,27 @@ extern "C" seed_status_t seed_infer_unroll(seed_infer_t* h, int32_t T, int32_t B
     seed_status_t st = run_torso_fc(h, s, T * B, obs);
     if (st != SEED_OK) return st;
     const size_t A = (size_t)a.num_actions, Hn = (size_t)a.lstm_units, mb = (size_t)a.max_batch;
+    if (!rec) {
+        // nothing depends on time: heads and selection over all T * B rows at once
+        return run_core_heads(h, s, 0, T * B, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, uniforms, nullptr,
+                              nullptr, action_out, logits_out, value_out, probs_out);
+    }
+    // Only the recurrent core is sequential.  Step t reads h_{t-1} from, and writes h_t to, rows t * B .. of one
+    // [T * B, units] buffer (the first quarter of d_roll); c alternates between two [B, units] buffers behind it
+    // and the last step writes the caller's.  The dueling hidden layers, the heads and the selection then run
+    // once over all T * B rows of that buffer instead of T times over B.
+    float* hseq = h->d_roll;
+    float* cb[2] = {h->d_roll + mb * Hn, h->d_roll + 2 * mb * Hn};
     for (int t = 0; t < T; ++t) {
         const size_t r = (size_t)t * B;
-        // states between steps alternate between the handle's two buffers; the last step writes the caller's
-        float* hb[2] = {h->d_roll, h->d_roll ? h->d_roll + 2 * mb * Hn : nullptr};
-        const float* hi = !rec ? nullptr : (t == 0 ? h0 : hb[(t - 1) & 1]);
-        const float* ci = !rec ? nullptr : (t == 0 ? c0 : hb[(t - 1) & 1] + mb * Hn);
-        float* ho = !rec ? nullptr : (t == T - 1 ? h_out : hb[t & 1]);
-        float* co = !rec ? nullptr : (t == T - 1 ? c_out : hb[t & 1] + mb * Hn);
-        st = run_core_heads(h, s, (int)r, B, rec ? prev_action + r : nullptr, rec ? prev_reward + r : nullptr, hi, ci,
-                            done ? done + r : nullptr, ho, co, uniforms ? uniforms + r * A : nullptr, nullptr, nullptr,
-                            action_out + r, logits_out + r * A, value_out + r, probs_out ? probs_out + r * A : nullptr);
+        st = run_core_heads(h, s, (int)r, B, prev_action + r, prev_reward + r, t == 0 ? h0 : hseq + (r - B) * Hn,
+                            t == 0 ? c0 : cb[(t - 1) & 1], done ? done + r : nullptr, hseq + r * Hn,
+                            t == T - 1 ? c_out : cb[t & 1], nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, PHASE_CORE);
         if (st != SEED_OK) return st;
     }
-    return SEED_OK;
+    HIP_TRY(h, hipMemcpyAsync(h_out, hseq + (size_t)(T - 1) * B * Hn, (size_t)B * Hn * sizeof(float), hipMemcpyDeviceToDevice, s));
+    return run_core_heads(h, s, 0, T * B, nullptr, nullptr, nullptr, nullptr, nullptr, hseq, nullptr, uniforms, nullptr, nullptr,
+                          action_out, logits_out, value_out, probs_out, PHASE_HEADS);
 }
 
 extern "C" seed_status_t seed_infer_set_weights(seed_infer_t* h, const float* weights_host, size_t n_weights,
