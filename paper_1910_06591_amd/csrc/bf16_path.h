@@ -519,6 +519,7 @@ inline seed_status_t bf16_create(const Plan& p, const float* d_w, Bf16State** ou
     BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
+    BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
     if (s->stack_fused) {
         BF_TRY(hipFuncSetAttribute((const void*)r2d2_torso_bf16_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, r2d2::LDS_BYTES));
         BF_TRY(hipFuncSetAttribute((const void*)r2d2_torso_bf16_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, r2d2::LDS_BYTES));
@@ -703,19 +704,19 @@ inline bool resblock_by_width(int C, F go)
     case 16: return go(std::integral_constant<int, 16>{});
     case 32: return go(std::integral_constant<int, 32>{});
     case 64: return go(std::integral_constant<int, 64>{});
+    case 128: return go(std::integral_constant<int, 128>{});
     default: return false;
     }
 }
 
-// Whether launch_resblock takes this block.  Measured at 1024 images against the two-launch form: 16 and 32
-// channels are faster fused at every map size (16 ch 54 x 72: 157 vs 308 us; 32 ch 27 x 36 and smaller: 60 vs 70;
-// 32 ch 36 x 48: 280 vs 284 and the pooling kernel need not write R), 64 channels up to 18 x 24 (95 vs 124); at
-// 64 channels on 36 x 48 and at 128 channels the small tiles LDS leaves room for lose (794 vs 526 us).
+// Whether launch_resblock takes this block: every width with a kernel whose tile fits.  Measured at 1024 images
+// against the two-launch form (LDS-tiled convolution kernel twice): 16 ch 54 x 72 149 vs 308 us; 32 ch 36 x 48 175
+// vs 284, 27 x 36 and smaller 52 vs 70; 64 ch 36 x 48 552 vs 640, 18 x 24 and 9 x 12 84 vs 124; 128 ch (18 x 24 and
+// 9 x 12, mean) 305 vs 412.
 inline bool resblock_fusable(const ConvLayer& ca, const ConvLayer& cb)
 {
     const int C = ca.Cin;
     if (ca.Cout != C || cb.Cin != C || cb.Cout != C || ca.H != cb.H || ca.W != cb.W) return false;
-    if (C > 64 || (C == 64 && ca.H * ca.W > 18 * 24)) return false;
     return resblock_by_width(C, [&](auto cc) {
         int th, tw;
         return ResBlockCfg<decltype(cc)::value>::choose(ca.H, ca.W, th, tw);

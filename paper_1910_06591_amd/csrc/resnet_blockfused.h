@@ -5,12 +5,19 @@
 // halo in LDS, computes U = ReLU(conv_a) on the tile plus a one-pixel halo into LDS (zero where that lies
 // outside the image: conv_b's SAME padding), then conv_b on the tile, adds x and writes x' (and / or its bf16
 // copy): HBM sees x once in and once out.  The halo of U is recomputed by neighbouring tiles ((TH + 2)(TW + 2) /
-// (TH TW) of conv_a's work); the path is HBM-bound, the matrix cores have that to spare.
+// (TH TW) of conv_a's work).
 //
 // Both convolutions are implicit GEMMs over planar LDS maps [C/8][rows][pitch][8 bf16] with the weight packing
 // of conv3x3_lds_kernel (A fragments [feature tile][chunk][lane][8], k = tap * C + ci, fetched from global
-// memory one chunk ahead).  A region's pixels are cut row-major into tiles of 16; wavefront w takes feature tiles
+// memory three chunks ahead).  A region's pixels are cut row-major into tiles of 16; wavefront w takes feature tiles
 // FTW * (w % NFG) ... and every NPG-th pixel tile from w / NFG, at most TPW of them.
+//
+// What set the time, in the order it was found (1024 images, 32 channels on 36 x 48): the weight fragments one
+// chunk ahead (each chunk waited out a trip to L2: 260 -> 230 us with three ahead), the staging loop's loads
+// one round at a time (280 -> 260), and tiles whose maps fill LDS so that one workgroup per compute unit
+// loads, multiplies and stores in turn (230 -> 175 with tiles for two).  At 64 and 128 channels the kernel is
+// bound by operand delivery: with two feature tiles per wavefront the weight fragments fill the vector L1's
+// bandwidth (16 wavefronts x 2 KiB per chunk) and the map fragments most of LDS's.
 #pragma once
 #include "bf16_common.h"
 
@@ -50,8 +57,11 @@ struct ResBlockCfg {
             for (int nx = 1; nx <= W; ++nx) {
                 const int tw = (W + nx - 1) / nx;
                 if ((th + 2) * (tw + 2) > MAX_PIX || lds_bytes(th, tw) > RB_LDS_MAX) continue;
-                // cost: conv_a work of all tiles (halo recomputation), then the tile count
-                const long cost = (long)ny * nx * ((th + 2) * (tw + 2) + th * tw);
+                // cost: the pixels both convolutions compute over all tiles (halo recomputation); half as much
+                // again when the maps leave no room for a second workgroup on the compute unit, whose MFMAs
+                // would run under this one's loads and stores
+                long cost = (long)ny * nx * ((th + 2) * (tw + 2) + th * tw);
+                if (lds_bytes(th, tw) > 80 * 1024) cost += cost / 2;
                 if (best < 0 || cost < best) { best = cost; TH = th; TW = tw; }
                 break;                                      // larger nx only shrinks tw further: more tiles, more halo
             }
@@ -79,27 +89,38 @@ __device__ __forceinline__ void rb_conv(const char* src, int PL, int PITCH, int 
         for (int j = 0; j < K::FTW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
     const bf16x8* wl = wp + (size_t)ft0 * kchunks * 64 + lane;
-    bf16x8 a[K::FTW], a_next[K::FTW];
+    // weight fragments run AHEAD chunks ahead of their use: they come from L2 (the first wavefront to ask) or the
+    // vector L1, and one chunk of MFMAs is shorter than either trip
+    constexpr int AHEAD = C == 16 ? 1 : 3;                  // measured at 16 channels (54 x 72): 150 us with 1, 178 with 3, 186 with all 5
+    bf16x8 a[AHEAD][K::FTW];
 #pragma unroll
-    for (int j = 0; j < K::FTW; ++j) a[j] = wl[(size_t)j * kchunks * 64];
-    for (int kc = 0; kc < kchunks; ++kc) {
-        const int kn = min(kc + 1, kchunks - 1);
+    for (int d = 0; d < AHEAD; ++d)
 #pragma unroll
-        for (int j = 0; j < K::FTW; ++j) a_next[j] = wl[((size_t)j * kchunks + kn) * 64];
-        // the lane's 8 consecutive k of this chunk: one tap, one channel group (k past 9 C has zero weights: any cell)
-        const int k0 = kc * 32 + g * 8;
-        const int tap = min(k0 / C, 8), cg = (k0 % C) >> 3;
-        const char* s = src + ((size_t)cg * PL + (tap / 3) * PITCH + tap % 3) * 16;
+        for (int j = 0; j < K::FTW; ++j) a[d][j] = wl[((size_t)j * kchunks + min(d, kchunks - 1)) * 64];
+    for (int kc0 = 0; kc0 < kchunks; kc0 += AHEAD) {
 #pragma unroll
-        for (int i = 0; i < RB_TPW; ++i) {
-            if (pg + K::NPG * i < ntiles) {                 // uniform
-                const bf16x8 b = *(const bf16x8*)(s + base[i] * 16);
+        for (int d = 0; d < AHEAD; ++d) {
+            const int kc = kc0 + d;
+            if (kc >= kchunks) break;                           // uniform
+            bf16x8 cur[K::FTW];
 #pragma unroll
-                for (int j = 0; j < K::FTW; ++j) acc[i][j] = mfma16(a[j], b, acc[i][j]);
+            for (int j = 0; j < K::FTW; ++j) cur[j] = a[d][j];
+            const int kn = min(kc + AHEAD, kchunks - 1);
+#pragma unroll
+            for (int j = 0; j < K::FTW; ++j) a[d][j] = wl[((size_t)j * kchunks + kn) * 64];
+            // the lane's 8 consecutive k of this chunk: one tap, one channel group (k past 9 C has zero weights: any cell)
+            const int k0 = kc * 32 + g * 8;
+            const int tap = min(k0 / C, 8), cg = (k0 % C) >> 3;
+            const char* s = src + ((size_t)cg * PL + (tap / 3) * PITCH + tap % 3) * 16;
+#pragma unroll
+            for (int i = 0; i < RB_TPW; ++i) {
+                if (pg + K::NPG * i < ntiles) {                 // uniform
+                    const bf16x8 b = *(const bf16x8*)(s + base[i] * 16);
+#pragma unroll
+                    for (int j = 0; j < K::FTW; ++j) acc[i][j] = mfma16(cur[j], b, acc[i][j]);
+                }
             }
         }
-#pragma unroll
-        for (int j = 0; j < K::FTW; ++j) a[j] = a_next[j];
     }
 }
 
@@ -121,20 +142,35 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
     const float* ximg = p.x_in + (size_t)b * p.H * p.W * C;
 
     // ---- R = ReLU(x) as bf16, zeros outside the image ----
+    // four items' loads are issued before the first is converted: one after the other, the rounds of this loop
+    // each wait out a trip to memory and the staging, not the bandwidth, sets the kernel's time
     const int rcells = (p.TH + 4) * RP;
-    for (int idx = tid; idx < rcells * K::NCG; idx += RB_THREADS) {
-        const int cell = idx / K::NCG, cg = idx - cell * K::NCG;           // a pixel's channel groups are adjacent in memory
-        const int r = cell / RP, c = cell - r * RP;
-        const int gy = y0 - 2 + r, gx = x0 - 2 + c;
-        bf16x8 v = {};
-        if (gy >= 0 && gy < p.H && gx >= 0 && gx < p.W) {
-            const float* s = ximg + ((size_t)gy * p.W + gx) * C + cg * 8;
-            const bf16x8 raw = to_bf16x8(*(const floatx4*)s, *(const floatx4*)(s + 4));
-            const bf16x4 lo = relu_bf16x4(__builtin_shufflevector(raw, raw, 0, 1, 2, 3));
-            const bf16x4 hi = relu_bf16x4(__builtin_shufflevector(raw, raw, 4, 5, 6, 7));
-            v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    constexpr int UNR = 4;
+    for (int idx0 = tid; idx0 < rcells * K::NCG; idx0 += UNR * RB_THREADS) {
+        floatx4 lo[UNR], hi[UNR];
+        int at[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int idx = idx0 + u * RB_THREADS;
+            const int cell = idx / K::NCG, cg = idx - cell * K::NCG;       // a pixel's channel groups are adjacent in memory
+            const int r = cell / RP, c = cell - r * RP;
+            const int gy = y0 - 2 + r, gx = x0 - 2 + c;
+            at[u] = idx < rcells * K::NCG ? (cg * RPL + cell) * 16 : -1;
+            lo[u] = hi[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (at[u] >= 0 && gy >= 0 && gy < p.H && gx >= 0 && gx < p.W) {
+                const float* s = ximg + ((size_t)gy * p.W + gx) * C + cg * 8;
+                lo[u] = *(const floatx4*)s;
+                hi[u] = *(const floatx4*)(s + 4);
+            }
         }
-        *(bf16x8*)(Rm + ((size_t)cg * RPL + cell) * 16) = v;
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (at[u] < 0) continue;
+            const bf16x8 raw = to_bf16x8(lo[u], hi[u]);
+            const bf16x4 l = relu_bf16x4(__builtin_shufflevector(raw, raw, 0, 1, 2, 3));
+            const bf16x4 h = relu_bf16x4(__builtin_shufflevector(raw, raw, 4, 5, 6, 7));
+            *(bf16x8*)(Rm + at[u]) = __builtin_shufflevector(l, h, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
     }
     __syncthreads();
 
