@@ -18,6 +18,7 @@
 #include "resnet_layerwise.h"
 #include "resnet_blockfused.h"
 #include "resnet_firstpool.h"
+#include "resnet_convpool.h"
 
 namespace seedinf {
 
@@ -697,6 +698,50 @@ inline bool launch_first_pool(hipStream_t st, const LwLayerDev& d, const bf16x8*
     }
 }
 
+// conv0 of a later section with its pooling as one launch (bf16 NHWC map -> fp32 x and, if r is given, ReLU(x) as
+// bf16); false when the channel pair has no fused kernel or no tile fits, and nothing was launched.
+template <class F>
+inline bool conv_pool_by_channels(int cin, int cout, F go)
+{
+    auto pair = [&](auto ci, auto co) { return go(ci, co); };
+    using I16 = std::integral_constant<int, 16>; using I32 = std::integral_constant<int, 32>;
+    using I64 = std::integral_constant<int, 64>; using I128 = std::integral_constant<int, 128>;
+    switch (cin * 1000 + cout) {
+    case 16016: return pair(I16{}, I16{});
+    case 16032: return pair(I16{}, I32{});
+    case 32032: return pair(I32{}, I32{});
+    case 32064: return pair(I32{}, I64{});
+    case 64064: return pair(I64{}, I64{});
+    case 64128: return pair(I64{}, I128{});
+    case 128128: return pair(I128{}, I128{});
+    default: return false;
+    }
+}
+
+inline bool launch_conv_pool(hipStream_t st, const LwLayerDev& d, const bf16x8* wp_conv, const float* d_w, const Section& sec, int B,
+                             const __bf16* in, float* x, __bf16* r)
+{
+    const ConvLayer& c = sec.conv0;
+    return conv_pool_by_channels(c.Cin, c.Cout, [&](auto ci, auto co) -> bool {
+        constexpr int CIN = decltype(ci)::value, COUT = decltype(co)::value;
+        using CP = ConvPoolCfg<CIN, COUT>;
+        ConvPoolArgs a{};
+        if (!CP::choose(sec.PH, sec.PW, a.PTH, a.PTW)) return false;
+        a.in = in; a.wp = wp_conv + d.wp_off / 8; a.bias = d_w + c.b_off; a.x = x; a.r = r;
+        a.B = B; a.H = c.H; a.W = c.W; a.PH = sec.PH; a.PW = sec.PW; a.pad_h = sec.pool_pad_h; a.pad_w = sec.pool_pad_w;
+        a.tiles_y = (sec.PH + a.PTH - 1) / a.PTH; a.tiles_x = (sec.PW + a.PTW - 1) / a.PTW; a.kchunks = d.kchunks;
+        static bool attr_set = false;                       // per instantiation: the kernel may ask for more than 64 KiB
+        if (!attr_set) {
+            if (hipFuncSetAttribute((const void*)conv_pool_kernel<CIN, COUT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CP_LDS_MAX) != hipSuccess)
+                return false;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL((conv_pool_kernel<CIN, COUT>), dim3((unsigned)((long)B * a.tiles_y * a.tiles_x)), dim3(RB_THREADS),
+                           CP::lds_bytes(a.PTH, a.PTW), st, a);
+        return true;
+    });
+}
+
 template <class F>
 inline bool resblock_by_width(int C, F go)
 {
@@ -778,12 +823,15 @@ inline seed_status_t bf16_torso_fc(Bf16State* s, const Plan& p, const float* d_w
             const bool need_r = !resblock_fusable(sec.block[0], sec.block[1]);
             if (si == 0 && launch_first_pool(st, s->lw[li], W.wp_conv, d_w, sec, B, obs, s->lw_x, need_r ? s->lw_r : nullptr)) {
                 ++li;
+            } else if (si > 0 && !need_r && launch_conv_pool(st, s->lw[li], W.wp_conv, d_w, sec, B, (const __bf16*)in, s->lw_x, nullptr)) {
+                // (not when R is wanted: it would land in lw_r, which is this layer's input)
+                ++li;
             } else {
                 conv(sec.conv0, in, si == 0, nullptr, nullptr, s->lw_c0, 0, 0);
                 const int C = sec.conv0.Cout;
                 const long total = (long)B * sec.PH * sec.PW * (C / 4);
                 hipLaunchKernelGGL(pool3x3s2_lw_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s->lw_c0, s->lw_x,
-                                   s->lw_r, B, sec.conv0.OH, sec.conv0.OW, C, sec.PH, sec.PW, sec.pool_pad_h, sec.pool_pad_w);
+                                   need_r ? s->lw_r : nullptr, B, sec.conv0.OH, sec.conv0.OW, C, sec.PH, sec.PW, sec.pool_pad_h, sec.pool_pad_w);
             }
             // a residual block in one launch where the width has a fused kernel and a tile fits; x ping-pongs between
             // lw_x and the (by now dead) conv0 map, since tiles read their neighbours' halos of the block's input

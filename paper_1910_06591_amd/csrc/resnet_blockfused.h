@@ -70,14 +70,15 @@ struct ResBlockCfg {
     }
 };
 
-// One implicit-GEMM pass: region of RW-wide pixels (npix of them) over the planar map `src` (plane cells PL, pitch
-// PITCH; a region pixel (r, c) has its tap (0, 0) at cell r * PITCH + c).  acc[i][j]: pixel tile pg + NPG * i,
-// feature tile ft0 + j.
-template <int C>
+// One implicit-GEMM pass, CIN -> COUT channels: region of RW-wide pixels (npix of them) over the planar map `src`
+// (plane cells PL, pitch PITCH; a region pixel (r, c) has its tap (0, 0) at cell r * PITCH + c).  acc[i][j]: pixel
+// tile pg + NPG * i, feature tile ft0 + j.
+template <int CIN, int COUT>
 __device__ __forceinline__ void rb_conv(const char* src, int PL, int PITCH, int RW, int npix, const bf16x8* __restrict__ wp,
-                                        int kchunks, int ft0, int pg, int lane, floatx4 (&acc)[RB_TPW][ResBlockCfg<C>::FTW])
+                                        int kchunks, int ft0, int pg, int lane, floatx4 (&acc)[RB_TPW][ResBlockCfg<COUT>::FTW])
 {
-    using K = ResBlockCfg<C>;
+    using K = ResBlockCfg<COUT>;
+    constexpr int C = CIN;
     const int g = lane >> 4, n = lane & 15;
     const int ntiles = (npix + 15) / 16;
     int base[RB_TPW];
@@ -91,7 +92,7 @@ __device__ __forceinline__ void rb_conv(const char* src, int PL, int PITCH, int 
     const bf16x8* wl = wp + (size_t)ft0 * kchunks * 64 + lane;
     // weight fragments run AHEAD chunks ahead of their use: they come from L2 (the first wavefront to ask) or the
     // vector L1, and one chunk of MFMAs is shorter than either trip
-    constexpr int AHEAD = C == 16 ? 1 : 3;                  // measured at 16 channels (54 x 72): 150 us with 1, 178 with 3, 186 with all 5
+    constexpr int AHEAD = COUT == 16 ? 1 : 3;                  // measured at 16 channels (54 x 72): 150 us with 1, 178 with 3, 186 with all 5
     bf16x8 a[AHEAD][K::FTW];
 #pragma unroll
     for (int d = 0; d < AHEAD; ++d)
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
     // ---- U = ReLU(conv_a(R) + bias) on the tile + 1, zero outside the image ----
     {
         const int UW = p.TW + 2, npix = (p.TH + 2) * UW;
-        rb_conv<C>(Rm, RPL, RP, UW, npix, p.wpa, p.kchunks, ft0, pg, lane, acc);
+        rb_conv<C, C>(Rm, RPL, RP, UW, npix, p.wpa, p.kchunks, ft0, pg, lane, acc);
         const int ntiles = (npix + 15) / 16;
 #pragma unroll
         for (int j = 0; j < K::FTW; ++j) {
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
     // ---- x' = x + conv_b(U) + bias on the tile ----
     {
         const int npix = p.TH * p.TW;
-        rb_conv<C>(Um, UPL, UP, p.TW, npix, p.wpb, p.kchunks, ft0, pg, lane, acc);
+        rb_conv<C, C>(Um, UPL, UP, p.TW, npix, p.wpb, p.kchunks, ft0, pg, lane, acc);
         const int ntiles = (npix + 15) / 16;
         const int hw = p.H * p.W;
 #pragma unroll

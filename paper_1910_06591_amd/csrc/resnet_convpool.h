@@ -1,0 +1,143 @@
+// conv0 of a later section of the layer-by-layer ResNet path with its pooling, in one launch: bf16 NHWC input
+// (the previous section's un-rectified output) -> 3x3 SAME convolution CIN -> COUT -> 3x3 / stride-2 max-pool with
+// TF-style SAME padding -> the section's fp32 residual stream x (and, on request, R = ReLU(x) as bf16).  As two
+// launches the full-resolution bf16 map goes out to HBM and comes back 2.25 times; here it lives in LDS.
+//
+// A workgroup takes a PTH x PTW tile of pooled pixels of one image: the input patch under the (2 PTH + 1) x
+// (2 PTW + 1) convolution pixels those windows cover is staged as planar bf16 [CIN/8][rows][pitch][8] (zero
+// outside the image), the convolution runs over it as in the fused residual block (rb_conv), its tile goes to LDS
+// as bf16 [pixel][COUT] (-inf outside the image, so the maximum ignores it) and is pooled from there.
+#pragma once
+#include "resnet_blockfused.h"
+
+namespace seedinf {
+
+struct ConvPoolArgs {
+    const __bf16* in;                  // [B, H, W, CIN]
+    const bf16x8* wp;                  // [COUT / 16][chunks][64 lanes][8], k = tap * CIN + ci
+    const float* bias;
+    float* x;                          // [B, PH, PW, COUT] fp32
+    __bf16* r;                         // [B, PH, PW, COUT] ReLU(x) as bf16, or nullptr
+    int B, H, W, PH, PW, pad_h, pad_w;
+    int PTH, PTW, tiles_y, tiles_x, kchunks;
+};
+
+constexpr size_t CP_LDS_MAX = 80 * 1024;                    // two workgroups per compute unit
+
+template <int CIN, int COUT>
+struct ConvPoolCfg {
+    using K = ResBlockCfg<COUT>;
+    static constexpr int NCG = CIN / 8;
+    __host__ __device__ static constexpr int patch_plane(int PTH, int PTW) { return ((2 * PTH + 3) * (2 * PTW + 3) + 15) / 16 * 16; }
+    static size_t lds_bytes(int PTH, int PTW)
+    {
+        return (size_t)NCG * patch_plane(PTH, PTW) * 16 + (size_t)(2 * PTH + 1) * (2 * PTW + 1) * COUT * 2;
+    }
+    // the fewest convolution pixels over all tiles whose region fits a workgroup and whose maps fit
+    static bool choose(int PH, int PW, int& PTH, int& PTW)
+    {
+        long best = -1;
+        for (int ny = 1; ny <= PH; ++ny)
+            for (int nx = 1; nx <= PW; ++nx) {
+                const int th = (PH + ny - 1) / ny, tw = (PW + nx - 1) / nx;
+                if ((2 * th + 1) * (2 * tw + 1) > K::MAX_PIX || lds_bytes(th, tw) > CP_LDS_MAX) continue;
+                const long cost = (long)ny * nx * ((2 * th + 1) * (2 * tw + 1) + 64);
+                if (best < 0 || cost < best) { best = cost; PTH = th; PTW = tw; }
+                break;
+            }
+        return best >= 0;
+    }
+};
+
+template <int CIN, int COUT>
+__global__ __launch_bounds__(RB_THREADS, 4) void conv_pool_kernel(ConvPoolArgs p)
+{
+    using CP = ConvPoolCfg<CIN, COUT>;
+    using K = ResBlockCfg<COUT>;
+    extern __shared__ __attribute__((aligned(16))) char cp_lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, n = lane & 15;
+    const int tiles = p.tiles_y * p.tiles_x;
+    const int b = blockIdx.x / tiles, t = blockIdx.x % tiles;
+    const int ph0 = (t / p.tiles_x) * p.PTH, pw0 = (t % p.tiles_x) * p.PTW;
+    const int cy0 = 2 * ph0 - p.pad_h, cx0 = 2 * pw0 - p.pad_w;           // image coordinates of convolution pixel (0, 0)
+    const int CRH = 2 * p.PTH + 1, CRW = 2 * p.PTW + 1;
+    const int PP = CRW + 2, PRH = CRH + 2, PL = CP::patch_plane(p.PTH, p.PTW);
+    char* patch = cp_lds;
+    char* cmap = cp_lds + (size_t)CP::NCG * PL * 16;
+
+    // ---- input patch: cell (r, c) = image pixel (cy0 - 1 + r, cx0 - 1 + c), loads in batches of four ----
+    const __bf16* img = p.in + (size_t)b * p.H * p.W * CIN;
+    constexpr int UNR = 4;
+    const int items = PRH * PP * CP::NCG;
+    for (int idx0 = tid; idx0 < items; idx0 += UNR * RB_THREADS) {
+        bf16x8 v[UNR];
+        int at[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int idx = idx0 + u * RB_THREADS;
+            const int cell = idx / CP::NCG, cg = idx - cell * CP::NCG;     // a pixel's channel groups are adjacent in memory
+            const int r = cell / PP, c = cell - r * PP;
+            const int y = cy0 - 1 + r, x = cx0 - 1 + c;
+            at[u] = idx < items ? (cg * PL + cell) * 16 : -1;
+            v[u] = bf16x8{};
+            if (at[u] >= 0 && y >= 0 && y < p.H && x >= 0 && x < p.W) v[u] = *(const bf16x8*)(img + ((size_t)y * p.W + x) * CIN + cg * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+            if (at[u] >= 0) *(bf16x8*)(patch + at[u]) = v[u];
+    }
+    __syncthreads();
+
+    // ---- convolution tile -> cmap ----
+    {
+        const int fg = wave % K::NFG, pg = wave / K::NFG;
+        const int ft0 = fg * K::FTW;
+        floatx4 acc[RB_TPW][K::FTW];
+        const int npix = CRH * CRW, ntiles = (npix + 15) / 16;
+        rb_conv<CIN, COUT>(patch, PL, PP, CRW, npix, p.wp, p.kchunks, ft0, pg, lane, acc);
+#pragma unroll
+        for (int j = 0; j < K::FTW; ++j) {
+            const int f = (ft0 + j) * 16 + g * 4;
+            const floatx4 bv = *(const floatx4*)(p.bias + f);
+#pragma unroll
+            for (int i = 0; i < RB_TPW; ++i) {
+                const int q = (pg + K::NPG * i) * 16 + n;
+                if (pg + K::NPG * i >= ntiles || q >= npix) continue;
+                const int r = q / CRW, c = q - r * CRW;
+                const int y = cy0 + r, x = cx0 + c;
+                floatx4 v = acc[i][j] + bv;
+                if (y < 0 || y >= p.H || x < 0 || x >= p.W) v = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                *(bf16x4*)(cmap + ((size_t)q * COUT + f) * 2) = to_bf16x4(v);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- 3x3 / 2 maximum: pooled pixel (ph, pw) covers region rows 2 ph .. 2 ph + 2, columns 2 pw .. 2 pw + 2 ----
+    constexpr int NCGO = COUT / 8;
+    for (int idx = tid; idx < p.PTH * p.PTW * NCGO; idx += RB_THREADS) {
+        const int pp = idx / NCGO, cg = idx - pp * NCGO;
+        const int ph = pp / p.PTW, pw = pp - ph * p.PTW;
+        if (ph0 + ph >= p.PH || pw0 + pw >= p.PW) continue;
+        floatx4 lo = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, hi = lo;
+#pragma unroll
+        for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+            for (int dx = 0; dx < 3; ++dx) {
+                const bf16x8 v = *(const bf16x8*)(cmap + ((size_t)((2 * ph + dy) * CRW + 2 * pw + dx) * COUT + cg * 8) * 2);
+                lo = max4(lo, to_floatx4(__builtin_shufflevector(v, v, 0, 1, 2, 3)));
+                hi = max4(hi, to_floatx4(__builtin_shufflevector(v, v, 4, 5, 6, 7)));
+            }
+        const size_t o = (((size_t)b * p.PH + ph0 + ph) * p.PW + pw0 + pw) * COUT + cg * 8;
+        *(floatx4*)(p.x + o) = lo;
+        *(floatx4*)(p.x + o + 4) = hi;
+        if (p.r) {
+            const bf16x4 rl = relu_bf16x4(to_bf16x4(lo)), rh = relu_bf16x4(to_bf16x4(hi));
+            *(bf16x8*)(p.r + o) = __builtin_shufflevector(rl, rh, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    }
+}
+
+}  // namespace seedinf

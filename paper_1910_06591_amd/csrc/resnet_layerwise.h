@@ -220,7 +220,8 @@ __global__ __launch_bounds__(LT_THREADS) void conv3x3_lds_kernel(LwConvArgs p, i
 }
 
 // 3x3 / stride-2 max-pool with TF-style SAME padding on a bf16 NHWC map: writes the pooled values as the fp32
-// residual stream x and their rectified bf16 copy R (the first block's input).  One thread per 4 channels.
+// residual stream x and, if r is given, their rectified bf16 copy R (the input of a block that runs as two
+// launches).  One thread per 4 channels.
 __global__ __launch_bounds__(256) void pool3x3s2_lw_kernel(const __bf16* __restrict__ in, float* __restrict__ x,
                                                            __bf16* __restrict__ r, int B, int H, int W, int C, int PH, int PW,
                                                            int pad_h, int pad_w)
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(256) void pool3x3s2_lw_kernel(const __bf16* __restr
     }
     const long o = ((b * PH + ph) * PW + pw) * C + c4 * 4;
     *(floatx4*)(x + o) = m;
-    *(bf16x4*)(r + o) = relu_bf16x4(to_bf16x4(m));
+    if (r) *(bf16x4*)(r + o) = relu_bf16x4(to_bf16x4(m));
 }
 
 }  // namespace seedinf
