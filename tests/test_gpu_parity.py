@@ -272,6 +272,13 @@ def test_bf16_head_and_core_variants(orc):
     ("odd frame 50x70x3, two sections, 48 channels", dict(obs_h=50, obs_w=70, sections=[16, 48]), 7),
     ("4-plane minimap 72x96x4", dict(obs_c=4, sections=[16, 32, 32, 32]), 6),
     ("odd frame 46x62x3, 32 then 96 channels", dict(obs_h=46, obs_w=62, sections=[32, 96]), 5),
+    # the per-section fused kernels (first layer + pool, conv0 + pool, residual block) on maps that leave ragged
+    # tiles and odd pooled sizes, at every channel pair they are built for
+    ("odd frame 45x61x3, sections 64/128/128", dict(obs_h=45, obs_w=61, sections=[64, 128, 128]), 3),
+    ("odd frame 37x53x1, sections 16/16/32/64", dict(obs_h=37, obs_w=53, obs_c=1, sections=[16, 16, 32, 64]), 4),
+    ("frame 67x41x8, sections 32/32/64/64", dict(obs_h=67, obs_w=41, obs_c=8, sections=[32, 32, 64, 64]), 3),
+    ("frame 33x99x2, sections 16/32", dict(obs_h=33, obs_w=99, obs_c=2, sections=[16, 32]), 5),
+    ("16-plane map 59x83, sections 64/64", dict(obs_h=59, obs_w=83, obs_c=16, sections=[64, 64]), 3),
 ])
 def test_bf16_model_size_variants_run_layer_by_layer(orc, label, over, B):
     """Model-size variants (Section 4.1: wider filters; Section 4.2: larger minimaps) have no fused kernel and
