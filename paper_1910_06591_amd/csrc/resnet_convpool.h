@@ -28,10 +28,12 @@ template <int CIN, int COUT>
 struct ConvPoolCfg {
     using K = ResBlockCfg<COUT>;
     static constexpr int NCG = CIN / 8;
+    // bytes between the convolution tile's pixels in LDS (16 more than the COUT values: see first_pool_kernel)
+    static constexpr int CSTRIDE = COUT * 2 + (COUT >= 64 ? 16 : 0);
     __host__ __device__ static constexpr int patch_plane(int PTH, int PTW) { return ((2 * PTH + 3) * (2 * PTW + 3) + 15) / 16 * 16; }
     static size_t lds_bytes(int PTH, int PTW)
     {
-        return (size_t)NCG * patch_plane(PTH, PTW) * 16 + (size_t)(2 * PTH + 1) * (2 * PTW + 1) * COUT * 2;
+        return (size_t)NCG * patch_plane(PTH, PTW) * 16 + (size_t)(2 * PTH + 1) * (2 * PTW + 1) * CSTRIDE;
     }
     // the fewest convolution pixels over all tiles whose region fits a workgroup and whose maps fit
     static bool choose(int PH, int PW, int& PTH, int& PTW)
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(RB_THREADS, 4) void conv_pool_kernel(ConvPoolArgs p
                 const int y = cy0 + r, x = cx0 + c;
                 floatx4 v = acc[i][j] + bv;
                 if (y < 0 || y >= p.H || x < 0 || x >= p.W) v = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-                *(bf16x4*)(cmap + ((size_t)q * COUT + f) * 2) = to_bf16x4(v);
+                *(bf16x4*)(cmap + (size_t)q * CP::CSTRIDE + f * 2) = to_bf16x4(v);
             }
         }
     }
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(RB_THREADS, 4) void conv_pool_kernel(ConvPoolArgs p
         for (int dy = 0; dy < 3; ++dy)
 #pragma unroll
             for (int dx = 0; dx < 3; ++dx) {
-                const bf16x8 v = *(const bf16x8*)(cmap + ((size_t)((2 * ph + dy) * CRW + 2 * pw + dx) * COUT + cg * 8) * 2);
+                const bf16x8 v = *(const bf16x8*)(cmap + (size_t)((2 * ph + dy) * CRW + 2 * pw + dx) * CP::CSTRIDE + cg * 16);
                 lo = max4(lo, to_floatx4(__builtin_shufflevector(v, v, 0, 1, 2, 3)));
                 hi = max4(hi, to_floatx4(__builtin_shufflevector(v, v, 4, 5, 6, 7)));
             }

@@ -49,9 +49,12 @@ struct FirstPoolCfg {
     static_assert(CELL == 4 || CELL == 8 || CELL == 16, "planes per frame cell");
     static constexpr int NFT = C0 / 16;
     static constexpr int KCH = CELL == 4 ? 2 : (9 * CELL + 31) / 32;
+    // bytes between the convolution tile's pixels in LDS: 16 more than the C0 values, so that the 16 pixels of an
+    // accumulator tile's 8-byte stores spread over the banks (at a power-of-two stride they fall on two to eight)
+    static constexpr int CSTRIDE = C0 * 2 + (C0 >= 64 ? 16 : 0);   // (narrower tiles: the padding costs more tile area than the conflicts cost time)
     __host__ __device__ static constexpr int patch_pitch(int PTW) { return 2 * PTW + 1 + 3; }     // + halo 2 + the zero-weight column
     __host__ __device__ static constexpr int patch_bytes(int PTH, int PTW) { return ((2 * PTH + 3) * patch_pitch(PTW) * CELL * 2 + 15) / 16 * 16; }
-    static size_t lds_bytes(int PTH, int PTW) { return (size_t)patch_bytes(PTH, PTW) + (size_t)(2 * PTH + 1) * (2 * PTW + 1) * C0 * 2; }
+    static size_t lds_bytes(int PTH, int PTW) { return (size_t)patch_bytes(PTH, PTW) + (size_t)(2 * PTH + 1) * (2 * PTW + 1) * CSTRIDE; }
     // the fewest tiles whose maps fit
     static bool choose(int PH, int PW, int& PTH, int& PTW)
     {
@@ -95,32 +98,54 @@ __global__ __launch_bounds__(FP_THREADS) void first_pool_kernel(FirstPoolArgs p)
 
     // ---- frame patch: cell (r, c) = frame pixel (cy0 - 1 + r, cx0 - 1 + c), CELL bf16 ----
     const uint8_t* img = p.obs + (size_t)b * p.H * p.W * p.Cin;
+    // (the loads of three rounds are issued before the first is converted: one round at a time, each waits out a
+    // trip to memory)
+    constexpr int UNR = 3;
     if constexpr (CELL == 4) {
-        for (int cell = tid; cell < PRH * PP; cell += FP_THREADS) {
-            const int r = cell / PP, c = cell - r * PP;
-            const int y = cy0 - 1 + r, x = cx0 - 1 + c;
-            floatx4 v = {0.f, 0.f, 0.f, 0.f};
-            if (y >= 0 && y < p.H && x >= 0 && x < p.W) {
-                const uint8_t* s = img + ((size_t)y * p.W + x) * p.Cin;
-                v[0] = (float)s[0];
-                if (p.Cin > 1) v[1] = (float)s[1];
-                if (p.Cin > 2) v[2] = (float)s[2];
-                if (p.Cin > 3) v[3] = (float)s[3];
+        for (int cell0 = tid; cell0 < PRH * PP; cell0 += UNR * FP_THREADS) {
+            uint32_t raw[UNR][4];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int cell = cell0 + u * FP_THREADS;
+                const int r = cell / PP, c = cell - r * PP;
+                const int y = cy0 - 1 + r, x = cx0 - 1 + c;
+                raw[u][0] = raw[u][1] = raw[u][2] = raw[u][3] = 0;
+                if (cell < PRH * PP && y >= 0 && y < p.H && x >= 0 && x < p.W) {
+                    const uint8_t* s = img + ((size_t)y * p.W + x) * p.Cin;
+                    raw[u][0] = s[0];
+                    if (p.Cin > 1) raw[u][1] = s[1];
+                    if (p.Cin > 2) raw[u][2] = s[2];
+                    if (p.Cin > 3) raw[u][3] = s[3];
+                }
             }
-            *(bf16x4*)(patch + cell * 8) = to_bf16x4(v);
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int cell = cell0 + u * FP_THREADS;
+                if (cell >= PRH * PP) continue;
+                const floatx4 v = {(float)raw[u][0], (float)raw[u][1], (float)raw[u][2], (float)raw[u][3]};
+                *(bf16x4*)(patch + cell * 8) = to_bf16x4(v);
+            }
         }
     } else {
         constexpr int HALVES = CELL / 8;                       // 8 planes = 8 aligned bytes of the frame -> 16 bytes of the cell
-        for (int idx = tid; idx < PRH * PP * HALVES; idx += FP_THREADS) {
-            const int cell = idx / HALVES, h = idx - cell * HALVES;
-            const int r = cell / PP, c = cell - r * PP;
-            const int y = cy0 - 1 + r, x = cx0 - 1 + c;
-            bf16x8 v = {};
-            if (y >= 0 && y < p.H && x >= 0 && x < p.W) {
-                const uint2 raw = *(const uint2*)(img + ((size_t)y * p.W + x) * CELL + h * 8);
-                v = u8x8_to_bf16x8(raw.x, raw.y);
+        for (int idx0 = tid; idx0 < PRH * PP * HALVES; idx0 += UNR * FP_THREADS) {
+            uint2 raw[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int idx = idx0 + u * FP_THREADS;
+                const int cell = idx / HALVES, h = idx - cell * HALVES;
+                const int r = cell / PP, c = cell - r * PP;
+                const int y = cy0 - 1 + r, x = cx0 - 1 + c;
+                raw[u] = uint2{0u, 0u};
+                if (idx < PRH * PP * HALVES && y >= 0 && y < p.H && x >= 0 && x < p.W)
+                    raw[u] = *(const uint2*)(img + ((size_t)y * p.W + x) * CELL + h * 8);
             }
-            *(bf16x8*)(patch + (size_t)cell * CELL * 2 + h * 16) = v;
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int idx = idx0 + u * FP_THREADS;
+                if (idx >= PRH * PP * HALVES) continue;
+                *(bf16x8*)(patch + (size_t)idx * 16) = u8x8_to_bf16x8(raw[u].x, raw[u].y);
+            }
         }
     }
     __syncthreads();
@@ -168,7 +193,7 @@ __global__ __launch_bounds__(FP_THREADS) void first_pool_kernel(FirstPoolArgs p)
                 for (int kc = 0; kc < KCH; ++kc) acc = mfma16(a[j][kc], bfrag[kc], acc);
                 floatx4 v = acc * p.scale + bv[j];
                 if (!inside) v = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-                if (tile * 16 + n < npix) *(bf16x4*)(cmap + ((size_t)q * C0 + j * 16 + g * 4) * 2) = to_bf16x4(v);
+                if (tile * 16 + n < npix) *(bf16x4*)(cmap + (size_t)q * K::CSTRIDE + (j * 16 + g * 4) * 2) = to_bf16x4(v);
             }
         }
     }
@@ -185,7 +210,7 @@ __global__ __launch_bounds__(FP_THREADS) void first_pool_kernel(FirstPoolArgs p)
         for (int dy = 0; dy < 3; ++dy)
 #pragma unroll
             for (int dx = 0; dx < 3; ++dx) {
-                const bf16x8 v = *(const bf16x8*)(cmap + ((size_t)((2 * ph + dy) * CRW + 2 * pw + dx) * C0 + cg * 8) * 2);
+                const bf16x8 v = *(const bf16x8*)(cmap + (size_t)((2 * ph + dy) * CRW + 2 * pw + dx) * K::CSTRIDE + cg * 16);
                 lo = max4(lo, to_floatx4(__builtin_shufflevector(v, v, 0, 1, 2, 3)));
                 hi = max4(hi, to_floatx4(__builtin_shufflevector(v, v, 4, 5, 6, 7)));
             }
