@@ -754,6 +754,9 @@ inline bool resblock_by_width(int C, F go)
     }
 }
 
+// pitch-wide regions (conflict-free map fragments) where measured faster: 64 channels on maps larger than 18 x 24
+inline bool resblock_flat(const ConvLayer& c) { return c.Cin == 64 && c.H * c.W > 18 * 24; }
+
 // Whether launch_resblock takes this block: every width with a kernel whose tile fits.  Measured at 1024 images
 // against the two-launch form (LDS-tiled convolution kernel twice): 16 ch 54 x 72 149 vs 308 us; 32 ch 36 x 48 175
 // vs 284, 27 x 36 and smaller 52 vs 70; 64 ch 36 x 48 552 vs 640, 18 x 24 and 9 x 12 84 vs 124; 128 ch (18 x 24 and
@@ -764,7 +767,7 @@ inline bool resblock_fusable(const ConvLayer& ca, const ConvLayer& cb)
     if (ca.Cout != C || cb.Cin != C || cb.Cout != C || ca.H != cb.H || ca.W != cb.W) return false;
     return resblock_by_width(C, [&](auto cc) {
         int th, tw;
-        return ResBlockCfg<decltype(cc)::value>::choose(ca.H, ca.W, th, tw);
+        return ResBlockCfg<decltype(cc)::value>::choose(ca.H, ca.W, resblock_flat(ca), th, tw);
     });
 }
 
@@ -779,14 +782,15 @@ inline bool launch_resblock(hipStream_t st, const LwLayerDev& da, const LwLayerD
         constexpr int CC = decltype(cc)::value;
         using K = ResBlockCfg<CC>;
         ResBlockArgs r{};
-        if (!K::choose(ca.H, ca.W, r.TH, r.TW)) return false;
+        r.flat = resblock_flat(ca);
+        if (!K::choose(ca.H, ca.W, r.flat != 0, r.TH, r.TW)) return false;
         r.x_in = x_in; r.wpa = wp_conv + da.wp_off / 8; r.wpb = wp_conv + db.wp_off / 8;
         r.bias_a = d_w + ca.b_off; r.bias_b = d_w + cb.b_off;
         r.x_out = x_out; r.y = y; r.y_relu = y_relu; r.ldy = ldy;
         r.B = B; r.H = ca.H; r.W = ca.W; r.kchunks = da.kchunks;
         r.tiles_y = (ca.H + r.TH - 1) / r.TH; r.tiles_x = (ca.W + r.TW - 1) / r.TW;
         hipLaunchKernelGGL(resblock_fused_kernel<CC>, dim3((unsigned)((long)B * r.tiles_y * r.tiles_x)), dim3(RB_THREADS),
-                           K::lds_bytes(r.TH, r.TW), st, r);
+                           K::lds_bytes(r.TH, r.TW, r.flat != 0), st, r);
         return true;
     });
 }

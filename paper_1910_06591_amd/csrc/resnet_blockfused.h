@@ -9,7 +9,7 @@
 //
 // Both convolutions are implicit GEMMs over planar LDS maps [C/8][rows][pitch][8 bf16] with the weight packing
 // of conv3x3_lds_kernel (A fragments [feature tile][chunk][lane][8], k = tap * C + ci, fetched from global
-// memory three chunks ahead).  A region's pixels are cut row-major into tiles of 16; wavefront w takes feature tiles
+// memory three chunks ahead).  A region is cut into tiles of 16 consecutive map cells; wavefront w takes feature tiles
 // FTW * (w % NFG) ... and every NPG-th pixel tile from w / NFG, at most TPW of them.
 //
 // What set the time, in the order it was found (1024 images, 32 channels on 36 x 48): the weight fragments one
@@ -32,6 +32,7 @@ struct ResBlockArgs {
     int y_relu;                        // rectify y
     int ldy;                           // 0: y is NHWC; > 0: y is the feature matrix [B, ldy], (h, w, c) order
     int B, H, W, TH, TW, tiles_y, tiles_x, kchunks;
+    int flat;                          // walk the regions as wide as their maps (see resblock_fused_kernel)
 };
 
 constexpr int RB_THREADS = 512, RB_TPW = 6;
@@ -46,22 +47,24 @@ struct ResBlockCfg {
     static_assert(8 % NFG == 0, "feature groups must divide the eight wavefronts");
     static constexpr int NPG = 8 / NFG;                     // wavefronts (pixel groups) per feature group
     static constexpr int MAX_PIX = 16 * RB_TPW * NPG;       // pixels of conv_a's region a workgroup can take
-    __host__ __device__ static constexpr int plane(int rows, int pitch) { return (rows * pitch + 15) / 16 * 16; }
-    static size_t lds_bytes(int TH, int TW) { return (size_t)NCG * (plane(TH + 4, TW + 4) + plane(TH + 2, TW + 2)) * 16; }
+    // cells of a map plane, in whole 256 bytes; walked flat, the last tile's taps reach two cells past the map
+    __host__ __device__ static constexpr int plane(int rows, int pitch, bool flat) { return (rows * pitch + (flat ? 2 : 0) + 15) / 16 * 16; }
+    static size_t lds_bytes(int TH, int TW, bool flat) { return (size_t)NCG * (plane(TH + 4, TW + 4, flat) + plane(TH + 2, TW + 2, flat)) * 16; }
     // tile extents for an H x W map: the fewest tiles whose conv_a region fits a workgroup and whose maps fit LDS
-    static bool choose(int H, int W, int& TH, int& TW)
+    static bool choose(int H, int W, bool flat, int& TH, int& TW)
     {
+        const int ea = flat ? 4 : 2, eb = flat ? 2 : 0;           // columns walked beyond the tile: conv_a's region, conv_b's
         long best = -1;
         for (int ny = 1; ny <= H; ++ny) {
             const int th = (H + ny - 1) / ny;
             for (int nx = 1; nx <= W; ++nx) {
                 const int tw = (W + nx - 1) / nx;
-                if ((th + 2) * (tw + 2) > MAX_PIX || lds_bytes(th, tw) > RB_LDS_MAX) continue;
+                if ((th + 2) * (tw + ea) > MAX_PIX || lds_bytes(th, tw, flat) > RB_LDS_MAX) continue;
                 // cost: the pixels both convolutions compute over all tiles (halo recomputation); half as much
                 // again when the maps leave no room for a second workgroup on the compute unit, whose MFMAs
                 // would run under this one's loads and stores
-                long cost = (long)ny * nx * ((th + 2) * (tw + 2) + th * tw);
-                if (lds_bytes(th, tw) > 80 * 1024) cost += cost / 2;
+                long cost = (long)ny * nx * ((th + 2) * (tw + ea) + th * (tw + eb));
+                if (lds_bytes(th, tw, flat) > 80 * 1024) cost += cost / 2;
                 if (best < 0 || cost < best) { best = cost; TH = th; TW = tw; }
                 break;                                      // larger nx only shrinks tw further: more tiles, more halo
             }
@@ -136,8 +139,8 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
     const int tiles = p.tiles_y * p.tiles_x;
     const int b = blockIdx.x / tiles, t = blockIdx.x % tiles;
     const int y0 = (t / p.tiles_x) * p.TH, x0 = (t % p.tiles_x) * p.TW;
-    const int RP = p.TW + 4, RPL = K::plane(p.TH + 4, RP);          // ReLU(x): tile + 2
-    const int UP = p.TW + 2, UPL = K::plane(p.TH + 2, UP);          // U: tile + 1
+    const int RP = p.TW + 4, RPL = K::plane(p.TH + 4, RP, p.flat != 0);          // ReLU(x): tile + 2
+    const int UP = p.TW + 2, UPL = K::plane(p.TH + 2, UP, p.flat != 0);          // U: tile + 1
     char* Rm = rb_lds;
     char* Um = rb_lds + (size_t)K::NCG * RPL * 16;
     const float* ximg = p.x_in + (size_t)b * p.H * p.W * C;
@@ -181,7 +184,12 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
 
     // ---- U = ReLU(conv_a(R) + bias) on the tile + 1, zero outside the image ----
     {
-        const int UW = p.TW + 2, npix = (p.TH + 2) * UW;
+        // `flat`: the region is walked as wide as the map (RP columns, the last two of each row computed and
+        // dropped): a tile is then 16 consecutive cells - 256 distinct bank bytes, the full LDS rate - where 16
+        // row-major pixels of an 18-wide region wrap rows two cells apart and read at 57 %.  It pays where the map
+        // fragments bound the kernel (64 channels on 36 x 48: 552 -> 502 us at 1024 images) and costs its extra
+        // columns elsewhere (128 channels: 305 -> 320; 16 channels: 149 -> 160), so the host decides.
+        const int UW = p.flat ? RP : p.TW + 2, npix = (p.TH + 2) * UW;
         rb_conv<C, C>(Rm, RPL, RP, UW, npix, p.wpa, p.kchunks, ft0, pg, lane, acc);
         const int ntiles = (npix + 15) / 16;
 #pragma unroll
@@ -193,6 +201,7 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
                 const int q = (pg + K::NPG * i) * 16 + n;
                 if (pg + K::NPG * i >= ntiles || q >= npix) continue;
                 const int r = q / UW, c = q - r * UW;
+                if (c >= p.TW + 2) continue;
                 const int gy = y0 - 1 + r, gx = x0 - 1 + c;
                 bf16x4 o = {};
                 if (gy >= 0 && gy < p.H && gx >= 0 && gx < p.W) o = relu_bf16x4(to_bf16x4(acc[i][j] + bv));
@@ -204,8 +213,8 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
 
     // ---- x' = x + conv_b(U) + bias on the tile ----
     {
-        const int npix = p.TH * p.TW;
-        rb_conv<C, C>(Um, UPL, UP, p.TW, npix, p.wpb, p.kchunks, ft0, pg, lane, acc);
+        const int BW = p.flat ? UP : p.TW, npix = p.TH * BW;
+        rb_conv<C, C>(Um, UPL, UP, BW, npix, p.wpb, p.kchunks, ft0, pg, lane, acc);
         const int ntiles = (npix + 15) / 16;
         const int hw = p.H * p.W;
 #pragma unroll
@@ -216,9 +225,9 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
             for (int i = 0; i < RB_TPW; ++i) {
                 const int q = (pg + K::NPG * i) * 16 + n;
                 if (pg + K::NPG * i >= ntiles || q >= npix) continue;
-                const int r = q / p.TW, c = q - r * p.TW;
+                const int r = q / BW, c = q - r * BW;
                 const int gy = y0 + r, gx = x0 + c;
-                if (gy >= p.H || gx >= p.W) continue;
+                if (c >= p.TW || gy >= p.H || gx >= p.W) continue;
                 const int pl = gy * p.W + gx;
                 const size_t pix = (size_t)b * hw + pl;
                 floatx4 v = acc[i][j] + bv;
