@@ -9,8 +9,9 @@
 //
 // Both convolutions are implicit GEMMs over planar LDS maps [C/8][rows][pitch][8 bf16] with the weight packing
 // of conv3x3_lds_kernel (A fragments [feature tile][chunk][lane][8], k = tap * C + ci, fetched from global
-// memory three chunks ahead).  A region is cut into tiles of 16 consecutive map cells; wavefront w takes feature tiles
-// FTW * (w % NFG) ... and every NPG-th pixel tile from w / NFG, at most TPW of them.
+// memory three chunks ahead).  A region's pixels are cut row-major into tiles of 16 (or, `flat`, the region is
+// walked as wide as its map and a tile is 16 consecutive cells); wavefront w takes feature tiles FTW * (w % NFG) ...
+// and every NPG-th pixel tile from w / NFG, at most TPW of them.
 //
 // What set the time, in the order it was found (1024 images, 32 channels on 36 x 48): the weight fragments one
 // chunk ahead (each chunk waited out a trip to L2: 260 -> 230 us with three ahead), the staging loop's loads
@@ -50,7 +51,7 @@ struct ResBlockCfg {
     // cells of a map plane, in whole 256 bytes; walked flat, the last tile's taps reach two cells past the map
     __host__ __device__ static constexpr int plane(int rows, int pitch, bool flat) { return (rows * pitch + (flat ? 2 : 0) + 15) / 16 * 16; }
     static size_t lds_bytes(int TH, int TW, bool flat) { return (size_t)NCG * (plane(TH + 4, TW + 4, flat) + plane(TH + 2, TW + 2, flat)) * 16; }
-    // tile extents for an H x W map: the fewest tiles whose conv_a region fits a workgroup and whose maps fit LDS
+    // tile extents for an H x W map: the cheapest cut whose conv_a region fits a workgroup and whose maps fit LDS
     static bool choose(int H, int W, bool flat, int& TH, int& TW)
     {
         const int ea = flat ? 4 : 2, eb = flat ? 2 : 0;           // columns walked beyond the tile: conv_a's region, conv_b's
@@ -66,7 +67,6 @@ struct ResBlockCfg {
                 long cost = (long)ny * nx * ((th + 2) * (tw + ea) + th * (tw + eb));
                 if (lds_bytes(th, tw, flat) > 80 * 1024) cost += cost / 2;
                 if (best < 0 || cost < best) { best = cost; TH = th; TW = tw; }
-                break;                                      // larger nx only shrinks tw further: more tiles, more halo
             }
         }
         return best >= 0;
