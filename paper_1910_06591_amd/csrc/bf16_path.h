@@ -19,6 +19,7 @@
 #include "resnet_blockfused.h"
 #include "resnet_firstpool.h"
 #include "resnet_convpool.h"
+#include "resnet_convtile.h"
 
 namespace seedinf {
 
@@ -754,6 +755,11 @@ inline bool resblock_by_width(int C, F go)
     }
 }
 
+// Blocks that run as two conv_tile_kernel launches.  Measured at 1024 images against the one-launch block: 128
+// channels (18 x 24 and 9 x 12, mean) 108 + 137 us vs 306; 64 channels on 36 x 48 219 + 323 vs 505, on 18 x 24 and
+// 9 x 12 42 + 52 vs 84 - so 128 channels only.
+inline bool conv_tile_preferred(const ConvLayer& c) { return c.Cin == c.Cout && c.Cin == 128; }
+
 // pitch-wide regions (conflict-free map fragments) where measured faster: 64 channels on maps larger than 18 x 24
 inline bool resblock_flat(const ConvLayer& c) { return c.Cin == 64 && c.H * c.W > 18 * 24; }
 
@@ -793,6 +799,39 @@ inline bool launch_resblock(hipStream_t st, const LwLayerDev& da, const LwLayerD
                            K::lds_bytes(r.TH, r.TW, r.flat != 0), st, r);
         return true;
     });
+}
+
+// One convolution of a residual block as a launch of its own over large LDS tiles (conv_tile_kernel); false when
+// the width has no such kernel or no tile fits, and nothing was launched.
+inline bool launch_conv_tile(hipStream_t st, const LwLayerDev& d, const bf16x8* wp_conv, const float* d_w, const ConvLayer& c, int B,
+                             const void* in, bool in_f32, const float* resid, float* x_out, __bf16* y, int y_relu, int ldy)
+{
+    if (c.Cin != c.Cout) return false;
+    auto go = [&](auto cc) -> bool {
+        constexpr int CC = decltype(cc)::value;
+        using CT = ConvTileCfg<CC>;
+        ConvTileArgs a{};
+        if (d.kchunks != (9 * CC + 31) / 32 || !CT::choose(c.H, c.W, a.TH, a.TW)) return false;
+        a.in = in; a.wp = wp_conv + d.wp_off / 8; a.bias = d_w + c.b_off; a.resid = resid; a.x_out = x_out; a.y = y;
+        a.y_relu = y_relu; a.ldy = ldy;
+        a.B = B; a.H = c.H; a.W = c.W; a.kchunks = d.kchunks;
+        a.tiles_y = (c.H + a.TH - 1) / a.TH; a.tiles_x = (c.W + a.TW - 1) / a.TW;
+        const dim3 grid((unsigned)((long)B * a.tiles_y * a.tiles_x));
+        static bool attr_set = false;                       // per width: the kernels may ask for more than 64 KiB
+        if (!attr_set) {
+            if (hipFuncSetAttribute((const void*)conv_tile_kernel<CC, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CT_LDS_MAX) != hipSuccess ||
+                hipFuncSetAttribute((const void*)conv_tile_kernel<CC, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CT_LDS_MAX) != hipSuccess)
+                return false;
+            attr_set = true;
+        }
+        if (in_f32) hipLaunchKernelGGL((conv_tile_kernel<CC, true>), grid, dim3(RB_THREADS), CT::lds_bytes(a.TH, a.TW), st, a);
+        else hipLaunchKernelGGL((conv_tile_kernel<CC, false>), grid, dim3(RB_THREADS), CT::lds_bytes(a.TH, a.TW), st, a);
+        return true;
+    };
+    switch (c.Cin) {
+    case 128: return go(std::integral_constant<int, 128>{});
+    default: return false;
+    }
 }
 
 // Torso and linear layer over B rows: leaves the rectified linear-layer output of row r in row r of
@@ -846,6 +885,18 @@ inline seed_status_t bf16_torso_fc(Bf16State* s, const Plan& p, const float* d_w
                 const bool to_next = !last_sec && blk == 1;         // the next section's conv0 takes x un-rectified
                 __bf16* y = closing ? s->feat : s->lw_r;
                 const int y_relu = to_next ? 0 : 1, ldy = closing ? s->ldf : 0;
+                // (two launches over larger tiles where the one-launch block is bound by operand delivery; conv_b adds
+                // and writes x in place: it reads no pixel of x but its own)
+                if (conv_tile_preferred(sec.block[2 * blk]) &&
+                    launch_conv_tile(st, s->lw[li], W.wp_conv, d_w, sec.block[2 * blk], B, x_cur, true, nullptr, nullptr, s->lw_u, 1, 0)) {
+                    if (!launch_conv_tile(st, s->lw[li + 1], W.wp_conv, d_w, sec.block[2 * blk + 1], B, s->lw_u, false, x_cur,
+                                          blk == 0 ? x_cur : nullptr, blk == 0 ? nullptr : y, y_relu, ldy)) {
+                        err = "residual block: second convolution has no tile kernel";
+                        return SEED_ERR_DEVICE;
+                    }
+                    li += 2;
+                    continue;
+                }
                 if (launch_resblock(st, s->lw[li], s->lw[li + 1], W.wp_conv, d_w, sec.block[2 * blk], sec.block[2 * blk + 1], B, x_cur,
                                     blk == 0 ? x_alt : nullptr, blk == 0 ? nullptr : y, y_relu, ldy)) {
                     li += 2;

@@ -76,17 +76,17 @@ struct ResBlockCfg {
 // One implicit-GEMM pass, CIN -> COUT channels: region of RW-wide pixels (npix of them) over the planar map `src`
 // (plane cells PL, pitch PITCH; a region pixel (r, c) has its tap (0, 0) at cell r * PITCH + c).  acc[i][j]: pixel
 // tile pg + NPG * i, feature tile ft0 + j.
-template <int CIN, int COUT>
+template <int CIN, int COUT, int TPW = RB_TPW>
 __device__ __forceinline__ void rb_conv(const char* src, int PL, int PITCH, int RW, int npix, const bf16x8* __restrict__ wp,
-                                        int kchunks, int ft0, int pg, int lane, floatx4 (&acc)[RB_TPW][ResBlockCfg<COUT>::FTW])
+                                        int kchunks, int ft0, int pg, int lane, floatx4 (&acc)[TPW][ResBlockCfg<COUT>::FTW])
 {
     using K = ResBlockCfg<COUT>;
     constexpr int C = CIN;
     const int g = lane >> 4, n = lane & 15;
     const int ntiles = (npix + 15) / 16;
-    int base[RB_TPW];
+    int base[TPW];
 #pragma unroll
-    for (int i = 0; i < RB_TPW; ++i) {
+    for (int i = 0; i < TPW; ++i) {
         const int q = min((pg + K::NPG * i) * 16 + n, npix - 1);
         base[i] = (q / RW) * PITCH + q % RW;
 #pragma unroll
@@ -117,7 +117,7 @@ __device__ __forceinline__ void rb_conv(const char* src, int PL, int PITCH, int 
             const int tap = min(k0 / C, 8), cg = (k0 % C) >> 3;
             const char* s = src + ((size_t)cg * PL + (tap / 3) * PITCH + tap % 3) * 16;
 #pragma unroll
-            for (int i = 0; i < RB_TPW; ++i) {
+            for (int i = 0; i < TPW; ++i) {
                 if (pg + K::NPG * i < ntiles) {                 // uniform
                     const bf16x8 b = *(const bf16x8*)(s + base[i] * 16);
 #pragma unroll

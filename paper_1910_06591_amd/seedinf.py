@@ -17,7 +17,7 @@ _ROOT = os.path.dirname(_PKG)
 LIB_PATH = os.environ.get("SEEDINF_LIB", os.path.join(_PKG, "libseedinf.so"))
 SOURCES = [os.path.join(_PKG, "csrc", f) for f in
            ("seedinf.hip", "plan.h", "kernels_fp32.h", "kernels_heads.h", "bf16_path.h", "bf16_common.h", "gemm_bf16.h", "gemm_bf16_lds.h",
-            "conv_stack_bf16.h", "conv_stack_fused.h", "resnet_fused.h", "resnet_layerwise.h", "resnet_blockfused.h", "resnet_firstpool.h", "resnet_convpool.h", "batcher.h", "host_pool.h")]
+            "conv_stack_bf16.h", "conv_stack_fused.h", "resnet_fused.h", "resnet_layerwise.h", "resnet_blockfused.h", "resnet_firstpool.h", "resnet_convpool.h", "resnet_convtile.h", "batcher.h", "host_pool.h")]
 PROBE_SOURCE = os.path.join(_PKG, "csrc", "probe.hip")
 PROBE_LIB_PATH = os.path.join(_PKG, "libseedprobe.so")
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
