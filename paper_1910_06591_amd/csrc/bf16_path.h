@@ -518,6 +518,23 @@ inline seed_status_t bf16_create(const Plan& p, const float* d_w, Bf16State** ou
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)conv3x3_lds_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LT_LDS_MAX));
+    {
+        // the per-section kernels of the layer-by-layer ResNet path may ask for more than 64 KiB as well
+        hipError_t e = hipSuccess;
+        auto set = [&](const void* f, size_t bytes) {
+            if (e == hipSuccess) e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        };
+        set((const void*)conv_pool_kernel<16, 16>, CP_LDS_MAX);
+        set((const void*)conv_pool_kernel<16, 32>, CP_LDS_MAX);
+        set((const void*)conv_pool_kernel<32, 32>, CP_LDS_MAX);
+        set((const void*)conv_pool_kernel<32, 64>, CP_LDS_MAX);
+        set((const void*)conv_pool_kernel<64, 64>, CP_LDS_MAX);
+        set((const void*)conv_pool_kernel<64, 128>, CP_LDS_MAX);
+        set((const void*)conv_pool_kernel<128, 128>, CP_LDS_MAX);
+        set((const void*)conv_tile_kernel<128, true>, CT_LDS_MAX);
+        set((const void*)conv_tile_kernel<128, false>, CT_LDS_MAX);
+        BF_TRY(e);
+    }
     BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
     BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
@@ -731,12 +748,6 @@ inline bool launch_conv_pool(hipStream_t st, const LwLayerDev& d, const bf16x8* 
         a.in = in; a.wp = wp_conv + d.wp_off / 8; a.bias = d_w + c.b_off; a.x = x; a.r = r;
         a.B = B; a.H = c.H; a.W = c.W; a.PH = sec.PH; a.PW = sec.PW; a.pad_h = sec.pool_pad_h; a.pad_w = sec.pool_pad_w;
         a.tiles_y = (sec.PH + a.PTH - 1) / a.PTH; a.tiles_x = (sec.PW + a.PTW - 1) / a.PTW; a.kchunks = d.kchunks;
-        static bool attr_set = false;                       // per instantiation: the kernel may ask for more than 64 KiB
-        if (!attr_set) {
-            if (hipFuncSetAttribute((const void*)conv_pool_kernel<CIN, COUT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CP_LDS_MAX) != hipSuccess)
-                return false;
-            attr_set = true;
-        }
         hipLaunchKernelGGL((conv_pool_kernel<CIN, COUT>), dim3((unsigned)((long)B * a.tiles_y * a.tiles_x)), dim3(RB_THREADS),
                            CP::lds_bytes(a.PTH, a.PTW), st, a);
         return true;
@@ -817,13 +828,6 @@ inline bool launch_conv_tile(hipStream_t st, const LwLayerDev& d, const bf16x8* 
         a.B = B; a.H = c.H; a.W = c.W; a.kchunks = d.kchunks;
         a.tiles_y = (c.H + a.TH - 1) / a.TH; a.tiles_x = (c.W + a.TW - 1) / a.TW;
         const dim3 grid((unsigned)((long)B * a.tiles_y * a.tiles_x));
-        static bool attr_set = false;                       // per width: the kernels may ask for more than 64 KiB
-        if (!attr_set) {
-            if (hipFuncSetAttribute((const void*)conv_tile_kernel<CC, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CT_LDS_MAX) != hipSuccess ||
-                hipFuncSetAttribute((const void*)conv_tile_kernel<CC, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)CT_LDS_MAX) != hipSuccess)
-                return false;
-            attr_set = true;
-        }
         if (in_f32) hipLaunchKernelGGL((conv_tile_kernel<CC, true>), grid, dim3(RB_THREADS), CT::lds_bytes(a.TH, a.TW), st, a);
         else hipLaunchKernelGGL((conv_tile_kernel<CC, false>), grid, dim3(RB_THREADS), CT::lds_bytes(a.TH, a.TW), st, a);
         return true;
