@@ -325,16 +325,15 @@ __device__ __forceinline__ void prefetch_issue(Prefetch<S>& p, const uint8_t* __
                 p.d[j][0] = s[0]; p.d[j][1] = s[1]; p.d[j][2] = s[2];
             }
         } else {
-            const int nin = r1 - r0 + 3;
+            // unconditional loads from a clamped row: a select on the loaded value here would wait for the memory
+            // round trip at once; rows outside the frame are zeroed when the registers are converted
 #pragma unroll
             for (int j = 0; j < S::PRE_N; ++j) {
                 const int i = tid + j * RN_THREADS;
                 const int ry = i / S::W, px = i % S::W;
-                const int iy = r0 - 1 + ry;
-                const bool inside = ry < nin && iy >= 0 && iy < S::H;
-                const uint4 v = *(const uint4*)(obs_img + ((size_t)(inside ? iy : 0) * S::W + px) * S::CIN);
-                p.d[j][0] = inside ? v.x : 0u; p.d[j][1] = inside ? v.y : 0u;
-                p.d[j][2] = inside ? v.z : 0u; p.d[j][3] = inside ? v.w : 0u;
+                const int iy = min(max(r0 - 1 + ry, 0), S::H - 1);
+                const uint4 v = *(const uint4*)(obs_img + ((size_t)iy * S::W + px) * S::CIN);
+                p.d[j][0] = v.x; p.d[j][1] = v.y; p.d[j][2] = v.z; p.d[j][3] = v.w;
             }
         }
     }
@@ -390,8 +389,11 @@ __device__ __forceinline__ void prefetch_commit(const Prefetch<S>& p, char* buf0
                 const int i = tid + j * RN_THREADS;
                 const int ry = i / S::W, px = i % S::W;
                 if (ry < nin) {
-                    *(bf16x8*)(buf0 + (ry * S::IPITCH + px + 1) * 16) = u8x8_to_bf16x8(p.d[j][0], p.d[j][1]);
-                    *(bf16x8*)(buf0 + (S::IPLANE + ry * S::IPITCH + px + 1) * 16) = u8x8_to_bf16x8(p.d[j][2], p.d[j][3]);
+                    const int iy = r0 - 1 + ry;
+                    const bool inside = iy >= 0 && iy < S::H;                   // the rows above and below the frame: zeros
+                    const bf16x8 z = {};
+                    *(bf16x8*)(buf0 + (ry * S::IPITCH + px + 1) * 16) = inside ? u8x8_to_bf16x8(p.d[j][0], p.d[j][1]) : z;
+                    *(bf16x8*)(buf0 + (S::IPLANE + ry * S::IPITCH + px + 1) * 16) = inside ? u8x8_to_bf16x8(p.d[j][2], p.d[j][3]) : z;
                 }
             }
             const bf16x8 z = {};
