@@ -119,6 +119,66 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, floatx4 (&acc)[
     }
 }
 
+// The LSTM epilogue's operands for one row tile, requested before the K loop so that their trips to memory run
+// beside the loop's own (taken one after another - flags, then weights, then the action row, then the cell -
+// the kernel is a chain of four memory latencies around a microsecond of arithmetic).
+struct LstmOperands {
+    floatx4 bg[4], wr[4], wa[4], c0;
+    int a;
+    float rew;
+    bool fresh;
+};
+
+// first round: everything whose address is known at once (`row` already clamped into the batch)
+__device__ __forceinline__ void lstm_prefetch(const GemmArgs& p, LstmOperands& o, int wt, int row, int g)
+{
+    const int Hn = p.Hn, G4 = 4 * p.Hn;
+    const int u = wt * 16 + g * 4;
+    o.a = p.prev_action[row];
+    o.rew = p.prev_reward[row];
+    o.fresh = p.done && p.done[row];
+    o.c0 = *(const floatx4*)(p.c_in + (size_t)row * Hn + u);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        o.bg[j] = *(const floatx4*)(p.lstm_b + j * Hn + u);
+        o.wr[j] = *(const floatx4*)(p.lstm_w + (size_t)(p.F + p.A) * G4 + j * Hn + u);
+    }
+}
+
+// second round: the previous action's weight row (from a clamped index: an action outside the range adds nothing,
+// which the epilogue decides, not this load)
+__device__ __forceinline__ void lstm_prefetch_action(const GemmArgs& p, LstmOperands& o, int wt, int g)
+{
+    const int Hn = p.Hn, G4 = 4 * p.Hn;
+    const int u = wt * 16 + g * 4;
+    const int aa = min(max(o.a, 0), p.A - 1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o.wa[j] = *(const floatx4*)(p.lstm_w + (size_t)(p.F + aa) * G4 + j * Hn + u);
+}
+
+// gates and cell of one row from prefetched operands: the arithmetic of gemm_epilogue's LSTM branch, term by term
+__device__ __forceinline__ void lstm_epilogue_row(const GemmArgs& p, const floatx4 (&acc)[4], const LstmOperands& o, int wt, int row, int g)
+{
+    const int Hn = p.Hn;
+    const int u = wt * 16 + g * 4;
+    floatx4 pre[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        pre[j] = acc[j] + o.bg[j] + o.rew * o.wr[j];
+        if (o.a >= 0 && o.a < p.A) pre[j] += o.wa[j];
+    }
+    floatx4 c0 = o.c0;
+    if (o.fresh) c0 = floatx4{0.f, 0.f, 0.f, 0.f};
+    floatx4 cn, hn;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        cn[i] = sigmoidf_(pre[1][i]) * c0[i] + sigmoidf_(pre[0][i]) * tanhf_(pre[2][i]);
+        hn[i] = sigmoidf_(pre[3][i]) * tanhf_(cn[i]);
+    }
+    *(floatx4*)(p.c_out + (size_t)row * Hn + u) = cn;
+    *(floatx4*)(p.h_out + (size_t)row * Hn + u) = hn;
+}
+
 // K loop over the chunks [kb, ke) of one source segment, branch-free inside: NST rotating fragment sets keep
 // NST-1 stages of loads in flight while one is multiplied (these loops are bound by load latency and L1
 // capacity, so bytes in flight and whole cache lines are what counts).  A stage is CPS consecutive chunks: with
@@ -267,11 +327,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
 #pragma unroll
     for (int j = 0; j < FT; ++j) wl[j] = p.wp + ((size_t)min(ft0 + j, p.n_ftiles - 1) * kct) * 64 + lane;
 
+    // the wavefront that will finish row tile `wave` requests that tile's epilogue operands now
+    LstmOperands lo;
+    const bool finisher = EPI == EPI_LSTM && wave < RT;                      // uniform
+    const int lrow = min(r0 + wave * 16 + n, p.rows - 1);
+    if constexpr (EPI == EPI_LSTM)
+        if (finisher) lstm_prefetch(p, lo, wt, lrow, g);
     bool fresh[RT];
 #pragma unroll
     for (int r = 0; r < RT; ++r) fresh[r] = EPI == EPI_LSTM && p.done && p.done[rowi[r]];
     gemm_k_loop<RT, 3, 2, false, FT>(acc, wl, p.x1, p.ld1, rowi, k0, min(k1, p.kc1), 0, 0, g, fresh);
     gemm_k_loop<RT, 3, 1, true, FT>(acc, wl, p.x2, p.ld2, rowi, max(k0, p.kc1), k1, p.kc1, p.k2, g, fresh);
+    if constexpr (EPI == EPI_LSTM)
+        if (finisher) lstm_prefetch_action(p, lo, wt, g);                 // in flight across the reduction below
 
     // K reduction through LDS.  With 8 wavefronts the upper four first hand everything to the lower four.
     if constexpr (NW == 8) {
@@ -309,7 +377,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
             for (int j = 0; j < FT; ++j) acc[r][j] += part[((w2 * RT + r) * 4 + j) * 64 + lane];
         }
     }
-    if constexpr (FT == 4) {
+    if constexpr (EPI == EPI_LSTM) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+            if (r == wave && r0 + r * 16 + n < p.rows) lstm_epilogue_row(p, acc[r], lo, wt, r0 + r * 16 + n, g);
+    } else if constexpr (FT == 4) {
         gemm_epilogue<RT, EPI>(p, acc, wave, wt, r0, lane);
     } else {
         // one or two feature tiles: bias, ReLU, store (row tile `wave` of this wavefront)
