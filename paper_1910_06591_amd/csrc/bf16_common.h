@@ -66,6 +66,26 @@ __device__ __forceinline__ floatx4 max4(floatx4 a, floatx4 b)
     return r;
 }
 
+// Maximum of two bf16 pairs with the packed fp16 maximum.  bf16 and fp16 are both sign-magnitude, so of two bit
+// patterns that are finite numbers in both formats (as bf16: |x| < 2^121, far beyond any activation) the larger
+// fp16 is the larger bf16, and the instruction returns that operand bit for bit (half-denormals included: the
+// fp16 denormal mode of these kernels keeps them).  Four times fewer instructions than widening to fp32.
+__device__ __forceinline__ uint32_t bf16x2_max(uint32_t a, uint32_t b)
+{
+    uint32_t d;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+// the padding value of such maxima, as a pair: the most negative pattern that is finite as fp16 (-2.6e36 as bf16)
+constexpr uint32_t BF16X2_LOWEST = 0xFBFFFBFFu;
+__device__ __forceinline__ uint4 bf16x8_max(uint4 a, uint4 b)
+{
+    return uint4{bf16x2_max(a.x, b.x), bf16x2_max(a.y, b.y), bf16x2_max(a.z, b.z), bf16x2_max(a.w, b.w)};
+}
+// the two bf16 of a pair as fp32
+__device__ __forceinline__ float bf16_lo_f32(uint32_t v) { return __builtin_bit_cast(float, v << 16); }
+__device__ __forceinline__ float bf16_hi_f32(uint32_t v) { return __builtin_bit_cast(float, v & 0xffff0000u); }
+
 // 8 fp32 -> 8 bf16 (round to nearest even, the hardware conversion)
 __device__ __forceinline__ bf16x8 to_bf16x8(floatx4 lo, floatx4 hi)
 {

@@ -6,7 +6,8 @@
 // A workgroup takes a PTH x PTW tile of pooled pixels of one image: the input patch under the (2 PTH + 1) x
 // (2 PTW + 1) convolution pixels those windows cover is staged as planar bf16 [CIN/8][rows][pitch][8] (zero
 // outside the image), the convolution runs over it as in the fused residual block (rb_conv), its tile goes to LDS
-// as bf16 [pixel][COUT] (-inf outside the image, so the maximum ignores it) and is pooled from there.
+// as bf16 [pixel][COUT] (outside the image a value below every activation, so the maximum ignores it) and is pooled from
+// there.
 #pragma once
 #include "resnet_blockfused.h"
 
@@ -109,9 +110,9 @@ __global__ __launch_bounds__(RB_THREADS, 4) void conv_pool_kernel(ConvPoolArgs p
                 if (pg + K::NPG * i >= ntiles || q >= npix) continue;
                 const int r = q / CRW, c = q - r * CRW;
                 const int y = cy0 + r, x = cx0 + c;
-                floatx4 v = acc[i][j] + bv;
-                if (y < 0 || y >= p.H || x < 0 || x >= p.W) v = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-                *(bf16x4*)(cmap + (size_t)q * CP::CSTRIDE + f * 2) = to_bf16x4(v);
+                uint2 o = __builtin_bit_cast(uint2, to_bf16x4(acc[i][j] + bv));
+                if (y < 0 || y >= p.H || x < 0 || x >= p.W) o = uint2{BF16X2_LOWEST, BF16X2_LOWEST};
+                *(uint2*)(cmap + (size_t)q * CP::CSTRIDE + f * 2) = o;
             }
         }
     }
@@ -123,20 +124,19 @@ __global__ __launch_bounds__(RB_THREADS, 4) void conv_pool_kernel(ConvPoolArgs p
         const int pp = idx / NCGO, cg = idx - pp * NCGO;
         const int ph = pp / p.PTW, pw = pp - ph * p.PTW;
         if (ph0 + ph >= p.PH || pw0 + pw >= p.PW) continue;
-        floatx4 lo = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, hi = lo;
+        const char* win = cmap + (size_t)(2 * ph * CRW + 2 * pw) * CP::CSTRIDE + cg * 16;
+        uint4 m = *(const uint4*)win;
 #pragma unroll
         for (int dy = 0; dy < 3; ++dy)
 #pragma unroll
-            for (int dx = 0; dx < 3; ++dx) {
-                const bf16x8 v = *(const bf16x8*)(cmap + (size_t)((2 * ph + dy) * CRW + 2 * pw + dx) * CP::CSTRIDE + cg * 16);
-                lo = max4(lo, to_floatx4(__builtin_shufflevector(v, v, 0, 1, 2, 3)));
-                hi = max4(hi, to_floatx4(__builtin_shufflevector(v, v, 4, 5, 6, 7)));
-            }
+            for (int dx = 0; dx < 3; ++dx)
+                if (dy + dx > 0) m = bf16x8_max(m, *(const uint4*)(win + (size_t)(dy * CRW + dx) * CP::CSTRIDE));
         const size_t o = (((size_t)b * p.PH + ph0 + ph) * p.PW + pw0 + pw) * COUT + cg * 8;
-        *(floatx4*)(p.x + o) = lo;
-        *(floatx4*)(p.x + o + 4) = hi;
+        *(floatx4*)(p.x + o) = floatx4{bf16_lo_f32(m.x), bf16_hi_f32(m.x), bf16_lo_f32(m.y), bf16_hi_f32(m.y)};
+        *(floatx4*)(p.x + o + 4) = floatx4{bf16_lo_f32(m.z), bf16_hi_f32(m.z), bf16_lo_f32(m.w), bf16_hi_f32(m.w)};
         if (p.r) {
-            const bf16x4 rl = relu_bf16x4(to_bf16x4(lo)), rh = relu_bf16x4(to_bf16x4(hi));
+            const bf16x8 mv = __builtin_bit_cast(bf16x8, m);
+            const bf16x4 rl = relu_bf16x4(__builtin_shufflevector(mv, mv, 0, 1, 2, 3)), rh = relu_bf16x4(__builtin_shufflevector(mv, mv, 4, 5, 6, 7));
             *(bf16x8*)(p.r + o) = __builtin_shufflevector(rl, rh, 0, 1, 2, 3, 4, 5, 6, 7);
         }
     }

@@ -7,7 +7,7 @@
 // A workgroup takes a PTH x PTW tile of pooled pixels of one image: it stages the frame patch under the
 // (2 PTH + 1) x (2 PTW + 1) convolution pixels those windows cover as bf16 cells of 4 channels (exact integers,
 // zero outside the frame, zero in the padding channels), multiplies, writes the convolution tile to LDS as
-// bf16 [pixel][C0] (-inf outside the frame, so the maximum ignores it) and pools from there.
+// bf16 [pixel][C0] (outside the frame a value below every activation, so the maximum ignores it) and pools from there.
 //
 // K layout, frames of up to 4 planes (CELL = 4; weights packed to match, `first_pool_k`): with 4-channel cells two
 // horizontally adjacent taps are 16 contiguous bytes, so a kernel row is padded to four columns (the fourth with
@@ -170,10 +170,16 @@ __global__ __launch_bounds__(FP_THREADS) void first_pool_kernel(FirstPoolArgs p)
         floatx4 bv[NFT];
 #pragma unroll
         for (int j = 0; j < NFT; ++j) bv[j] = *(const floatx4*)(p.bias + j * 16 + g * 4);
-        for (int tile = wave; tile < ntiles; tile += FP_THREADS / 64) {
-            const int q = min(tile * 16 + n, npix - 1);
-            const int r = q / CRW, c = q - r * CRW;
-            const char* s = patch + (size_t)(r * PP + c) * CELL * 2;
+        // the lane's pixel walks the region FP_THREADS / 4 pixels per round: one division here, none in the loop
+        constexpr int QSTEP = FP_THREADS / 4;
+        const int dr = QSTEP / CRW, dc = QSTEP - dr * CRW;
+        int r = (wave * 16 + n) / CRW, c = wave * 16 + n - r * CRW;
+        for (int tile = wave; tile < ntiles; tile += FP_THREADS / 64, r += dr, c += dc) {
+            if (c >= CRW) { c -= CRW; ++r; }
+            const bool tail = tile * 16 + n >= npix;                   // past the region: the last pixel again, not stored
+            const int q = tail ? npix - 1 : tile * 16 + n;
+            const int rr = tail ? CRH - 1 : r, cc = tail ? CRW - 1 : c;
+            const char* s = patch + (size_t)(rr * PP + cc) * CELL * 2;
             bf16x8 bfrag[KCH];
 #pragma unroll
             for (int kc = 0; kc < KCH; ++kc) {
@@ -184,16 +190,16 @@ __global__ __launch_bounds__(FP_THREADS) void first_pool_kernel(FirstPoolArgs p)
                     bfrag[kc] = *(const bf16x8*)(s + off[kc]);
                 }
             }
-            const int y = cy0 + r, x = cx0 + c;
+            const int y = cy0 + rr, x = cx0 + cc;
             const bool inside = y >= 0 && y < p.H && x >= 0 && x < p.W;
 #pragma unroll
             for (int j = 0; j < NFT; ++j) {
                 floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kc = 0; kc < KCH; ++kc) acc = mfma16(a[j][kc], bfrag[kc], acc);
-                floatx4 v = acc * p.scale + bv[j];
-                if (!inside) v = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-                if (tile * 16 + n < npix) *(bf16x4*)(cmap + (size_t)q * K::CSTRIDE + (j * 16 + g * 4) * 2) = to_bf16x4(v);
+                uint2 o = __builtin_bit_cast(uint2, to_bf16x4(acc * p.scale + bv[j]));
+                if (!inside) o = uint2{BF16X2_LOWEST, BF16X2_LOWEST};
+                if (!tail) *(uint2*)(cmap + (size_t)q * K::CSTRIDE + (j * 16 + g * 4) * 2) = o;
             }
         }
     }
@@ -205,20 +211,19 @@ __global__ __launch_bounds__(FP_THREADS) void first_pool_kernel(FirstPoolArgs p)
         const int pp = idx / NCG, cg = idx - pp * NCG;
         const int ph = pp / p.PTW, pw = pp - ph * p.PTW;
         if (ph0 + ph >= p.PH || pw0 + pw >= p.PW) continue;
-        floatx4 lo = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, hi = lo;
+        const char* win = cmap + (size_t)(2 * ph * CRW + 2 * pw) * K::CSTRIDE + cg * 16;
+        uint4 m = *(const uint4*)win;
 #pragma unroll
         for (int dy = 0; dy < 3; ++dy)
 #pragma unroll
-            for (int dx = 0; dx < 3; ++dx) {
-                const bf16x8 v = *(const bf16x8*)(cmap + (size_t)((2 * ph + dy) * CRW + 2 * pw + dx) * K::CSTRIDE + cg * 16);
-                lo = max4(lo, to_floatx4(__builtin_shufflevector(v, v, 0, 1, 2, 3)));
-                hi = max4(hi, to_floatx4(__builtin_shufflevector(v, v, 4, 5, 6, 7)));
-            }
+            for (int dx = 0; dx < 3; ++dx)
+                if (dy + dx > 0) m = bf16x8_max(m, *(const uint4*)(win + (size_t)(dy * CRW + dx) * K::CSTRIDE));
         const size_t o = (((size_t)b * p.PH + ph0 + ph) * p.PW + pw0 + pw) * C0 + cg * 8;
-        *(floatx4*)(p.x + o) = lo;
-        *(floatx4*)(p.x + o + 4) = hi;
+        *(floatx4*)(p.x + o) = floatx4{bf16_lo_f32(m.x), bf16_hi_f32(m.x), bf16_lo_f32(m.y), bf16_hi_f32(m.y)};
+        *(floatx4*)(p.x + o + 4) = floatx4{bf16_lo_f32(m.z), bf16_hi_f32(m.z), bf16_lo_f32(m.w), bf16_hi_f32(m.w)};
         if (p.r) {
-            const bf16x4 rl = relu_bf16x4(to_bf16x4(lo)), rh = relu_bf16x4(to_bf16x4(hi));
+            const bf16x8 mv = __builtin_bit_cast(bf16x8, m);
+            const bf16x4 rl = relu_bf16x4(__builtin_shufflevector(mv, mv, 0, 1, 2, 3)), rh = relu_bf16x4(__builtin_shufflevector(mv, mv, 4, 5, 6, 7));
             *(bf16x8*)(p.r + o) = __builtin_shufflevector(rl, rh, 0, 1, 2, 3, 4, 5, 6, 7);
         }
     }
