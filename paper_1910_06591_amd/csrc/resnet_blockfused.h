@@ -76,23 +76,17 @@ struct ResBlockCfg {
 // One implicit-GEMM pass, CIN -> COUT channels: region of RW-wide pixels (npix of them) over the planar map `src`
 // (plane cells PL, pitch PITCH; a region pixel (r, c) has its tap (0, 0) at cell r * PITCH + c).  acc[i][j]: pixel
 // tile pg + NPG * i, feature tile ft0 + j.
-template <int CIN, int COUT, int TPW = RB_TPW>
-__device__ __forceinline__ void rb_conv(const char* src, int PL, int PITCH, int RW, int npix, const bf16x8* __restrict__ wp,
-                                        int kchunks, int ft0, int pg, int lane, floatx4 (&acc)[TPW][ResBlockCfg<COUT>::FTW])
+//
+// rb_conv_n is the loop for a wavefront that owns exactly NT pixel tiles: with the count a constant a chunk is one
+// straight run - NT map fragments requested, then NT * FTW MFMAs, each waiting only for its own fragment - where
+// a test per tile ("does this wavefront have an i-th tile?") cuts the chunk into NT blocks of load, wait, multiply,
+// and every fragment's LDS latency is paid in full.
+template <int CIN, int COUT, int TPW, int NT>
+__device__ __forceinline__ void rb_conv_n(const char* src, int PL, int PITCH, const int (&base)[TPW], const bf16x8* __restrict__ wl,
+                                          int kchunks, int g, floatx4 (&acc)[TPW][ResBlockCfg<COUT>::FTW])
 {
     using K = ResBlockCfg<COUT>;
     constexpr int C = CIN;
-    const int g = lane >> 4, n = lane & 15;
-    const int ntiles = (npix + 15) / 16;
-    int base[TPW];
-#pragma unroll
-    for (int i = 0; i < TPW; ++i) {
-        const int q = min((pg + K::NPG * i) * 16 + n, npix - 1);
-        base[i] = (q / RW) * PITCH + q % RW;
-#pragma unroll
-        for (int j = 0; j < K::FTW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
-    const bf16x8* wl = wp + (size_t)ft0 * kchunks * 64 + lane;
     // weight fragments run AHEAD chunks ahead of their use: they come from L2 (the first wavefront to ask) or the
     // vector L1, and one chunk of MFMAs is shorter than either trip
     constexpr int AHEAD = COUT == 16 ? 1 : 3;                  // measured at 16 channels (54 x 72): 150 us with 1, 178 with 3, 186 with all 5
@@ -116,15 +110,45 @@ __device__ __forceinline__ void rb_conv(const char* src, int PL, int PITCH, int 
             const int k0 = kc * 32 + g * 8;
             const int tap = min(k0 / C, 8), cg = (k0 % C) >> 3;
             const char* s = src + ((size_t)cg * PL + (tap / 3) * PITCH + tap % 3) * 16;
+            bf16x8 bfr[NT];
 #pragma unroll
-            for (int i = 0; i < TPW; ++i) {
-                if (pg + K::NPG * i < ntiles) {                 // uniform
-                    const bf16x8 b = *(const bf16x8*)(s + base[i] * 16);
+            for (int i = 0; i < NT; ++i) bfr[i] = *(const bf16x8*)(s + base[i] * 16);
 #pragma unroll
-                    for (int j = 0; j < K::FTW; ++j) acc[i][j] = mfma16(cur[j], b, acc[i][j]);
-                }
-            }
+            for (int i = 0; i < NT; ++i)
+#pragma unroll
+                for (int j = 0; j < K::FTW; ++j) acc[i][j] = mfma16(cur[j], bfr[i], acc[i][j]);
         }
+    }
+}
+
+template <int CIN, int COUT, int TPW = RB_TPW>
+__device__ __forceinline__ void rb_conv(const char* src, int PL, int PITCH, int RW, int npix, const bf16x8* __restrict__ wp,
+                                        int kchunks, int ft0, int pg, int lane, floatx4 (&acc)[TPW][ResBlockCfg<COUT>::FTW])
+{
+    using K = ResBlockCfg<COUT>;
+    const int g = lane >> 4, n = lane & 15;
+    const int ntiles = (npix + 15) / 16;
+    int base[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int q = min((pg + K::NPG * i) * 16 + n, npix - 1);
+        base[i] = (q / RW) * PITCH + q % RW;
+#pragma unroll
+        for (int j = 0; j < K::FTW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    const bf16x8* wl = wp + (size_t)ft0 * kchunks * 64 + lane;
+    const int nt = min(max((ntiles - pg + K::NPG - 1) / K::NPG, 0), TPW);      // this wavefront's tiles (uniform)
+    static_assert(TPW <= 8, "tile counts up to eight");
+    switch (nt) {
+    case 1: rb_conv_n<CIN, COUT, TPW, 1>(src, PL, PITCH, base, wl, kchunks, g, acc); break;
+    case 2: rb_conv_n<CIN, COUT, TPW, 2>(src, PL, PITCH, base, wl, kchunks, g, acc); break;
+    case 3: rb_conv_n<CIN, COUT, TPW, TPW >= 3 ? 3 : TPW>(src, PL, PITCH, base, wl, kchunks, g, acc); break;
+    case 4: rb_conv_n<CIN, COUT, TPW, TPW >= 4 ? 4 : TPW>(src, PL, PITCH, base, wl, kchunks, g, acc); break;
+    case 5: rb_conv_n<CIN, COUT, TPW, TPW >= 5 ? 5 : TPW>(src, PL, PITCH, base, wl, kchunks, g, acc); break;
+    case 6: rb_conv_n<CIN, COUT, TPW, TPW >= 6 ? 6 : TPW>(src, PL, PITCH, base, wl, kchunks, g, acc); break;
+    case 7: rb_conv_n<CIN, COUT, TPW, TPW >= 7 ? 7 : TPW>(src, PL, PITCH, base, wl, kchunks, g, acc); break;
+    case 8: rb_conv_n<CIN, COUT, TPW, TPW >= 8 ? 8 : TPW>(src, PL, PITCH, base, wl, kchunks, g, acc); break;
+    default: break;
     }
 }
 
