@@ -85,6 +85,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, floatx4 (&acc)[
         }
     } else {
         // tile group wt = unit tile; feature tile j = gate j of units wt*16 .. wt*16+15
+        // Two rounds of loads for all row tiles together, then the arithmetic and the stores: written row tile by
+        // row tile, each tile's loads stay behind the previous tile's stores (they may alias as far as the
+        // compiler knows) and the epilogue is a chain of two trips to memory per tile.
         const int Hn = p.Hn, G4 = 4 * p.Hn;
         const int u = wt * 16 + g * 4;                  // this lane's 4 consecutive units
         floatx4 bg[4], wr[4];
@@ -93,24 +96,43 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, floatx4 (&acc)[
             bg[j] = *(const floatx4*)(p.lstm_b + j * Hn + u);
             wr[j] = *(const floatx4*)(p.lstm_w + (size_t)(p.F + p.A) * G4 + j * Hn + u);
         }
+        int act[RT];
+        float rew[RT];
+        bool fresh[RT];
+        floatx4 c0[RT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            const int row = min(r0 + r * 16 + n, p.rows - 1);
+            act[r] = p.prev_action[row];
+            rew[r] = p.prev_reward[row];
+            fresh[r] = p.done && p.done[row];
+            c0[r] = *(const floatx4*)(p.c_in + (size_t)row * Hn + u);
+        }
+        // second round: the previous actions' weight rows (from a clamped index: whether a row counts is decided below)
+        floatx4 wa[RT][4];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            const int aa = min(max(act[r], 0), p.A - 1);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wa[r][j] = *(const floatx4*)(p.lstm_w + (size_t)(p.F + aa) * G4 + j * Hn + u);
+        }
 #pragma unroll
         for (int r = 0; r < RT; ++r) {
             const int row = r0 + r * 16 + n;
             if ((only_r >= 0 && r != only_r) || row >= p.rows) continue;
-            const int a = p.prev_action[row];
-            const float rew = p.prev_reward[row];
+            const int a = act[r];
             floatx4 pre[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                pre[j] = acc[r][j] + bg[j] + rew * wr[j];
-                if (a >= 0 && a < p.A) pre[j] += *(const floatx4*)(p.lstm_w + (size_t)(p.F + a) * G4 + j * Hn + u);
+                pre[j] = acc[r][j] + bg[j] + rew[r] * wr[j];
+                if (a >= 0 && a < p.A) pre[j] += wa[r][j];
             }
-            floatx4 c0 = *(const floatx4*)(p.c_in + (size_t)row * Hn + u);
-            if (p.done && p.done[row]) c0 = floatx4{0.f, 0.f, 0.f, 0.f};
+            floatx4 cp = c0[r];
+            if (fresh[r]) cp = floatx4{0.f, 0.f, 0.f, 0.f};
             floatx4 cn, hn;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                cn[i] = sigmoidf_(pre[1][i]) * c0[i] + sigmoidf_(pre[0][i]) * tanhf_(pre[2][i]);
+                cn[i] = sigmoidf_(pre[1][i]) * cp[i] + sigmoidf_(pre[0][i]) * tanhf_(pre[2][i]);
                 hn[i] = sigmoidf_(pre[3][i]) * tanhf_(cn[i]);
             }
             *(floatx4*)(p.c_out + (size_t)row * Hn + u) = cn;
@@ -328,17 +350,20 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
     for (int j = 0; j < FT; ++j) wl[j] = p.wp + ((size_t)min(ft0 + j, p.n_ftiles - 1) * kct) * 64 + lane;
 
     // the wavefront that will finish row tile `wave` requests that tile's epilogue operands now
+    // (tiles of up to two row tiles: with four the kernel has no registers to spare and the operands are fetched
+    // by the epilogue itself)
+    constexpr bool LSTM_AHEAD = EPI == EPI_LSTM && RT <= 2;
     LstmOperands lo;
-    const bool finisher = EPI == EPI_LSTM && wave < RT;                      // uniform
+    const bool finisher = LSTM_AHEAD && wave < RT;                           // uniform
     const int lrow = min(r0 + wave * 16 + n, p.rows - 1);
-    if constexpr (EPI == EPI_LSTM)
+    if constexpr (LSTM_AHEAD)
         if (finisher) lstm_prefetch(p, lo, wt, lrow, g);
     bool fresh[RT];
 #pragma unroll
     for (int r = 0; r < RT; ++r) fresh[r] = EPI == EPI_LSTM && p.done && p.done[rowi[r]];
     gemm_k_loop<RT, 3, 2, false, FT>(acc, wl, p.x1, p.ld1, rowi, k0, min(k1, p.kc1), 0, 0, g, fresh);
     gemm_k_loop<RT, 3, 1, true, FT>(acc, wl, p.x2, p.ld2, rowi, max(k0, p.kc1), k1, p.kc1, p.k2, g, fresh);
-    if constexpr (EPI == EPI_LSTM)
+    if constexpr (LSTM_AHEAD)
         if (finisher) lstm_prefetch_action(p, lo, wt, g);                 // in flight across the reduction below
 
     // K reduction through LDS.  With 8 wavefronts the upper four first hand everything to the lower four.
@@ -377,7 +402,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_splitk_kernel(GemmArgs p)
             for (int j = 0; j < FT; ++j) acc[r][j] += part[((w2 * RT + r) * 4 + j) * 64 + lane];
         }
     }
-    if constexpr (EPI == EPI_LSTM) {
+    if constexpr (LSTM_AHEAD) {
 #pragma unroll
         for (int r = 0; r < RT; ++r)
             if (r == wave && r0 + r * 16 + n < p.rows) lstm_epilogue_row(p, acc[r], lo, wt, r0 + r * 16 + n, g);
