@@ -228,9 +228,21 @@ template <typename TIn>
 static void launch_conv_f32(hipStream_t s, const TIn* x, const float* w, const ConvLayer& c, const float* resid,
                             float* y, int B, int relu_in, int relu_out)
 {
-    size_t total = (size_t)B * c.OH * c.OW * c.Cout;
-    hipLaunchKernelGGL(conv2d_f32_kernel<TIn>, dim3(blocks_for(total)), dim3(256), 0, s, x, w + c.w_off, w + c.b_off,
-                       resid, y, B, c.H, c.W, c.Cin, c.OH, c.OW, c.Cout, c.k, c.stride, c.pad, relu_in, relu_out);
+    // four output channels per lane where the layer and the buffers allow 16-byte weight and activation accesses
+    auto aligned = [](const void* q, size_t a) { return ((uintptr_t)q & (a - 1)) == 0; };
+    const size_t per_img = (size_t)c.OH * c.OW * (c.Cout / 4), in_img = (size_t)c.H * c.W * c.Cin;
+    const bool v4 = c.Cout % 4 == 0 && c.Cin % 4 == 0 && per_img < ((size_t)1 << 31) && in_img < ((size_t)1 << 31) &&
+                    (size_t)c.k * c.k * c.Cin < ((size_t)1 << 24) && aligned(w + c.w_off, 16) && aligned(w + c.b_off, 16) &&
+                    aligned(x, sizeof(TIn) * 4) && aligned(y, 16) && (!resid || aligned(resid, 16));
+    if (v4) {
+        hipLaunchKernelGGL((conv2d_f32_v4_kernel<TIn>), dim3((unsigned)((per_img + 63) / 64), (unsigned)(B < 65535 ? B : 65535)), dim3(256), 0,
+                           s, x, w + c.w_off, w + c.b_off, resid, y, B, c.H, c.W, c.Cin, c.OH, c.OW, c.Cout, c.k, c.stride, c.pad, relu_in,
+                           relu_out);
+    } else {
+        size_t total = (size_t)B * c.OH * c.OW * c.Cout * CONV_F32_KS;
+        hipLaunchKernelGGL((conv2d_f32_kernel<TIn>), dim3(blocks_for(total)), dim3(256), 0, s, x, w + c.w_off, w + c.b_off,
+                           resid, y, B, c.H, c.W, c.Cin, c.OH, c.OW, c.Cout, c.k, c.stride, c.pad, relu_in, relu_out);
+    }
 }
 
 // fp32 torso + linear layer.  Leaves the rectified linear output in h->d_fc.
@@ -268,7 +280,7 @@ static void torso_fc_f32(seed_infer* h, hipStream_t s, int B, const uint8_t* obs
     }
     h->feat_f32 = cur;
     const seed_arch_t& a = p.arch;
-    hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (a.fc_units + 63) / 64), dim3(DENSE_F32_WAVES * 64), 0, s, cur, w + p.fc_w, w + p.fc_b,
+    hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (a.fc_units + DENSE_F32_COLS - 1) / DENSE_F32_COLS), dim3(DENSE_F32_WAVES * 64), 0, s, cur, w + p.fc_w, w + p.fc_b,
                        h->d_fc, (int)p.flat, a.fc_units, (int)p.flat, a.fc_units, 1);
 }
 
@@ -361,9 +373,9 @@ static seed_status_t run_core_heads(seed_infer* h, hipStream_t s, int row0, int 
         }
         if (a.head == SEED_HEAD_DUELING_Q && (phases & PHASE_HEADS)) {
             int hid = a.head_hidden;
-            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(DENSE_F32_WAVES * 64), 0, s, core, w + p.v1_w, w + p.v1_b,
+            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + DENSE_F32_COLS - 1) / DENSE_F32_COLS), dim3(DENSE_F32_WAVES * 64), 0, s, core, w + p.v1_w, w + p.v1_b,
                                h->d_hid, p.core, hid, ld_core, 2 * hid, 1);
-            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + 63) / 64), dim3(DENSE_F32_WAVES * 64), 0, s, core, w + p.a1_w, w + p.a1_b,
+            hipLaunchKernelGGL(dense_f32_kernel, dim3(B, (hid + DENSE_F32_COLS - 1) / DENSE_F32_COLS), dim3(DENSE_F32_WAVES * 64), 0, s, core, w + p.a1_w, w + p.a1_b,
                                h->d_hid + hid, p.core, hid, ld_core, 2 * hid, 1);
         }
     } else {
