@@ -104,10 +104,10 @@ __global__ __launch_bounds__(256) void conv2d_f32_kernel(
 // The same for layers whose channel counts are multiples of four (and whose operands are aligned for it).  A lane
 // takes FOUR consecutive output channels of a pixel, so a term's weights are one 16-byte load and its input value
 // serves four sums, and the input's channels come four at a time (one dword of a uint8 frame, 16 bytes of an fp32
-// map).  The k * k taps are split over the block's four WAVEFRONTS, not over lanes: a wavefront's taps are then
+// map).  The k * k taps are split over the block's eight WAVEFRONTS, not over lanes: a wavefront's taps are then
 // uniform, their index arithmetic runs on the scalar unit, and a lane's instruction stream - whose length is this
 // kernel's time at small batch, where a SIMD holds a single wavefront - shrinks to a few adds, the loads and the
-// multiply-adds per term.  A block is 64 (pixel, channel group) items of one image; the four partial sums meet in
+// multiply-adds per term.  A block is 64 (pixel, channel group) items of one image; the eight partial sums meet in
 // LDS in a fixed order.  Which of the two kernels runs depends on the layer and the buffers' alignment only.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ f32x4 load_raw4(const uint8_t* p, int i)
@@ -119,13 +119,14 @@ __device__ __forceinline__ f32x4 load_raw4(const float* p, int i) { return *(con
 
 // requires Cin % 4 == 0, Cout % 4 == 0, OH * OW * Cout / 4 and H * W * Cin below 2^31, 16-byte aligned w, bias, y, resid
 // and fp32 x (4-byte aligned uint8 x).  Grid: (ceil(OH * OW * Cout / 4 / 64), min(B, 65535)).
+constexpr int CONV_F32_V4_WAVES = 8;
 template <typename TIn>
-__global__ __launch_bounds__(256) void conv2d_f32_v4_kernel(
+__global__ __launch_bounds__(CONV_F32_V4_WAVES * 64) void conv2d_f32_v4_kernel(
     const TIn* __restrict__ x, const float* __restrict__ w, const float* __restrict__ bias,
     const float* resid, float* y, int B, int H, int W, int Cin, int OH, int OW, int Cout, int k,
     int stride, int pad, int relu_in, int relu_out)
 {
-    constexpr int KS = CONV_F32_KS;
+    constexpr int KS = CONV_F32_V4_WAVES;
     __shared__ f32x4 red[KS - 1][64];
     const int lane = threadIdx.x & 63;
     const int sl = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

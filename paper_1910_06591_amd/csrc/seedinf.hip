@@ -235,7 +235,7 @@ static void launch_conv_f32(hipStream_t s, const TIn* x, const float* w, const C
                     (size_t)c.k * c.k * c.Cin < ((size_t)1 << 24) && aligned(w + c.w_off, 16) && aligned(w + c.b_off, 16) &&
                     aligned(x, sizeof(TIn) * 4) && aligned(y, 16) && (!resid || aligned(resid, 16));
     if (v4) {
-        hipLaunchKernelGGL((conv2d_f32_v4_kernel<TIn>), dim3((unsigned)((per_img + 63) / 64), (unsigned)(B < 65535 ? B : 65535)), dim3(256), 0,
+        hipLaunchKernelGGL((conv2d_f32_v4_kernel<TIn>), dim3((unsigned)((per_img + 63) / 64), (unsigned)(B < 65535 ? B : 65535)), dim3(CONV_F32_V4_WAVES * 64), 0,
                            s, x, w + c.w_off, w + c.b_off, resid, y, B, c.H, c.W, c.Cin, c.OH, c.OW, c.Cout, c.k, c.stride, c.pad, relu_in,
                            relu_out);
     } else {
