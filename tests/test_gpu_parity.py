@@ -65,6 +65,25 @@ def test_fp32_odd_shapes(orc):
     run_case(orc, cfg2, 2, "fp32")
 
 
+@pytest.mark.parametrize("case", ["stack_mult4", "stack_k5", "resnet_mult4", "stack_generic_lanes"])
+def test_fp32_convolution_kernels(orc, case):
+    """Both fp32 convolution kernels against the oracle: the one with four output channels per lane and the taps
+    over the block's wavefronts (channel counts in multiples of four; tap counts 9, 16 and 25, which do and do not
+    divide by eight; SAME padding and the residual add in the ResNet), and the generic one with the taps over
+    adjacent lanes (other channel counts)."""
+    base = dict(fc_units=24, lstm_units=0, num_actions=5, head=0, head_hidden=0, select=1, precision="fp32",
+                obs_kind="uniform")
+    cfgs = {
+        "stack_mult4": dict(base, label="fp32 stack x4", obs_h=29, obs_w=31, obs_c=4, torso=0, convs=[(8, 4, 2), (12, 3, 1)], index=71),
+        "stack_k5": dict(base, label="fp32 stack k5", obs_h=21, obs_w=23, obs_c=8, torso=0,
+                                                 convs=[(4, 5, 2), (20, 3, 2)], index=72),
+        "resnet_mult4": dict(base, label="fp32 resnet x4", obs_h=21, obs_w=27, obs_c=4, torso=1, sections=[8, 12], index=73),
+        "stack_generic_lanes": dict(base, label="fp32 stack generic", obs_h=20, obs_w=17, obs_c=3, torso=0,
+                                    convs=[(6, 4, 2), (7, 3, 1)], index=74),
+    }
+    run_case(orc, cfgs[case], 5, "fp32")
+
+
 def test_fp32_b1_and_max_batch_larger_than_b(orc):
     cfg = wl.CONFIGS["C1"]
     run_case(orc, cfg, 1, "fp32", max_batch=16)
@@ -473,7 +492,7 @@ def test_create_destroy_returns_device_memory():
     assert free0 - free1 < 32 * 1024 * 1024, (free0, free1)
 
 
-@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+@pytest.mark.parametrize("precision", ["fp32", "fp32_channels_x4", "bf16"])
 def test_largest_batch_the_interface_allows(orc, precision):
     """B = max_batch = 2^20 rows, the limit of the interface, on small networks: 8.6e9 activation values per
     layer in fp32 mode (more than 2^32 elements: the elementwise kernels' capped grids) and an 11 GB feature
@@ -483,6 +502,11 @@ def test_largest_batch_the_interface_allows(orc, precision):
         cfg = dict(label="largest batch, fp32", obs_h=18, obs_w=18, obs_c=1, torso=0, convs=[(32, 3, 1)], fc_units=16,
                    lstm_units=8, num_actions=4, head=0, head_hidden=0, select=1, precision="fp32", obs_kind="uniform",
                    index=120)
+    elif precision == "fp32_channels_x4":
+        # the convolution kernel with four output channels per lane walks the images beyond the grid's 65535 rows
+        cfg = dict(label="largest batch, fp32, channels x4", obs_h=10, obs_w=10, obs_c=4, torso=0, convs=[(8, 3, 1)], fc_units=16,
+                   lstm_units=0, num_actions=4, head=0, head_hidden=0, select=1, precision="fp32", obs_kind="uniform",
+                   index=122)
     else:
         cfg = dict(label="largest batch, bf16", obs_h=12, obs_w=16, obs_c=8, torso=0, convs=[(32, 2, 1)], fc_units=32,
                    lstm_units=16, num_actions=5, head=1, head_hidden=16, select=0, precision="bf16", obs_kind="uniform",
