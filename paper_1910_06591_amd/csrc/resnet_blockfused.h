@@ -73,6 +73,25 @@ struct ResBlockCfg {
     }
 };
 
+// Region coordinates (row, column) of the lane's pixel in the pixel tiles first, first + stride, ... of a
+// region RW pixels wide (a tile is 16 consecutive pixels of the row-major region, the lane's is pixel n of it): one
+// division for the first tile, then steps whose sizes are uniform.  A division per tile and feature tile was half
+// of the vector instructions of these kernels' epilogues, and those - not the MFMAs - fill most of their time.
+template <int NTILE>
+__device__ __forceinline__ void tile_coords(int first, int stride, int n, int RW, int (&r)[NTILE], int (&c)[NTILE])
+{
+    const int q0 = first * 16 + n;
+    r[0] = q0 / RW;
+    c[0] = q0 - r[0] * RW;
+    const int step = stride * 16, dr = step / RW, dc = step - dr * RW;
+#pragma unroll
+    for (int i = 1; i < NTILE; ++i) {
+        const bool wrap = c[i - 1] + dc >= RW;
+        c[i] = c[i - 1] + dc - (wrap ? RW : 0);
+        r[i] = r[i - 1] + dr + (wrap ? 1 : 0);
+    }
+}
+
 // One implicit-GEMM pass, CIN -> COUT channels: region of RW-wide pixels (npix of them) over the planar map `src`
 // (plane cells PL, pitch PITCH; a region pixel (r, c) has its tap (0, 0) at cell r * PITCH + c).  acc[i][j]: pixel
 // tile pg + NPG * i, feature tile ft0 + j.
@@ -128,11 +147,12 @@ __device__ __forceinline__ void rb_conv(const char* src, int PL, int PITCH, int 
     using K = ResBlockCfg<COUT>;
     const int g = lane >> 4, n = lane & 15;
     const int ntiles = (npix + 15) / 16;
-    int base[TPW];
+    int base[TPW], pr[TPW], pc[TPW];
+    tile_coords<TPW>(pg, K::NPG, n, RW, pr, pc);
+    const int last = ((npix - 1) / RW) * PITCH + (npix - 1) % RW;          // uniform: pixels past the region read its last one
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
-        const int q = min((pg + K::NPG * i) * 16 + n, npix - 1);
-        base[i] = (q / RW) * PITCH + q % RW;
+        base[i] = (pg + K::NPG * i) * 16 + n < npix ? pr[i] * PITCH + pc[i] : last;
 #pragma unroll
         for (int j = 0; j < K::FTW; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
@@ -215,21 +235,25 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
         // columns elsewhere (128 channels: 305 -> 320; 16 channels: 149 -> 160), so the host decides.
         const int UW = p.flat ? RP : p.TW + 2, npix = (p.TH + 2) * UW;
         rb_conv<C, C>(Rm, RPL, RP, UW, npix, p.wpa, p.kchunks, ft0, pg, lane, acc);
-        const int ntiles = (npix + 15) / 16;
+        int er[RB_TPW], ec[RB_TPW];
+        tile_coords<RB_TPW>(pg, K::NPG, n, UW, er, ec);
+        floatx4 bva[K::FTW];
 #pragma unroll
-        for (int j = 0; j < K::FTW; ++j) {
-            const int f = (ft0 + j) * 16 + g * 4;
-            const floatx4 bv = *(const floatx4*)(p.bias_a + f);
+        for (int j = 0; j < K::FTW; ++j) bva[j] = *(const floatx4*)(p.bias_a + (ft0 + j) * 16 + g * 4);
 #pragma unroll
-            for (int i = 0; i < RB_TPW; ++i) {
-                const int q = (pg + K::NPG * i) * 16 + n;
-                if (pg + K::NPG * i >= ntiles || q >= npix) continue;
-                const int r = q / UW, c = q - r * UW;
-                if (c >= p.TW + 2) continue;
-                const int gy = y0 - 1 + r, gx = x0 - 1 + c;
+        for (int i = 0; i < RB_TPW; ++i) {
+            const int q = (pg + K::NPG * i) * 16 + n;
+            const int r = er[i], c = ec[i];
+            if (q >= npix || c >= p.TW + 2) continue;
+            const int gy = y0 - 1 + r, gx = x0 - 1 + c;
+            const bool inside = gy >= 0 && gy < p.H && gx >= 0 && gx < p.W;
+            char* cell = Um + (r * UP + c) * 16 + (g & 1) * 8;
+#pragma unroll
+            for (int j = 0; j < K::FTW; ++j) {
+                const int f = (ft0 + j) * 16 + g * 4;
                 bf16x4 o = {};
-                if (gy >= 0 && gy < p.H && gx >= 0 && gx < p.W) o = relu_bf16x4(to_bf16x4(acc[i][j] + bv));
-                *(bf16x4*)(Um + ((size_t)(f >> 3) * UPL + r * UP + c) * 16 + (g & 1) * 8) = o;
+                if (inside) o = relu_bf16x4(to_bf16x4(acc[i][j] + bva[j]));
+                *(bf16x4*)(cell + (f >> 3) * UPL * 16) = o;
             }
         }
     }
@@ -239,28 +263,29 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
     {
         const int BW = p.flat ? UP : p.TW, npix = p.TH * BW;
         rb_conv<C, C>(Um, UPL, UP, BW, npix, p.wpb, p.kchunks, ft0, pg, lane, acc);
-        const int ntiles = (npix + 15) / 16;
         const int hw = p.H * p.W;
+        int er[RB_TPW], ec[RB_TPW];
+        tile_coords<RB_TPW>(pg, K::NPG, n, BW, er, ec);
+        floatx4 bvb[K::FTW];
 #pragma unroll
-        for (int j = 0; j < K::FTW; ++j) {
-            const int f = (ft0 + j) * 16 + g * 4;
-            const floatx4 bv = *(const floatx4*)(p.bias_b + f);
+        for (int j = 0; j < K::FTW; ++j) bvb[j] = *(const floatx4*)(p.bias_b + (ft0 + j) * 16 + g * 4);
 #pragma unroll
-            for (int i = 0; i < RB_TPW; ++i) {
-                const int q = (pg + K::NPG * i) * 16 + n;
-                if (pg + K::NPG * i >= ntiles || q >= npix) continue;
-                const int r = q / BW, c = q - r * BW;
-                const int gy = y0 + r, gx = x0 + c;
-                if (c >= p.TW || gy >= p.H || gx >= p.W) continue;
-                const int pl = gy * p.W + gx;
-                const size_t pix = (size_t)b * hw + pl;
-                floatx4 v = acc[i][j] + bv;
+        for (int i = 0; i < RB_TPW; ++i) {
+            const int q = (pg + K::NPG * i) * 16 + n;
+            const int gy = y0 + er[i], gx = x0 + ec[i];
+            if (q >= npix || ec[i] >= p.TW || gy >= p.H || gx >= p.W) continue;
+            const int pl = gy * p.W + gx;
+            const size_t pix = (size_t)b * hw + pl;
+            const size_t ybase = p.ldy > 0 ? (size_t)b * p.ldy + (size_t)pl * C : pix * C;
+#pragma unroll
+            for (int j = 0; j < K::FTW; ++j) {
+                const int f = (ft0 + j) * 16 + g * 4;
+                floatx4 v = acc[i][j] + bvb[j];
                 v += *(const floatx4*)(p.x_in + pix * C + f);
                 if (p.x_out) *(floatx4*)(p.x_out + pix * C + f) = v;
                 if (p.y) {
                     const bf16x4 o = to_bf16x4(v);
-                    const size_t at = p.ldy > 0 ? (size_t)b * p.ldy + (size_t)pl * C + f : pix * C + f;
-                    *(bf16x4*)(p.y + at) = p.y_relu ? relu_bf16x4(o) : o;
+                    *(bf16x4*)(p.y + ybase + f) = p.y_relu ? relu_bf16x4(o) : o;
                 }
             }
         }

@@ -98,21 +98,25 @@ __global__ __launch_bounds__(RB_THREADS, 4) void conv_pool_kernel(ConvPoolArgs p
         const int fg = wave % K::NFG, pg = wave / K::NFG;
         const int ft0 = fg * K::FTW;
         floatx4 acc[RB_TPW][K::FTW];
-        const int npix = CRH * CRW, ntiles = (npix + 15) / 16;
+        const int npix = CRH * CRW;
         rb_conv<CIN, COUT>(patch, PL, PP, CRW, npix, p.wp, p.kchunks, ft0, pg, lane, acc);
+        int er[RB_TPW], ec[RB_TPW];
+        tile_coords<RB_TPW>(pg, K::NPG, n, CRW, er, ec);
+        floatx4 bvs[K::FTW];
 #pragma unroll
-        for (int j = 0; j < K::FTW; ++j) {
-            const int f = (ft0 + j) * 16 + g * 4;
-            const floatx4 bv = *(const floatx4*)(p.bias + f);
+        for (int j = 0; j < K::FTW; ++j) bvs[j] = *(const floatx4*)(p.bias + (ft0 + j) * 16 + g * 4);
 #pragma unroll
-            for (int i = 0; i < RB_TPW; ++i) {
-                const int q = (pg + K::NPG * i) * 16 + n;
-                if (pg + K::NPG * i >= ntiles || q >= npix) continue;
-                const int r = q / CRW, c = q - r * CRW;
-                const int y = cy0 + r, x = cx0 + c;
-                uint2 o = __builtin_bit_cast(uint2, to_bf16x4(acc[i][j] + bv));
-                if (y < 0 || y >= p.H || x < 0 || x >= p.W) o = uint2{BF16X2_LOWEST, BF16X2_LOWEST};
-                *(uint2*)(cmap + (size_t)q * CP::CSTRIDE + f * 2) = o;
+        for (int i = 0; i < RB_TPW; ++i) {
+            const int q = (pg + K::NPG * i) * 16 + n;
+            if (q >= npix) continue;
+            const int y = cy0 + er[i], x = cx0 + ec[i];
+            const bool outside = y < 0 || y >= p.H || x < 0 || x >= p.W;
+            char* cell = cmap + q * CP::CSTRIDE + g * 8;
+#pragma unroll
+            for (int j = 0; j < K::FTW; ++j) {
+                uint2 o = __builtin_bit_cast(uint2, to_bf16x4(acc[i][j] + bvs[j]));
+                if (outside) o = uint2{BF16X2_LOWEST, BF16X2_LOWEST};
+                *(uint2*)(cell + (ft0 + j) * 32) = o;
             }
         }
     }

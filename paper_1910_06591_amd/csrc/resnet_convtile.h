@@ -108,29 +108,31 @@ __global__ __launch_bounds__(RB_THREADS, 4) void conv_tile_kernel(ConvTileArgs p
     const int fg = wave % K::NFG, pg = wave / K::NFG;
     const int ft0 = fg * K::FTW;
     floatx4 acc[CT_TPW][K::FTW];
-    const int npix = p.TH * p.TW, ntiles = (npix + 15) / 16;
+    const int npix = p.TH * p.TW;
     rb_conv<C, C, CT_TPW>(ct_lds, PL, PP, p.TW, npix, p.wp, p.kchunks, ft0, pg, lane, acc);
     const int hw = p.H * p.W;
+    int er[CT_TPW], ec[CT_TPW];
+    tile_coords<CT_TPW>(pg, K::NPG, n, p.TW, er, ec);
+    floatx4 bvs[K::FTW];
 #pragma unroll
-    for (int j = 0; j < K::FTW; ++j) {
-        const int f = (ft0 + j) * 16 + g * 4;
-        const floatx4 bv = *(const floatx4*)(p.bias + f);
+    for (int j = 0; j < K::FTW; ++j) bvs[j] = *(const floatx4*)(p.bias + (ft0 + j) * 16 + g * 4);
 #pragma unroll
-        for (int i = 0; i < CT_TPW; ++i) {
-            const int q = (pg + K::NPG * i) * 16 + n;
-            if (pg + K::NPG * i >= ntiles || q >= npix) continue;
-            const int r = q / p.TW, c = q - r * p.TW;
-            const int gy = y0 + r, gx = x0 + c;
-            if (gy >= p.H || gx >= p.W) continue;
-            const int pl = gy * p.W + gx;
-            const size_t pix = (size_t)b * hw + pl;
-            floatx4 v = acc[i][j] + bv;
+    for (int i = 0; i < CT_TPW; ++i) {
+        const int q = (pg + K::NPG * i) * 16 + n;
+        const int gy = y0 + er[i], gx = x0 + ec[i];
+        if (q >= npix || gy >= p.H || gx >= p.W) continue;
+        const int pl = gy * p.W + gx;
+        const size_t pix = (size_t)b * hw + pl;
+        const size_t ybase = p.ldy > 0 ? (size_t)b * p.ldy + (size_t)pl * C : pix * C;
+#pragma unroll
+        for (int j = 0; j < K::FTW; ++j) {
+            const int f = (ft0 + j) * 16 + g * 4;
+            floatx4 v = acc[i][j] + bvs[j];
             if (p.resid) v += *(const floatx4*)(p.resid + pix * C + f);
             if (p.x_out) *(floatx4*)(p.x_out + pix * C + f) = v;
             if (p.y) {
                 const bf16x4 o = to_bf16x4(v);
-                const size_t at = p.ldy > 0 ? (size_t)b * p.ldy + (size_t)pl * C + f : pix * C + f;
-                *(bf16x4*)(p.y + at) = p.y_relu ? relu_bf16x4(o) : o;
+                *(bf16x4*)(p.y + ybase + f) = p.y_relu ? relu_bf16x4(o) : o;
             }
         }
     }
