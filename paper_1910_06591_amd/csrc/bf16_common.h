@@ -66,6 +66,23 @@ __device__ __forceinline__ floatx4 max4(floatx4 a, floatx4 b)
     return r;
 }
 
+// (row, column) of an index that advances by a fixed step through a row-major region `rw` wide: one division at the
+// start, then adds (the step's row and column parts are uniform).  The staging and pooling loops of the
+// layer-by-layer kernels walk their regions with it: a division per item was a large part of their instructions.
+struct RowWalk {
+    int r, c, dr, dc, rw;
+    __device__ __forceinline__ RowWalk(int first, int step, int width) : rw(width)
+    {
+        r = first / width; c = first - r * width;
+        dr = step / width; dc = step - dr * width;
+    }
+    __device__ __forceinline__ void next()
+    {
+        c += dc; r += dr;
+        if (c >= rw) { c -= rw; ++r; }
+    }
+};
+
 // Maximum of two bf16 pairs with the packed fp16 maximum.  bf16 and fp16 are both sign-magnitude, so of two bit
 // patterns that are finite numbers in both formats (as bf16: |x| < 2^121, far beyond any activation) the larger
 // fp16 is the larger bf16, and the instruction returns that operand bit for bit (half-denormals included: the

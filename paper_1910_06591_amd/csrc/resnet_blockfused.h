@@ -194,16 +194,20 @@ __global__ __launch_bounds__(RB_THREADS, 4) void resblock_fused_kernel(ResBlockA
     // each wait out a trip to memory and the staging, not the bandwidth, sets the kernel's time
     const int rcells = (p.TH + 4) * RP;
     constexpr int UNR = 4;
-    for (int idx0 = tid; idx0 < rcells * K::NCG; idx0 += UNR * RB_THREADS) {
+    static_assert(RB_THREADS % K::NCG == 0, "a thread keeps its channel group");
+    constexpr int CSTEP = RB_THREADS / K::NCG;
+    const int cg = tid % K::NCG;                                           // a pixel's channel groups are adjacent in memory
+    RowWalk rw(tid / K::NCG, CSTEP, RP);
+    for (int cell0 = tid / K::NCG; cell0 < rcells; cell0 += UNR * CSTEP) {
         floatx4 lo[UNR], hi[UNR];
         int at[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int idx = idx0 + u * RB_THREADS;
-            const int cell = idx / K::NCG, cg = idx - cell * K::NCG;       // a pixel's channel groups are adjacent in memory
-            const int r = cell / RP, c = cell - r * RP;
+            const int cell = cell0 + u * CSTEP;
+            const int r = rw.r, c = rw.c;
+            rw.next();
             const int gy = y0 - 2 + r, gx = x0 - 2 + c;
-            at[u] = idx < rcells * K::NCG ? (cg * RPL + cell) * 16 : -1;
+            at[u] = cell < rcells ? (cg * RPL + cell) * 16 : -1;
             lo[u] = hi[u] = floatx4{0.f, 0.f, 0.f, 0.f};
             if (at[u] >= 0 && gy >= 0 && gy < p.H && gx >= 0 && gx < p.W) {
                 const float* s = ximg + ((size_t)gy * p.W + gx) * C + cg * 8;

@@ -73,17 +73,22 @@ __global__ __launch_bounds__(RB_THREADS, 4) void conv_pool_kernel(ConvPoolArgs p
     // ---- input patch: cell (r, c) = image pixel (cy0 - 1 + r, cx0 - 1 + c), loads in batches of four ----
     const __bf16* img = p.in + (size_t)b * p.H * p.W * CIN;
     constexpr int UNR = 4;
-    const int items = PRH * PP * CP::NCG;
-    for (int idx0 = tid; idx0 < items; idx0 += UNR * RB_THREADS) {
+    const int cells = PRH * PP;
+    static_assert(RB_THREADS % CP::NCG == 0, "a thread keeps its channel group");
+    constexpr int CSTEP = RB_THREADS / CP::NCG;
+    const int cgi = tid % CP::NCG;                                         // a pixel's channel groups are adjacent in memory
+    RowWalk rw(tid / CP::NCG, CSTEP, PP);
+    for (int cell0 = tid / CP::NCG; cell0 < cells; cell0 += UNR * CSTEP) {
         bf16x8 v[UNR];
         int at[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int idx = idx0 + u * RB_THREADS;
-            const int cell = idx / CP::NCG, cg = idx - cell * CP::NCG;     // a pixel's channel groups are adjacent in memory
-            const int r = cell / PP, c = cell - r * PP;
+            const int cell = cell0 + u * CSTEP;
+            const int cg = cgi;
+            const int r = rw.r, c = rw.c;
+            rw.next();
             const int y = cy0 - 1 + r, x = cx0 - 1 + c;
-            at[u] = idx < items ? (cg * PL + cell) * 16 : -1;
+            at[u] = cell < cells ? (cg * PL + cell) * 16 : -1;
             v[u] = bf16x8{};
             if (at[u] >= 0 && y >= 0 && y < p.H && x >= 0 && x < p.W) v[u] = *(const bf16x8*)(img + ((size_t)y * p.W + x) * CIN + cg * 8);
         }
@@ -124,9 +129,12 @@ __global__ __launch_bounds__(RB_THREADS, 4) void conv_pool_kernel(ConvPoolArgs p
 
     // ---- 3x3 / 2 maximum: pooled pixel (ph, pw) covers region rows 2 ph .. 2 ph + 2, columns 2 pw .. 2 pw + 2 ----
     constexpr int NCGO = COUT / 8;
-    for (int idx = tid; idx < p.PTH * p.PTW * NCGO; idx += RB_THREADS) {
-        const int pp = idx / NCGO, cg = idx - pp * NCGO;
-        const int ph = pp / p.PTW, pw = pp - ph * p.PTW;
+    static_assert(RB_THREADS % NCGO == 0, "a thread keeps its channel group");
+    const int cg = tid % NCGO;
+    RowWalk pwk(tid / NCGO, RB_THREADS / NCGO, p.PTW);
+    for (int pp = tid / NCGO; pp < p.PTH * p.PTW; pp += RB_THREADS / NCGO) {
+        const int ph = pwk.r, pw = pwk.c;
+        pwk.next();
         if (ph0 + ph >= p.PH || pw0 + pw >= p.PW) continue;
         const char* win = cmap + (size_t)(2 * ph * CRW + 2 * pw) * CP::CSTRIDE + cg * 16;
         uint4 m = *(const uint4*)win;

@@ -66,18 +66,22 @@ __global__ __launch_bounds__(RB_THREADS, 4) void conv_tile_kernel(ConvTileArgs p
 
     // ---- input patch: cell (r, c) = image pixel (y0 - 1 + r, x0 - 1 + c), zeros outside the image; loads in batches ----
     constexpr int UNR = 4;
-    const int items = (p.TH + 2) * PP * CT::NCG;
-    for (int idx0 = tid; idx0 < items; idx0 += UNR * RB_THREADS) {
+    const int cells = (p.TH + 2) * PP;
+    static_assert(RB_THREADS % CT::NCG == 0, "a thread keeps its channel group");
+    constexpr int CSTEP = RB_THREADS / CT::NCG;
+    const int cg = tid % CT::NCG;                                          // a pixel's channel groups are adjacent in memory
+    RowWalk rw(tid / CT::NCG, CSTEP, PP);
+    for (int cell0 = tid / CT::NCG; cell0 < cells; cell0 += UNR * CSTEP) {
         floatx4 lo[UNR], hi[UNR];
         bf16x8 v[UNR];
         int at[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int idx = idx0 + u * RB_THREADS;
-            const int cell = idx / CT::NCG, cg = idx - cell * CT::NCG;     // a pixel's channel groups are adjacent in memory
-            const int r = cell / PP, c = cell - r * PP;
+            const int cell = cell0 + u * CSTEP;
+            const int r = rw.r, c = rw.c;
+            rw.next();
             const int gy = y0 - 1 + r, gx = x0 - 1 + c;
-            at[u] = idx < items ? (cg * PL + cell) * 16 : -1;
+            at[u] = cell < cells ? (cg * PL + cell) * 16 : -1;
             const bool inside = at[u] >= 0 && gy >= 0 && gy < p.H && gx >= 0 && gx < p.W;
             const size_t off = img + ((size_t)gy * p.W + gx) * C + cg * 8;
             if constexpr (IN_F32) {

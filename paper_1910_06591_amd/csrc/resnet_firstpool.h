@@ -102,12 +102,14 @@ __global__ __launch_bounds__(FP_THREADS) void first_pool_kernel(FirstPoolArgs p)
     // trip to memory)
     constexpr int UNR = 3;
     if constexpr (CELL == 4) {
+        RowWalk rw(tid, FP_THREADS, PP);
         for (int cell0 = tid; cell0 < PRH * PP; cell0 += UNR * FP_THREADS) {
             uint32_t raw[UNR][4];
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
                 const int cell = cell0 + u * FP_THREADS;
-                const int r = cell / PP, c = cell - r * PP;
+                const int r = rw.r, c = rw.c;
+                rw.next();
                 const int y = cy0 - 1 + r, x = cx0 - 1 + c;
                 raw[u][0] = raw[u][1] = raw[u][2] = raw[u][3] = 0;
                 if (cell < PRH * PP && y >= 0 && y < p.H && x >= 0 && x < p.W) {
@@ -128,13 +130,15 @@ __global__ __launch_bounds__(FP_THREADS) void first_pool_kernel(FirstPoolArgs p)
         }
     } else {
         constexpr int HALVES = CELL / 8;                       // 8 planes = 8 aligned bytes of the frame -> 16 bytes of the cell
+        const int h = tid % HALVES;
+        RowWalk rw(tid / HALVES, FP_THREADS / HALVES, PP);
         for (int idx0 = tid; idx0 < PRH * PP * HALVES; idx0 += UNR * FP_THREADS) {
             uint2 raw[UNR];
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
                 const int idx = idx0 + u * FP_THREADS;
-                const int cell = idx / HALVES, h = idx - cell * HALVES;
-                const int r = cell / PP, c = cell - r * PP;
+                const int r = rw.r, c = rw.c;
+                rw.next();
                 const int y = cy0 - 1 + r, x = cx0 - 1 + c;
                 raw[u] = uint2{0u, 0u};
                 if (idx < PRH * PP * HALVES && y >= 0 && y < p.H && x >= 0 && x < p.W)
@@ -207,9 +211,12 @@ __global__ __launch_bounds__(FP_THREADS) void first_pool_kernel(FirstPoolArgs p)
 
     // ---- 3x3 / 2 maximum: pooled pixel (ph, pw) covers region rows 2 ph .. 2 ph + 2, columns 2 pw .. 2 pw + 2 ----
     constexpr int NCG = C0 / 8;
-    for (int idx = tid; idx < p.PTH * p.PTW * NCG; idx += FP_THREADS) {
-        const int pp = idx / NCG, cg = idx - pp * NCG;
-        const int ph = pp / p.PTW, pw = pp - ph * p.PTW;
+    static_assert(FP_THREADS % NCG == 0, "a thread keeps its channel group");
+    const int cg = tid % NCG;
+    RowWalk pwk(tid / NCG, FP_THREADS / NCG, p.PTW);
+    for (int pp = tid / NCG; pp < p.PTH * p.PTW; pp += FP_THREADS / NCG) {
+        const int ph = pwk.r, pw = pwk.c;
+        pwk.next();
         if (ph0 + ph >= p.PH || pw0 + pw >= p.PW) continue;
         const char* win = cmap + (size_t)(2 * ph * CRW + 2 * pw) * K::CSTRIDE + cg * 16;
         uint4 m = *(const uint4*)win;
