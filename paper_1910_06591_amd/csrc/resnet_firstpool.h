@@ -32,7 +32,6 @@ struct FirstPoolArgs {
 };
 
 constexpr int FP_THREADS = 512;
-constexpr size_t FP_LDS_MAX = 40 * 1024;        // four workgroups per compute unit: the kernel is a chain of latencies
 
 // value(f, k) for pack_a: k = chunk * 32 + group * 8 + e -> (kernel row, kernel column, channel), see above
 inline void first_pool_k(int k, int& dy, int& dx, int& ci)
@@ -49,6 +48,10 @@ struct FirstPoolCfg {
     static_assert(CELL == 4 || CELL == 8 || CELL == 16, "planes per frame cell");
     static constexpr int NFT = C0 / 16;
     static constexpr int KCH = CELL == 4 ? 2 : (9 * CELL + 31) / 32;
+    // LDS per workgroup: four workgroups per compute unit up to 32 channels (the kernel is a chain of latencies:
+    // patch, convolution, pooling, store), two at 64, where a tile's fixed costs weigh more than the overlap
+    // (measured at 1024 images: x4 variant 2.61 -> 2.51 ms with 80 KB; x2 and the 144 x 108 map 1 - 2 % slower)
+    static constexpr size_t LDS_MAX = (C0 >= 64 ? 80 : 40) * 1024;
     // bytes between the convolution tile's pixels in LDS: 16 more than the C0 values, so that the 16 pixels of an
     // accumulator tile's 8-byte stores spread over the banks (at a power-of-two stride they fall on two to eight)
     static constexpr int CSTRIDE = C0 * 2 + (C0 >= 64 ? 16 : 0);   // (narrower tiles: the padding costs more tile area than the conflicts cost time)
@@ -62,7 +65,7 @@ struct FirstPoolCfg {
         for (int ny = 1; ny <= PH; ++ny)
             for (int nx = 1; nx <= PW; ++nx) {
                 const int th = (PH + ny - 1) / ny, tw = (PW + nx - 1) / nx;
-                if (lds_bytes(th, tw) > FP_LDS_MAX) continue;
+                if (lds_bytes(th, tw) > LDS_MAX) continue;
                 const long cost = (long)ny * nx * ((2 * th + 1) * (2 * tw + 1) + 64);     // convolution pixels + a fixed price per tile
                 if (best < 0 || cost < best) { best = cost; PTH = th; PTW = tw; }
                 break;
