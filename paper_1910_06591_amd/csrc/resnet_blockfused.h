@@ -16,7 +16,9 @@
 // What set the time, in the order it was found (1024 images, 32 channels on 36 x 48): the weight fragments one
 // chunk ahead (each chunk waited out a trip to L2: 260 -> 230 us with three ahead), the staging loop's loads
 // one round at a time (280 -> 260), and tiles whose maps fill LDS so that one workgroup per compute unit
-// loads, multiplies and stores in turn (230 -> 175 with tiles for two).  At 64 and 128 channels the kernel is
+// loads, multiplies and stores in turn (230 -> 175 with tiles for two), a test per pixel tile inside a chunk of the
+// convolution loop (rb_conv_n), and a division per (pixel tile, feature tile) in the epilogues (tile_coords: 172 ->
+// 156; the vector ALU, not the matrix pipe, was the busiest unit of these kernels).  At 64 and 128 channels the kernel is
 // bound by operand delivery: with two feature tiles per wavefront the weight fragments fill the vector L1's
 // bandwidth (16 wavefronts x 2 KiB per chunk) and the map fragments most of LDS's.
 #pragma once
