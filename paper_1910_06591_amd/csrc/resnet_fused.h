@@ -1266,10 +1266,15 @@ __device__ __forceinline__ void pooled_x(const char* cmap, int (&tb)[S::NT], flo
         if (wave + S::NWA * i >= S::NTILES) break;
 #pragma unroll
         for (int j = 0; j < S::FT; ++j) {
-            floatx4 m = to_floatx4(wv[i][j][0]);
+            // nine-value maxima on bf16 pairs (packed fp16 maximum, exact for these values: see bf16x2_max), widened once
+            uint2 m = __builtin_bit_cast(uint2, wv[i][j][0]);
 #pragma unroll
-            for (int d = 1; d < 9; ++d) m = max4(m, to_floatx4(wv[i][j][d]));
-            x[i][j] = m;
+            for (int d = 1; d < 9; ++d) {
+                const uint2 w = __builtin_bit_cast(uint2, wv[i][j][d]);
+                m.x = bf16x2_max(m.x, w.x);
+                m.y = bf16x2_max(m.y, w.y);
+            }
+            x[i][j] = floatx4{bf16_lo_f32(m.x), bf16_hi_f32(m.x), bf16_lo_f32(m.y), bf16_hi_f32(m.y)};
         }
     }
 }
