@@ -1228,7 +1228,7 @@ struct LdsMap {
     static constexpr int BUF0 = 0;
     static constexpr int BUF1 = r256(B0_);
     static constexpr int EDGE = BUF1 + r256(B1_);
-    static constexpr int NEUTRAL = EDGE + EDGE_;                   // 8 bytes of bf16 -inf: 'no edge column'
+    static constexpr int NEUTRAL = EDGE + EDGE_;                   // 8 bytes below every activation: 'no edge column'
     static constexpr int TRASH = EDGE + r256(EDGE_ + 16);         // 512 B: where lanes with nothing to store write
     static constexpr int WSA = TRASH + 512;
     static constexpr int WSB_HI = WSA + WSLOT_BYTES;
@@ -1424,7 +1424,7 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                 tb[i] = y * S::PITCH + xx;
                 if (!S::SLIDE && !tile_ok) break;
                 // the pooled value of a strip's last column lacks its right neighbour: it is the next strip's edge
-                // column; every other lane reads the neutral (-inf) cell instead
+                // column; every other lane reads the neutral cell instead
                 const bool fix = !S::POOL3 && (xx & 7) == 7 && xx + 1 < S::PW;
                 const int eoff = fix ? M::EDGE + (((((xx + 1) >> 3) * S::PH + y) * S::C + g * 4) * 2) : M::NEUTRAL;
                 const int ejmp = fix ? 32 : 0;
@@ -1446,8 +1446,11 @@ __device__ __forceinline__ void run_section(char* lds, const SecWeights& sw, con
                         x[i][j] = to_floatx4(pv[i][j]);
                         r = pv[i][j];
                     } else {
-                        x[i][j] = max4(to_floatx4(pv[i][j]), to_floatx4(ev[i][j]));
-                        r = to_bf16x4(x[i][j]);
+                        // maximum on the bf16 pairs (bf16x2_max), widened once; R needs no conversion back
+                        const uint2 a = __builtin_bit_cast(uint2, pv[i][j]), e = __builtin_bit_cast(uint2, ev[i][j]);
+                        const uint2 m = {bf16x2_max(a.x, e.x), bf16x2_max(a.y, e.y)};
+                        x[i][j] = floatx4{bf16_lo_f32(m.x), bf16_hi_f32(m.x), bf16_lo_f32(m.y), bf16_hi_f32(m.y)};
+                        r = __builtin_bit_cast(bf16x4, m);
                     }
                     // a short chain's missing tiles rewrite its last tile with the same values
                     if (S::SLIDE || ok[i]) *(bf16x4*)(buf0 + off + j * (2 * S::PLANE * 16)) = relu_bf16x4(r);
@@ -1634,9 +1637,7 @@ __global__ __launch_bounds__(RN_THREADS) void resnet3_bf16_kernel(TorsoArgs a)
     constexpr size_t FRAME = (size_t)S1::H * S1::W * S1::CIN;
     if ((int)blockIdx.x >= a.B) return;
     if (tid == 0) {   // the neutral edge cell
-        bf16x4 ninf;
-        ninf[0] = ninf[1] = ninf[2] = ninf[3] = (__bf16)(-INFINITY);
-        *(bf16x4*)(lds + M::NEUTRAL) = ninf;
+        *(uint2*)(lds + M::NEUTRAL) = uint2{BF16X2_LOWEST, BF16X2_LOWEST};
     }
     // the resident first-layer weight set
     stage_set<S1::W0_SET>(a.sec[0].w0, lds + M::PERM, tid & 63, __builtin_amdgcn_readfirstlane(tid >> 6));
@@ -1709,9 +1710,7 @@ __global__ __launch_bounds__(RN_THREADS) void resnet4_bf16_kernel(TorsoArgs a)
     constexpr size_t FRAME = (size_t)S1::H * S1::W * S1::CIN;
     if ((int)blockIdx.x >= a.B) return;
     if (tid == 0) {   // the neutral edge cell
-        bf16x4 ninf;
-        ninf[0] = ninf[1] = ninf[2] = ninf[3] = (__bf16)(-INFINITY);
-        *(bf16x4*)(lds + M::NEUTRAL) = ninf;
+        *(uint2*)(lds + M::NEUTRAL) = uint2{BF16X2_LOWEST, BF16X2_LOWEST};
     }
     stage_set<S1::W0_SET>(a.sec[0].w0, lds + M::PERM, tid & 63, __builtin_amdgcn_readfirstlane(tid >> 6));
     Prefetch<S1> pre;
