@@ -281,16 +281,18 @@ seed_status_t seed_infer_unroll(seed_infer_t* handle, int32_t T, int32_t B,
  *                 copied into the handle's pinned staging buffer before the call
  *                 returns: the caller may reuse the buffer at once.
  *
- * The handle keeps two device copies of its weights.  The call enqueues, on
- * `hip_stream`, the upload of the flat vector into the idle copy and (bf16 mode)
- * one kernel that packs it into the matrix-core kernels' operand layouts, then
- * makes that copy the active one: steps enqueued afterwards use the new
- * weights, steps enqueued before keep the old ones.  The host's share is one
- * copy of the flat vector (spread over a few threads); a step enqueued right
- * behind the call is ordered behind the upload on its stream.  If an enqueue
- * fails the active weights are unchanged.  Steps and updates must be enqueued
- * on the same stream (or be ordered by the caller): the update after next
- * overwrites the copy that steps enqueued before this call are still reading.
+ * The handle keeps two device copies of its weights.  The call enqueues, on a
+ * stream the handle owns (default priority), the upload of the flat vector into
+ * the idle copy and (bf16 mode) one kernel that packs it into the matrix-core
+ * kernels' operand layouts, makes `hip_stream` wait for them, and makes that
+ * copy the active one: steps enqueued on `hip_stream` afterwards use the new
+ * weights, steps enqueued before keep the old ones and are not waited for - the
+ * upload runs beside them.  The host's share is one copy of the flat vector
+ * (spread over a few threads).  If an enqueue fails the active weights are
+ * unchanged.  Steps and updates must be enqueued on the same stream (or be
+ * ordered by the caller): the update after next overwrites the copy that steps
+ * enqueued before this call are still reading, and waits only for what was
+ * enqueued on `hip_stream` before the previous update.
  * The call waits only for the upload of the update BEFORE the previous one
  * (two staging buffers are used alternately).  Allocates no device or pinned
  * memory.

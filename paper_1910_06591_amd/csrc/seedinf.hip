@@ -31,6 +31,12 @@ struct seed_infer {
     size_t staging_bytes = 0;
     hipEvent_t staged[2] = {nullptr, nullptr}; // recorded after the copy that reads staging[i]
     int stage_next = 0;
+    // weight updates travel on a stream of the handle's own, so that an upload runs beside the steps already
+    // enqueued on the caller's stream (they read the other copy) instead of behind them
+    hipStream_t up_stream = nullptr;
+    hipEvent_t uploaded[2] = {nullptr, nullptr};  // recorded on up_stream behind the update of copy i; the caller's stream waits for it
+    hipEvent_t retired[2] = {nullptr, nullptr};   // recorded on the caller's stream when copy i stopped being the active one
+    bool retired_set[2] = {false, false};
     float* d_act[2] = {nullptr, nullptr};   // fp32 ping-pong activations (fp32 mode)
     float* d_fc = nullptr;         // [max_batch, fc_units] fp32 (fp32 mode)
     float* d_hid = nullptr;        // [max_batch, 2*head_hidden] dueling hidden, fp32
@@ -135,7 +141,10 @@ static void free_all(seed_infer* h)
     if (h->bf) { bf16_destroy(h->bf); h->bf = nullptr; }
     for (hipEvent_t e : h->ev) (void)hipEventDestroy(e);
     delete h->pool;
+    if (h->up_stream) { (void)hipStreamSynchronize(h->up_stream); (void)hipStreamDestroy(h->up_stream); }
     for (int i = 0; i < 2; ++i) {
+        if (h->uploaded[i]) (void)hipEventDestroy(h->uploaded[i]);
+        if (h->retired[i]) (void)hipEventDestroy(h->retired[i]);
         if (h->staged[i]) (void)hipEventDestroy(h->staged[i]);
         if (h->staging[i]) (void)hipHostFree(h->staging[i]);
     }
@@ -176,7 +185,10 @@ static seed_status_t create_impl(seed_infer* h, const float* weights_host)
     for (int i = 0; i < 2; ++i) {
         HIP_TRY(h, hipHostMalloc((void**)&h->staging[i], h->staging_bytes, hipHostMallocDefault));
         HIP_TRY(h, hipEventCreateWithFlags(&h->staged[i], hipEventDisableTiming));
+        HIP_TRY(h, hipEventCreateWithFlags(&h->retired[i], hipEventDisableTiming));
+        HIP_TRY(h, hipEventCreateWithFlags(&h->uploaded[i], hipEventDisableTiming));
     }
+    HIP_TRY(h, hipStreamCreateWithFlags(&h->up_stream, hipStreamNonBlocking));        // default priority
     void* scratch = nullptr;                   // seed_infer_step_static's workspace on this device
     HIP_TRY(h, scratch_address(h->device, &scratch));
     HIP_TRY(h, hipDeviceSynchronize());
@@ -687,14 +699,24 @@ extern "C" seed_status_t seed_infer_set_weights(seed_infer_t* h, const float* we
     const int idle = 1 - h->active;
     const size_t wb = p.n_weights * sizeof(float);
     pool_memcpy(host_pool(h), h->staging[sb], weights_host, wb);
-    HIP_TRY(h, hipMemcpyAsync(h->d_w_set[idle], h->staging[sb], wb, hipMemcpyHostToDevice, s));
-    HIP_TRY(h, hipEventRecord(h->staged[sb], s));
+    // The update runs on the handle's own stream.  The idle copy was last read by the steps enqueued before the
+    // PREVIOUS update made it idle (an event on the caller's stream marks that point), so the upload need not wait
+    // for the steps enqueued since, which read the active copy: it runs beside them.
+    hipStream_t up = h->up_stream;
+    if (h->retired_set[idle]) HIP_TRY(h, hipStreamWaitEvent(up, h->retired[idle], 0));
+    HIP_TRY(h, hipMemcpyAsync(h->d_w_set[idle], h->staging[sb], wb, hipMemcpyHostToDevice, up));
+    HIP_TRY(h, hipEventRecord(h->staged[sb], up));
     h->stage_next = 1 - sb;
     if (h->bf) {
         // the matrix-core kernels' operand layouts are a fixed gather of the flat vector: packed on the device
-        bf16_repack(h->bf, h->d_w_set[idle], idle, s);
+        bf16_repack(h->bf, h->d_w_set[idle], idle, up);
         HIP_TRY(h, hipGetLastError());
     }
+    HIP_TRY(h, hipEventRecord(h->uploaded[idle], up));
+    // what the caller enqueues from here on waits for the update; the copy that was active until now retires here
+    HIP_TRY(h, hipStreamWaitEvent(s, h->uploaded[idle], 0));
+    HIP_TRY(h, hipEventRecord(h->retired[h->active], s));
+    h->retired_set[h->active] = true;
     // every piece of the update is enqueued: steps enqueued from here on read the new set
     if (h->bf) h->bf->active = idle;
     h->active = idle;
