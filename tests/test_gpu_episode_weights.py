@@ -163,3 +163,36 @@ def test_set_weights_swaps_and_restores(orc, name, precision, B):
     assert torch.equal(o5["logits"], o2["logits"])
     net.close()
     fresh.close()
+
+
+def test_set_weights_interleaved_with_long_steps(orc):
+    """Updates and steps enqueued back to back with no synchronisation, at a batch whose step outlasts an upload
+    several times over: the upload of update k + 1 runs on the handle's own stream while step k still reads the
+    other copy, and update k + 2 overwrites the copy step k read.  Every step must equal, bit for bit, a fresh
+    handle's step on the weights that were current when it was enqueued."""
+    import torch
+    cfg = wl.CONFIGS["C3"]
+    B = 2048
+    ws = [wl.make_weights(cfg, seed=100 + i, bf16_representable=True) for i in range(3)]
+    batch = to_device(wl.make_batch(cfg, B))
+    arch = seedinf.make_arch(cfg, max_batch=B, precision="bf16")
+    want = []
+    for w in ws:
+        fresh = seedinf.SeedInfer(arch, w)
+        o = fresh.step(**batch)
+        torch.cuda.synchronize()
+        want.append({k: o[k].clone() for k in ("logits", "h", "action")})
+        fresh.close()
+    assert not torch.equal(want[0]["logits"], want[1]["logits"]) and not torch.equal(want[1]["logits"], want[2]["logits"])
+    net = seedinf.SeedInfer(arch, ws[0])
+    got = []
+    order = [1, 2, 0, 2, 1, 0, 1, 1, 2]
+    for i in order:
+        net.set_weights(ws[i])
+        o = net.step(**batch)
+        got.append({k: o[k].clone() for k in ("logits", "h", "action")})
+    torch.cuda.synchronize()
+    for n, i in enumerate(order):
+        for k in got[n]:
+            assert torch.equal(got[n][k], want[i][k]), (n, i, k)
+    net.close()
