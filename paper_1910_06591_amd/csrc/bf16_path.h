@@ -533,6 +533,9 @@ inline seed_status_t bf16_create(const Plan& p, const float* d_w, Bf16State** ou
         set((const void*)conv_pool_kernel<128, 128>, CP_LDS_MAX);
         set((const void*)conv_tile_kernel<128, true>, CT_LDS_MAX);
         set((const void*)conv_tile_kernel<128, false>, CT_LDS_MAX);
+        set((const void*)first_pool_kernel<64, 4>, FirstPoolCfg<64, 4>::LDS_MAX);
+        set((const void*)first_pool_kernel<64, 8>, FirstPoolCfg<64, 8>::LDS_MAX);
+        set((const void*)first_pool_kernel<64, 16>, FirstPoolCfg<64, 16>::LDS_MAX);
         BF_TRY(e);
     }
     BF_TRY(hipFuncSetAttribute((const void*)resblock_fused_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RB_LDS_MAX));
